@@ -1,0 +1,133 @@
+"""CPU oracle of the Compact NGP encoding path.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes marshalling around oracle/cngp_oracle.c (plain C, fp64).  Only
+tests, the smoke check and the benchmark's CPU-baseline leg import this
+package; the product package never does, and this package never imports the
+product.  All arithmetic lives in the C file; this file converts arrays and
+threads shapes through.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from .build import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(_build())
+        _lib.cngp_oracle_level_resolutions.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u32(v):
+    return ctypes.c_uint32(int(v))
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def num_threads() -> int:
+    """Threads the OpenMP loops of the oracle use (OMP_NUM_THREADS or all cores)."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env:
+        return int(env.split(",")[0])
+    return len(os.sched_getaffinity(0))
+
+
+def level_resolutions(N_min, N_max, L) -> np.ndarray:
+    out = np.zeros(L, dtype=np.uint32)
+    rc = lib().cngp_oracle_level_resolutions(_u32(N_min), _u32(N_max), ctypes.c_int(L), _p(out))
+    if rc != 0:
+        raise ValueError("invalid N_min / N_max / L")
+    return out
+
+
+def _res(w, res):
+    if res is None:
+        res = level_resolutions(w.N_min, w.N_max, w.L)
+    res = np.ascontiguousarray(res, dtype=np.uint32)
+    assert res.shape == (w.L,)
+    return res
+
+
+def _x(w, x):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert x.ndim == 2 and x.shape[1] == w.d
+    return x
+
+
+def indices(w, x, D_c=None, res=None, want_weight=False):
+    """base, h2, probe, feat_idx as [N, L, 2^d] arrays (and the weights if asked)."""
+    x = _x(w, x); res = _res(w, res)
+    N = x.shape[0]
+    shp = (N, w.L, 1 << w.d)
+    base = np.zeros(shp, np.uint32); h2 = np.zeros(shp, np.uint32)
+    probe = np.zeros(shp, np.uint8); fidx = np.zeros(shp, np.uint32)
+    wt = np.zeros(shp, np.float64) if want_weight else None
+    if D_c is not None:
+        D_c = np.ascontiguousarray(D_c, dtype=np.uint8)
+        assert D_c.shape == (w.L, w.N_c)
+    lib().cngp_oracle_indices(w.d, w.L, _u32(w.N_f), _u32(w.N_c), _u32(w.N_p), _p(res), _p(x),
+                              ctypes.c_int64(N), _p(D_c), _p(base), _p(h2), _p(probe), _p(fidx), _p(wt))
+    return (base, h2, probe, fidx, wt) if want_weight else (base, h2, probe, fidx)
+
+
+def encode_fwd(w, x, D_f, D_c, res=None):
+    """Hard forward.  Returns (y, ymag), both float64 [N, L*F]."""
+    x = _x(w, x); res = _res(w, res)
+    N = x.shape[0]
+    D_f = _f64(D_f); assert D_f.shape == (w.L, w.N_f, w.F)
+    D_c = np.ascontiguousarray(D_c, dtype=np.uint8); assert D_c.shape == (w.L, w.N_c)
+    assert int(D_c.max(initial=0)) < w.N_p
+    y = np.zeros((N, w.L * w.F)); ymag = np.zeros((N, w.L * w.F))
+    lib().cngp_oracle_encode_fwd(w.d, w.L, w.F, _u32(w.N_f), _u32(w.N_c), _u32(w.N_p), _p(res),
+                                 _p(x), ctypes.c_int64(N), _p(D_f), _p(D_c), _p(y), _p(ymag))
+    return y, ymag
+
+
+def encode_soft_fwd(w, x, D_f, Dhat_c, res=None):
+    """Softmax-relaxed forward (test helper): float64 [N, L*F]."""
+    x = _x(w, x); res = _res(w, res)
+    N = x.shape[0]
+    D_f = _f64(D_f); assert D_f.shape == (w.L, w.N_f, w.F)
+    Dhat_c = _f64(Dhat_c); assert Dhat_c.shape == (w.L, w.N_c, w.N_p)
+    y = np.zeros((N, w.L * w.F))
+    lib().cngp_oracle_encode_soft_fwd(w.d, w.L, w.F, _u32(w.N_f), _u32(w.N_c), _u32(w.N_p), _p(res),
+                                      _p(x), ctypes.c_int64(N), _p(D_f), _p(Dhat_c), _p(y))
+    return y
+
+
+def encode_bwd(w, x, D_f, Dhat_c, dy, res=None, want_abs=True):
+    """Backward.  Returns (gD_f, gDhat_c, A_f, A_c) in float64 (A_* None if not asked)."""
+    x = _x(w, x); res = _res(w, res)
+    N = x.shape[0]
+    D_f = _f64(D_f); assert D_f.shape == (w.L, w.N_f, w.F)
+    Dhat_c = _f64(Dhat_c); assert Dhat_c.shape == (w.L, w.N_c, w.N_p)
+    dy = _f64(dy); assert dy.shape == (N, w.L * w.F)
+    gDf = np.zeros_like(D_f); gDc = np.zeros_like(Dhat_c)
+    Af = np.zeros_like(D_f) if want_abs else None
+    Ac = np.zeros_like(Dhat_c) if want_abs else None
+    lib().cngp_oracle_encode_bwd(w.d, w.L, w.F, _u32(w.N_f), _u32(w.N_c), _u32(w.N_p), _p(res),
+                                 _p(x), ctypes.c_int64(N), _p(D_f), _p(Dhat_c), _p(dy),
+                                 _p(gDf), _p(gDc), _p(Af), _p(Ac))
+    return gDf, gDc, Af, Ac
+
+
+def bake_probes(Dhat_c) -> np.ndarray:
+    """argmax along the last axis, uint8, same leading shape."""
+    Dhat_c = np.ascontiguousarray(Dhat_c, dtype=np.float32)
+    N_p = Dhat_c.shape[-1]
+    rows = Dhat_c.size // N_p if N_p else 0
+    out = np.zeros(Dhat_c.shape[:-1], dtype=np.uint8)
+    lib().cngp_oracle_bake_probes(_p(Dhat_c), ctypes.c_int64(rows), _u32(N_p), _p(out))
+    return out

@@ -1,0 +1,428 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something that
+is not the oracle -- closed forms, brute force over a resolved dense grid with a
+library interpolator, the reduction to the plain hash grid, exact adjoint and
+finite-difference identities of the softmax-relaxed forward, and the invariants
+the method's definition implies.  CPU only.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+from scipy.interpolate import RegularGridInterpolator
+
+import oracle
+import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+M32 = 0xFFFFFFFF
+
+# Constants as the readings fix them (Eq. 3: "large prime numbers, optionally pi_0 = 1").
+PI = (1, 2654435761, 805459861)
+PI2 = (1580030173, 1367130559, 3037000507)
+
+
+def py_hash(v, primes):
+    """Eq. 3 with Python integers, every product reduced to 32 bits."""
+    h = 0
+    for vi, p in zip(v, primes):
+        h ^= (int(vi) * p) & M32
+    return h
+
+
+def py_feat_index(v, N_f, N_c, N_p, D_c_level):
+    """Eq. 6, literally."""
+    return (N_p * py_hash(v, PI)) % N_f + int(D_c_level[py_hash(v, PI2) % N_c])
+
+
+def small(d=2, **kw):
+    base = dict(d=d, L=3, F=2, N_f=64, N_c=32, N_p=4, N_min=3, N_max=11, N=160)
+    base.update(kw)
+    return W.custom(**base)
+
+
+def random_tables(w, seed=0, scale=1.0):
+    rng = np.random.default_rng(seed)
+    D_f = rng.uniform(-scale, scale, (w.L, w.N_f, w.F))
+    Dhat = rng.standard_normal((w.L, w.N_c, w.N_p)).astype(np.float32)
+    x = rng.random((w.N, w.d)).astype(np.float32)
+    dy = rng.standard_normal((w.N, w.L * w.F))
+    return x, D_f, Dhat, dy
+
+
+# --------------------------------------------------------------------------- constants
+
+def _is_prime(n):
+    if n < 2:
+        return False
+    if n % 2 == 0:
+        return n == 2
+    i = 3
+    while i * i <= n:
+        if n % i == 0:
+            return False
+        i += 2
+    return True
+
+
+def test_hash_constants_are_distinct_primes():
+    for p in PI[1:] + PI2:
+        assert _is_prime(p) and p < 2**32
+    assert len(set(PI + PI2)) == 6
+    assert PI[0] == 1                      # "optionally pi_0 = 1" (Eq. 3)
+
+
+# --------------------------------------------------------------------------- level table
+
+def _golden_tables():
+    rows = []
+    for line in open(os.path.join(GOLDEN, "level_tables.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        head, tail = line.split(":")
+        nmin, nmax, L = map(int, head.split())
+        rows.append((nmin, nmax, L, list(map(int, tail.split()))))
+    return rows
+
+
+@pytest.mark.parametrize("nmin,nmax,L,expect", _golden_tables())
+def test_level_table_golden(nmin, nmax, L, expect):
+    assert oracle.level_resolutions(nmin, nmax, L).tolist() == expect
+
+
+@pytest.mark.parametrize("nmin,nmax,L", [(16, 512, 16), (16, 524288, 16), (16, 2048, 16), (4, 4, 5),
+                                         (1, 1024, 11), (16, 2048, 2), (7, 100, 3)])
+def test_level_table_closed_forms(nmin, nmax, L):
+    """Table 1: coarsest resolution N_min, finest N_max; growth is monotone and geometric."""
+    r = oracle.level_resolutions(nmin, nmax, L).astype(np.int64)
+    assert r[0] == nmin and r[-1] == nmax
+    assert np.all(np.diff(r) >= 0)
+    b = (nmax / nmin) ** (1.0 / (L - 1))
+    exact = nmin * b ** np.arange(L)
+    assert np.all(r <= exact + 1e-5) and np.all(r > exact - 1.0)
+
+
+def test_level_table_exact_powers():
+    # b = 2 exactly: every level must be the exact power (plain floor() would lose some to rounding).
+    assert oracle.level_resolutions(1, 1024, 11).tolist() == [2**i for i in range(11)]
+    assert oracle.level_resolutions(16, 16, 1).tolist() == [16]
+    assert oracle.level_resolutions(5, 99, 1).tolist() == [5]      # L == 1: N_max ignored
+
+
+# --------------------------------------------------------------------------- hashes and indices
+
+def test_index_closed_forms_at_origin():
+    """x = 0: the lower corner is the all-zero vertex (hash = 0), corner 1 is the unit vector e_0
+    (hash = pi_0 = 1, so base = N_p), and with d = 1-like inputs hash(v) = v."""
+    w = small(d=3, L=1, N_min=8, N_f=256, N_c=64, N_p=8)
+    x = np.zeros((1, 3), np.float32)
+    base, h2, probe, fidx = oracle.indices(w, x, None)
+    assert base[0, 0, 0] == 0 and h2[0, 0, 0] == 0
+    assert base[0, 0, 1] == w.N_p                       # N_p * hash(e_0) = N_p
+    assert h2[0, 0, 1] == PI2[0] % w.N_c
+    assert base[0, 0, 2] == (w.N_p * PI[1]) % w.N_f     # e_1
+    assert base[0, 0, 4] == (w.N_p * PI[2]) % w.N_f     # e_2
+    assert base[0, 0, 7] == (w.N_p * (1 ^ PI[1] ^ PI[2])) % w.N_f
+    # moving along dimension 0 only: hash(v) = v_0 (pi_0 = 1) while v_0 < N_f / N_p
+    xs = np.zeros((8, 3), np.float32); xs[:, 0] = np.arange(8) / 8.0
+    base, _, _, _ = oracle.indices(w, xs, None)
+    assert base[:, 0, 0].tolist() == [(w.N_p * i) % w.N_f for i in range(8)]
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_indices_match_bigint_evaluation_and_bit_concatenation(d):
+    """Every index of the dump equals an evaluation of Eq. 3 / Eq. 6 with Python integers, and
+    Eq. 6's arithmetic form equals the bitwise concatenation described in the Fig. 3 caption:
+    hashed most significant bits, learned least significant bits."""
+    w = small(d=d, L=4, N_min=5, N_max=1000, N_f=1024, N_c=128, N_p=8, N=300)
+    rng = np.random.default_rng(7)
+    x = rng.random((w.N, d)).astype(np.float32)
+    x[0] = 0.0; x[1] = 1.0; x[2] = 0.5
+    D_c = rng.integers(0, w.N_p, (w.L, w.N_c)).astype(np.uint8)
+    res = oracle.level_resolutions(w.N_min, w.N_max, w.L)
+    base, h2, probe, fidx = oracle.indices(w, x, D_c)
+    logp = w.N_p.bit_length() - 1
+    for n in range(w.N):
+        for l in range(w.L):
+            pos = x[n].astype(np.float32) * np.float32(res[l])        # fp32 product
+            v0 = np.floor(pos).astype(np.int64)
+            for c in range(1 << d):
+                v = [int(v0[i]) + ((c >> i) & 1) for i in range(d)]
+                h = py_hash(v, PI)
+                g = py_hash(v, PI2) % w.N_c
+                assert base[n, l, c] == (w.N_p * h) % w.N_f
+                assert h2[n, l, c] == g
+                assert probe[n, l, c] == D_c[l, g]
+                assert fidx[n, l, c] == py_feat_index(v, w.N_f, w.N_c, w.N_p, D_c[l])
+                concat = ((h % (w.N_f // w.N_p)) << logp) | int(D_c[l, g])
+                assert fidx[n, l, c] == concat
+                assert fidx[n, l, c] < w.N_f
+
+
+def test_weights_partition_unity_and_vertex_positions():
+    w = small(d=3, L=2, N_min=4, N_max=16, N=50)
+    rng = np.random.default_rng(3)
+    x = rng.random((w.N, 3)).astype(np.float32)
+    *_, wt = oracle.indices(w, x, None, want_weight=True)
+    assert np.allclose(wt.sum(axis=2), 1.0, rtol=0, atol=1e-15)
+    assert np.all(wt >= 0)
+    # the weighted mean of the corner offsets reproduces the fractional position
+    res = oracle.level_resolutions(w.N_min, w.N_max, w.L)
+    for l in range(w.L):
+        pos = (x * np.float32(res[l])).astype(np.float64)
+        frac = pos - np.floor(pos)
+        for i in range(3):
+            delta = np.array([(c >> i) & 1 for c in range(8)], dtype=np.float64)
+            assert np.allclose((wt[:, l, :] * delta).sum(axis=1), frac[:, i], atol=1e-15)
+
+
+# --------------------------------------------------------------------------- hard forward
+
+def resolved_grid(w, Nl, D_f_level, D_c_level):
+    """Dense array T[v] = D_f[f(v)] over every vertex 0..Nl+1 per axis (Eq. 6 evaluated per vertex)."""
+    n = Nl + 2
+    T = np.zeros((n,) * w.d + (w.F,))
+    for v in itertools.product(range(n), repeat=w.d):
+        T[v] = D_f_level[py_feat_index(v, w.N_f, w.N_c, w.N_p, D_c_level)]
+    return T
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_forward_equals_library_interpolation_of_resolved_grid(d):
+    w = small(d=d)
+    x, D_f, Dhat, _ = random_tables(w, seed=11)
+    x[:3] = [[0.0] * d, [1.0] * d, [0.25] * d]
+    D_c = np.random.default_rng(5).integers(0, w.N_p, (w.L, w.N_c)).astype(np.uint8)
+    y, ymag = oracle.encode_fwd(w, x, D_f, D_c)
+    res = oracle.level_resolutions(w.N_min, w.N_max, w.L)
+    for l in range(w.L):
+        Nl = int(res[l])
+        T = resolved_grid(w, Nl, D_f[l], D_c[l])
+        axes = [np.arange(Nl + 2, dtype=np.float64)] * d
+        pos = (x * np.float32(Nl)).astype(np.float64)            # the fp32 product, widened
+        for f in range(w.F):
+            interp = RegularGridInterpolator(axes, T[..., f], method="linear")
+            assert np.allclose(y[:, l * w.F + f], interp(pos), rtol=0, atol=1e-14)
+    assert np.all(ymag >= np.abs(y) - 1e-15)
+
+
+def test_forward_on_vertices_returns_table_entries():
+    """x = v / N_l with N_l a power of two is exact in fp32: y is the looked-up feature itself."""
+    w = small(d=3, L=1, N_min=8, N_f=128, N_c=64, N_p=4)
+    rng = np.random.default_rng(2)
+    D_f = rng.standard_normal((1, w.N_f, w.F))
+    D_c = rng.integers(0, w.N_p, (1, w.N_c)).astype(np.uint8)
+    vs = rng.integers(0, 9, (64, 3))
+    x = (vs / 8.0).astype(np.float32)
+    y, _ = oracle.encode_fwd(w, x, D_f, D_c)
+    for n, v in enumerate(vs):
+        assert np.array_equal(y[n], D_f[0, py_feat_index(v, w.N_f, w.N_c, w.N_p, D_c[0])])
+
+
+def test_forward_constant_codebook_gives_constant():
+    w = small(d=3)
+    x, D_f, _, _ = random_tables(w)
+    D_f[:] = 0.375
+    D_c = np.zeros((w.L, w.N_c), np.uint8)
+    y, _ = oracle.encode_fwd(w, x, D_f, D_c)
+    assert np.allclose(y, 0.375, rtol=0, atol=1e-15)
+
+
+def plain_hash_grid(x, res, D_f, primes=PI):
+    """Eq. 3: multiresolution hash grid without probing, D_f[hash(v) mod N_f], vectorised numpy."""
+    N, d = x.shape
+    L, N_f, F = D_f.shape
+    y = np.zeros((N, L * F))
+    for l in range(L):
+        pos = (x * np.float32(res[l])).astype(np.float64)
+        v0 = np.floor(pos).astype(np.uint64)
+        fr = pos - np.floor(pos)
+        for c in range(1 << d):
+            h = np.zeros(N, dtype=np.uint64)
+            wgt = np.ones(N)
+            for i in range(d):
+                bit = (c >> i) & 1
+                h ^= ((v0[:, i] + np.uint64(bit)) * np.uint64(primes[i])) & np.uint64(M32)
+                wgt *= fr[:, i] if bit else 1.0 - fr[:, i]
+            y[:, l * F:(l + 1) * F] += wgt[:, None] * D_f[l, (h % np.uint64(N_f)).astype(np.int64)]
+    return y
+
+
+@pytest.mark.parametrize("d,N_c", [(2, 1), (3, 1), (3, 16)])
+def test_probe_range_one_is_plain_hash_grid(d, N_c):
+    """N_p = 1 turns the method into the unprobed hash grid (Sec. 3 "Selecting hyperparameters")."""
+    w = small(d=d, N_p=1, N_c=N_c, N_f=128, L=4, N_min=4, N_max=64)
+    x, D_f, _, _ = random_tables(w, seed=21)
+    D_c = np.zeros((w.L, w.N_c), np.uint8)
+    y, _ = oracle.encode_fwd(w, x, D_f, D_c)
+    res = oracle.level_resolutions(w.N_min, w.N_max, w.L)
+    assert np.allclose(y, plain_hash_grid(x, res, D_f), rtol=0, atol=1e-14)
+
+
+def test_single_row_index_codebook_is_global_probe():
+    """N_c = 1: one learned probe p for the whole level: a plain hash grid over the N_f / N_p
+    entries p, p + N_p, p + 2 N_p, ... of the feature codebook."""
+    w = small(d=3, N_c=1, N_p=4, N_f=64, L=3)
+    x, D_f, _, _ = random_tables(w, seed=4)
+    D_c = np.array([[1], [3], [0]], np.uint8)
+    y, _ = oracle.encode_fwd(w, x, D_f, D_c)
+    res = oracle.level_resolutions(w.N_min, w.N_max, w.L)
+    sub = np.stack([D_f[l, int(D_c[l, 0])::w.N_p] for l in range(w.L)])     # [L, N_f/N_p, F]
+    assert np.allclose(y, plain_hash_grid(x, res, sub), rtol=0, atol=1e-14)
+
+
+# --------------------------------------------------------------------------- soft forward / backward
+
+def loss_soft(w, x, D_f, Dhat, dy):
+    return float(np.sum(oracle.encode_soft_fwd(w, x, D_f, Dhat) * dy))
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_soft_forward_is_softmax_mix_of_hard_forwards(d):
+    """With N_c = 1 the relaxed forward is the softmax-weighted mix of the N_p hard forwards."""
+    w = small(d=d, N_c=1, N_p=4, L=2)
+    x, D_f, Dhat, _ = random_tables(w, seed=9)
+    ys = oracle.encode_soft_fwd(w, x, D_f, Dhat)
+    mix = np.zeros_like(ys)
+    for l in range(w.L):
+        e = np.exp(Dhat[l, 0].astype(np.float64)); s = e / e.sum()
+        for k in range(w.N_p):
+            D_c = np.zeros((w.L, 1), np.uint8); D_c[l, 0] = k
+            yk, _ = oracle.encode_fwd(w, x, D_f, D_c)
+            mix[:, l * w.F:(l + 1) * w.F] += s[k] * yk[:, l * w.F:(l + 1) * w.F]
+    assert np.allclose(ys, mix, rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_backward_adjoint_identity(d):
+    """The relaxed forward is linear in D_f, so <y~(D_f), dy> = <D_f, gD_f> exactly."""
+    w = small(d=d)
+    x, D_f, Dhat, dy = random_tables(w, seed=13)
+    gDf, gDc, Af, Ac = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    lhs = loss_soft(w, x, D_f, Dhat, dy)
+    rhs = float(np.sum(D_f * gDf))
+    assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+    assert np.all(Af >= np.abs(gDf) - 1e-12) and np.all(Ac >= np.abs(gDc) - 1e-12)
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_backward_matches_finite_differences(d):
+    w = small(d=d, N=120)
+    x, D_f, Dhat, dy = random_tables(w, seed=17)
+    gDf, gDc, _, _ = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    rng = np.random.default_rng(1)
+    Dh64 = Dhat.astype(np.float64)
+    # feature codebook: pick entries with the largest gradients plus random ones
+    flat = np.argsort(-np.abs(gDf).ravel())[:6].tolist() + rng.integers(0, gDf.size, 6).tolist()
+    for idx in flat:
+        i = np.unravel_index(idx, gDf.shape)
+        h = 1e-3
+        Dp = D_f.copy(); Dp[i] += h
+        Dm = D_f.copy(); Dm[i] -= h
+        fd = (loss_soft(w, x, Dp, Dh64, dy) - loss_soft(w, x, Dm, Dh64, dy)) / (2 * h)
+        assert abs(fd - gDf[i]) <= 1e-8 * max(1.0, abs(gDf[i]))
+    # confidence values
+    flat = np.argsort(-np.abs(gDc).ravel())[:8].tolist() + rng.integers(0, gDc.size, 6).tolist()
+    for idx in flat:
+        i = np.unravel_index(idx, gDc.shape)
+        h = 1e-5
+        Dp = Dh64.copy(); Dp[i] += h
+        Dm = Dh64.copy(); Dm[i] -= h
+        fd = (loss_soft(w, x, D_f, Dp, dy) - loss_soft(w, x, D_f, Dm, dy)) / (2 * h)
+        assert abs(fd - gDc[i]) <= 1e-6 * max(1.0, abs(gDc[i]))
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_backward_invariants(d):
+    w = small(d=d)
+    x, D_f, Dhat, dy = random_tables(w, seed=19)
+    gDf, gDc, _, _ = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    # softmax Jacobian annihilates constants: every row of the logit gradient sums to zero
+    assert np.allclose(gDc.sum(axis=2), 0.0, rtol=0, atol=1e-12)
+    # sigma and the interpolation weights each sum to one: gradient mass is conserved per level/feature
+    want = dy.reshape(w.N, w.L, w.F).sum(axis=0)
+    assert np.allclose(gDf.sum(axis=1), want, rtol=0, atol=1e-11)
+    # a constant added to a row of confidence values changes nothing
+    shift = np.random.default_rng(0).standard_normal((w.L, w.N_c, 1))
+    g2 = oracle.encode_bwd(w, x, D_f, Dhat.astype(np.float64) + shift, dy)
+    assert np.allclose(g2[0], gDf, rtol=0, atol=1e-12) and np.allclose(g2[1], gDc, rtol=0, atol=1e-12)
+    # backward accumulates: linear in dy
+    g3 = oracle.encode_bwd(w, x, D_f, Dhat, 2.0 * dy)
+    assert np.allclose(g3[0], 2 * gDf, atol=1e-12) and np.allclose(g3[1], 2 * gDc, atol=1e-12)
+
+
+def test_one_hot_confidences_make_soft_equal_hard():
+    """Confident rows: softmax -> one-hot, the relaxed forward is the hard forward of the baked
+    codebook, the feature gradient is the true gradient of the hard forward and the logit gradient
+    vanishes."""
+    w = small(d=3)
+    x, D_f, _, dy = random_tables(w, seed=23)
+    D_c = np.random.default_rng(8).integers(0, w.N_p, (w.L, w.N_c)).astype(np.uint8)
+    Dhat = np.zeros((w.L, w.N_c, w.N_p))
+    np.put_along_axis(Dhat, D_c[..., None].astype(np.int64), 800.0, axis=2)
+    assert np.array_equal(oracle.bake_probes(Dhat), D_c)
+    yh, _ = oracle.encode_fwd(w, x, D_f, D_c)
+    assert np.allclose(oracle.encode_soft_fwd(w, x, D_f, Dhat), yh, rtol=0, atol=1e-15)
+    gDf, gDc, _, _ = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    assert np.allclose(gDc, 0.0, atol=1e-15)
+    # gradient of the hard forward <y(D_f), dy> by finite differences (it is linear in D_f)
+    for idx in np.argsort(-np.abs(gDf).ravel())[:6]:
+        i = np.unravel_index(idx, gDf.shape)
+        Dp = D_f.copy(); Dp[i] += 1.0
+        fd = float(np.sum((oracle.encode_fwd(w, x, Dp, D_c)[0] - yh) * dy))
+        assert abs(fd - gDf[i]) <= 1e-10 * max(1.0, abs(fd))
+
+
+def test_probe_range_one_backward_is_hash_grid_backward():
+    """N_p = 1: sigma = 1, the logit gradient is zero and gD_f is the scatter of weight * dy."""
+    w = small(d=2, N_p=1, N_c=8, N_f=32, L=2)
+    x, D_f, Dhat, dy = random_tables(w, seed=29)
+    gDf, gDc, _, _ = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    assert np.all(gDc == 0.0)
+    base, _, _, fidx, wt = oracle.indices(w, x, None, want_weight=True)
+    want = np.zeros_like(gDf)
+    for n in range(w.N):
+        for l in range(w.L):
+            for c in range(4):
+                want[l, fidx[n, l, c]] += wt[n, l, c] * dy[n, l * w.F:(l + 1) * w.F]
+    assert np.allclose(gDf, want, rtol=0, atol=1e-13)
+
+
+# --------------------------------------------------------------------------- bake
+
+def test_bake_properties():
+    rng = np.random.default_rng(31)
+    for N_p in (1, 2, 4, 8, 16):
+        Dhat = rng.standard_normal((3, 50, N_p)).astype(np.float32)
+        D_c = oracle.bake_probes(Dhat)
+        assert D_c.dtype == np.uint8 and D_c.shape == (3, 50)
+        assert D_c.max() < N_p                                   # D_c in {0..N_p-1} (Sec. 3)
+        assert np.array_equal(D_c, np.argmax(Dhat, axis=2))
+        assert np.array_equal(oracle.bake_probes(Dhat * 3.0 + 5.0), D_c)      # shift / positive scale
+        hot = rng.integers(0, N_p, (3, 50))
+        onehot = np.zeros((3, 50, N_p), np.float32)
+        np.put_along_axis(onehot, hot[..., None], 1.0, axis=2)
+        assert np.array_equal(oracle.bake_probes(onehot), hot)
+
+
+def test_bake_ties_and_nan():
+    rows = np.array([[1, 1, 1, 1], [0, 2, 2, 1], [np.nan, 0, np.nan, 0], [np.nan] * 4,
+                     [-np.inf, -np.inf, -np.inf, -np.inf], [np.nan, -np.inf, 3, 3]], np.float32)
+    assert oracle.bake_probes(rows).tolist() == [0, 1, 1, 0, 0, 2]
+
+
+# --------------------------------------------------------------------------- storage conventions
+
+def test_model_sizes_consistent_with_table_3():
+    """Table 3's file sizes fix the storage conventions by arithmetic: one codebook pair per level,
+    F = 2 half-precision features, log2(N_p)-bit probe indices.  The printed sizes (which also hold
+    an MLP and, apparently, smaller coarse levels) are a little below L * (2 F N_f + N_c log2 N_p / 8)."""
+    for line in open(os.path.join(GOLDEN, "table3_sizes.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        _, N_f, N_c, N_p, kB = line.split()
+        N_f, N_c, N_p, kB = int(N_f), int(N_c), int(N_p), float(kB)
+        bits = N_p.bit_length() - 1
+        full = 16 * (N_f * 2 * 2 + N_c * bits / 8) / 1000.0
+        assert 0.8 * full <= kB <= full
