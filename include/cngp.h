@@ -1,0 +1,141 @@
+/*
+ * cngp.h -- C ABI of the Compact NGP encoding library for AMD MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of "Compact Neural Graphics
+ * Primitives with Learned Hash Probing": a multiresolution hash-grid input
+ * encoding y = psi(x; theta) whose feature index is
+ *
+ *     f(v) = D_f[ (N_p * hash(v)) mod N_f + D_c[hash2(v)] ]            (Eq. 6)
+ *
+ * with hash / hash2 two spatial hashes (Eq. 3) over different primes, D_f the
+ * feature codebook, D_c the index codebook of learned probe offsets, and D^_c its
+ * training-time version holding N_p confidence values per row (Sec. 3).
+ *
+ * Conventions shared by every entry point
+ *   - Pointers marked "dev" are device (HBM) addresses, "host" are host addresses.
+ *     Every buffer is allocated, owned and freed by the caller.  The library keeps no
+ *     device state, allocates no device memory and never synchronises the device:
+ *     all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     null stream) and the call returns once it is enqueued.
+ *   - Arrays are dense, row-major, with the shapes given below; no strides.
+ *   - Return value: 0 (CNGP_OK) or a negative cngp_status.  All argument checks run on
+ *     the host before anything is launched, so they need no GPU.  N == 0 is a successful
+ *     no-op.  Nothing throws across this boundary.
+ *   - Preconditions that are NOT checked on the device: x finite and inside [0, 1]^d;
+ *     every entry of D_c smaller than N_p.
+ *   - Corner numbering: corner c of a grid cell has offset (c >> i) & 1 along dimension i.
+ *   - Level l uses rows [l] of every codebook; output column l*F + f holds feature f of level l.
+ */
+#ifndef CNGP_H
+#define CNGP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CNGP_OK              =  0,
+    CNGP_ERR_NULL        = -1,  /* a required pointer is NULL                                  */
+    CNGP_ERR_INVALID     = -2,  /* a size is out of range or not a power of two where required  */
+    CNGP_ERR_UNSUPPORTED = -3,  /* valid in the paper's terms, not built here (e.g. F != 2)     */
+    CNGP_ERR_WORKSPACE   = -4,  /* workspace missing, misaligned or smaller than required       */
+    CNGP_ERR_HIP         = -5   /* a HIP call failed; see cngp_last_hip_error()                 */
+} cngp_status;
+
+typedef enum { CNGP_F32 = 0, CNGP_F16 = 1 } cngp_dtype;
+
+/* Layout of the baked index codebook D_c.
+ *   CNGP_IDX_U8      one byte per entry, [L, N_c]
+ *   CNGP_IDX_PACKED4 two entries per byte, [L, N_c / 2]; entry 2i is the low nibble of byte i.
+ *                    Needs N_c >= 2 (N_p <= 16 always fits four bits). */
+typedef enum { CNGP_IDX_U8 = 0, CNGP_IDX_PACKED4 = 1 } cngp_index_format;
+
+enum { CNGP_ZERO_GRADS = 1u };  /* cngp_encode_bwd clears both gradient arrays before accumulating */
+
+/* Hyper-parameters of the encoding (Table 1 of the paper, same symbols). */
+typedef struct {
+    int32_t  d;            /* dimension of the input domain, 2 or 3                            */
+    int32_t  L;            /* number of resolution levels, 1 .. 32                             */
+    int32_t  F;            /* features per codebook entry; only 2 is built                     */
+    uint32_t N_f;          /* entries of the feature codebook per level, power of two          */
+    uint32_t N_c;          /* rows of the index codebook per level, power of two               */
+    uint32_t N_p;          /* probing range, power of two, 1 .. 16, N_p <= N_f                 */
+    uint32_t N_min;        /* coarsest grid resolution, >= 1                                   */
+    uint32_t N_max;        /* finest grid resolution, >= N_min, <= 2^24 (ignored when L == 1)  */
+    int32_t  feat_dtype;   /* cngp_dtype of D_f                                                */
+    int32_t  io_dtype;     /* cngp_dtype of y and dL/dy                                        */
+    int32_t  index_format; /* cngp_index_format of D_c                                         */
+    uint32_t flags;        /* CNGP_ZERO_GRADS or 0                                             */
+} cngp_config;
+
+/* Grid resolution of every level (Table 1: N_min, N_max, L; geometric growth):
+ * N_l = floor(N_min * b^l + 1e-6), b = exp(ln(N_max / N_min) / (L - 1)); L == 1 gives N_min.
+ * out_N_l: host, L entries.  Runs on the host. */
+int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l);
+
+/* Bytes of device scratch the calls below need for N points (may be 0).  The workspace
+ * must be 256-byte aligned; its contents are undefined before and after each call.
+ * Returns 0 for an invalid configuration as well (the encode calls then report the error). */
+size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N);
+
+/* Forward encoding (Eq. 6; Fig. 3: enclosing vertices, two hashes, probe lookup, feature
+ * gather, d-linear interpolation, concatenation over levels; the forward pass uses the baked
+ * D_c, Sec. 3 "Training").
+ *   x    dev  float32 [N, d], inside [0,1]^d; scaled per level as one fp32 multiply x * N_l
+ *   D_f  dev  feat_dtype [L, N_f, F]
+ *   D_c  dev  index_format, see above
+ *   y    dev  io_dtype [N, L*F], written (not accumulated); fp32 arithmetic, one final rounding */
+int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N,
+                    const void *D_f, const void *D_c, void *y,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward pass (Sec. 3 "Training"; Fig. 3: straight-through estimator).  The gradient of the
+ * forward pass with the hard maximum replaced by a softmax over each row of D^_c: for every
+ * enclosing vertex, with g = weight * dL/dy, sigma = softmax(D^_c[l][hash2(v)]) and
+ * q_k = <D_f[l][base + k], g>,
+ *     grad_D_f[l][base + k][f]       += sigma_k * g[f]                    for all k < N_p
+ *     grad_Dhat_c[l][hash2(v)][k]    += sigma_k * (q_k - sum_j sigma_j q_j)
+ * Uses D^_c only, never D_c.  No gradient with respect to x.
+ *   Dhat_c       dev float32 [L, N_c, N_p]
+ *   dy           dev io_dtype [N, L*F]
+ *   grad_D_f     dev float32 [L, N_f, F]      accumulated (+=), or cleared first with CNGP_ZERO_GRADS
+ *   grad_Dhat_c  dev float32 [L, N_c, N_p]    same
+ * Sums are formed with floating-point atomics: their order, hence the last bits, vary run to run. */
+int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N,
+                    const void *D_f, const float *Dhat_c, const void *dy,
+                    float *grad_D_f, float *grad_Dhat_c,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bake (Fig. 3; Sec. 3): D_c[l][r] = index of the largest confidence value in row r of D^_c.
+ * Ties: lowest index; NaN never wins; an all-NaN row gives 0.  Result always < N_p.
+ *   Dhat_c dev float32 [L, N_c, N_p];  D_c dev, written in cfg->index_format. */
+int cngp_bake_probes(const cngp_config *cfg, const float *Dhat_c, void *D_c, void *stream);
+
+/* Index dump for parity checks: for every (point, level, corner) the integers of Eq. 6.
+ * All outputs dev, shape [N, L, 2^d]; any of them may be NULL.
+ *   base      (N_p * hash(v)) mod N_f        h2        hash2(v) mod N_c
+ *   probe     D_c[l][h2]                     feat_idx  base + probe */
+int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const void *D_c,
+                       uint32_t *base, uint32_t *h2, uint8_t *probe, uint32_t *feat_idx,
+                       void *stream);
+
+/* Per-kernel timing, off by default.  When enabled every kernel the library launches is bracketed
+ * by HIP events on its stream.  cngp_profile_read() waits for those events, adds each kernel's
+ * elapsed milliseconds and launch count into the caller's arrays (host, `max_kernels` entries;
+ * kernel i is named cngp_profile_kernel_name(i)), clears the record and returns the number of
+ * kernel kinds.  Not thread safe; meant for benchmarks. */
+int         cngp_profile_enable(int on);
+int         cngp_profile_read(double *ms_sum, int64_t *launches, int max_kernels);
+const char *cngp_profile_kernel_name(int i);
+
+const char *cngp_error_string(int status);
+const char *cngp_last_hip_error(void);   /* text of the last failed HIP call in this thread, or "" */
+int         cngp_version(void);          /* major * 10000 + minor * 100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CNGP_H */

@@ -1,0 +1,250 @@
+"""Python binding of libcngp.so, the Compact NGP encoding library for MI355X.
+
+Argument marshalling only: every function below checks tensor types and shapes, passes
+device pointers and torch's current HIP stream to the C ABI declared in include/cngp.h and
+returns.  All arithmetic of the method runs in the library's HIP kernels; there is no CPU
+or PyTorch fallback, and importing this package fails if the library has not been built
+(run `python paper_2312_17241_amd/build.py` or `__graft_entry__.build()`).
+
+Function names mirror the C entry points: level_resolutions, workspace_bytes, encode_fwd,
+encode_bwd, bake_probes, debug_indices.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcngp.so")
+
+F32, F16 = 0, 1
+IDX_U8, IDX_PACKED4 = 0, 1
+ZERO_GRADS = 1
+
+OK, ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
+
+
+class CConfig(ctypes.Structure):
+    """Mirror of the C struct cngp_config (Table 1 of the paper: same symbols)."""
+    _fields_ = [("d", ctypes.c_int32), ("L", ctypes.c_int32), ("F", ctypes.c_int32),
+                ("N_f", ctypes.c_uint32), ("N_c", ctypes.c_uint32), ("N_p", ctypes.c_uint32),
+                ("N_min", ctypes.c_uint32), ("N_max", ctypes.c_uint32),
+                ("feat_dtype", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+                ("index_format", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class CngpError(RuntimeError):
+    def __init__(self, status, detail=""):
+        self.status = status
+        msg = _lib.cngp_error_string(status).decode()
+        super().__init__(f"cngp status {status}: {msg}{(' -- ' + detail) if detail else ''}")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python paper_2312_17241_amd/build.py` "
+            "(hipcc, gfx950).  There is no fallback path.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+    cfgp = ctypes.POINTER(CConfig)
+    lib.cngp_version.restype = ctypes.c_int
+    lib.cngp_error_string.restype = ctypes.c_char_p
+    lib.cngp_error_string.argtypes = [ctypes.c_int]
+    lib.cngp_last_hip_error.restype = ctypes.c_char_p
+    lib.cngp_level_resolutions.restype = ctypes.c_int
+    lib.cngp_level_resolutions.argtypes = [cfgp, vp]
+    lib.cngp_workspace_bytes.restype = sz
+    lib.cngp_workspace_bytes.argtypes = [cfgp, i64]
+    lib.cngp_encode_fwd.restype = ctypes.c_int
+    lib.cngp_encode_fwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, sz, vp]
+    lib.cngp_encode_bwd.restype = ctypes.c_int
+    lib.cngp_encode_bwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cngp_bake_probes.restype = ctypes.c_int
+    lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
+    lib.cngp_debug_indices.restype = ctypes.c_int
+    lib.cngp_debug_indices.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.cngp_profile_enable.restype = ctypes.c_int
+    lib.cngp_profile_enable.argtypes = [ctypes.c_int]
+    lib.cngp_profile_read.restype = ctypes.c_int
+    lib.cngp_profile_read.argtypes = [vp, vp, ctypes.c_int]
+    lib.cngp_profile_kernel_name.restype = ctypes.c_char_p
+    lib.cngp_profile_kernel_name.argtypes = [ctypes.c_int]
+    return lib
+
+
+_lib = _load()
+
+_DT = {"f32": F32, "f16": F16, F32: F32, F16: F16}
+_TORCH_DT = {F32: torch.float32, F16: torch.float16}
+
+
+@dataclass(frozen=True)
+class Config:
+    """Hyper-parameters of the encoding; field names follow Table 1 of the paper."""
+    d: int
+    L: int
+    F: int
+    N_f: int
+    N_c: int
+    N_p: int
+    N_min: int
+    N_max: int
+    feat_dtype: int = F32
+    io_dtype: int = F32
+    index_format: int = IDX_U8
+    flags: int = 0
+
+    @staticmethod
+    def from_workload(w, index_format=IDX_U8, flags=0, **over):
+        kw = dict(d=w.d, L=w.L, F=w.F, N_f=w.N_f, N_c=w.N_c, N_p=w.N_p, N_min=w.N_min, N_max=w.N_max,
+                  feat_dtype=_DT[w.feat_dtype], io_dtype=_DT[w.io_dtype],
+                  index_format=index_format, flags=flags)
+        kw.update(over)
+        return Config(**kw)
+
+    def c(self) -> CConfig:
+        return CConfig(self.d, self.L, self.F, self.N_f, self.N_c, self.N_p, self.N_min, self.N_max,
+                       self.feat_dtype, self.io_dtype, self.index_format, self.flags)
+
+    @property
+    def index_cols(self) -> int:
+        return self.N_c // 2 if self.index_format == IDX_PACKED4 else self.N_c
+
+
+def _check(status):
+    if status != OK:
+        detail = _lib.cngp_last_hip_error().decode() if status == ERR_HIP else ""
+        raise CngpError(status, detail)
+
+
+def _dev(t, dtype, shape, name):
+    if t is None:
+        raise CngpError(ERR_NULL, f"{name} is None")
+    if not (isinstance(t, torch.Tensor) and t.is_cuda):
+        raise TypeError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return ctypes.c_void_p(0), 0
+    return ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def version() -> int:
+    return _lib.cngp_version()
+
+
+def error_string(status: int) -> str:
+    return _lib.cngp_error_string(status).decode()
+
+
+def level_resolutions(cfg: Config) -> np.ndarray:
+    out = np.zeros(max(cfg.L, 1), dtype=np.uint32)
+    c = cfg.c()
+    _check(_lib.cngp_level_resolutions(ctypes.byref(c), out.ctypes.data_as(ctypes.c_void_p)))
+    return out[:cfg.L]
+
+
+def workspace_bytes(cfg: Config, N: int) -> int:
+    c = cfg.c()
+    return int(_lib.cngp_workspace_bytes(ctypes.byref(c), N))
+
+
+def alloc_workspace(cfg: Config, N: int, device="cuda"):
+    """A device buffer large enough for encode_fwd / encode_bwd on N points (None if none is needed)."""
+    nbytes = workspace_bytes(cfg, N)
+    if nbytes == 0:
+        return None
+    return torch.empty((nbytes + 255) // 256 * 256, dtype=torch.uint8, device=device)
+
+
+def encode_fwd(cfg: Config, x, D_f, D_c, y=None, workspace=None):
+    N = x.shape[0]
+    if y is None:
+        y = torch.empty((N, cfg.L * cfg.F), dtype=_TORCH_DT[cfg.io_dtype], device=x.device)
+    c = cfg.c()
+    wp, wb = _ws(workspace)
+    _check(_lib.cngp_encode_fwd(
+        ctypes.byref(c), _dev(x, torch.float32, (N, cfg.d), "x"), N,
+        _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"),
+        _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c"),
+        _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), wp, wb, _stream()))
+    return y
+
+
+def encode_bwd(cfg: Config, x, D_f, Dhat_c, dy, grad_D_f=None, grad_Dhat_c=None, workspace=None):
+    N = x.shape[0]
+    if grad_D_f is None:
+        grad_D_f = torch.zeros((cfg.L, cfg.N_f, cfg.F), dtype=torch.float32, device=x.device)
+    if grad_Dhat_c is None:
+        grad_Dhat_c = torch.zeros((cfg.L, cfg.N_c, cfg.N_p), dtype=torch.float32, device=x.device)
+    c = cfg.c()
+    wp, wb = _ws(workspace)
+    _check(_lib.cngp_encode_bwd(
+        ctypes.byref(c), _dev(x, torch.float32, (N, cfg.d), "x"), N,
+        _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"),
+        _dev(Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "Dhat_c"),
+        _dev(dy, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "dy"),
+        _dev(grad_D_f, torch.float32, (cfg.L, cfg.N_f, cfg.F), "grad_D_f"),
+        _dev(grad_Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "grad_Dhat_c"), wp, wb, _stream()))
+    return grad_D_f, grad_Dhat_c
+
+
+def bake_probes(cfg: Config, Dhat_c, D_c=None):
+    if D_c is None:
+        D_c = torch.empty((cfg.L, cfg.index_cols), dtype=torch.uint8, device=Dhat_c.device)
+    c = cfg.c()
+    _check(_lib.cngp_bake_probes(
+        ctypes.byref(c), _dev(Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "Dhat_c"),
+        _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c"), _stream()))
+    return D_c
+
+
+def debug_indices(cfg: Config, x, D_c):
+    """base, h2, probe, feat_idx of every (point, level, corner): tensors of shape [N, L, 2^d]."""
+    N = x.shape[0]
+    shp = (N, cfg.L, 1 << cfg.d)
+    base = torch.empty(shp, dtype=torch.int32, device=x.device)
+    h2 = torch.empty(shp, dtype=torch.int32, device=x.device)
+    probe = torch.empty(shp, dtype=torch.uint8, device=x.device)
+    fidx = torch.empty(shp, dtype=torch.int32, device=x.device)
+    c = cfg.c()
+    _check(_lib.cngp_debug_indices(
+        ctypes.byref(c), _dev(x, torch.float32, (N, cfg.d), "x"), N,
+        _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c"),
+        ctypes.c_void_p(base.data_ptr()), ctypes.c_void_p(h2.data_ptr()),
+        ctypes.c_void_p(probe.data_ptr()), ctypes.c_void_p(fidx.data_ptr()), _stream()))
+    return base, h2, probe, fidx
+
+
+def profile_enable(on: bool) -> bool:
+    return bool(_lib.cngp_profile_enable(1 if on else 0))
+
+
+def profile_read() -> dict:
+    """{kernel name: (total ms, launches)} since the last read; waits for the recorded events."""
+    n = 16
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    k = _lib.cngp_profile_read(ms, cnt, n)
+    return {_lib.cngp_profile_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(min(k, n)) if cnt[i]}
+
+
+def pack4(D_c_u8):
+    """Repack a [L, N_c] uint8 index codebook into the two-entries-per-byte layout (entry 2i in
+    the low nibble of byte i).  Pure data movement on whatever device the tensor lives on."""
+    return (D_c_u8[..., 0::2] | (D_c_u8[..., 1::2] << 4)).contiguous()

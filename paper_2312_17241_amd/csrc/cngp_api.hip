@@ -1,0 +1,305 @@
+// C ABI of the Compact NGP encoding library: argument checks, level table, kernel
+// selection and launches.  See include/cngp.h for the contract of every entry point.
+#include "../../include/cngp.h"
+#include "cngp_kernels.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace {
+
+using namespace cngp;
+
+thread_local std::string g_hip_error;
+
+bool is_pow2(uint32_t v) { return v != 0 && (v & (v - 1)) == 0; }
+uint32_t ilog2(uint32_t v) { uint32_t r = 0; while (v > 1) { v >>= 1; ++r; } return r; }
+
+int hip_fail(hipError_t e, const char *what) {
+    g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return CNGP_ERR_HIP;
+}
+#define CNGP_HIP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return hip_fail(e_, #call); } while (0)
+
+// ---------------------------------------------------------------- validation (host only)
+int validate(const cngp_config *c) {
+    if (!c) return CNGP_ERR_NULL;
+    if (c->d != 2 && c->d != 3) return CNGP_ERR_INVALID;
+    if (c->L < 1 || c->L > kMaxLevels) return CNGP_ERR_INVALID;
+    if (c->F < 1) return CNGP_ERR_INVALID;
+    if (!is_pow2(c->N_f) || !is_pow2(c->N_c) || !is_pow2(c->N_p)) return CNGP_ERR_INVALID;
+    if (c->N_p > 16 || c->N_p > c->N_f) return CNGP_ERR_INVALID;
+    if (c->N_f > (1u << 30) || c->N_c > (1u << 30)) return CNGP_ERR_INVALID;
+    if (c->N_min < 1) return CNGP_ERR_INVALID;
+    if (c->L > 1 && (c->N_max < c->N_min || c->N_max > (1u << 24))) return CNGP_ERR_INVALID;
+    if (c->N_min > (1u << 24)) return CNGP_ERR_INVALID;
+    if (c->feat_dtype != CNGP_F32 && c->feat_dtype != CNGP_F16) return CNGP_ERR_INVALID;
+    if (c->io_dtype != CNGP_F32 && c->io_dtype != CNGP_F16) return CNGP_ERR_INVALID;
+    if (c->index_format != CNGP_IDX_U8 && c->index_format != CNGP_IDX_PACKED4) return CNGP_ERR_INVALID;
+    if (c->index_format == CNGP_IDX_PACKED4 && c->N_c < 2) return CNGP_ERR_INVALID;
+    if (c->flags & ~(uint32_t)CNGP_ZERO_GRADS) return CNGP_ERR_INVALID;
+    if (c->F != 2) return CNGP_ERR_UNSUPPORTED;
+    return CNGP_OK;
+}
+
+// Table 1 (N_min, N_max, L): geometric growth, floor with a 1e-6 guard so that exact powers
+// (in particular N_{L-1} = N_max) survive the rounding of exp / pow.
+void level_table(const cngp_config *c, uint32_t *out) {
+    if (c->L == 1) { out[0] = c->N_min; return; }
+    const double b = std::exp(std::log((double)c->N_max / (double)c->N_min) / (double)(c->L - 1));
+    for (int l = 0; l < c->L; ++l)
+        out[l] = (uint32_t)std::floor((double)c->N_min * std::pow(b, (double)l) + 1e-6);
+}
+
+Params make_params(const cngp_config *c) {
+    Params p;
+    std::memset(&p, 0, sizeof(p));
+    level_table(c, p.N_l);
+    p.L = c->L;
+    p.N_f = c->N_f;
+    p.N_c = c->N_c;
+    p.row_mask = c->N_f / c->N_p - 1;
+    p.c_mask = c->N_c - 1;
+    p.log2_Np = ilog2(c->N_p);
+    return p;
+}
+
+int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INVALID : CNGP_OK; }
+
+// ---------------------------------------------------------------- per-kernel timing
+enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BAKE, K_ZERO, K_DEBUG, K_COUNT };
+const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "bake_probes", "zero", "debug_indices"};
+
+struct TimedLaunch { int id; hipEvent_t t0, t1; };
+bool g_profile = false;
+std::vector<TimedLaunch> g_timed;
+
+struct LaunchTimer {
+    hipStream_t s; int id; hipEvent_t t0 = nullptr, t1 = nullptr; bool on;
+    LaunchTimer(hipStream_t s_, int id_) : s(s_), id(id_), on(g_profile) {
+        if (on && (hipEventCreate(&t0) != hipSuccess || hipEventCreate(&t1) != hipSuccess)) on = false;
+        if (on) (void)hipEventRecord(t0, s);
+    }
+    ~LaunchTimer() {
+        if (on) { (void)hipEventRecord(t1, s); g_timed.push_back({id, t0, t1}); }
+    }
+};
+
+int launch_status(const char *what) {
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? CNGP_OK : hip_fail(e, what);
+}
+
+// ---------------------------------------------------------------- launches
+int launch_zero(float *ptr, int64_t n, hipStream_t s) {
+    if (n <= 0) return CNGP_OK;
+    // the head up to 16-byte alignment and the tail go through the scalar path
+    int64_t head = 0;
+    while (head < n && ((uintptr_t)(ptr + head) & 15u)) ++head;
+    if (head) {
+        LaunchTimer t(s, K_ZERO);
+        zero_kernel<<<1, kBlock, 0, s>>>(nullptr, 0, ptr, (int)head);
+    }
+    const int64_t n4 = (n - head) / 4;
+    const int ntail = (int)((n - head) - n4 * 4);
+    int64_t blocks = (n4 + kBlock - 1) / kBlock;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    LaunchTimer t(s, K_ZERO);
+    zero_kernel<<<(unsigned)blocks, kBlock, 0, s>>>(reinterpret_cast<float4 *>(ptr + head), n4,
+                                                     ptr + head + n4 * 4, ntail);
+    return launch_status("zero_kernel");
+}
+
+template <int D, typename FeatT, typename IoT>
+int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
+               const void *D_c, void *y, hipStream_t s) {
+    const int64_t pairs = N * c->L;
+    const int64_t blocks = (pairs + kBlock - 1) / kBlock;
+    if (int rc = check_blocks(blocks)) return rc;
+    LaunchTimer t(s, K_FWD);
+    if (c->index_format == CNGP_IDX_PACKED4)
+        encode_fwd_kernel<D, FeatT, IoT, true><<<(unsigned)blocks, kBlock, 0, s>>>(
+            p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, pairs);
+    else
+        encode_fwd_kernel<D, FeatT, IoT, false><<<(unsigned)blocks, kBlock, 0, s>>>(
+            p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, pairs);
+    return launch_status("encode_fwd_kernel");
+}
+
+template <int D, int NP, typename FeatT, typename IoT>
+int launch_bwd_direct(const cngp_config *c, const Params &p, int level0, int nlevels, const float *x,
+                      int64_t N, const void *D_f, const float *Dhat_c, const void *dy, float *gD_f,
+                      float *gDhat_c, hipStream_t s) {
+    (void)c;
+    if (nlevels <= 0) return CNGP_OK;
+    constexpr int PTS = kBlock / NP;
+    const int64_t blocks = (N + PTS - 1) / PTS;
+    if (int rc = check_blocks(blocks)) return rc;
+    LaunchTimer t(s, K_BWD_DIRECT);
+    encode_bwd_direct_kernel<D, NP, FeatT, IoT><<<dim3((unsigned)blocks, (unsigned)nlevels), kBlock, 0, s>>>(
+        p, level0, x, (const FeatT *)D_f, Dhat_c, (const IoT *)dy, gD_f, gDhat_c, N);
+    return launch_status("encode_bwd_direct_kernel");
+}
+
+template <int D, typename FeatT, typename IoT>
+int dispatch_bwd_np(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
+                    const float *Dhat_c, const void *dy, float *gD_f, float *gDhat_c, hipStream_t s) {
+    switch (c->N_p) {
+    case 1:  return launch_bwd_direct<D, 1, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
+    case 2:  return launch_bwd_direct<D, 2, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
+    case 4:  return launch_bwd_direct<D, 4, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
+    case 8:  return launch_bwd_direct<D, 8, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
+    default: return launch_bwd_direct<D, 16, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
+    }
+}
+
+// d x feat_dtype x io_dtype -> template instance
+#define CNGP_DISPATCH_TYPES(FN, ...)                                                             \
+    do {                                                                                         \
+        const bool f16 = cfg->feat_dtype == CNGP_F16, io16 = cfg->io_dtype == CNGP_F16;          \
+        if (cfg->d == 2) {                                                                       \
+            if (f16) return io16 ? FN<2, __half, __half>(__VA_ARGS__) : FN<2, __half, float>(__VA_ARGS__); \
+            return io16 ? FN<2, float, __half>(__VA_ARGS__) : FN<2, float, float>(__VA_ARGS__);  \
+        }                                                                                        \
+        if (f16) return io16 ? FN<3, __half, __half>(__VA_ARGS__) : FN<3, __half, float>(__VA_ARGS__);     \
+        return io16 ? FN<3, float, __half>(__VA_ARGS__) : FN<3, float, float>(__VA_ARGS__);      \
+    } while (0)
+
+}  // namespace
+
+// ==================================================================== exported C ABI
+extern "C" {
+
+int cngp_version(void) { return 100; }
+
+const char *cngp_error_string(int status) {
+    switch (status) {
+    case CNGP_OK:              return "success";
+    case CNGP_ERR_NULL:        return "a required pointer is NULL";
+    case CNGP_ERR_INVALID:     return "invalid argument (size out of range or not a power of two)";
+    case CNGP_ERR_UNSUPPORTED: return "configuration not supported by this build (F must be 2)";
+    case CNGP_ERR_WORKSPACE:   return "workspace missing, misaligned or too small";
+    case CNGP_ERR_HIP:         return "a HIP call failed (see cngp_last_hip_error)";
+    default:                   return "unknown status";
+    }
+}
+
+const char *cngp_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l) {
+    if (!cfg || !out_N_l) return CNGP_ERR_NULL;
+    int rc = validate(cfg);
+    if (rc != CNGP_OK && rc != CNGP_ERR_UNSUPPORTED) return rc;
+    level_table(cfg, out_N_l);
+    return CNGP_OK;
+}
+
+size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N) {
+    if (validate(cfg) != CNGP_OK || N < 0) return 0;
+    return 0;
+}
+
+int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const void *D_c,
+                    void *y, void *workspace, size_t workspace_bytes, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    if (N == 0) return CNGP_OK;
+    if (!x || !D_f || !D_c || !y) return CNGP_ERR_NULL;
+    (void)workspace; (void)workspace_bytes;
+    const Params p = make_params(cfg);
+    hipStream_t s = (hipStream_t)stream;
+    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s);
+}
+
+int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const void *D_f,
+                    const float *Dhat_c, const void *dy, float *grad_D_f, float *grad_Dhat_c,
+                    void *workspace, size_t workspace_bytes, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    if (!grad_D_f || !grad_Dhat_c) return CNGP_ERR_NULL;
+    if (N > 0 && (!x || !D_f || !Dhat_c || !dy)) return CNGP_ERR_NULL;
+    (void)workspace; (void)workspace_bytes;
+    hipStream_t s = (hipStream_t)stream;
+    if (cfg->flags & CNGP_ZERO_GRADS) {
+        if (int rc = launch_zero(grad_D_f, (int64_t)cfg->L * cfg->N_f * cfg->F, s)) return rc;
+        if (int rc = launch_zero(grad_Dhat_c, (int64_t)cfg->L * cfg->N_c * cfg->N_p, s)) return rc;
+    }
+    if (N == 0) return CNGP_OK;
+    const Params p = make_params(cfg);
+    CNGP_DISPATCH_TYPES(dispatch_bwd_np, cfg, p, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, s);
+}
+
+int cngp_bake_probes(const cngp_config *cfg, const float *Dhat_c, void *D_c, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    if (!Dhat_c || !D_c) return CNGP_ERR_NULL;
+    const bool packed = cfg->index_format == CNGP_IDX_PACKED4;
+    const int64_t rows = (int64_t)cfg->L * cfg->N_c;
+    const int64_t bytes_out = packed ? rows / 2 : rows;
+    const int64_t blocks = (bytes_out + kBlock - 1) / kBlock;
+    if (int rc = check_blocks(blocks)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    LaunchTimer t(s, K_BAKE);
+#define CNGP_BAKE(NP)                                                                                  \
+    if (packed) bake_probes_kernel<NP, true><<<(unsigned)blocks, kBlock, 0, s>>>(Dhat_c, (uint8_t *)D_c, bytes_out); \
+    else        bake_probes_kernel<NP, false><<<(unsigned)blocks, kBlock, 0, s>>>(Dhat_c, (uint8_t *)D_c, bytes_out)
+    switch (cfg->N_p) {
+    case 1:  CNGP_BAKE(1); break;
+    case 2:  CNGP_BAKE(2); break;
+    case 4:  CNGP_BAKE(4); break;
+    case 8:  CNGP_BAKE(8); break;
+    default: CNGP_BAKE(16); break;
+    }
+#undef CNGP_BAKE
+    return launch_status("bake_probes_kernel");
+}
+
+int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const void *D_c, uint32_t *base,
+                       uint32_t *h2, uint8_t *probe, uint32_t *feat_idx, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    if (N == 0) return CNGP_OK;
+    if (!x) return CNGP_ERR_NULL;
+    if (!D_c && (probe || feat_idx)) return CNGP_ERR_NULL;
+    const Params p = make_params(cfg);
+    const int64_t pairs = N * cfg->L;
+    const int64_t blocks = (pairs + kBlock - 1) / kBlock;
+    if (int rc = check_blocks(blocks)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const bool packed = cfg->index_format == CNGP_IDX_PACKED4;
+    LaunchTimer t(s, K_DEBUG);
+#define CNGP_DBG(D)                                                                                      \
+    if (packed) debug_indices_kernel<D, true><<<(unsigned)blocks, kBlock, 0, s>>>(p, x, (const uint8_t *)D_c, base, h2, probe, feat_idx, pairs); \
+    else        debug_indices_kernel<D, false><<<(unsigned)blocks, kBlock, 0, s>>>(p, x, (const uint8_t *)D_c, base, h2, probe, feat_idx, pairs)
+    if (cfg->d == 2) { CNGP_DBG(2); } else { CNGP_DBG(3); }
+#undef CNGP_DBG
+    return launch_status("debug_indices_kernel");
+}
+
+int cngp_profile_enable(int on) {
+    const int was = g_profile ? 1 : 0;
+    g_profile = on != 0;
+    return was;
+}
+
+const char *cngp_profile_kernel_name(int i) { return (i >= 0 && i < K_COUNT) ? kKernelNames[i] : ""; }
+
+int cngp_profile_read(double *ms_sum, int64_t *launches, int max_kernels) {
+    for (auto &t : g_timed) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(t.t1) == hipSuccess && hipEventElapsedTime(&ms, t.t0, t.t1) == hipSuccess &&
+            t.id < max_kernels) {
+            if (ms_sum) ms_sum[t.id] += (double)ms;
+            if (launches) launches[t.id] += 1;
+        }
+        (void)hipEventDestroy(t.t0);
+        (void)hipEventDestroy(t.t1);
+    }
+    g_timed.clear();
+    return K_COUNT;
+}
+
+}  // extern "C"

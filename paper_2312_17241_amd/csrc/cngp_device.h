@@ -1,0 +1,106 @@
+// Device-side building blocks shared by the gfx950 kernels: grid-cell location,
+// the two spatial hashes (Eq. 3) and the probed feature index (Eq. 6).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace cngp {
+
+constexpr int kMaxLevels = 32;
+constexpr int kBlock = 256;          // threads per workgroup = 4 wavefronts of 64
+
+// Eq. 3: hash(v) = XOR_i v_i * pi_i in uint32.  pi: the primes of the hash encoding the
+// method generalises (pi_0 = 1); pi2: a second, disjoint set for hash2 (Sec. 3).
+__device__ constexpr uint32_t kPi[3]  = {1u, 2654435761u, 805459861u};
+__device__ constexpr uint32_t kPi2[3] = {1580030173u, 1367130559u, 3037000507u};
+
+// Everything a kernel needs to know about the encoding, passed by value.
+struct Params {
+    uint32_t N_l[kMaxLevels];   // grid resolution per level
+    int32_t  L;
+    uint32_t N_f, N_c;
+    uint32_t row_mask;          // N_f / N_p - 1 : hashed most significant bits of the index
+    uint32_t c_mask;            // N_c - 1
+    uint32_t log2_Np;
+};
+
+// The cell of one level that contains a point: lower vertex, fractional position and the
+// per-dimension hash terms of the lower (a*) and upper (b*) vertex coordinate.
+template <int D>
+struct Cell {
+    float    w[D];
+    uint32_t a1[D], b1[D];      // v0_i * pi_i,  (v0_i + 1) * pi_i
+    uint32_t a2[D], b2[D];      // same with pi2
+
+    // x scaled by the level resolution in ONE fp32 multiply (no fused multiply-add), so the
+    // integer cell is the same on every implementation that follows this rule.
+    __device__ __forceinline__ void locate(const float *xp, uint32_t N_l) {
+        const float s = (float)N_l;
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            float pos = __fmul_rn(xp[i], s);
+            float fl  = floorf(pos);
+            w[i] = __fsub_rn(pos, fl);
+            uint32_t v0 = (uint32_t)fl;
+            a1[i] = v0 * kPi[i];   b1[i] = a1[i] + kPi[i];
+            a2[i] = v0 * kPi2[i];  b2[i] = a2[i] + kPi2[i];
+        }
+    }
+    // corner c: offset (c >> i) & 1 along dimension i
+    __device__ __forceinline__ uint32_t hash1(int c) const {
+        uint32_t h = 0;
+#pragma unroll
+        for (int i = 0; i < D; ++i) h ^= ((c >> i) & 1) ? b1[i] : a1[i];
+        return h;
+    }
+    __device__ __forceinline__ uint32_t hash2(int c) const {
+        uint32_t h = 0;
+#pragma unroll
+        for (int i = 0; i < D; ++i) h ^= ((c >> i) & 1) ? b2[i] : a2[i];
+        return h;
+    }
+    __device__ __forceinline__ float weight(int c) const {
+        float wt = 1.0f;
+#pragma unroll
+        for (int i = 0; i < D; ++i) wt *= ((c >> i) & 1) ? w[i] : 1.0f - w[i];
+        return wt;
+    }
+};
+
+// Eq. 6: (N_p * hash(v)) mod N_f, i.e. the low log2(N_f / N_p) bits of the hash moved above
+// the log2(N_p) learned bits.
+__device__ __forceinline__ uint32_t probe_base(uint32_t h1, const Params &p) {
+    return (h1 & p.row_mask) << p.log2_Np;
+}
+
+// Baked index codebook readers.
+template <bool PACKED4>
+__device__ __forceinline__ uint32_t read_probe(const uint8_t *D_c_level, uint32_t r) {
+    if (PACKED4) {
+        uint32_t b = D_c_level[r >> 1];
+        return (b >> ((r & 1u) * 4u)) & 0xFu;
+    }
+    return D_c_level[r];
+}
+
+// Two-feature codebook entry as a pair of floats.
+__device__ __forceinline__ float2 load_pair(const float *base, size_t entry) {
+    return *reinterpret_cast<const float2 *>(base + 2 * entry);
+}
+__device__ __forceinline__ float2 load_pair(const __half *base, size_t entry) {
+    return __half22float2(*reinterpret_cast<const __half2 *>(base + 2 * entry));
+}
+__device__ __forceinline__ void store_pair(float *base, size_t entry, float a, float b) {
+    *reinterpret_cast<float2 *>(base + 2 * entry) = make_float2(a, b);
+}
+__device__ __forceinline__ void store_pair(__half *base, size_t entry, float a, float b) {
+    *reinterpret_cast<__half2 *>(base + 2 * entry) = __floats2half2_rn(a, b);
+}
+
+// Relaxed device-scope floating-point add without a return value.
+__device__ __forceinline__ void atomic_add(float *addr, float v) {
+    (void)__hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace cngp

@@ -1,0 +1,186 @@
+// gfx950 kernels of the encoding path: forward gather + interpolation, backward
+// scatter-add with wavefront-cooperative probe rows, bake, index dump, fill.
+#pragma once
+#include "cngp_device.h"
+
+namespace cngp {
+
+// ------------------------------------------------------------------ forward (Eq. 6 + interpolation)
+// One thread per (point, level) pair, pairs numbered n * L + l, so that the F = 2 outputs
+// of consecutive threads are consecutive in y: every wavefront writes one contiguous run.
+template <int D, typename FeatT, typename IoT, bool PACKED4>
+__global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
+    const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
+    const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t pairs)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= pairs) return;
+    const int64_t n = i / p.L;
+    const int     l = (int)(i - n * p.L);
+
+    float xp[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
+    Cell<D> cell;
+    cell.locate(xp, p.N_l[l]);
+
+    const FeatT   *F_l = D_f + (size_t)l * p.N_f * 2;
+    const uint32_t c_stride = PACKED4 ? (p.N_c >> 1) : p.N_c;
+    const uint8_t *C_l = D_c + (size_t)l * c_stride;
+
+    // issue all probe reads, then all feature reads, so the gathers overlap
+    uint32_t idx[1 << D];
+#pragma unroll
+    for (int c = 0; c < (1 << D); ++c)
+        idx[c] = read_probe<PACKED4>(C_l, cell.hash2(c) & p.c_mask);
+#pragma unroll
+    for (int c = 0; c < (1 << D); ++c) idx[c] += probe_base(cell.hash1(c), p);
+    float2 feat[1 << D];
+#pragma unroll
+    for (int c = 0; c < (1 << D); ++c) feat[c] = load_pair(F_l, idx[c]);
+    float y0 = 0.0f, y1 = 0.0f;
+#pragma unroll
+    for (int c = 0; c < (1 << D); ++c) {
+        const float wt = cell.weight(c);
+        y0 = fmaf(wt, feat[c].x, y0);
+        y1 = fmaf(wt, feat[c].y, y1);
+    }
+    store_pair(y, (size_t)i, y0, y1);
+}
+
+// ------------------------------------------------------------------ backward (Sec. 3 "Training")
+// Reduction over the NP lanes that share one probe row.
+template <int NP>
+__device__ __forceinline__ float group_max(float v) {
+#pragma unroll
+    for (int o = NP / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, NP));
+    return v;
+}
+template <int NP>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+    for (int o = NP / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, NP);
+    return v;
+}
+
+// Direct backward: NP adjacent lanes own one (point, level) pair and walk its 2^d corners;
+// lane k is candidate k of the probing range, so the NP lanes read and update one contiguous
+// row of D^_c / grad D^_c and one contiguous run of D_f / grad D_f per corner.
+// blockIdx.y is the level: the whole grid works through one level's tables at a time.
+template <int D, int NP, typename FeatT, typename IoT>
+__global__ __launch_bounds__(kBlock) void encode_bwd_direct_kernel(
+    const Params p, const int level0, const float *__restrict__ x, const FeatT *__restrict__ D_f,
+    const float *__restrict__ Dhat_c, const IoT *__restrict__ dy,
+    float *__restrict__ gD_f, float *__restrict__ gDhat_c, const int64_t N)
+{
+    constexpr int PTS = kBlock / NP;
+    const int     l = level0 + (int)blockIdx.y;
+    const int     k = threadIdx.x % NP;
+    const int64_t n = (int64_t)blockIdx.x * PTS + threadIdx.x / NP;
+    if (n >= N) return;           // whole lane groups leave together (PTS * NP == kBlock)
+
+    float xp[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
+    Cell<D> cell;
+    cell.locate(xp, p.N_l[l]);
+    const float2 g_up = load_pair(dy, (size_t)n * p.L + l);
+
+    const FeatT *F_l  = D_f + (size_t)l * p.N_f * 2;
+    const float *C_l  = Dhat_c + (size_t)l * p.N_c * NP;
+    float       *gF_l = gD_f + (size_t)l * p.N_f * 2;
+    float       *gC_l = gDhat_c + (size_t)l * p.N_c * NP;
+
+#pragma unroll
+    for (int c = 0; c < (1 << D); ++c) {
+        const uint32_t entry = probe_base(cell.hash1(c), p) + k;
+        const uint32_t slot  = (cell.hash2(c) & p.c_mask) * NP + k;
+        const float    logit = C_l[slot];
+        const float2   feat  = load_pair(F_l, entry);
+        const float    wt = cell.weight(c);
+        const float    g0 = wt * g_up.x, g1 = wt * g_up.y;
+
+        const float m     = group_max<NP>(logit);
+        const float e     = expf(logit - m);
+        const float sigma = e / group_sum<NP>(e);
+        const float q     = fmaf(feat.x, g0, feat.y * g1);
+        const float qbar  = group_sum<NP>(sigma * q);
+
+        atomic_add(gF_l + 2 * (size_t)entry, sigma * g0);
+        atomic_add(gF_l + 2 * (size_t)entry + 1, sigma * g1);
+        if (NP > 1) atomic_add(gC_l + slot, sigma * (q - qbar));
+    }
+}
+
+// ------------------------------------------------------------------ bake (Fig. 3: argmax per row)
+// One thread per output byte: one row (u8) or two rows (packed nibbles).
+template <int NP>
+__device__ __forceinline__ uint32_t argmax_row(const float *__restrict__ row) {
+    uint32_t best = 0;
+    bool     have = false;
+    float    bv = 0.0f;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const float v = row[k];
+        const bool  take = (v == v) && (!have || v > bv);   // NaN never wins; first maximum wins
+        if (take) { best = k; bv = v; have = true; }
+    }
+    return best;
+}
+
+template <int NP, bool PACKED4>
+__global__ __launch_bounds__(kBlock) void bake_probes_kernel(
+    const float *__restrict__ Dhat_c, uint8_t *__restrict__ D_c, const int64_t bytes_out)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= bytes_out) return;
+    if (PACKED4) {
+        const uint32_t lo = argmax_row<NP>(Dhat_c + (size_t)(2 * i) * NP);
+        const uint32_t hi = argmax_row<NP>(Dhat_c + (size_t)(2 * i + 1) * NP);
+        D_c[i] = (uint8_t)(lo | (hi << 4));
+    } else {
+        D_c[i] = (uint8_t)argmax_row<NP>(Dhat_c + (size_t)i * NP);
+    }
+}
+
+// ------------------------------------------------------------------ index dump (parity checks)
+template <int D, bool PACKED4>
+__global__ __launch_bounds__(kBlock) void debug_indices_kernel(
+    const Params p, const float *__restrict__ x, const uint8_t *__restrict__ D_c,
+    uint32_t *__restrict__ base_out, uint32_t *__restrict__ h2_out, uint8_t *__restrict__ probe_out,
+    uint32_t *__restrict__ idx_out, const int64_t pairs)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= pairs) return;
+    const int64_t n = i / p.L;
+    const int     l = (int)(i - n * p.L);
+    float xp[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
+    Cell<D> cell;
+    cell.locate(xp, p.N_l[l]);
+    const uint32_t c_stride = PACKED4 ? (p.N_c >> 1) : p.N_c;
+#pragma unroll
+    for (int c = 0; c < (1 << D); ++c) {
+        const uint32_t base = probe_base(cell.hash1(c), p);
+        const uint32_t r    = cell.hash2(c) & p.c_mask;
+        const uint32_t pr   = D_c ? read_probe<PACKED4>(D_c + (size_t)l * c_stride, r) : 0u;
+        const size_t   o    = (size_t)i * (1 << D) + c;
+        if (base_out)  base_out[o] = base;
+        if (h2_out)    h2_out[o] = r;
+        if (probe_out) probe_out[o] = (uint8_t)pr;
+        if (idx_out)   idx_out[o] = base + pr;
+    }
+}
+
+// ------------------------------------------------------------------ fill with zeros
+__global__ __launch_bounds__(kBlock) void zero_kernel(float4 *__restrict__ p4, const int64_t n4,
+                                                      float *__restrict__ tail, const int ntail)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride)
+        p4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0.0f;
+}
+
+}  // namespace cngp

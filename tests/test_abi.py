@@ -1,0 +1,129 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header declares,
+validates arguments before touching the GPU, and computes the level table.  No GPU needed:
+no call here reaches a kernel launch.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2312_17241_amd as cngp
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "cngp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cngp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"cngp_encode_fwd", "cngp_encode_bwd", "cngp_bake_probes", "cngp_level_resolutions",
+            "cngp_workspace_bytes", "cngp_debug_indices"} <= set(names)
+    lib = ctypes.CDLL(cngp.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_error_strings():
+    assert cngp.version() >= 100
+    seen = {cngp.error_string(s) for s in range(0, -6, -1)}
+    assert len(seen) == 6 and all(seen)
+    assert "unknown" in cngp.error_string(-99)
+
+
+def base_cfg(**kw):
+    return cngp.Config.from_workload(W.WORKLOADS["nerf3d"], **kw)
+
+
+@pytest.mark.parametrize("nmin,nmax,L,expect", [
+    (int(h.split()[0]), int(h.split()[1]), int(h.split()[2]), list(map(int, t.split())))
+    for h, t in (ln.split(":") for ln in open(os.path.join(GOLDEN, "level_tables.txt"))
+                 if ln.strip() and not ln.startswith("#"))])
+def test_level_table_golden(nmin, nmax, L, expect):
+    cfg = base_cfg(N_min=nmin, N_max=nmax, L=L)
+    assert cngp.level_resolutions(cfg).tolist() == expect
+
+
+def test_level_table_edge_cases():
+    assert cngp.level_resolutions(base_cfg(L=1, N_min=7, N_max=3)).tolist() == [7]
+    assert cngp.level_resolutions(base_cfg(L=11, N_min=1, N_max=1024)).tolist() == [2**i for i in range(11)]
+    r = cngp.level_resolutions(base_cfg(L=16, N_min=16, N_max=524288))
+    assert r[0] == 16 and r[-1] == 524288 and np.all(np.diff(r.astype(np.int64)) > 0)
+
+
+BAD = [
+    dict(d=1), dict(d=4), dict(L=0), dict(L=33), dict(F=0),
+    dict(N_f=0), dict(N_f=3000), dict(N_c=0), dict(N_c=100), dict(N_p=0), dict(N_p=3), dict(N_p=32),
+    dict(N_p=16, N_f=8), dict(N_min=0), dict(N_max=8), dict(N_max=2**25),
+    dict(feat_dtype=2), dict(io_dtype=-1), dict(index_format=2), dict(flags=2),
+    dict(index_format=cngp.IDX_PACKED4, N_c=1, N_p=1),
+]
+
+
+@pytest.mark.parametrize("over", BAD, ids=[str(b) for b in BAD])
+def test_invalid_configs_are_rejected_on_the_host(over):
+    c = base_cfg(**over).c()
+    one = ctypes.c_void_p(256)          # never dereferenced: validation fails first
+    lib = cngp._lib
+    assert lib.cngp_encode_fwd(ctypes.byref(c), one, 8, one, one, one, None, 0, None) == cngp.ERR_INVALID
+    assert lib.cngp_encode_bwd(ctypes.byref(c), one, 8, one, one, one, one, one, None, 0, None) == cngp.ERR_INVALID
+    assert lib.cngp_bake_probes(ctypes.byref(c), one, one, None) == cngp.ERR_INVALID
+    assert lib.cngp_debug_indices(ctypes.byref(c), one, 8, one, one, one, one, one, None) == cngp.ERR_INVALID
+    assert cngp.workspace_bytes(base_cfg(**over), 8) == 0
+
+
+def test_unsupported_feature_width():
+    c = base_cfg(F=4).c()
+    one = ctypes.c_void_p(256)
+    assert cngp._lib.cngp_encode_fwd(ctypes.byref(c), one, 8, one, one, one, None, 0, None) == cngp.ERR_UNSUPPORTED
+    out = np.zeros(16, np.uint32)        # the level table does not depend on F
+    assert cngp._lib.cngp_level_resolutions(ctypes.byref(c), out.ctypes.data_as(ctypes.c_void_p)) == cngp.OK
+
+
+def test_null_pointers_and_negative_counts():
+    c = base_cfg().c()
+    one = ctypes.c_void_p(256)
+    lib = cngp._lib
+    assert lib.cngp_encode_fwd(None, one, 8, one, one, one, None, 0, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_fwd(ctypes.byref(c), None, 8, one, one, one, None, 0, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_fwd(ctypes.byref(c), one, 8, None, one, one, None, 0, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_fwd(ctypes.byref(c), one, 8, one, None, one, None, 0, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_fwd(ctypes.byref(c), one, 8, one, one, None, None, 0, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_fwd(ctypes.byref(c), one, -1, one, one, one, None, 0, None) == cngp.ERR_INVALID
+    assert lib.cngp_encode_fwd(ctypes.byref(c), None, 0, None, None, None, None, 0, None) == cngp.OK   # N == 0
+    assert lib.cngp_encode_bwd(ctypes.byref(c), one, 8, one, one, one, None, one, None, 0, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_bwd(ctypes.byref(c), one, 8, one, None, one, one, one, None, 0, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_bwd(ctypes.byref(c), one, -5, one, one, one, one, one, None, 0, None) == cngp.ERR_INVALID
+    assert lib.cngp_bake_probes(ctypes.byref(c), None, one, None) == cngp.ERR_NULL
+    assert lib.cngp_bake_probes(ctypes.byref(c), one, None, None) == cngp.ERR_NULL
+    assert lib.cngp_debug_indices(ctypes.byref(c), None, 8, one, one, one, one, one, None) == cngp.ERR_NULL
+    assert lib.cngp_debug_indices(ctypes.byref(c), one, 8, None, one, one, one, None, None) == cngp.ERR_NULL
+    assert lib.cngp_level_resolutions(ctypes.byref(c), None) == cngp.ERR_NULL
+
+
+def test_binding_rejects_host_tensors_and_wrong_shapes():
+    import torch
+    cfg = base_cfg()
+    x = torch.zeros((4, 3))
+    with pytest.raises(TypeError):
+        cngp.encode_fwd(cfg, x, x, x, y=x)
+
+
+def test_product_does_not_import_the_oracle():
+    """The product package and its sources never reference the test oracle."""
+    pkg = os.path.join(ROOT, "paper_2312_17241_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "cngp_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            assert "paper_2312_17241_amd" not in open(os.path.join(ROOT, "oracle", f)).read(), f

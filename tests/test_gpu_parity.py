@@ -1,0 +1,273 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integers bit-exact, floating point within the bars of tests/parity.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2312_17241_amd as cngp
+import workloads as W
+from parity import check_close, check_exact
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def tables(w, n=None):
+    x = W.make_points(w, n)
+    return x, W.make_feature_codebook(w), W.make_probe_logits(w), W.make_upstream_grad(w, x.shape[0])
+
+
+def run_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8):
+    cfg = cngp.Config.from_workload(w, index_format=index_format)
+    D_c_dev = dev(D_c)
+    if index_format == cngp.IDX_PACKED4:
+        D_c_dev = cngp.pack4(D_c_dev)
+    ws = cngp.alloc_workspace(cfg, x.shape[0])
+    y = cngp.encode_fwd(cfg, dev(x), dev(D_f), D_c_dev, workspace=ws)
+    torch.cuda.synchronize()
+    return host(y)
+
+
+def run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS, init=None):
+    cfg = cngp.Config.from_workload(w, flags=flags)
+    gF = torch.full((w.L, w.N_f, w.F), float("nan") if init is None else init, device=DEV)
+    gC = torch.full((w.L, w.N_c, w.N_p), float("nan") if init is None else init, device=DEV)
+    ws = cngp.alloc_workspace(cfg, x.shape[0])
+    cngp.encode_bwd(cfg, dev(x), dev(D_f), dev(Dhat), dev(dy), gF, gC, workspace=ws)
+    torch.cuda.synchronize()
+    return host(gF), host(gC)
+
+
+def check_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8, name=""):
+    y_ref, ymag = oracle.encode_fwd(w, x, D_f, D_c)
+    y = run_fwd(w, x, D_f, D_c, index_format)
+    return check_close(f"y {name}", y, y_ref, ymag, fp16_out=(w.io_dtype == "f16"))
+
+
+def check_bwd(w, x, D_f, Dhat, dy, name=""):
+    gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    gF, gC = run_bwd(w, x, D_f, Dhat, dy)
+    e1 = check_close(f"grad D_f {name}", gF, gF_ref, A_f, fp16_out=False)
+    e2 = check_close(f"grad Dhat_c {name}", gC, gC_ref, A_c, fp16_out=False)
+    return e1, e2
+
+
+# ------------------------------------------------------------------ indices, bit-exact
+
+@pytest.mark.parametrize("name", ["tiny2d", "nerf3d", "sdf3d", "image2d"])
+@pytest.mark.parametrize("fmt", [cngp.IDX_U8, cngp.IDX_PACKED4])
+def test_indices_bit_exact(name, fmt):
+    w = W.WORKLOADS[name]
+    n = min(w.N, 20000 + 37)
+    x = W.make_points(w, n)
+    x[:4] = [[0.0] * w.d, [1.0] * w.d, [0.5] * w.d, [1.0] + [0.0] * (w.d - 1)]
+    D_c = oracle.bake_probes(W.make_probe_logits(w))
+    cfg = cngp.Config.from_workload(w, index_format=fmt)
+    D_c_dev = dev(D_c) if fmt == cngp.IDX_U8 else cngp.pack4(dev(D_c))
+    got = cngp.debug_indices(cfg, dev(x), D_c_dev)
+    torch.cuda.synchronize()
+    want = oracle.indices(w, x, D_c)
+    for nm, g, r in zip(("base", "h2", "probe", "feat_idx"), got, want):
+        check_exact(f"{nm} {name}", host(g).view(r.dtype), r)
+    assert int(host(got[3]).max()) < w.N_f
+
+
+def test_indices_large_resolution_bit_exact():
+    """Finest resolution of Table 1's range (N_max = 524288): fp32 scaling must round identically."""
+    w = W.custom(d=3, L=16, N_f=2**12, N_c=2**10, N_p=16, N_min=16, N_max=524288, N=5000)
+    x = W.make_points(w)
+    D_c = np.random.default_rng(3).integers(0, w.N_p, (w.L, w.N_c)).astype(np.uint8)
+    got = cngp.debug_indices(cngp.Config.from_workload(w), dev(x), dev(D_c))
+    want = oracle.indices(w, x, D_c)
+    for nm, g, r in zip(("base", "h2", "probe", "feat_idx"), got, want):
+        check_exact(nm, host(g).view(r.dtype), r)
+
+
+# ------------------------------------------------------------------ bake, bit-exact
+
+@pytest.mark.parametrize("N_p", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("fmt", [cngp.IDX_U8, cngp.IDX_PACKED4])
+def test_bake_bit_exact(N_p, fmt):
+    w = W.custom(L=3, N_c=2048 + 0, N_p=N_p, N_f=4096)
+    rng = np.random.default_rng(N_p)
+    Dhat = rng.standard_normal((w.L, w.N_c, w.N_p)).astype(np.float32)
+    # degenerate rows: all equal, ties, NaN, infinities
+    Dhat[0, 0] = 1.0
+    Dhat[0, 1] = np.nan
+    Dhat[0, 2] = -np.inf
+    if N_p >= 4:
+        Dhat[0, 3] = 0.0; Dhat[0, 3, 1] = 2.0; Dhat[0, 3, 2] = 2.0
+        Dhat[0, 4] = np.nan; Dhat[0, 4, N_p - 1] = -5.0
+        Dhat[0, 5, 0] = np.nan; Dhat[0, 5, 1] = np.inf
+    want = oracle.bake_probes(Dhat)
+    assert want.max() < N_p
+    cfg = cngp.Config.from_workload(w, index_format=fmt)
+    got = cngp.bake_probes(cfg, dev(Dhat))
+    torch.cuda.synchronize()
+    if fmt == cngp.IDX_PACKED4:
+        packed = host(got)
+        assert packed.shape == (w.L, w.N_c // 2)
+        got_u8 = np.empty((w.L, w.N_c), np.uint8)
+        got_u8[:, 0::2] = packed & 0xF
+        got_u8[:, 1::2] = packed >> 4
+    else:
+        got_u8 = host(got)
+    check_exact("D_c", got_u8, want)
+
+
+@pytest.mark.parametrize("name", ["tiny2d", "nerf3d"])
+def test_bake_workload_tables(name):
+    w = W.WORKLOADS[name]
+    Dhat = W.make_probe_logits(w)
+    got = cngp.bake_probes(cngp.Config.from_workload(w), dev(Dhat))
+    check_exact("D_c", host(got), oracle.bake_probes(Dhat))
+
+
+# ------------------------------------------------------------------ forward / backward, small sweeps
+
+SWEEP = [
+    # d, N_p, feat, io
+    (2, 1, "f32", "f32"), (2, 4, "f32", "f32"), (2, 8, "f16", "f16"), (2, 16, "f16", "f32"),
+    (3, 1, "f16", "f16"), (3, 2, "f32", "f16"), (3, 4, "f32", "f32"), (3, 8, "f16", "f16"),
+    (3, 16, "f16", "f16"), (3, 16, "f32", "f32"),
+]
+
+
+def sweep_workload(d, N_p, feat, io, N=3000 + 77):
+    return W.custom(cfg=50 + d * 17 + N_p, d=d, L=5, N_f=2**11, N_c=2**9, N_p=N_p, N_min=4, N_max=300,
+                    N=N, feat_dtype=feat, io_dtype=io)
+
+
+@pytest.mark.parametrize("d,N_p,feat,io", SWEEP)
+def test_forward_parity_sweep(d, N_p, feat, io):
+    w = sweep_workload(d, N_p, feat, io)
+    x, D_f, Dhat, _ = tables(w)
+    x[:3] = [[0.0] * d, [1.0] * d, [0.5] * d]
+    D_c = oracle.bake_probes(Dhat)
+    check_fwd(w, x, D_f, D_c, cngp.IDX_U8, "u8")
+    if w.N_c >= 2:
+        check_fwd(w, x, D_f, D_c, cngp.IDX_PACKED4, "packed4")
+
+
+@pytest.mark.parametrize("d,N_p,feat,io", SWEEP)
+def test_backward_parity_sweep(d, N_p, feat, io):
+    w = sweep_workload(d, N_p, feat, io)
+    x, D_f, Dhat, dy = tables(w)
+    x[:3] = [[0.0] * d, [1.0] * d, [0.5] * d]
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)      # O(1) features: logit gradients well scaled
+    check_bwd(w, x, D_f, Dhat, dy)
+
+
+def test_backward_accumulates_without_zero_flag():
+    w = sweep_workload(3, 4, "f32", "f32", N=500)
+    x, D_f, Dhat, dy = tables(w)
+    gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=0, init=1.5)
+    check_close("grad D_f (+=)", gF, gF_ref + 1.5, A_f + 1.5, fp16_out=False)
+    check_close("grad Dhat_c (+=)", gC, gC_ref + 1.5, A_c + 1.5, fp16_out=False)
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_empty_batch_is_a_noop_and_zeroes_grads():
+    w = sweep_workload(3, 4, "f32", "f32", N=0)
+    cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS)
+    x = torch.empty((0, 3), device=DEV)
+    D_f = dev(W.make_feature_codebook(w)); Dhat = dev(W.make_probe_logits(w))
+    y = cngp.encode_fwd(cfg, x, D_f, cngp.bake_probes(cfg, Dhat))
+    assert y.shape == (0, w.L * w.F)
+    gF = torch.ones((w.L, w.N_f, w.F), device=DEV); gC = torch.ones((w.L, w.N_c, w.N_p), device=DEV)
+    cngp.encode_bwd(cfg, x, D_f, Dhat, torch.empty((0, w.L * w.F), device=DEV), gF, gC)
+    torch.cuda.synchronize()
+    assert float(gF.abs().max()) == 0.0 and float(gC.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("N", [1, 63, 64, 65, 255, 257])
+def test_ragged_tails(N):
+    w = sweep_workload(3, 16, "f16", "f16", N=N)
+    x, D_f, Dhat, dy = tables(w)
+    check_fwd(w, x, D_f, oracle.bake_probes(Dhat))
+    check_bwd(w, x, D_f, Dhat, dy)
+
+
+@pytest.mark.parametrize("over", [dict(L=1, N_min=9), dict(L=32, N_min=2, N_max=5000), dict(N_c=1), dict(N_c=2),
+                                  dict(N_f=16, N_p=16), dict(N_f=2, N_p=2, N_c=4), dict(N_min=1, N_max=1, L=2),
+                                  dict(N_f=2**20, N_c=2**18, N_p=2)])
+def test_degenerate_configurations(over):
+    kw = dict(cfg=77, d=3, L=4, N_f=256, N_c=64, N_p=4, N_min=4, N_max=64, N=700, feat_dtype="f32", io_dtype="f32")
+    kw.update(over)
+    w = W.custom(**kw)
+    x, D_f, Dhat, dy = tables(w)
+    x[:2] = [[0.0] * 3, [1.0] * 3]
+    D_c = oracle.bake_probes(Dhat)
+    check_fwd(w, x, D_f, D_c)
+    if w.N_c >= 2:
+        check_fwd(w, x, D_f, D_c, cngp.IDX_PACKED4)
+    check_bwd(w, x, D_f, Dhat, dy)
+
+
+def test_points_on_grid_vertices_and_cube_faces():
+    """Points on vertices (zero-weight corners still looked up) and on the faces x_i in {0, 1}."""
+    w = W.custom(cfg=78, d=3, L=3, N_f=512, N_c=128, N_p=8, N_min=8, N_max=32, N=4096)
+    rng = np.random.default_rng(0)
+    x = (rng.integers(0, 33, (w.N, 3)) / 32.0).astype(np.float32)
+    x[::3, 0] = 1.0; x[1::3, 1] = 0.0
+    _, D_f, Dhat, dy = tables(w)
+    check_fwd(w, x, D_f, oracle.bake_probes(Dhat))
+    check_bwd(w, x, D_f, Dhat, dy)
+
+
+def test_probe_range_one_matches_unprobed_hash_grid():
+    """N_p = 1 (Sec. 3 "Selecting hyperparameters"): the index codebook plays no role."""
+    w = W.custom(cfg=79, d=3, L=6, N_f=2**12, N_c=1, N_p=1, N_min=8, N_max=256, N=5000,
+                 feat_dtype="f16", io_dtype="f16")
+    x, D_f, Dhat, dy = tables(w)
+    check_fwd(w, x, D_f, np.zeros((w.L, 1), np.uint8))
+    gF, gC = run_bwd(w, x, D_f, Dhat, dy)
+    assert np.all(gC == 0.0)
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+
+@pytest.mark.parametrize("name", ["tiny2d", "nerf3d", "image2d", "sdf3d"])
+def test_full_size_forward_backward(name):
+    w = W.WORKLOADS[name]
+    x, D_f, Dhat, dy = tables(w)
+    D_c = oracle.bake_probes(Dhat)
+    e_y = check_fwd(w, x, D_f, D_c, name=name)
+    e_f, e_c = check_bwd(w, x, D_f, Dhat, dy, name=name)
+    print(f"\n{name}: max rel err  y {e_y:.2e}  grad D_f {e_f:.2e}  grad Dhat_c {e_c:.2e}")
+
+
+def test_full_size_inference_sampled():
+    """2^24-point forward with the 4-bit packed index codebook; the oracle evaluates a random
+    sample of the points one by one."""
+    w = W.WORKLOADS["infer3d"]
+    x = W.make_points(w)
+    D_f = W.make_feature_codebook(w)
+    D_c = oracle.bake_probes(W.make_probe_logits(w))
+    cfg = cngp.Config.from_workload(w, index_format=cngp.IDX_PACKED4)
+    y = cngp.encode_fwd(cfg, dev(x), dev(D_f), cngp.pack4(dev(D_c)))
+    torch.cuda.synchronize()
+    pick = np.random.default_rng(5).choice(w.N, 1 << 16, replace=False)
+    pick[:2] = [0, w.N - 1]
+    y_ref, ymag = oracle.encode_fwd(w, x[pick], D_f, D_c)
+    check_close("y infer3d sample", host(y[torch.from_numpy(pick).to(DEV)]), y_ref, ymag, fp16_out=True)
+    # the unprobed hash grid (N_p = 1) at the same N_f, run alongside
+    w1 = W.custom(cfg=w.cfg, d=3, L=16, N_f=w.N_f, N_c=1, N_p=1, N_min=16, N_max=2048, N=w.N,
+                  feat_dtype="f16", io_dtype="f16")
+    cfg1 = cngp.Config.from_workload(w1)
+    zeros = np.zeros((16, 1), np.uint8)
+    y1 = cngp.encode_fwd(cfg1, dev(x), dev(D_f), dev(zeros))
+    y1_ref, y1mag = oracle.encode_fwd(w1, x[pick], D_f, zeros)
+    check_close("y hash grid sample", host(y1[torch.from_numpy(pick).to(DEV)]), y1_ref, y1mag, fp16_out=True)
