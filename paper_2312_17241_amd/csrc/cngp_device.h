@@ -35,13 +35,16 @@ struct Cell {
 
     // x scaled by the level resolution in ONE fp32 multiply (no fused multiply-add), so the
     // integer cell is the same on every implementation that follows this rule.
+    // The pragma keeps the compiler from fusing the multiply into pos - floor(pos): the fraction
+    // must come from the ROUNDED product, as everywhere else.
     __device__ __forceinline__ void locate(const float *xp, uint32_t N_l) {
+#pragma clang fp contract(off)
         const float s = (float)N_l;
 #pragma unroll
         for (int i = 0; i < D; ++i) {
-            float pos = __fmul_rn(xp[i], s);
+            float pos = xp[i] * s;
             float fl  = floorf(pos);
-            w[i] = __fsub_rn(pos, fl);
+            w[i] = pos - fl;
             uint32_t v0 = (uint32_t)fl;
             a1[i] = v0 * kPi[i];   b1[i] = a1[i] + kPi[i];
             a2[i] = v0 * kPi2[i];  b2[i] = a2[i] + kPi2[i];
