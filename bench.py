@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the Compact NGP encoding path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: bake (argmax of the confidence values into the index codebook), forward
+encoding, backward pass (gradient arrays cleared, then accumulated).  The default workload
+is the 3D NeRF-shaped configuration the headline metric is quoted on (d = 3, L = 16, F = 2,
+N_f = 2^16, N_c = 2^14, N_p = 16, 2^18 points = 4096 rays x 64 samples, fp16 features and I/O).
+
+Prints ONE JSON line: throughput in encoded points/s, the roofline of the dominant kernel
+(algorithmic bytes per launch / its average duration measured with HIP events on the launch
+stream, against the 8 TB/s HBM peak) and the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(w, n):
+    """Compulsory HBM bytes per launch of each kernel kind: every input read once, every output
+    written once (tables included; random re-reads of cached rows are not algorithmic)."""
+    fb = 2 if w.feat_dtype == "f16" else 4
+    iob = 2 if w.io_dtype == "f16" else 4
+    D_f = w.L * w.N_f * w.F * fb
+    D_c = w.L * w.N_c
+    Dhat = w.L * w.N_c * w.N_p * 4
+    gD_f = w.L * w.N_f * w.F * 4
+    pts = n * (4 * w.d + w.L * w.F * iob)
+    return {
+        "encode_fwd": pts + D_f + D_c,
+        "encode_bwd": pts + D_f + Dhat + gD_f + Dhat,
+        "bake_probes": Dhat + D_c,
+        "zero": gD_f + Dhat,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="nerf3d", help="nerf3d (headline) | image2d | sdf3d | tiny2d | infer3d")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2312_17241_amd as cngp
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    w = W.WORKLOADS[args.workload]
+    fwd_only = args.workload == "infer3d"
+    fmt = cngp.IDX_PACKED4 if fwd_only else cngp.IDX_U8
+    cfg = cngp.Config.from_workload(w, index_format=fmt, flags=cngp.ZERO_GRADS)
+
+    x_h = W.make_points(w)
+    D_f_h = W.make_feature_codebook(w)
+    Dhat_h = W.make_probe_logits(w)
+    N = x_h.shape[0]
+    x = torch.from_numpy(x_h).to(dev)
+    D_f = torch.from_numpy(D_f_h).to(dev)
+    Dhat = torch.from_numpy(Dhat_h).to(dev)
+    D_c = torch.empty((w.L, cfg.index_cols), dtype=torch.uint8, device=dev)
+    y = torch.empty((N, w.L * w.F), dtype=torch.float16 if w.io_dtype == "f16" else torch.float32, device=dev)
+    ws = cngp.alloc_workspace(cfg, N, dev)
+    if not fwd_only:
+        dy_h = W.make_upstream_grad(w)
+        dy = torch.from_numpy(dy_h).to(dev)
+        gF = torch.empty((w.L, w.N_f, w.F), dtype=torch.float32, device=dev)
+        gC = torch.empty((w.L, w.N_c, w.N_p), dtype=torch.float32, device=dev)
+
+    def step():
+        cngp.bake_probes(cfg, Dhat, D_c)
+        cngp.encode_fwd(cfg, x, D_f, D_c, y, workspace=ws)
+        if not fwd_only:
+            cngp.encode_bwd(cfg, x, D_f, Dhat, dy, gF, gC, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps, every kernel bracketed by HIP events on its launch stream
+    cngp.profile_enable(True)
+    cngp.profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernels = cngp.profile_read()
+    cngp.profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = N * args.steps / (t1 - t0)
+
+    # roofline of the dominant kernel kind
+    alg = algorithmic_bytes(w, N)
+    per_kernel = {}
+    for name, (ms, cnt) in kernels.items():
+        kind = "encode_bwd" if name.startswith("encode_bwd") else name
+        d = per_kernel.setdefault(kind, {"ms": 0.0, "launches": 0, "parts": {}})
+        d["ms"] += ms
+        d["launches"] += cnt
+        d["parts"][name] = {"avg_us": round(ms * 1e3 / cnt, 2), "launches": cnt}
+    dom = max(per_kernel, key=lambda k: per_kernel[k]["ms"])
+    dom_ms_per_step = per_kernel[dom]["ms"] / args.steps        # all parts of that kind, per step
+    achieved = alg[dom] / (dom_ms_per_step * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"{dom}:{args.workload}")
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
+                "algorithmic_bytes_per_launch": alg[dom], "avg_launch_us": round(dom_ms_per_step * 1e3, 2)}
+
+    out = {
+        "metric": "encoded points/s fwd+bwd (d=3, L=16)" if not fwd_only else "encoded points/s fwd",
+        "value": round(value, 1), "unit": "points/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: d={w.d} L={w.L} F={w.F} N_f={w.N_f} N_c={w.N_c} N_p={w.N_p} "
+                               f"N_min={w.N_min} N_max={w.N_max} points={N} ({w.points}) "
+                               f"D_f={w.feat_dtype} y/dy={w.io_dtype}",
+                   "step": "bake + fwd" if fwd_only else "bake + fwd + bwd (grads cleared each step)"},
+        "roofline": roofline,
+        "kernels_us_per_step": {k: round(v["ms"] * 1e3 / args.steps, 2) for k, v in per_kernel.items()},
+        "kernel_parts": {k: v["parts"] for k, v in per_kernel.items() if len(v["parts"]) > 1},
+    }
+
+    if not args.no_check or not args.no_cpu_baseline:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from parity import check_close, check_exact
+        # bounded sample of the same workload for the CPU leg: the first n_cpu points
+        n_cpu = min(N, 1 << 18)
+        xs = x_h[:n_cpu]
+        t0 = time.perf_counter()
+        D_c_ref = oracle.bake_probes(Dhat_h)
+        y_ref, ymag = oracle.encode_fwd(w, xs, D_f_h, D_c_ref)
+        if not fwd_only:
+            g_ref = oracle.encode_bwd(w, xs, D_f_h, Dhat_h, dy_h[:n_cpu], want_abs=not args.no_check)
+        t_cpu = time.perf_counter() - t0
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 1), "unit": "points/s",
+                                   "cores": oracle.num_threads(), "kind": "oracle",
+                                   "sample": f"first {n_cpu} of {N} points, one pass of bake + fwd"
+                                             + ("" if fwd_only else " + bwd") + f", {t_cpu:.2f} s"}
+        if not args.no_check:
+            # self-check of the timed configuration against the oracle (same launch configuration)
+            unpack = D_c if fmt == cngp.IDX_U8 else torch.stack([D_c & 0xF, D_c >> 4], dim=-1).reshape(w.L, w.N_c)
+            check_exact("D_c", unpack.cpu().numpy(), D_c_ref)
+            e = {"y": check_close("y", y[:n_cpu].cpu().numpy(), y_ref, ymag, fp16_out=(w.io_dtype == "f16"))}
+            if not fwd_only and n_cpu == N:
+                e["grad_D_f"] = check_close("grad D_f", gF.cpu().numpy(), g_ref[0], g_ref[2], fp16_out=False)
+                e["grad_Dhat_c"] = check_close("grad Dhat_c", gC.cpu().numpy(), g_ref[1], g_ref[3], fp16_out=False)
+            out["parity_max_rel_err"] = {k: float(f"{v:.3e}") for k, v in e.items()}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

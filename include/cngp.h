@@ -53,7 +53,12 @@ typedef enum { CNGP_F32 = 0, CNGP_F16 = 1 } cngp_dtype;
  *                    Needs N_c >= 2 (N_p <= 16 always fits four bits). */
 typedef enum { CNGP_IDX_U8 = 0, CNGP_IDX_PACKED4 = 1 } cngp_index_format;
 
-enum { CNGP_ZERO_GRADS = 1u };  /* cngp_encode_bwd clears both gradient arrays before accumulating */
+/* cngp_config.flags */
+enum {
+    CNGP_ZERO_GRADS = 1u,   /* cngp_encode_bwd clears both gradient arrays before accumulating            */
+    CNGP_BWD_DIRECT = 2u,   /* force the backward variant that adds straight into HBM with global atomics  */
+    CNGP_BWD_SLICED = 4u    /* force the variant that accumulates table slices in LDS (needs workspace)   */
+};                          /* neither: the library picks by table size and N                              */
 
 /* Hyper-parameters of the encoding (Table 1 of the paper, same symbols). */
 typedef struct {
@@ -68,7 +73,7 @@ typedef struct {
     int32_t  feat_dtype;   /* cngp_dtype of D_f                                                */
     int32_t  io_dtype;     /* cngp_dtype of y and dL/dy                                        */
     int32_t  index_format; /* cngp_index_format of D_c                                         */
-    uint32_t flags;        /* CNGP_ZERO_GRADS or 0                                             */
+    uint32_t flags;        /* bitwise OR of the CNGP_* flags above                             */
 } cngp_config;
 
 /* Grid resolution of every level (Table 1: N_min, N_max, L; geometric growth):

@@ -2,10 +2,12 @@
 // selection and launches.  See include/cngp.h for the contract of every entry point.
 #include "../../include/cngp.h"
 #include "cngp_kernels.h"
+#include "cngp_bwd_sliced.h"
 
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 #include <string>
 #include <vector>
 
@@ -40,7 +42,8 @@ int validate(const cngp_config *c) {
     if (c->io_dtype != CNGP_F32 && c->io_dtype != CNGP_F16) return CNGP_ERR_INVALID;
     if (c->index_format != CNGP_IDX_U8 && c->index_format != CNGP_IDX_PACKED4) return CNGP_ERR_INVALID;
     if (c->index_format == CNGP_IDX_PACKED4 && c->N_c < 2) return CNGP_ERR_INVALID;
-    if (c->flags & ~(uint32_t)CNGP_ZERO_GRADS) return CNGP_ERR_INVALID;
+    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED)) return CNGP_ERR_INVALID;
+    if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & CNGP_BWD_SLICED)) return CNGP_ERR_INVALID;
     if (c->F != 2) return CNGP_ERR_UNSUPPORTED;
     return CNGP_OK;
 }
@@ -70,8 +73,10 @@ Params make_params(const cngp_config *c) {
 int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INVALID : CNGP_OK; }
 
 // ---------------------------------------------------------------- per-kernel timing
-enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BAKE, K_ZERO, K_DEBUG, K_COUNT };
-const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "bake_probes", "zero", "debug_indices"};
+enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_FEAT, K_BWD_LOGIT, K_BAKE, K_ZERO, K_DEBUG, K_COUNT };
+const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_softmax_table",
+                                           "encode_bwd_transpose_dy", "encode_bwd_feat_sliced",
+                                           "encode_bwd_logit_sliced", "bake_probes", "zero", "debug_indices"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -145,16 +150,139 @@ int launch_bwd_direct(const cngp_config *c, const Params &p, int level0, int nle
     return launch_status("encode_bwd_direct_kernel");
 }
 
-template <int D, typename FeatT, typename IoT>
-int dispatch_bwd_np(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
-                    const float *Dhat_c, const void *dy, float *gD_f, float *gDhat_c, hipStream_t s) {
-    switch (c->N_p) {
-    case 1:  return launch_bwd_direct<D, 1, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
-    case 2:  return launch_bwd_direct<D, 2, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
-    case 4:  return launch_bwd_direct<D, 4, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
-    case 8:  return launch_bwd_direct<D, 8, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
-    default: return launch_bwd_direct<D, 16, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s);
+
+// ---------------------------------------------------------------- backward plan
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct BwdPlan {
+    bool     sliced;
+    uint32_t rows_f_log2, slices_f;     // feature-gradient slices per level
+    uint32_t rows_c_log2, slices_c;     // logit-gradient slices per level (0 when N_p == 1)
+    uint32_t chunks, chunk_pts;
+    size_t   lds_f, lds_c;              // dynamic LDS bytes of the two kernels
+    size_t   sigma_off, dyT_off, ws_bytes;
+};
+
+constexpr uint32_t kMaxSlicesPerLevel = 128;   // beyond this the replicated scan costs more than global atomics
+constexpr int64_t  kMinSlicedPoints = 2048;
+
+BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
+    BwdPlan b;
+    std::memset(&b, 0, sizeof(b));
+    const uint32_t groups = c->N_f / c->N_p;                               // hashed rows of D_f
+    const uint32_t max_rows_f = (uint32_t)kSliceBytes / (c->N_p * 2 * 8);
+    const uint32_t rows_f = groups < max_rows_f ? groups : max_rows_f;
+    b.rows_f_log2 = ilog2(rows_f);
+    b.slices_f = groups / rows_f;
+    if (c->N_p > 1) {
+        const uint32_t max_rows_c = (uint32_t)kSliceBytes / (c->N_p * 8);
+        const uint32_t rows_c = c->N_c < max_rows_c ? c->N_c : max_rows_c;
+        b.rows_c_log2 = ilog2(rows_c);
+        b.slices_c = c->N_c / rows_c;
     }
+    const uint32_t per_level = b.slices_f + b.slices_c;
+    b.sliced = per_level <= kMaxSlicesPerLevel && N >= kMinSlicedPoints;
+    if (c->flags & CNGP_BWD_DIRECT) b.sliced = false;
+    if ((c->flags & CNGP_BWD_SLICED) && per_level <= 65535u) b.sliced = true;
+    // enough workgroups for three rounds over the 256 CUs, but chunks of at least 16384 points
+    int64_t chunks = (768 + (int64_t)per_level * c->L - 1) / ((int64_t)per_level * c->L);
+    const int64_t max_chunks = (N + 16383) / 16384;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    int64_t chunk_pts = (N + chunks - 1) / chunks;
+    chunk_pts = (chunk_pts + 63) / 64 * 64;
+    if (chunk_pts < 64) chunk_pts = 64;
+    b.chunks = (uint32_t)((N + chunk_pts - 1) / chunk_pts);
+    if (b.chunks < 1) b.chunks = 1;
+    b.chunk_pts = (uint32_t)chunk_pts;
+    const size_t queues = (size_t)kSlicedWaves * kQueueCap * sizeof(QEntry);
+    b.lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8 + queues;
+    b.lds_c = ((size_t)1 << b.rows_c_log2) * c->N_p * 8 + queues;
+    if (b.sliced) {
+        const size_t io = c->io_dtype == CNGP_F16 ? 2 : 4;
+        b.sigma_off = 0;
+        b.dyT_off = align256((size_t)c->L * c->N_c * c->N_p * sizeof(float));
+        b.ws_bytes = b.dyT_off + align256((size_t)N * c->L * c->F * io);
+    }
+    return b;
+}
+
+template <int NP>
+int launch_softmax_table(const cngp_config *c, const float *Dhat_c, float *sigma, hipStream_t s) {
+    const int64_t elems = (int64_t)c->L * c->N_c * NP;
+    const int64_t blocks = (elems + kBlock - 1) / kBlock;
+    if (int rc = check_blocks(blocks)) return rc;
+    LaunchTimer t(s, K_BWD_SOFTMAX);
+    softmax_table_kernel<NP><<<(unsigned)blocks, kBlock, 0, s>>>(Dhat_c, sigma, elems);
+    return launch_status("softmax_table_kernel");
+}
+
+template <typename PairT>
+int launch_transpose_dy(const cngp_config *c, const void *dy, void *dyT, int64_t N, hipStream_t s) {
+    const int64_t blocks = (N + kBlock - 1) / kBlock;
+    if (int rc = check_blocks(blocks)) return rc;
+    LaunchTimer t(s, K_BWD_TRANSPOSE);
+    transpose_dy_kernel<PairT><<<(unsigned)blocks, kBlock, 0, s>>>((const PairT *)dy, (PairT *)dyT, N, c->L);
+    return launch_status("transpose_dy_kernel");
+}
+
+template <typename K>
+int allow_big_lds(K kernel, size_t bytes) {
+    if (bytes <= 64 * 1024) return CNGP_OK;
+    hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    return e == hipSuccess ? CNGP_OK : hip_fail(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+}
+
+template <int D, int NP, typename FeatT, typename IoT>
+int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, const float *x, int64_t N,
+                      const void *D_f, const float *Dhat_c, const void *dy, float *gD_f, float *gDhat_c,
+                      void *workspace, hipStream_t s) {
+    float *sigma = reinterpret_cast<float *>((char *)workspace + b.sigma_off);
+    IoT   *dyT = reinterpret_cast<IoT *>((char *)workspace + b.dyT_off);
+    if (NP > 1)
+        if (int rc = launch_softmax_table<NP>(c, Dhat_c, sigma, s)) return rc;
+    using PairT = typename std::conditional<sizeof(IoT) == 2, uint32_t, float2>::type;
+    if (int rc = launch_transpose_dy<PairT>(c, dy, dyT, N, s)) return rc;
+
+    SliceParams sp;
+    sp.level0 = 0;
+    sp.chunk_pts = b.chunk_pts;
+    sp.store_direct = (b.chunks == 1 && (c->flags & CNGP_ZERO_GRADS)) ? 1 : 0;
+    {
+        sp.rows_log2 = b.rows_f_log2;
+        auto kernel = bwd_feat_sliced_kernel<D, NP, IoT>;
+        if (int rc = allow_big_lds(kernel, b.lds_f)) return rc;
+        LaunchTimer t(s, K_BWD_FEAT);
+        kernel<<<dim3(b.chunks, b.slices_f, (unsigned)c->L), kSlicedBlock, b.lds_f, s>>>(p, sp, x, sigma, dyT, gD_f, N);
+        if (int rc = launch_status("bwd_feat_sliced_kernel")) return rc;
+    }
+    if (NP > 1) {
+        sp.rows_log2 = b.rows_c_log2;
+        auto kernel = bwd_logit_sliced_kernel<D, NP, FeatT, IoT>;
+        if (int rc = allow_big_lds(kernel, b.lds_c)) return rc;
+        LaunchTimer t(s, K_BWD_LOGIT);
+        kernel<<<dim3(b.chunks, b.slices_c, (unsigned)c->L), kSlicedBlock, b.lds_c, s>>>(
+            p, sp, x, (const FeatT *)D_f, sigma, dyT, gDhat_c, N);
+        if (int rc = launch_status("bwd_logit_sliced_kernel")) return rc;
+    }
+    return CNGP_OK;
+}
+
+template <int D, typename FeatT, typename IoT>
+int dispatch_bwd_np(const cngp_config *c, const Params &p, const BwdPlan &b, const float *x, int64_t N,
+                    const void *D_f, const float *Dhat_c, const void *dy, float *gD_f, float *gDhat_c,
+                    void *workspace, hipStream_t s) {
+#define CNGP_BWD_CASE(NP)                                                                                        \
+    return b.sliced ? launch_bwd_sliced<D, NP, FeatT, IoT>(c, p, b, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, workspace, s) \
+                    : launch_bwd_direct<D, NP, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s)
+    switch (c->N_p) {
+    case 1:  CNGP_BWD_CASE(1);
+    case 2:  CNGP_BWD_CASE(2);
+    case 4:  CNGP_BWD_CASE(4);
+    case 8:  CNGP_BWD_CASE(8);
+    default: CNGP_BWD_CASE(16);
+    }
+#undef CNGP_BWD_CASE
 }
 
 // d x feat_dtype x io_dtype -> template instance
@@ -199,8 +327,8 @@ int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l) {
 }
 
 size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N) {
-    if (validate(cfg) != CNGP_OK || N < 0) return 0;
-    return 0;
+    if (validate(cfg) != CNGP_OK || N <= 0) return 0;
+    return make_bwd_plan(cfg, N).ws_bytes;
 }
 
 int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const void *D_c,
@@ -222,15 +350,22 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     if (N < 0) return CNGP_ERR_INVALID;
     if (!grad_D_f || !grad_Dhat_c) return CNGP_ERR_NULL;
     if (N > 0 && (!x || !D_f || !Dhat_c || !dy)) return CNGP_ERR_NULL;
-    (void)workspace; (void)workspace_bytes;
     hipStream_t s = (hipStream_t)stream;
+    const BwdPlan b = make_bwd_plan(cfg, N);
+    if (N > 0 && b.sliced) {
+        if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < b.ws_bytes) return CNGP_ERR_WORKSPACE;
+    }
+    // the sliced path with a single chunk writes every gradient entry itself
+    const bool sliced_stores = N > 0 && b.sliced && b.chunks == 1;
     if (cfg->flags & CNGP_ZERO_GRADS) {
-        if (int rc = launch_zero(grad_D_f, (int64_t)cfg->L * cfg->N_f * cfg->F, s)) return rc;
-        if (int rc = launch_zero(grad_Dhat_c, (int64_t)cfg->L * cfg->N_c * cfg->N_p, s)) return rc;
+        if (!sliced_stores)
+            if (int rc = launch_zero(grad_D_f, (int64_t)cfg->L * cfg->N_f * cfg->F, s)) return rc;
+        if (!sliced_stores || cfg->N_p == 1)
+            if (int rc = launch_zero(grad_Dhat_c, (int64_t)cfg->L * cfg->N_c * cfg->N_p, s)) return rc;
     }
     if (N == 0) return CNGP_OK;
     const Params p = make_params(cfg);
-    CNGP_DISPATCH_TYPES(dispatch_bwd_np, cfg, p, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, s);
+    CNGP_DISPATCH_TYPES(dispatch_bwd_np, cfg, p, b, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, workspace, s);
 }
 
 int cngp_bake_probes(const cngp_config *cfg, const float *Dhat_c, void *D_c, void *stream) {

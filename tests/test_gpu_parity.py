@@ -54,12 +54,19 @@ def check_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8, name=""):
     return check_close(f"y {name}", y, y_ref, ymag, fp16_out=(w.io_dtype == "f16"))
 
 
-def check_bwd(w, x, D_f, Dhat, dy, name=""):
+# the three ways the library can run the backward pass: its own choice, and each variant forced
+BWD_PATHS = {"auto": 0, "direct": cngp.BWD_DIRECT, "sliced": cngp.BWD_SLICED}
+
+
+def check_bwd(w, x, D_f, Dhat, dy, name="", paths=("auto", "direct", "sliced")):
     gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
-    gF, gC = run_bwd(w, x, D_f, Dhat, dy)
-    e1 = check_close(f"grad D_f {name}", gF, gF_ref, A_f, fp16_out=False)
-    e2 = check_close(f"grad Dhat_c {name}", gC, gC_ref, A_c, fp16_out=False)
-    return e1, e2
+    worst = (0.0, 0.0)
+    for path in paths:
+        gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS | BWD_PATHS[path])
+        e1 = check_close(f"grad D_f {name} [{path}]", gF, gF_ref, A_f, fp16_out=False)
+        e2 = check_close(f"grad Dhat_c {name} [{path}]", gC, gC_ref, A_c, fp16_out=False)
+        worst = (max(worst[0], e1), max(worst[1], e2))
+    return worst
 
 
 # ------------------------------------------------------------------ indices, bit-exact
@@ -168,13 +175,34 @@ def test_backward_parity_sweep(d, N_p, feat, io):
     check_bwd(w, x, D_f, Dhat, dy)
 
 
-def test_backward_accumulates_without_zero_flag():
+@pytest.mark.parametrize("path", ["direct", "sliced"])
+def test_backward_accumulates_without_zero_flag(path):
     w = sweep_workload(3, 4, "f32", "f32", N=500)
     x, D_f, Dhat, dy = tables(w)
     gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
-    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=0, init=1.5)
+    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=BWD_PATHS[path], init=1.5)
     check_close("grad D_f (+=)", gF, gF_ref + 1.5, A_f + 1.5, fp16_out=False)
     check_close("grad Dhat_c (+=)", gC, gC_ref + 1.5, A_c + 1.5, fp16_out=False)
+
+
+def test_sliced_backward_many_chunks_and_slices():
+    """Tables larger than one LDS slice and enough points for several chunks per slice."""
+    w = W.custom(cfg=81, d=3, L=2, N_f=2**15, N_c=2**12, N_p=16, N_min=16, N_max=512, N=70000 + 5,
+                 feat_dtype="f16", io_dtype="f16")
+    x, D_f, Dhat, dy = tables(w)
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    check_bwd(w, x, D_f, Dhat, dy, paths=("sliced", "auto"))
+
+
+def test_sliced_backward_needs_workspace():
+    w = sweep_workload(3, 4, "f32", "f32", N=5000)
+    cfg = cngp.Config.from_workload(w, flags=cngp.BWD_SLICED)
+    assert cngp.workspace_bytes(cfg, w.N) > 0
+    x, D_f, Dhat, dy = tables(w)
+    with pytest.raises(cngp.CngpError) as e:
+        cngp.encode_bwd(cfg, dev(x), dev(D_f), dev(Dhat), dev(dy), workspace=None)
+    assert e.value.status == cngp.ERR_WORKSPACE
+    assert cngp.workspace_bytes(cngp.Config.from_workload(w, flags=cngp.BWD_DIRECT), w.N) == 0
 
 
 # ------------------------------------------------------------------ edge cases
@@ -233,8 +261,10 @@ def test_probe_range_one_matches_unprobed_hash_grid():
                  feat_dtype="f16", io_dtype="f16")
     x, D_f, Dhat, dy = tables(w)
     check_fwd(w, x, D_f, np.zeros((w.L, 1), np.uint8))
-    gF, gC = run_bwd(w, x, D_f, Dhat, dy)
-    assert np.all(gC == 0.0)
+    for path in ("direct", "sliced"):
+        gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS | BWD_PATHS[path])
+        assert np.all(gC == 0.0)
+    check_bwd(w, x, D_f, Dhat, dy)
 
 
 # ------------------------------------------------------------------ full benchmark sizes
