@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--workload", default="nerf3d", help="nerf3d (headline) | image2d | sdf3d | tiny2d | infer3d")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run one plain device-to-device copy of this many MiB (reads and writes that many "
+                         "bytes): the reference that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, sharding); "
@@ -96,6 +99,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.ones(args.copy_calibration << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # timed region: exactly K steps, every kernel bracketed by HIP events on its launch stream
     cngp.profile_enable(True)

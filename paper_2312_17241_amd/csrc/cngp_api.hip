@@ -181,9 +181,12 @@ BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
         b.slices_c = c->N_c / rows_c;
     }
     const uint32_t per_level = b.slices_f + b.slices_c;
+    // a queued reference packs (row inside the slice, row of the other table) into 32 bits
+    const bool keys_fit = b.rows_f_log2 + ilog2(c->N_c) <= 32 && b.rows_c_log2 + ilog2(groups) <= 32;
     b.sliced = per_level <= kMaxSlicesPerLevel && N >= kMinSlicedPoints;
     if (c->flags & CNGP_BWD_DIRECT) b.sliced = false;
-    if ((c->flags & CNGP_BWD_SLICED) && per_level <= 65535u) b.sliced = true;
+    if ((c->flags & CNGP_BWD_SLICED) && (uint64_t)per_level * 32u * 64u < 0x7fffffffull) b.sliced = true;
+    if (!keys_fit) b.sliced = false;
     // enough workgroups for three rounds over the 256 CUs, but chunks of at least 16384 points
     int64_t chunks = (768 + (int64_t)per_level * c->L - 1) / ((int64_t)per_level * c->L);
     const int64_t max_chunks = (N + 16383) / 16384;
@@ -195,7 +198,7 @@ BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
     b.chunks = (uint32_t)((N + chunk_pts - 1) / chunk_pts);
     if (b.chunks < 1) b.chunks = 1;
     b.chunk_pts = (uint32_t)chunk_pts;
-    const size_t queues = (size_t)kSlicedWaves * kQueueCap * sizeof(QEntry);
+    const size_t queues = (size_t)kSlicedWaves * kRingBytes;
     b.lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8 + queues;
     b.lds_c = ((size_t)1 << b.rows_c_log2) * c->N_p * 8 + queues;
     if (b.sliced) {
@@ -245,23 +248,26 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
     if (int rc = launch_transpose_dy<PairT>(c, dy, dyT, N, s)) return rc;
 
     SliceParams sp;
-    sp.level0 = 0;
+    sp.chunks = b.chunks;
     sp.chunk_pts = b.chunk_pts;
+    const unsigned levels_padded = (unsigned)((c->L + kXcds - 1) / kXcds * kXcds);
     sp.store_direct = (b.chunks == 1 && (c->flags & CNGP_ZERO_GRADS)) ? 1 : 0;
     {
         sp.rows_log2 = b.rows_f_log2;
+        sp.slices = b.slices_f;
         auto kernel = bwd_feat_sliced_kernel<D, NP, IoT>;
         if (int rc = allow_big_lds(kernel, b.lds_f)) return rc;
         LaunchTimer t(s, K_BWD_FEAT);
-        kernel<<<dim3(b.chunks, b.slices_f, (unsigned)c->L), kSlicedBlock, b.lds_f, s>>>(p, sp, x, sigma, dyT, gD_f, N);
+        kernel<<<levels_padded * b.slices_f * b.chunks, kSlicedBlock, b.lds_f, s>>>(p, sp, x, sigma, dyT, gD_f, N);
         if (int rc = launch_status("bwd_feat_sliced_kernel")) return rc;
     }
     if (NP > 1) {
         sp.rows_log2 = b.rows_c_log2;
+        sp.slices = b.slices_c;
         auto kernel = bwd_logit_sliced_kernel<D, NP, FeatT, IoT>;
         if (int rc = allow_big_lds(kernel, b.lds_c)) return rc;
         LaunchTimer t(s, K_BWD_LOGIT);
-        kernel<<<dim3(b.chunks, b.slices_c, (unsigned)c->L), kSlicedBlock, b.lds_c, s>>>(
+        kernel<<<levels_padded * b.slices_c * b.chunks, kSlicedBlock, b.lds_c, s>>>(
             p, sp, x, (const FeatT *)D_f, sigma, dyT, gDhat_c, N);
         if (int rc = launch_status("bwd_logit_sliced_kernel")) return rc;
     }

@@ -23,21 +23,35 @@ namespace cngp {
 
 constexpr int kSlicedBlock = 1024;                  // 16 wavefronts share one slice
 constexpr int kSlicedWaves = kSlicedBlock / 64;
-constexpr int kQueueCap    = 96;                    // pending corner references per wavefront
+constexpr int kRing        = 128;                   // pending corner references per wavefront (ring buffer)
+constexpr int kRingBytes   = kRing * 12;            // 4-byte key + two floats per reference
 constexpr int kSliceBytes  = 128 * 1024;            // LDS bytes of fp64 accumulators per workgroup
 
 struct SliceParams {
-    int32_t  level0;        // first level of this launch (blockIdx.z counts from it)
     uint32_t rows_log2;     // log2(table rows per slice)
-    uint32_t chunk_pts;     // points per blockIdx.x
+    uint32_t slices;        // slices per level
+    uint32_t chunks;        // point chunks per slice
+    uint32_t chunk_pts;     // points per chunk
     int32_t  store_direct;  // 1: every slice is written by exactly one workgroup -> plain stores
 };
 
-struct __align__(16) QEntry {
-    uint32_t row;           // row inside this workgroup's slice
-    uint32_t other;         // index into the table the drain step reads (sigma row / D_f row group)
-    float    g0, g1;        // weight * dL/dy of the corner
-};
+// Which (level, slice, chunk) a workgroup of the 1-D grid works on.  Workgroups are handed to the
+// 8 XCDs round-robin by their linear index, and every XCD has an L2 of its own; the mapping keeps
+// all workgroups of one level on one XCD (level l on XCD l mod 8, levels in ascending order), so the
+// rows a level gathers at random (its softmax table, its slice of D_f) stay in that one L2 instead
+// of all levels' tables competing for every L2.
+constexpr int kXcds = 8;
+struct SliceCoord { int level; uint32_t slice, chunk; };
+__device__ __forceinline__ SliceCoord slice_coord(const SliceParams &sp) {
+    const uint32_t i = blockIdx.x, xcd = i % kXcds, j = i / kXcds;
+    const uint32_t per_level = sp.slices * sp.chunks;
+    const uint32_t rem = j % per_level;
+    SliceCoord c;
+    c.level = (int)((j / per_level) * kXcds + xcd);
+    c.slice = rem / sp.chunks;
+    c.chunk = rem % sp.chunks;
+    return c;
+}
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -73,106 +87,195 @@ __global__ __launch_bounds__(kBlock) void transpose_dy_kernel(const PairT *__res
 }
 
 // ------------------------------------------------------------------ shared scan loop
-// Walks the chunk of points, 64 per wavefront step; for every corner whose `row_of` falls into this
-// workgroup's slice appends an entry to the wavefront's queue and drains the queue when it fills.
-template <int D, bool BY_FEATURE_ROW, typename IoT, typename Drain>
-__device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &sp, const int l,
+// One wavefront walks its share of the chunk, 64 points per step:
+//   1. locate each point's cell and test its 2^d corners against the workgroup's slice with the
+//      slice-selecting hash only (a bit mask per lane);
+//   2. emit the accepted corners, one per lane and round, into the wavefront's ring buffer in LDS:
+//      key = row inside the slice | (index of the row the other table is read at) << rows_log2,
+//      and g = weight * dL/dy (the weight and the second hash are computed for accepted corners only);
+//   3. software pipeline: the gathers (`load`) of the references emitted in one step are issued at
+//      the end of that step and consumed (`accum`: LDS atomics) at the end of the next one, so the
+//      memory latency hides behind the next step's hashing.
+// NP lanes cooperate on one reference (lane k = candidate k of the probing range), 64 / NP
+// references per wavefront instruction.  T is what `load` brings per lane.
+template <int D, int NP, bool BY_FEATURE_ROW, int U, typename T, typename IoT, typename Load, typename Accum>
+__device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &sp, const SliceCoord &co,
                                            const float *__restrict__ x, const IoT *__restrict__ dy_l,
-                                           const int64_t N, QEntry *queue, Drain drain)
+                                           const int64_t N, unsigned char *ring_mem, Load load, Accum accum)
 {
+    constexpr int  EPI = 64 / NP;                                   // references per wavefront instruction
     const int      lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t slice = blockIdx.y;
+    const uint32_t sub = lane / NP;
+    uint32_t *ring_key = reinterpret_cast<uint32_t *>(ring_mem + (size_t)wave * kRingBytes);
+    float2   *ring_g   = reinterpret_cast<float2 *>(ring_key + kRing);
+    const uint32_t mine_mask   = BY_FEATURE_ROW ? p.row_mask : p.c_mask;
+    const uint32_t other_mask  = BY_FEATURE_ROW ? p.c_mask : p.row_mask;
     const uint32_t row_lo_mask = (1u << sp.rows_log2) - 1u;
-    const int64_t  n0 = (int64_t)blockIdx.x * sp.chunk_pts;
+    const uint32_t slice_sel   = mine_mask & ~row_lo_mask;          // bits of the hash that name the slice
+    const uint32_t slice_val   = co.slice << sp.rows_log2;
+    const int64_t  n0 = (int64_t)co.chunk * sp.chunk_pts;
     const int64_t  n1 = (n0 + sp.chunk_pts < N) ? n0 + sp.chunk_pts : N;
-    uint32_t       qn = 0;                                    // wavefront-uniform queue length
+    const float    res = (float)p.N_l[co.level];
 
-    for (int64_t nb = n0 + wave * 64; nb < n1; nb += kSlicedBlock) {
-        const int64_t n = nb + lane;
-        const bool    valid = n < n1;
-        float xp[D];
+    uint32_t head = 0, tail = 0, pn = 0;                            // wavefront-uniform ring state
+    T        inflight[U];
+    // Both loops run a wavefront-uniform number of full instructions; in the last, partial one the
+    // surplus lanes re-read the newest reference and add zero.
+    auto issue = [&]() {                                            // start the gathers of the oldest references
+        const uint32_t have = tail - head;
+        pn = have < (uint32_t)(U * EPI) ? have : (uint32_t)(U * EPI);
 #pragma unroll
-        for (int j = 0; j < D; ++j) xp[j] = valid ? x[n * D + j] : 0.0f;
-        Cell<D> cell;
-        cell.locate(xp, p.N_l[l]);
-        float2 g = make_float2(0.f, 0.f);
-        if (valid) g = load_pair(dy_l, (size_t)n);
-#pragma unroll
-        for (int c = 0; c < (1 << D); ++c) {
-            const uint32_t r1 = cell.hash1(c) & p.row_mask;    // hashed row group of D_f
-            const uint32_t r2 = cell.hash2(c) & p.c_mask;      // row of D^_c
-            const uint32_t mine = BY_FEATURE_ROW ? r1 : r2;
-            const bool     take = valid && (mine >> sp.rows_log2) == slice;
-            const uint64_t m = __ballot(take);
-            if (take) {
-                const float wt = cell.weight(c);
-                QEntry e;
-                e.row = mine & row_lo_mask;
-                e.other = BY_FEATURE_ROW ? r2 : r1;
-                e.g0 = wt * g.x;
-                e.g1 = wt * g.y;
-                queue[qn + lanes_below(m)] = e;
-            }
-            qn += (uint32_t)__popcll(m);
-            if (qn > (uint32_t)(kQueueCap - 64)) {             // the next corner may add up to 64
-                wave_lds_fence();
-                drain(qn);
-                wave_lds_fence();
-                qn = 0;
+        for (int u = 0; u < U; ++u) {
+            if ((uint32_t)(u * EPI) < pn) {
+                const uint32_t e = u * EPI + sub;
+                inflight[u] = load(ring_key[(head + (e < pn ? e : pn - 1)) & (kRing - 1)]);
             }
         }
+    };
+    auto complete = [&]() {                                         // accumulate what `issue` started
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if ((uint32_t)(u * EPI) < pn) {
+                const uint32_t e = u * EPI + sub;
+                const uint32_t i = (head + (e < pn ? e : pn - 1)) & (kRing - 1);
+                float2 g = ring_g[i];
+                if (e >= pn) g = make_float2(0.f, 0.f);
+                accum(ring_key[i], g, inflight[u]);
+            }
+        }
+        head += pn;
+        pn = 0;
+    };
+
+    // software prefetch of the next step's point and upstream gradient
+    float   xn[D];
+    float2  gn = make_float2(0.f, 0.f);
+    int64_t nb = n0 + wave * 64;
+    {
+        const int64_t n = nb + lane;
+#pragma unroll
+        for (int j = 0; j < D; ++j) xn[j] = n < n1 ? x[n * D + j] : 0.0f;
+        if (n < n1) gn = load_pair(dy_l, (size_t)n);
+    }
+    for (; nb < n1; nb += kSlicedBlock) {
+        const bool valid = nb + lane < n1;
+        float xp[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) xp[j] = xn[j];
+        const float2 g = gn;
+        {
+            const int64_t n = nb + kSlicedBlock + lane;
+            const bool    more = n < n1;
+#pragma unroll
+            for (int j = 0; j < D; ++j) xn[j] = more ? x[n * D + j] : 0.0f;
+            gn = more ? load_pair(dy_l, (size_t)n) : make_float2(0.f, 0.f);
+        }
+
+        // cell of the point: fraction, lower vertex and the slice hash's terms per dimension
+        float    w[D], w1[D];                                       // fraction and 1 - fraction
+        uint32_t a[D], b[D], ao[D], bo[D];                          // hash terms: slice hash, other hash
+        {
+#pragma clang fp contract(off)
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                const float pos = xp[i] * res;                      // one rounded fp32 multiply
+                const float fl = floorf(pos);
+                w[i] = pos - fl;
+                w1[i] = 1.0f - w[i];
+                const uint32_t v0 = (uint32_t)fl;
+                const uint32_t pi = BY_FEATURE_ROW ? kPi[i] : kPi2[i];
+                const uint32_t po = BY_FEATURE_ROW ? kPi2[i] : kPi[i];
+                a[i] = v0 * pi;
+                b[i] = a[i] + pi;
+                ao[i] = v0 * po;
+                bo[i] = ao[i] + po;
+            }
+        }
+        uint32_t pending = 0;                                       // corners of this lane's point in the slice
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) {
+            uint32_t h = 0;
+#pragma unroll
+            for (int i = 0; i < D; ++i) h ^= ((c >> i) & 1) ? b[i] : a[i];
+            if ((h & slice_sel) == slice_val) pending |= 1u << c;
+        }
+        if (!valid) pending = 0;
+
+        for (;;) {
+            const bool     take = pending != 0;
+            const uint64_t m = __ballot(take);
+            if (m == 0) break;
+            while (kRing - (tail - head) < 64u) {                   // a round may add up to 64 references
+                wave_lds_fence();
+                if (pn == 0) issue();
+                complete();
+            }
+            if (take) {
+                const int c = __ffs(pending) - 1;
+                pending &= pending - 1;
+                uint32_t h = 0, ho = 0;
+                float    wt = 1.0f;
+#pragma unroll
+                for (int i = 0; i < D; ++i) {
+                    const bool up = (c >> i) & 1;
+                    h ^= up ? b[i] : a[i];
+                    ho ^= up ? bo[i] : ao[i];
+                    wt *= up ? w[i] : w1[i];
+                }
+                const uint32_t i = (tail + lanes_below(m)) & (kRing - 1);
+                ring_key[i] = (h & row_lo_mask) | ((ho & other_mask) << sp.rows_log2);
+                ring_g[i] = make_float2(wt * g.x, wt * g.y);
+            }
+            tail += (uint32_t)__popcll(m);
+        }
+        wave_lds_fence();
+        if (pn) complete();                                         // gathers issued one step ago
+        issue();                                                    // gathers for this step's references
     }
     wave_lds_fence();
-    drain(qn);
+    while (pn || tail != head) {
+        if (pn == 0) issue();
+        complete();
+    }
 }
 
 // ------------------------------------------------------------------ feature gradient
+// Accumulators: two planes (f = 0, 1) of rows * NP doubles, so that the NP lanes of a reference
+// add to NP consecutive doubles.
 template <int D, int NP, typename IoT>
 __global__ __launch_bounds__(kSlicedBlock) void bwd_feat_sliced_kernel(
     const Params p, const SliceParams sp, const float *__restrict__ x, const float *__restrict__ sigma,
     const IoT *__restrict__ dyT, float *__restrict__ gD_f, const int64_t N)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int  RW = NP * 2;                               // accumulators per row group (F = 2)
-    constexpr int  EPI = 64 / RW;                             // queue entries per wavefront instruction
     const uint32_t rows = 1u << sp.rows_log2;
+    const uint32_t plane = rows * NP;
     double *acc = reinterpret_cast<double *>(smem);
-    QEntry *queue = reinterpret_cast<QEntry *>(smem + (size_t)rows * RW * sizeof(double)) +
-                    (threadIdx.x >> 6) * kQueueCap;
-    const int l = sp.level0 + (int)blockIdx.z;
+    unsigned char *ring_mem = smem + (size_t)plane * 2 * sizeof(double);
+    const SliceCoord co = slice_coord(sp);
+    const int l = co.level;
+    if (l >= p.L) return;                                     // padding of the level count to a multiple of 8
 
-    for (uint32_t i = threadIdx.x; i < rows * RW; i += kSlicedBlock) acc[i] = 0.0;
+    for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) acc[i] = 0.0;
     __syncthreads();
 
-    const float *sig_l = sigma + (size_t)l * p.N_c * NP;
-    const int    lane = threadIdx.x & 63;
-    const int    sub = lane / RW, j = lane % RW;              // entry slot, accumulator within the row group
-    auto drain = [&](const uint32_t qn) {
-        constexpr int U = 4;                                  // entries in flight per lane group
-        for (uint32_t e0 = 0; e0 < qn; e0 += EPI * U) {
-            QEntry q[U];
-            float  s[U];
-            bool   ok[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t e = e0 + u * EPI + sub;
-                ok[u] = e < qn;
-                q[u] = queue[ok[u] ? e : 0];
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                s[u] = (NP == 1 || !ok[u]) ? 1.0f : sig_l[(size_t)q[u].other * NP + (j >> 1)];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (ok[u]) atomicAdd(&acc[q[u].row * RW + j], (double)(s[u] * ((j & 1) ? q[u].g1 : q[u].g0)));
-        }
+    const float   *sig_l = sigma + (size_t)l * p.N_c * NP;
+    const uint32_t k = (threadIdx.x & 63) % NP;
+    const uint32_t row_lo_mask = rows - 1u, rows_log2 = sp.rows_log2;
+    auto load = [&](const uint32_t key) -> float {
+        return NP == 1 ? 1.0f : sig_l[(size_t)(key >> rows_log2) * NP + k];
     };
-    scan_chunk<D, true>(p, sp, l, x, dyT + (size_t)l * N * 2, N, queue, drain);
+    auto accum = [&](const uint32_t key, const float2 g, const float s) {
+        double *a = acc + (key & row_lo_mask) * NP + k;
+        atomicAdd(a, (double)(s * g.x));
+        atomicAdd(a + plane, (double)(s * g.y));
+    };
+    scan_chunk<D, NP, true, 16, float>(p, sp, co, x, dyT + (size_t)l * N * 2, N, ring_mem, load, accum);
     __syncthreads();
 
-    float *out = gD_f + (size_t)l * p.N_f * 2 + (size_t)blockIdx.y * rows * RW;
-    for (uint32_t i = threadIdx.x; i < rows * RW; i += kSlicedBlock) {
-        const float v = (float)acc[i];
+    float *out = gD_f + (size_t)l * p.N_f * 2 + (size_t)co.slice * plane * 2;
+    for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) {     // i = (row * NP + k) * 2 + f
+        const float v = (float)acc[(i & 1u) * plane + (i >> 1)];
         if (sp.store_direct) out[i] = v;
         else if (v != 0.0f) atomic_add(out + i, v);
     }
@@ -185,44 +288,30 @@ __global__ __launch_bounds__(kSlicedBlock) void bwd_logit_sliced_kernel(
     const float *__restrict__ sigma, const IoT *__restrict__ dyT, float *__restrict__ gDhat_c, const int64_t N)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int  EPI = 64 / NP;
     const uint32_t rows = 1u << sp.rows_log2;
     double *acc = reinterpret_cast<double *>(smem);
-    QEntry *queue = reinterpret_cast<QEntry *>(smem + (size_t)rows * NP * sizeof(double)) +
-                    (threadIdx.x >> 6) * kQueueCap;
-    const int l = sp.level0 + (int)blockIdx.z;
+    unsigned char *ring_mem = smem + (size_t)rows * NP * sizeof(double);
+    const SliceCoord co = slice_coord(sp);
+    const int l = co.level;
+    if (l >= p.L) return;
 
     for (uint32_t i = threadIdx.x; i < rows * NP; i += kSlicedBlock) acc[i] = 0.0;
     __syncthreads();
 
-    const FeatT *F_l = D_f + (size_t)l * p.N_f * 2;
-    const int    lane = threadIdx.x & 63;
-    const int    sub = lane / NP, k = lane % NP;
-    auto drain = [&](const uint32_t qn) {
-        constexpr int U = 4;
-        for (uint32_t e0 = 0; e0 < qn; e0 += EPI * U) {
-            QEntry q[U];
-            float2 feat[U];
-            bool   ok[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t e = e0 + u * EPI + sub;
-                ok[u] = e < qn;
-                q[u] = queue[ok[u] ? e : 0];
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                feat[u] = ok[u] ? load_pair(F_l, (size_t)q[u].other * NP + k) : make_float2(0.f, 0.f);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (ok[u]) atomicAdd(&acc[q[u].row * NP + k], (double)fmaf(feat[u].x, q[u].g0, feat[u].y * q[u].g1));
-        }
+    const FeatT   *F_l = D_f + (size_t)l * p.N_f * 2;
+    const uint32_t k = (threadIdx.x & 63) % NP;
+    const uint32_t row_lo_mask = rows - 1u, rows_log2 = sp.rows_log2;
+    auto load = [&](const uint32_t key) -> float2 {
+        return load_pair(F_l, (size_t)(key >> rows_log2) * NP + k);
     };
-    scan_chunk<D, false>(p, sp, l, x, dyT + (size_t)l * N * 2, N, queue, drain);
+    auto accum = [&](const uint32_t key, const float2 g, const float2 feat) {
+        atomicAdd(acc + (key & row_lo_mask) * NP + k, (double)fmaf(feat.x, g.x, feat.y * g.y));
+    };
+    scan_chunk<D, NP, false, 8, float2>(p, sp, co, x, dyT + (size_t)l * N * 2, N, ring_mem, load, accum);
     __syncthreads();
 
     // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
-    const size_t row0 = (size_t)l * p.N_c + (size_t)blockIdx.y * rows;
+    const size_t row0 = (size_t)l * p.N_c + (size_t)co.slice * rows;
     const float *sig = sigma + row0 * NP;
     float       *out = gDhat_c + row0 * NP;
     for (uint32_t i = threadIdx.x; i < rows * NP; i += kSlicedBlock) {
