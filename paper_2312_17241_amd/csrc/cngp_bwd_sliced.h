@@ -18,6 +18,7 @@
 // small kernels prepare in the workspace.
 #pragma once
 #include "cngp_kernels.h"
+#include <type_traits>
 
 namespace cngp {
 
@@ -52,6 +53,17 @@ __device__ __forceinline__ SliceCoord slice_coord(const SliceParams &sp) {
     c.chunk = rem % sp.chunks;
     return c;
 }
+
+// A two-feature codebook entry as it sits in memory.
+template <typename FeatT> struct RawPair;
+template <> struct RawPair<float> {
+    using type = float2;
+    static __device__ __forceinline__ float2 to_float2(float2 v) { return v; }
+};
+template <> struct RawPair<__half> {
+    using type = __half2;
+    static __device__ __forceinline__ float2 to_float2(__half2 v) { return __half22float2(v); }
+};
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -90,22 +102,29 @@ __global__ __launch_bounds__(kBlock) void transpose_dy_kernel(const PairT *__res
 // One wavefront walks its share of the chunk, 64 points per step:
 //   1. locate each point's cell and test its 2^d corners against the workgroup's slice with the
 //      slice-selecting hash only (a bit mask per lane);
-//   2. emit the accepted corners, one per lane and round, into the wavefront's ring buffer in LDS:
-//      key = row inside the slice | (index of the row the other table is read at) << rows_log2,
-//      and g = weight * dL/dy (the weight and the second hash are computed for accepted corners only);
-//   3. software pipeline: the gathers (`load`) of the references emitted in one step are issued at
-//      the end of that step and consumed (`accum`: LDS atomics) at the end of the next one, so the
-//      memory latency hides behind the next step's hashing.
-// NP lanes cooperate on one reference (lane k = candidate k of the probing range), 64 / NP
-// references per wavefront instruction.  T is what `load` brings per lane.
-template <int D, int NP, bool BY_FEATURE_ROW, int U, typename T, typename IoT, typename Load, typename Accum>
+//   2. in two phases (low and high half of the corners) emit the accepted corners, one per lane and
+//      round, into the wavefront's ring buffer in LDS: key = row inside the slice | (row the other
+//      table is read at) << rows_log2, and g = weight * dL/dy (weight and second hash are computed
+//      for accepted corners only);
+//   3. software pipeline over fixed batches of kBatch references: after every phase the batch whose
+//      gathers (`load`) were issued one phase ago is accumulated (`accum`: LDS atomics) and the next
+//      full batch is issued, so memory latency hides behind the hashing of the phase in between.
+// NP lanes cooperate on one reference (lane k = candidate k of the probing range): 64 / NP
+// references per wavefront instruction, U = kBatch * NP / 64 instructions per batch.  T is what
+// `load` brings per lane.  Batches start at multiples of kBatch in the ring, so a batch never wraps.
+constexpr int kBatch = 32;
+static_assert(kRing % kBatch == 0 && kRing >= 64 + 2 * kBatch, "ring holds a round, a batch in flight and slack");
+
+template <int D, int NP, bool BY_FEATURE_ROW, typename T, typename IoT, typename Load, typename Accum>
 __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &sp, const SliceCoord &co,
                                            const float *__restrict__ x, const IoT *__restrict__ dy_l,
                                            const int64_t N, unsigned char *ring_mem, Load load, Accum accum)
 {
-    constexpr int  EPI = 64 / NP;                                   // references per wavefront instruction
+    constexpr int  EPI = (64 / NP < kBatch) ? 64 / NP : kBatch;     // references per wavefront instruction
+    constexpr int  U = kBatch / EPI;                                // instructions per batch
     const int      lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t sub = lane / NP;
+    const uint32_t sub = lane / NP;                                 // reference slot of this lane
+    const bool     slot_ok = sub < (uint32_t)EPI;                   // N_p = 1: only the first kBatch lanes work
     uint32_t *ring_key = reinterpret_cast<uint32_t *>(ring_mem + (size_t)wave * kRingBytes);
     float2   *ring_g   = reinterpret_cast<float2 *>(ring_key + kRing);
     const uint32_t mine_mask   = BY_FEATURE_ROW ? p.row_mask : p.c_mask;
@@ -117,34 +136,27 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
     const int64_t  n1 = (n0 + sp.chunk_pts < N) ? n0 + sp.chunk_pts : N;
     const float    res = (float)p.N_l[co.level];
 
-    uint32_t head = 0, tail = 0, pn = 0;                            // wavefront-uniform ring state
+    // wavefront-uniform ring state: [head, mid) in flight, [mid, tail) waiting; head, mid multiples of kBatch
+    uint32_t head = 0, mid = 0, tail = 0;
     T        inflight[U];
-    // Both loops run a wavefront-uniform number of full instructions; in the last, partial one the
-    // surplus lanes re-read the newest reference and add zero.
-    auto issue = [&]() {                                            // start the gathers of the oldest references
-        const uint32_t have = tail - head;
-        pn = have < (uint32_t)(U * EPI) ? have : (uint32_t)(U * EPI);
+    auto issue = [&]() {                                            // gathers of the batch at mid
+        const uint32_t base = (mid & (kRing - 1)) + sub;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if ((uint32_t)(u * EPI) < pn) {
-                const uint32_t e = u * EPI + sub;
-                inflight[u] = load(ring_key[(head + (e < pn ? e : pn - 1)) & (kRing - 1)]);
-            }
-        }
+        for (int u = 0; u < U; ++u)
+            if (slot_ok) inflight[u] = load(ring_key[base + u * EPI]);
+        mid += kBatch;
     };
-    auto complete = [&]() {                                         // accumulate what `issue` started
+    auto complete = [&]() {                                         // accumulate the batch at head
+        const uint32_t base = (head & (kRing - 1)) + sub;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if ((uint32_t)(u * EPI) < pn) {
-                const uint32_t e = u * EPI + sub;
-                const uint32_t i = (head + (e < pn ? e : pn - 1)) & (kRing - 1);
-                float2 g = ring_g[i];
-                if (e >= pn) g = make_float2(0.f, 0.f);
-                accum(ring_key[i], g, inflight[u]);
-            }
-        }
-        head += pn;
-        pn = 0;
+        for (int u = 0; u < U; ++u)
+            if (slot_ok) accum(ring_key[base + u * EPI], ring_g[base + u * EPI], inflight[u]);
+        head += kBatch;
+    };
+    auto pump = [&]() {                                             // one pipeline beat
+        wave_lds_fence();
+        if (mid != head) complete();
+        if (tail - mid >= (uint32_t)kBatch) issue();
     };
 
     // software prefetch of the next step's point and upstream gradient
@@ -171,9 +183,9 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
             gn = more ? load_pair(dy_l, (size_t)n) : make_float2(0.f, 0.f);
         }
 
-        // cell of the point: fraction, lower vertex and the slice hash's terms per dimension
+        // cell of the point: fraction and the two hashes' terms per dimension
         float    w[D], w1[D];                                       // fraction and 1 - fraction
-        uint32_t a[D], b[D], ao[D], bo[D];                          // hash terms: slice hash, other hash
+        uint32_t a[D], b[D], ao[D], bo[D];                          // slice hash, other hash: lower / upper vertex
         {
 #pragma clang fp contract(off)
 #pragma unroll
@@ -191,52 +203,61 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
                 bo[i] = ao[i] + po;
             }
         }
-        uint32_t pending = 0;                                       // corners of this lane's point in the slice
+        uint32_t accepted = 0;                                      // corners of this lane's point in the slice
 #pragma unroll
         for (int c = 0; c < (1 << D); ++c) {
             uint32_t h = 0;
 #pragma unroll
             for (int i = 0; i < D; ++i) h ^= ((c >> i) & 1) ? b[i] : a[i];
-            if ((h & slice_sel) == slice_val) pending |= 1u << c;
+            if ((h & slice_sel) == slice_val) accepted |= 1u << c;
         }
-        if (!valid) pending = 0;
+        if (!valid) accepted = 0;
 
-        for (;;) {
-            const bool     take = pending != 0;
-            const uint64_t m = __ballot(take);
-            if (m == 0) break;
-            while (kRing - (tail - head) < 64u) {                   // a round may add up to 64 references
-                wave_lds_fence();
-                if (pn == 0) issue();
-                complete();
-            }
-            if (take) {
-                const int c = __ffs(pending) - 1;
-                pending &= pending - 1;
-                uint32_t h = 0, ho = 0;
-                float    wt = 1.0f;
-#pragma unroll
-                for (int i = 0; i < D; ++i) {
-                    const bool up = (c >> i) & 1;
-                    h ^= up ? b[i] : a[i];
-                    ho ^= up ? bo[i] : ao[i];
-                    wt *= up ? w[i] : w1[i];
+        constexpr uint32_t kHalf = (1u << ((1 << D) / 2)) - 1u;     // low half of the corners
+#pragma unroll 1
+        for (int phase = 0; phase < 2; ++phase) {
+            uint32_t pending = phase == 0 ? (accepted & kHalf) : (accepted & ~kHalf);
+            for (;;) {
+                const bool     take = pending != 0;
+                const uint64_t m = __ballot(take);
+                if (m == 0) break;
+                while (kRing - (tail - head) < 64u) {               // a round may add up to 64 references
+                    wave_lds_fence();
+                    if (mid == head) issue();                       // (then tail - mid >= kBatch)
+                    complete();
                 }
-                const uint32_t i = (tail + lanes_below(m)) & (kRing - 1);
-                ring_key[i] = (h & row_lo_mask) | ((ho & other_mask) << sp.rows_log2);
-                ring_g[i] = make_float2(wt * g.x, wt * g.y);
+                if (take) {
+                    const int c = __ffs(pending) - 1;
+                    pending &= pending - 1;
+                    uint32_t h = 0, ho = 0;
+                    float    wt = 1.0f;
+#pragma unroll
+                    for (int i = 0; i < D; ++i) {
+                        const bool up = (c >> i) & 1;
+                        h ^= up ? b[i] : a[i];
+                        ho ^= up ? bo[i] : ao[i];
+                        wt *= up ? w[i] : w1[i];
+                    }
+                    const uint32_t i = (tail + lanes_below(m)) & (kRing - 1);
+                    ring_key[i] = (h & row_lo_mask) | ((ho & other_mask) << sp.rows_log2);
+                    ring_g[i] = make_float2(wt * g.x, wt * g.y);
+                }
+                tail += (uint32_t)__popcll(m);
             }
-            tail += (uint32_t)__popcll(m);
+            pump();
         }
-        wave_lds_fence();
-        if (pn) complete();                                         // gathers issued one step ago
-        issue();                                                    // gathers for this step's references
     }
-    wave_lds_fence();
-    while (pn || tail != head) {
-        if (pn == 0) issue();
-        complete();
+    // drain: pad the last batch with references that add zero to row 0, then empty the pipeline
+    {
+        const uint32_t pad = (kBatch - (tail & (kBatch - 1))) & (kBatch - 1);
+        if ((uint32_t)lane < pad) {
+            const uint32_t i = (tail + lane) & (kRing - 1);
+            ring_key[i] = 0u;
+            ring_g[i] = make_float2(0.f, 0.f);
+        }
+        tail += pad;
     }
+    while (head != tail) pump();
 }
 
 // ------------------------------------------------------------------ feature gradient
@@ -263,14 +284,14 @@ __global__ __launch_bounds__(kSlicedBlock) void bwd_feat_sliced_kernel(
     const uint32_t k = (threadIdx.x & 63) % NP;
     const uint32_t row_lo_mask = rows - 1u, rows_log2 = sp.rows_log2;
     auto load = [&](const uint32_t key) -> float {
-        return NP == 1 ? 1.0f : sig_l[(size_t)(key >> rows_log2) * NP + k];
+        return NP == 1 ? 1.0f : sig_l[(key >> rows_log2) * NP + k];
     };
     auto accum = [&](const uint32_t key, const float2 g, const float s) {
         double *a = acc + (key & row_lo_mask) * NP + k;
         atomicAdd(a, (double)(s * g.x));
         atomicAdd(a + plane, (double)(s * g.y));
     };
-    scan_chunk<D, NP, true, 16, float>(p, sp, co, x, dyT + (size_t)l * N * 2, N, ring_mem, load, accum);
+    scan_chunk<D, NP, true, float>(p, sp, co, x, dyT + (size_t)l * N * 2, N, ring_mem, load, accum);
     __syncthreads();
 
     float *out = gD_f + (size_t)l * p.N_f * 2 + (size_t)co.slice * plane * 2;
@@ -301,13 +322,15 @@ __global__ __launch_bounds__(kSlicedBlock) void bwd_logit_sliced_kernel(
     const FeatT   *F_l = D_f + (size_t)l * p.N_f * 2;
     const uint32_t k = (threadIdx.x & 63) % NP;
     const uint32_t row_lo_mask = rows - 1u, rows_log2 = sp.rows_log2;
-    auto load = [&](const uint32_t key) -> float2 {
-        return load_pair(F_l, (size_t)(key >> rows_log2) * NP + k);
+    using Raw = typename RawPair<FeatT>::type;                // the entry as loaded; converted when it is used
+    auto load = [&](const uint32_t key) -> Raw {
+        return reinterpret_cast<const Raw *>(F_l)[(key >> rows_log2) * NP + k];
     };
-    auto accum = [&](const uint32_t key, const float2 g, const float2 feat) {
+    auto accum = [&](const uint32_t key, const float2 g, const Raw raw) {
+        const float2 feat = RawPair<FeatT>::to_float2(raw);
         atomicAdd(acc + (key & row_lo_mask) * NP + k, (double)fmaf(feat.x, g.x, feat.y * g.y));
     };
-    scan_chunk<D, NP, false, 8, float2>(p, sp, co, x, dyT + (size_t)l * N * 2, N, ring_mem, load, accum);
+    scan_chunk<D, NP, false, Raw>(p, sp, co, x, dyT + (size_t)l * N * 2, N, ring_mem, load, accum);
     __syncthreads();
 
     // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
