@@ -57,8 +57,10 @@ typedef enum { CNGP_IDX_U8 = 0, CNGP_IDX_PACKED4 = 1 } cngp_index_format;
 enum {
     CNGP_ZERO_GRADS = 1u,   /* cngp_encode_bwd clears both gradient arrays before accumulating            */
     CNGP_BWD_DIRECT = 2u,   /* force the backward variant that adds straight into HBM with global atomics  */
-    CNGP_BWD_SLICED = 4u    /* force the variant that accumulates table slices in LDS (needs workspace)   */
-};                          /* neither: the library picks by table size and N                              */
+    CNGP_BWD_SLICED = 4u,   /* force the variant that accumulates table slices in LDS (needs workspace)   */
+                            /* neither of the two: the library picks by table size and N                   */
+    CNGP_BWD_NO_PREREDUCE = 8u /* LDS variant only: do not pre-reduce coarse levels per grid vertex        */
+};
 
 /* Hyper-parameters of the encoding (Table 1 of the paper, same symbols). */
 typedef struct {

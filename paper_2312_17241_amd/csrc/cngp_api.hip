@@ -7,9 +7,12 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <type_traits>
 #include <string>
 #include <vector>
+#include <algorithm>
+#include <utility>
 
 namespace {
 
@@ -42,7 +45,7 @@ int validate(const cngp_config *c) {
     if (c->io_dtype != CNGP_F32 && c->io_dtype != CNGP_F16) return CNGP_ERR_INVALID;
     if (c->index_format != CNGP_IDX_U8 && c->index_format != CNGP_IDX_PACKED4) return CNGP_ERR_INVALID;
     if (c->index_format == CNGP_IDX_PACKED4 && c->N_c < 2) return CNGP_ERR_INVALID;
-    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED)) return CNGP_ERR_INVALID;
+    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE)) return CNGP_ERR_INVALID;
     if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & CNGP_BWD_SLICED)) return CNGP_ERR_INVALID;
     if (c->F != 2) return CNGP_ERR_UNSUPPORTED;
     return CNGP_OK;
@@ -73,10 +76,11 @@ Params make_params(const cngp_config *c) {
 int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INVALID : CNGP_OK; }
 
 // ---------------------------------------------------------------- per-kernel timing
-enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_FEAT, K_BWD_LOGIT, K_BAKE, K_ZERO, K_DEBUG, K_COUNT };
+enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_VERTEX_GRID, K_BWD_SLICED,
+                K_BAKE, K_ZERO, K_DEBUG, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_softmax_table",
-                                           "encode_bwd_transpose_dy", "encode_bwd_feat_sliced",
-                                           "encode_bwd_logit_sliced", "bake_probes", "zero", "debug_indices"};
+                                           "encode_bwd_transpose_dy", "encode_bwd_vertex_grid", "encode_bwd_sliced",
+                                           "bake_probes", "zero", "debug_indices"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -154,19 +158,104 @@ int launch_bwd_direct(const cngp_config *c, const Params &p, int level0, int nle
 // ---------------------------------------------------------------- backward plan
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// How one sliced kernel launch splits its items (points or grid vertices) into chunks.
+struct Geom { uint32_t chunks, chunk_items; };
+
 struct BwdPlan {
     bool     sliced;
     uint32_t rows_f_log2, slices_f;     // feature-gradient slices per level
     uint32_t rows_c_log2, slices_c;     // logit-gradient slices per level (0 when N_p == 1)
-    uint32_t chunks, chunk_pts;
+    Geom     feat_pts, logit_pts;       // hashed levels: chunks of points
+    Geom     feat_vtx, logit_vtx;       // dense levels: chunks of grid vertices
+    Geom     grid;                      // vertex-grid accumulation: chunks of points
     size_t   lds_f, lds_c;              // dynamic LDS bytes of the two kernels
-    size_t   sigma_off, dyT_off, ws_bytes;
+    size_t   sigma_off, dyT_off, G_off, ws_bytes;
+    DenseLevels dense;                  // levels pre-reduced per grid vertex (a prefix of the levels)
+    uint32_t dense_slices, dense_verts, dense_max_verts;
 };
 
 constexpr uint32_t kMaxSlicesPerLevel = 128;   // beyond this the replicated scan costs more than global atomics
 constexpr int64_t  kMinSlicedPoints = 2048;
+constexpr uint64_t kMaxDenseVerts = 32ull * kDenseSliceVerts;   // largest vertex grid that is pre-reduced
+constexpr int64_t  kMinRefsPerVertex = 4;      // below this reuse the vertex pass saves nothing
+constexpr int64_t  kCus = 256;
 
-BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
+// Chunk count that minimises (rounds of workgroups over the CUs) x (items per chunk + fixed cost per
+// workgroup, in items: clearing and flushing its LDS slice).  `groups` workgroups exist per chunk.
+Geom pick_chunks(int64_t items, int64_t groups, int64_t fixed, int64_t min_chunk) {
+    Geom best = {1, (uint32_t)((items + 63) / 64 * 64)};
+    int64_t best_cost = -1;
+    for (int64_t c = 1; c <= 64; ++c) {
+        int64_t chunk = ((items + c - 1) / c + 63) / 64 * 64;
+        if (chunk < 64) chunk = 64;
+        if (c > 1 && chunk < min_chunk) break;
+        const int64_t real = (items + chunk - 1) / chunk;                 // chunks that hold items
+        const int64_t rounds = (groups * real + kCus - 1) / kCus;
+        const int64_t cost = rounds * (chunk + fixed);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = {(uint32_t)real, (uint32_t)chunk}; }
+    }
+    if (best.chunks < 1) best.chunks = 1;
+    return best;
+}
+
+// Chunk counts of the four roles of the sliced kernel, by simulating its launch: workgroups are
+// handed out in grid order to the first free of 256 CUs; a workgroup costs a fixed part (clearing and
+// flushing its LDS slice, about 12000 scanned points' worth) plus its items times a per-item cost that
+// grows with the share of corners it keeps.  Measured on MI355X: fewer, longer workgroups win unless a
+// finer split fills the last round.
+double simulate_makespan(const std::vector<std::pair<int64_t, double>> &batches /* count, duration */) {
+    std::vector<double> cu(kCus, 0.0);                      // min-heap of CU free times
+    auto cmp = [](double a, double b) { return a > b; };
+    double end = 0.0;
+    for (const auto &bt : batches)
+        for (int64_t i = 0; i < bt.first; ++i) {
+            std::pop_heap(cu.begin(), cu.end(), cmp);
+            cu.back() += bt.second;
+            if (cu.back() > end) end = cu.back();
+            std::push_heap(cu.begin(), cu.end(), cmp);
+        }
+    return end;
+}
+
+Geom chunks_of(int64_t items, int64_t c) {
+    int64_t chunk = ((items + c - 1) / c + 63) / 64 * 64;
+    if (chunk < 64) chunk = 64;
+    return {(uint32_t)((items + chunk - 1) / chunk), (uint32_t)chunk};
+}
+
+void choose_geometry(const cngp_config *c, int64_t N, BwdPlan &b) {
+    const int    Ld = b.dense.count, Lh = c->L - Ld;
+    const double corners = (double)(1 << c->d);
+    const double fixed = 12000.0;
+    const double item_f = 1.0 + 2.0 * corners / b.slices_f;                      // per point, feature role
+    const double item_c = b.slices_c ? 1.0 + 1.5 * corners / b.slices_c : 0.0;   // per point, logit role
+    const double vtx_f = 0.6 + 2.0 / b.slices_f, vtx_c = b.slices_c ? 0.6 + 1.5 / b.slices_c : 0.0;
+    b.feat_vtx = b.logit_vtx = chunks_of(b.dense_max_verts ? b.dense_max_verts : 64, 1);
+    if (Ld > 0) {
+        b.grid = pick_chunks(N, b.dense_slices, 4096, 8192);
+        const int64_t cv = (b.dense_max_verts + 16383) / 16384;                  // vertex chunks of <= 16384
+        b.feat_vtx = b.logit_vtx = chunks_of(b.dense_max_verts, cv > 0 ? cv : 1);
+    }
+    double best = -1.0;
+    const int64_t cmax = N / 16384 > 1 ? (N / 16384 < 12 ? N / 16384 : 12) : 1;
+    for (int64_t cc = 1; cc <= (b.slices_c ? cmax : 1); ++cc)
+        for (int64_t cf = 1; cf <= cmax; ++cf) {
+            const Geom gc = chunks_of(N, cc), gf = chunks_of(N, cf);
+            std::vector<std::pair<int64_t, double>> batches;
+            if (Lh > 0 && b.slices_c)
+                batches.push_back({(int64_t)Lh * b.slices_c * gc.chunks, fixed + gc.chunk_items * item_c});
+            if (Lh > 0)
+                batches.push_back({(int64_t)Lh * b.slices_f * gf.chunks, fixed + gf.chunk_items * item_f});
+            if (Ld > 0 && b.slices_c)
+                batches.push_back({(int64_t)Ld * b.slices_c * b.logit_vtx.chunks, fixed + b.logit_vtx.chunk_items * vtx_c});
+            if (Ld > 0)
+                batches.push_back({(int64_t)Ld * b.slices_f * b.feat_vtx.chunks, fixed + b.feat_vtx.chunk_items * vtx_f});
+            const double t = simulate_makespan(batches);
+            if (best < 0.0 || t < best) { best = t; b.logit_pts = gc; b.feat_pts = gf; }
+        }
+}
+
+BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     BwdPlan b;
     std::memset(&b, 0, sizeof(b));
     const uint32_t groups = c->N_f / c->N_p;                               // hashed rows of D_f
@@ -187,17 +276,34 @@ BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
     if (c->flags & CNGP_BWD_DIRECT) b.sliced = false;
     if ((c->flags & CNGP_BWD_SLICED) && (uint64_t)per_level * 32u * 64u < 0x7fffffffull) b.sliced = true;
     if (!keys_fit) b.sliced = false;
-    // enough workgroups for three rounds over the 256 CUs, but chunks of at least 16384 points
-    int64_t chunks = (768 + (int64_t)per_level * c->L - 1) / ((int64_t)per_level * c->L);
-    const int64_t max_chunks = (N + 16383) / 16384;
-    if (chunks > max_chunks) chunks = max_chunks;
-    if (chunks < 1) chunks = 1;
-    int64_t chunk_pts = (N + chunks - 1) / chunks;
-    chunk_pts = (chunk_pts + 63) / 64 * 64;
-    if (chunk_pts < 64) chunk_pts = 64;
-    b.chunks = (uint32_t)((N + chunk_pts - 1) / chunk_pts);
-    if (b.chunks < 1) b.chunks = 1;
-    b.chunk_pts = (uint32_t)chunk_pts;
+    // coarse levels whose dense vertex grid is small, much smaller than the number of references, and
+    // takes clearly fewer slice scans than the level's hashed tables
+    if (b.sliced && !(c->flags & CNGP_BWD_NO_PREREDUCE)) {
+        uint32_t res[kMaxLevels];
+        level_table(c, res);
+        for (int l = 0; l < c->L && l < kMaxDense; ++l) {
+            uint64_t verts = 1;
+            for (int i = 0; i < c->d; ++i) verts *= (uint64_t)res[l] + 2;
+            const uint64_t slices = (verts + kDenseSliceVerts - 1) / kDenseSliceVerts;
+            if (verts > kMaxDenseVerts || (N << c->d) < kMinRefsPerVertex * (int64_t)verts) break;
+            if (slices * 3 > per_level && slices > 1) break;
+            b.dense.side[l] = res[l] + 2;
+            b.dense.verts[l] = (uint32_t)verts;
+            b.dense.slices[l] = (uint32_t)slices;
+            b.dense.g_off[l] = b.dense_verts;
+            b.dense_verts += (uint32_t)verts;
+            b.dense_slices += (uint32_t)slices;
+            if (verts > b.dense_max_verts) b.dense_max_verts = (uint32_t)verts;
+            b.dense.count = l + 1;
+        }
+    }
+    const int Ld = b.dense.count, Lh = c->L - Ld;
+    if (b.sliced) choose_geometry(c, N, b);
+#ifdef CNGP_EXPERIMENT
+    if (const char *e = getenv("CNGP_CHUNKS_F")) { int cn = atoi(e); int64_t ch = ((N + cn - 1) / cn + 63) / 64 * 64; b.feat_pts = {(uint32_t)((N + ch - 1) / ch), (uint32_t)ch}; }
+    if (const char *e = getenv("CNGP_CHUNKS_C")) { int cn = atoi(e); int64_t ch = ((N + cn - 1) / cn + 63) / 64 * 64; b.logit_pts = {(uint32_t)((N + ch - 1) / ch), (uint32_t)ch}; }
+    if (const char *e = getenv("CNGP_CHUNKS_G")) { int cn = atoi(e); int64_t ch = ((N + cn - 1) / cn + 63) / 64 * 64; b.grid = {(uint32_t)((N + ch - 1) / ch), (uint32_t)ch}; }
+#endif
     const size_t queues = (size_t)kSlicedWaves * kRingBytes;
     b.lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8 + queues;
     b.lds_c = ((size_t)1 << b.rows_c_log2) * c->N_p * 8 + queues;
@@ -205,9 +311,22 @@ BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
         const size_t io = c->io_dtype == CNGP_F16 ? 2 : 4;
         b.sigma_off = 0;
         b.dyT_off = align256((size_t)c->L * c->N_c * c->N_p * sizeof(float));
-        b.ws_bytes = b.dyT_off + align256((size_t)N * c->L * c->F * io);
+        b.G_off = b.dyT_off + align256((size_t)N * c->L * c->F * io);
+        b.ws_bytes = b.G_off + align256((size_t)b.dense_verts * 2 * sizeof(float));
     }
     return b;
+}
+
+// The plan depends on (configuration, N) only; the last one is kept (host memory, per thread).
+BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
+    thread_local cngp_config last_cfg;
+    thread_local int64_t     last_N = -1;
+    thread_local BwdPlan     last_plan;
+    if (last_N == N && std::memcmp(&last_cfg, c, sizeof(*c)) == 0) return last_plan;
+    last_plan = make_bwd_plan_uncached(c, N);
+    last_cfg = *c;
+    last_N = N;
+    return last_plan;
 }
 
 template <int NP>
@@ -247,29 +366,53 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
     using PairT = typename std::conditional<sizeof(IoT) == 2, uint32_t, float2>::type;
     if (int rc = launch_transpose_dy<PairT>(c, dy, dyT, N, s)) return rc;
 
-    SliceParams sp;
-    sp.chunks = b.chunks;
-    sp.chunk_pts = b.chunk_pts;
-    const unsigned levels_padded = (unsigned)((c->L + kXcds - 1) / kXcds * kXcds);
-    sp.store_direct = (b.chunks == 1 && (c->flags & CNGP_ZERO_GRADS)) ? 1 : 0;
-    {
-        sp.rows_log2 = b.rows_f_log2;
-        sp.slices = b.slices_f;
-        auto kernel = bwd_feat_sliced_kernel<D, NP, IoT>;
-        if (int rc = allow_big_lds(kernel, b.lds_f)) return rc;
-        LaunchTimer t(s, K_BWD_FEAT);
-        kernel<<<levels_padded * b.slices_f * b.chunks, kSlicedBlock, b.lds_f, s>>>(p, sp, x, sigma, dyT, gD_f, N);
-        if (int rc = launch_status("bwd_feat_sliced_kernel")) return rc;
+    // per-vertex sums of weight * dL/dy on the dense levels
+    float *G = reinterpret_cast<float *>((char *)workspace + b.G_off);
+    const int Ld = b.dense.count, Lh = c->L - Ld;
+    if (Ld > 0) {
+        const int direct = b.grid.chunks == 1;
+        if (!direct)
+            if (int rc = launch_zero(G, (int64_t)b.dense_verts * 2, s)) return rc;
+        auto kernel = bwd_vertex_grid_kernel<D, IoT>;
+        const size_t lds = (size_t)kDenseSliceVerts * 2 * sizeof(double);
+        if (int rc = allow_big_lds(kernel, lds)) return rc;
+        LaunchTimer t(s, K_BWD_VERTEX_GRID);
+        kernel<<<b.dense_slices * b.grid.chunks, kSlicedBlock, lds, s>>>(p, b.dense, b.grid.chunks, b.grid.chunk_items,
+                                                                        direct, x, dyT, G, N);
+        if (int rc = launch_status("bwd_vertex_grid_kernel")) return rc;
     }
-    if (NP > 1) {
-        sp.rows_log2 = b.rows_c_log2;
-        sp.slices = b.slices_c;
-        auto kernel = bwd_logit_sliced_kernel<D, NP, FeatT, IoT>;
-        if (int rc = allow_big_lds(kernel, b.lds_c)) return rc;
-        LaunchTimer t(s, K_BWD_LOGIT);
-        kernel<<<levels_padded * b.slices_c * b.chunks, kSlicedBlock, b.lds_c, s>>>(
-            p, sp, x, (const FeatT *)D_f, sigma, dyT, gDhat_c, N);
-        if (int rc = launch_status("bwd_logit_sliced_kernel")) return rc;
+
+    // feature and logit gradients: hashed levels scan the points, dense levels scan their vertex grid
+    const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
+    BwdRoles roles;
+    std::memset(&roles, 0, sizeof(roles));
+    uint32_t next = 0;
+    auto add_role = [&](int role, bool present, const Geom &g, uint32_t rows_log2, uint32_t slices, int level0,
+                        int nlevels) {
+        SliceParams &sp = roles.sp[role];
+        sp.rows_log2 = rows_log2;
+        sp.slices = slices ? slices : 1;
+        sp.chunks = g.chunks ? g.chunks : 1;
+        sp.chunk_pts = g.chunk_items;
+        sp.store_direct = (g.chunks == 1 && zero_first) ? 1 : 0;     // matches the clearing in cngp_encode_bwd
+        sp.level0 = level0;
+        sp.nlevels = present ? nlevels : 0;
+        roles.first[role] = next;
+        if (present && nlevels > 0)      // 8 equal runs of (level, slice, chunk) units, one per XCD
+            next += (uint32_t)kXcds * (((uint32_t)nlevels * sp.slices * sp.chunks + kXcds - 1) / kXcds);
+    };
+    add_role(ROLE_LOGIT_PTS, NP > 1, b.logit_pts, b.rows_c_log2, b.slices_c, Ld, Lh);
+    add_role(ROLE_FEAT_PTS, true, b.feat_pts, b.rows_f_log2, b.slices_f, Ld, Lh);
+    add_role(ROLE_LOGIT_VTX, NP > 1, b.logit_vtx, b.rows_c_log2, b.slices_c, 0, Ld);
+    add_role(ROLE_FEAT_VTX, true, b.feat_vtx, b.rows_f_log2, b.slices_f, 0, Ld);
+    roles.first[ROLE_COUNT] = next;
+    {
+        auto kernel = bwd_sliced_kernel<D, NP, FeatT, IoT>;
+        const size_t lds = b.lds_f > b.lds_c ? b.lds_f : b.lds_c;
+        if (int rc = allow_big_lds(kernel, lds)) return rc;
+        LaunchTimer t(s, K_BWD_SLICED);
+        kernel<<<next, kSlicedBlock, lds, s>>>(p, roles, b.dense, x, (const FeatT *)D_f, sigma, dyT, G, gD_f, gDhat_c, N);
+        if (int rc = launch_status("bwd_sliced_kernel")) return rc;
     }
     return CNGP_OK;
 }
@@ -361,13 +504,21 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     if (N > 0 && b.sliced) {
         if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < b.ws_bytes) return CNGP_ERR_WORKSPACE;
     }
-    // the sliced path with a single chunk writes every gradient entry itself
-    const bool sliced_stores = N > 0 && b.sliced && b.chunks == 1;
+    // A sliced launch with a single chunk writes every gradient entry of its levels itself; the other
+    // level ranges (dense levels 0 .. Ld-1, hashed levels Ld .. L-1) are cleared here.
     if (cfg->flags & CNGP_ZERO_GRADS) {
-        if (!sliced_stores)
-            if (int rc = launch_zero(grad_D_f, (int64_t)cfg->L * cfg->N_f * cfg->F, s)) return rc;
-        if (!sliced_stores || cfg->N_p == 1)
-            if (int rc = launch_zero(grad_Dhat_c, (int64_t)cfg->L * cfg->N_c * cfg->N_p, s)) return rc;
+        const int64_t per_f = (int64_t)cfg->N_f * cfg->F, per_c = (int64_t)cfg->N_c * cfg->N_p;
+        const bool    sl = N > 0 && b.sliced;
+        const int     Ld = sl ? b.dense.count : 0, Lh = cfg->L - Ld;
+        if (!(sl && b.feat_vtx.chunks == 1) && Ld > 0)
+            if (int rc = launch_zero(grad_D_f, per_f * Ld, s)) return rc;
+        if (!(sl && b.feat_pts.chunks == 1) && Lh > 0)
+            if (int rc = launch_zero(grad_D_f + per_f * Ld, per_f * Lh, s)) return rc;
+        const bool logit = sl && cfg->N_p > 1;
+        if (!(logit && b.logit_vtx.chunks == 1) && Ld > 0)
+            if (int rc = launch_zero(grad_Dhat_c, per_c * Ld, s)) return rc;
+        if (!(logit && b.logit_pts.chunks == 1) && Lh > 0)
+            if (int rc = launch_zero(grad_Dhat_c + per_c * Ld, per_c * Lh, s)) return rc;
     }
     if (N == 0) return CNGP_OK;
     const Params p = make_params(cfg);

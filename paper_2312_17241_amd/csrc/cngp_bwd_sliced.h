@@ -9,13 +9,21 @@
 // references that hash into its slice, accumulates them with LDS atomics and writes the slice
 // to HBM once.  Scanning is replicated per slice (hashing is cheap, atomics are not).
 //
-// Two kernels share the structure:
+// Two roles of one kernel share the structure:
 //   feature gradient  grad_D_f[base + k][f] += sigma_k * g[f]              slice = range of hashed rows
 //   logit gradient    Q[h2][k] += <D_f[base + k], g>, then per row          slice = range of D^_c rows
 //                     grad_Dhat_c[h2][k] += sigma_k * (Q_k - sum_j sigma_j Q_j)
 // (the softmax Jacobian is linear in Q, so it is applied once per row when the slice is flushed).
 // Both read a softmax table sigma = softmax(D^_c) and a level-major copy of dL/dy that two
 // small kernels prepare in the workspace.
+//
+// Coarse levels are pre-reduced per grid vertex.  The backward pass is linear in g = weight * dL/dy
+// of a corner reference, and both hashes depend on the vertex only, so all references to one vertex
+// can be summed first: a third kernel accumulates G[v] = sum of g over the references to vertex v
+// into the level's dense vertex grid (LDS slices again, no hashing), and the two kernels above then
+// scan the grid's vertices (one "corner" of weight 1 with g = G[v]) instead of the points.  A level
+// with few vertices and many points (2M references onto 5832 vertices on the coarsest NeRF level)
+// costs almost nothing this way.
 #pragma once
 #include "cngp_kernels.h"
 #include <type_traits>
@@ -34,21 +42,42 @@ struct SliceParams {
     uint32_t chunks;        // point chunks per slice
     uint32_t chunk_pts;     // points per chunk
     int32_t  store_direct;  // 1: every slice is written by exactly one workgroup -> plain stores
+    int32_t  level0;        // levels [level0, level0 + nlevels) are covered by this launch
+    int32_t  nlevels;
 };
 
-// Which (level, slice, chunk) a workgroup of the 1-D grid works on.  Workgroups are handed to the
-// 8 XCDs round-robin by their linear index, and every XCD has an L2 of its own; the mapping keeps
-// all workgroups of one level on one XCD (level l on XCD l mod 8, levels in ascending order), so the
-// rows a level gathers at random (its softmax table, its slice of D_f) stay in that one L2 instead
-// of all levels' tables competing for every L2.
+// Levels whose dense vertex grid is small enough to pre-reduce the upstream gradient per vertex.
+// They are the first `count` levels; a grid has side = N_l + 2 vertices per axis (x = 1 reaches
+// vertex N_l + 1).
+constexpr int      kMaxDense = 16;
+constexpr uint32_t kDenseSliceVerts = 8192;          // vertices per LDS slice (2 fp64 accumulators each)
+struct DenseLevels {
+    int32_t  count;
+    uint32_t side[kMaxDense];
+    uint32_t verts[kMaxDense];                       // side^d
+    uint32_t slices[kMaxDense];                      // ceil(verts / kDenseSliceVerts)
+    uint32_t g_off[kMaxDense];                       // offset of the level's grid in G, in vertices
+};
+
+// Which (level, slice, chunk) a workgroup works on.  Workgroups are handed to the 8 XCDs round-robin
+// by their linear index, and every XCD has an L2 of its own.  The (level, slice, chunk) units of a
+// role, numbered level-major, are cut into 8 equal contiguous runs, one per XCD: the workgroups of a
+// level then sit on one XCD (two where a run boundary falls inside the level), so the rows a level
+// gathers at random (its softmax table, its slice of D_f) stay in that L2 instead of all levels'
+// tables competing for every L2, and every XCD gets the same amount of work.  `i` is the workgroup's
+// index within its role; every role starts at a multiple of 8 in the grid, so i mod 8 is the XCD.
 constexpr int kXcds = 8;
-struct SliceCoord { int level; uint32_t slice, chunk; };
-__device__ __forceinline__ SliceCoord slice_coord(const SliceParams &sp) {
-    const uint32_t i = blockIdx.x, xcd = i % kXcds, j = i / kXcds;
+struct SliceCoord { int level, index; uint32_t slice, chunk; };   // index = level - level0; index < 0: no work
+__device__ __forceinline__ SliceCoord slice_coord(const SliceParams &sp, const uint32_t i) {
+    const uint32_t xcd = i % kXcds, j = i / kXcds;
     const uint32_t per_level = sp.slices * sp.chunks;
-    const uint32_t rem = j % per_level;
+    const uint32_t total = per_level * (uint32_t)sp.nlevels;
+    const uint32_t per_xcd = (total + kXcds - 1) / kXcds;
+    const uint32_t unit = xcd * per_xcd + j;
     SliceCoord c;
-    c.level = (int)((j / per_level) * kXcds + xcd);
+    const uint32_t rem = unit % per_level;
+    c.index = (j < per_xcd && unit < total) ? (int)(unit / per_level) : -1;
+    c.level = sp.level0 + c.index;
     c.slice = rem / sp.chunks;
     c.chunk = rem % sp.chunks;
     return c;
@@ -115,10 +144,14 @@ __global__ __launch_bounds__(kBlock) void transpose_dy_kernel(const PairT *__res
 constexpr int kBatch = 32;
 static_assert(kRing % kBatch == 0 && kRing >= 64 + 2 * kBatch, "ring holds a round, a batch in flight and slack");
 
-template <int D, int NP, bool BY_FEATURE_ROW, typename T, typename IoT, typename Load, typename Accum>
+//
+// VERTEX mode (pre-reduced coarse levels): the "points" are the n_items vertices of the level's dense
+// grid, g_l holds their summed gradient G[v], and each has exactly one corner of weight 1: itself.
+template <int D, int NP, bool BY_FEATURE_ROW, bool VERTEX, typename T, typename GradT, typename Load, typename Accum>
 __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &sp, const SliceCoord &co,
-                                           const float *__restrict__ x, const IoT *__restrict__ dy_l,
-                                           const int64_t N, unsigned char *ring_mem, Load load, Accum accum)
+                                           const float *__restrict__ x, const GradT *__restrict__ g_l,
+                                           const int64_t n_items, const uint32_t side,
+                                           unsigned char *ring_mem, Load load, Accum accum)
 {
     constexpr int  EPI = (64 / NP < kBatch) ? 64 / NP : kBatch;     // references per wavefront instruction
     constexpr int  U = kBatch / EPI;                                // instructions per batch
@@ -133,7 +166,7 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
     const uint32_t slice_sel   = mine_mask & ~row_lo_mask;          // bits of the hash that name the slice
     const uint32_t slice_val   = co.slice << sp.rows_log2;
     const int64_t  n0 = (int64_t)co.chunk * sp.chunk_pts;
-    const int64_t  n1 = (n0 + sp.chunk_pts < N) ? n0 + sp.chunk_pts : N;
+    const int64_t  n1 = (n0 + sp.chunk_pts >= n_items) ? n_items : n0 + sp.chunk_pts;
     const float    res = (float)p.N_l[co.level];
 
     // wavefront-uniform ring state: [head, mid) in flight, [mid, tail) waiting; head, mid multiples of kBatch
@@ -159,34 +192,48 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
         if (tail - mid >= (uint32_t)kBatch) issue();
     };
 
-    // software prefetch of the next step's point and upstream gradient
-    float   xn[D];
-    float2  gn = make_float2(0.f, 0.f);
-    int64_t nb = n0 + wave * 64;
-    {
-        const int64_t n = nb + lane;
+    // software prefetch of the next step's point (or vertex) and its upstream gradient
+    auto fetch = [&](const int64_t n, float (&xo)[D], float2 &go) {
+        const bool ok = n < n1;
+        if (!VERTEX) {
 #pragma unroll
-        for (int j = 0; j < D; ++j) xn[j] = n < n1 ? x[n * D + j] : 0.0f;
-        if (n < n1) gn = load_pair(dy_l, (size_t)n);
-    }
+            for (int j = 0; j < D; ++j) xo[j] = ok ? x[n * D + j] : 0.0f;
+        }
+        go = ok ? load_pair(g_l, (size_t)n) : make_float2(0.f, 0.f);
+    };
+    float   xn[D] = {};
+    float2  gn;
+    int64_t nb = n0 + wave * 64;
+    fetch(nb + lane, xn, gn);
     for (; nb < n1; nb += kSlicedBlock) {
         const bool valid = nb + lane < n1;
         float xp[D];
 #pragma unroll
         for (int j = 0; j < D; ++j) xp[j] = xn[j];
         const float2 g = gn;
-        {
-            const int64_t n = nb + kSlicedBlock + lane;
-            const bool    more = n < n1;
-#pragma unroll
-            for (int j = 0; j < D; ++j) xn[j] = more ? x[n * D + j] : 0.0f;
-            gn = more ? load_pair(dy_l, (size_t)n) : make_float2(0.f, 0.f);
-        }
+        fetch(nb + kSlicedBlock + lane, xn, gn);
 
-        // cell of the point: fraction and the two hashes' terms per dimension
         float    w[D], w1[D];                                       // fraction and 1 - fraction
         uint32_t a[D], b[D], ao[D], bo[D];                          // slice hash, other hash: lower / upper vertex
-        {
+        uint32_t accepted = 0;                                      // corners of this lane's item in the slice
+        if (VERTEX) {
+            // grid coordinates of vertex number nb + lane; its only corner is itself, weight 1
+            uint32_t rest = (uint32_t)(nb + lane);
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                const uint32_t v = (i == D - 1) ? rest : rest % side;
+                rest /= side;
+                a[i] = b[i] = v * (BY_FEATURE_ROW ? kPi[i] : kPi2[i]);
+                ao[i] = bo[i] = v * (BY_FEATURE_ROW ? kPi2[i] : kPi[i]);
+                w[i] = 0.0f;
+                w1[i] = 1.0f;
+            }
+            uint32_t h = 0;
+#pragma unroll
+            for (int i = 0; i < D; ++i) h ^= a[i];
+            if (valid && (g.x != 0.0f || g.y != 0.0f) && (h & slice_sel) == slice_val) accepted = 1u;
+        } else {
+            // cell of the point: fraction and the two hashes' terms per dimension
 #pragma clang fp contract(off)
 #pragma unroll
             for (int i = 0; i < D; ++i) {
@@ -202,21 +249,20 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
                 ao[i] = v0 * po;
                 bo[i] = ao[i] + po;
             }
-        }
-        uint32_t accepted = 0;                                      // corners of this lane's point in the slice
 #pragma unroll
-        for (int c = 0; c < (1 << D); ++c) {
-            uint32_t h = 0;
+            for (int c = 0; c < (1 << D); ++c) {
+                uint32_t h = 0;
 #pragma unroll
-            for (int i = 0; i < D; ++i) h ^= ((c >> i) & 1) ? b[i] : a[i];
-            if ((h & slice_sel) == slice_val) accepted |= 1u << c;
+                for (int i = 0; i < D; ++i) h ^= ((c >> i) & 1) ? b[i] : a[i];
+                if ((h & slice_sel) == slice_val) accepted |= 1u << c;
+            }
+            if (!valid) accepted = 0;
         }
-        if (!valid) accepted = 0;
 
         constexpr uint32_t kHalf = (1u << ((1 << D) / 2)) - 1u;     // low half of the corners
 #pragma unroll 1
-        for (int phase = 0; phase < 2; ++phase) {
-            uint32_t pending = phase == 0 ? (accepted & kHalf) : (accepted & ~kHalf);
+        for (int phase = 0; phase < (VERTEX ? 1 : 2); ++phase) {
+            uint32_t pending = VERTEX ? accepted : phase == 0 ? (accepted & kHalf) : (accepted & ~kHalf);
             for (;;) {
                 const bool     take = pending != 0;
                 const uint64_t m = __ballot(take);
@@ -263,19 +309,19 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
 // ------------------------------------------------------------------ feature gradient
 // Accumulators: two planes (f = 0, 1) of rows * NP doubles, so that the NP lanes of a reference
 // add to NP consecutive doubles.
-template <int D, int NP, typename IoT>
-__global__ __launch_bounds__(kSlicedBlock) void bwd_feat_sliced_kernel(
-    const Params p, const SliceParams sp, const float *__restrict__ x, const float *__restrict__ sigma,
-    const IoT *__restrict__ dyT, float *__restrict__ gD_f, const int64_t N)
+template <int D, int NP, bool VERTEX, typename GradT>
+__device__ __forceinline__ void bwd_feat_sliced(
+    const Params &p, const SliceParams &sp, const DenseLevels &dl, const uint32_t wg, unsigned char *smem,
+    const float *__restrict__ x, const float *__restrict__ sigma, const GradT *__restrict__ grad,
+    float *__restrict__ gD_f, const int64_t N)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t rows = 1u << sp.rows_log2;
     const uint32_t plane = rows * NP;
     double *acc = reinterpret_cast<double *>(smem);
     unsigned char *ring_mem = smem + (size_t)plane * 2 * sizeof(double);
-    const SliceCoord co = slice_coord(sp);
+    const SliceCoord co = slice_coord(sp, wg);
     const int l = co.level;
-    if (l >= p.L) return;                                     // padding of the level count to a multiple of 8
+    if (co.index < 0) return;                                 // padding of the role's grid to 8 equal runs
 
     for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) acc[i] = 0.0;
     __syncthreads();
@@ -291,7 +337,11 @@ __global__ __launch_bounds__(kSlicedBlock) void bwd_feat_sliced_kernel(
         atomicAdd(a, (double)(s * g.x));
         atomicAdd(a + plane, (double)(s * g.y));
     };
-    scan_chunk<D, NP, true, float>(p, sp, co, x, dyT + (size_t)l * N * 2, N, ring_mem, load, accum);
+    if (VERTEX)   // grad = G: summed gradient per vertex of the dense levels' grids
+        scan_chunk<D, NP, true, true, float>(p, sp, co, x, grad + (size_t)dl.g_off[co.index] * 2,
+                                             (int64_t)dl.verts[co.index], dl.side[co.index], ring_mem, load, accum);
+    else          // grad = level-major dL/dy
+        scan_chunk<D, NP, true, false, float>(p, sp, co, x, grad + (size_t)l * N * 2, N, 0u, ring_mem, load, accum);
     __syncthreads();
 
     float *out = gD_f + (size_t)l * p.N_f * 2 + (size_t)co.slice * plane * 2;
@@ -303,18 +353,18 @@ __global__ __launch_bounds__(kSlicedBlock) void bwd_feat_sliced_kernel(
 }
 
 // ------------------------------------------------------------------ logit gradient
-template <int D, int NP, typename FeatT, typename IoT>
-__global__ __launch_bounds__(kSlicedBlock) void bwd_logit_sliced_kernel(
-    const Params p, const SliceParams sp, const float *__restrict__ x, const FeatT *__restrict__ D_f,
-    const float *__restrict__ sigma, const IoT *__restrict__ dyT, float *__restrict__ gDhat_c, const int64_t N)
+template <int D, int NP, bool VERTEX, typename FeatT, typename GradT>
+__device__ __forceinline__ void bwd_logit_sliced(
+    const Params &p, const SliceParams &sp, const DenseLevels &dl, const uint32_t wg, unsigned char *smem,
+    const float *__restrict__ x, const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
+    const GradT *__restrict__ grad, float *__restrict__ gDhat_c, const int64_t N)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t rows = 1u << sp.rows_log2;
     double *acc = reinterpret_cast<double *>(smem);
     unsigned char *ring_mem = smem + (size_t)rows * NP * sizeof(double);
-    const SliceCoord co = slice_coord(sp);
+    const SliceCoord co = slice_coord(sp, wg);
     const int l = co.level;
-    if (l >= p.L) return;
+    if (co.index < 0) return;
 
     for (uint32_t i = threadIdx.x; i < rows * NP; i += kSlicedBlock) acc[i] = 0.0;
     __syncthreads();
@@ -330,7 +380,11 @@ __global__ __launch_bounds__(kSlicedBlock) void bwd_logit_sliced_kernel(
         const float2 feat = RawPair<FeatT>::to_float2(raw);
         atomicAdd(acc + (key & row_lo_mask) * NP + k, (double)fmaf(feat.x, g.x, feat.y * g.y));
     };
-    scan_chunk<D, NP, false, Raw>(p, sp, co, x, dyT + (size_t)l * N * 2, N, ring_mem, load, accum);
+    if (VERTEX)
+        scan_chunk<D, NP, false, true, Raw>(p, sp, co, x, grad + (size_t)dl.g_off[co.index] * 2,
+                                            (int64_t)dl.verts[co.index], dl.side[co.index], ring_mem, load, accum);
+    else
+        scan_chunk<D, NP, false, false, Raw>(p, sp, co, x, grad + (size_t)l * N * 2, N, 0u, ring_mem, load, accum);
     __syncthreads();
 
     // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
@@ -345,6 +399,110 @@ __global__ __launch_bounds__(kSlicedBlock) void bwd_logit_sliced_kernel(
         for (int o = NP / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, NP);
         const float v = (float)(s * (Q - dot));
         if (sp.store_direct) out[i] = v;
+        else if (v != 0.0f) atomic_add(out + i, v);
+    }
+}
+
+// ------------------------------------------------------------------ one launch for all four roles
+// The grid lists, in this order, the workgroups of: logit gradient over points, feature gradient over
+// points (hashed levels), logit gradient over vertices, feature gradient over vertices (dense levels).
+// One launch instead of four keeps all CUs busy across the roles' different run times.
+enum { ROLE_LOGIT_PTS = 0, ROLE_FEAT_PTS, ROLE_LOGIT_VTX, ROLE_FEAT_VTX, ROLE_COUNT };
+struct BwdRoles {
+    uint32_t    first[ROLE_COUNT + 1];      // first workgroup of each role (multiples of 8); [ROLE_COUNT] = grid size
+    SliceParams sp[ROLE_COUNT];
+};
+
+template <int D, int NP, typename FeatT, typename IoT>
+__global__ __launch_bounds__(kSlicedBlock) void bwd_sliced_kernel(
+    const Params p, const BwdRoles roles, const DenseLevels dl, const float *__restrict__ x,
+    const FeatT *__restrict__ D_f, const float *__restrict__ sigma, const IoT *__restrict__ dyT,
+    const float *__restrict__ G, float *__restrict__ gD_f, float *__restrict__ gDhat_c, const int64_t N)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const uint32_t wg = blockIdx.x;
+    if (wg < roles.first[ROLE_FEAT_PTS]) {
+        if (NP > 1)
+            bwd_logit_sliced<D, NP, false, FeatT, IoT>(p, roles.sp[ROLE_LOGIT_PTS], dl, wg - roles.first[ROLE_LOGIT_PTS],
+                                                       smem, x, D_f, sigma, dyT, gDhat_c, N);
+    } else if (wg < roles.first[ROLE_LOGIT_VTX]) {
+        bwd_feat_sliced<D, NP, false, IoT>(p, roles.sp[ROLE_FEAT_PTS], dl, wg - roles.first[ROLE_FEAT_PTS], smem, x,
+                                           sigma, dyT, gD_f, N);
+    } else if (wg < roles.first[ROLE_FEAT_VTX]) {
+        if (NP > 1)
+            bwd_logit_sliced<D, NP, true, FeatT, float>(p, roles.sp[ROLE_LOGIT_VTX], dl, wg - roles.first[ROLE_LOGIT_VTX],
+                                                        smem, x, D_f, sigma, G, gDhat_c, N);
+    } else {
+        bwd_feat_sliced<D, NP, true, float>(p, roles.sp[ROLE_FEAT_VTX], dl, wg - roles.first[ROLE_FEAT_VTX], smem, x,
+                                            sigma, G, gD_f, N);
+    }
+}
+
+// ------------------------------------------------------------------ per-vertex pre-reduction
+// G[l][v][f] = sum over the corner references to vertex v of level l of weight * dL/dy[n, l, f], for the
+// dense levels.  A workgroup owns kDenseSliceVerts consecutive vertices (row-major: dimension 0 fastest)
+// of one level as fp64 accumulators in LDS and scans a chunk of the points; no hashing is involved.
+template <int D, typename IoT>
+__global__ __launch_bounds__(kSlicedBlock) void bwd_vertex_grid_kernel(
+    const Params p, const DenseLevels dl, const uint32_t chunks, const uint32_t chunk_pts, const int store_direct,
+    const float *__restrict__ x, const IoT *__restrict__ dyT, float *__restrict__ G, const int64_t N)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *acc = reinterpret_cast<double *>(smem);
+    uint32_t wg = blockIdx.x;
+    int l = 0;
+    while (l < dl.count - 1 && wg >= dl.slices[l] * chunks) { wg -= dl.slices[l] * chunks; ++l; }
+    const uint32_t slice = wg / chunks, chunk = wg % chunks;
+    const uint32_t side = dl.side[l];
+    const uint32_t first = slice * kDenseSliceVerts;
+    const uint32_t count = dl.verts[l] - first < kDenseSliceVerts ? dl.verts[l] - first : kDenseSliceVerts;
+
+    for (uint32_t i = threadIdx.x; i < count * 2; i += kSlicedBlock) acc[i] = 0.0;
+    __syncthreads();
+
+    const int64_t n0 = (int64_t)chunk * chunk_pts;
+    const int64_t n1 = (n0 + chunk_pts < N) ? n0 + chunk_pts : N;
+    const float   res = (float)p.N_l[l];
+    const IoT    *dy_l = dyT + (size_t)l * N * 2;
+    for (int64_t n = n0 + threadIdx.x; n < n1; n += kSlicedBlock) {
+        float    w[D];
+        uint32_t base = 0, stride = 1, step[D];
+        {
+#pragma clang fp contract(off)
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                const float pos = x[n * D + i] * res;               // one rounded fp32 multiply
+                const float fl = floorf(pos);
+                w[i] = pos - fl;
+                base += (uint32_t)fl * stride;
+                step[i] = stride;
+                stride *= side;
+            }
+        }
+        const float2 g = load_pair(dy_l, (size_t)n);
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) {
+            uint32_t v = base;
+            float    wt = 1.0f;
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                const bool up = (c >> i) & 1;
+                v += up ? step[i] : 0u;
+                wt *= up ? w[i] : 1.0f - w[i];
+            }
+            const uint32_t rel = v - first;
+            if (rel < count) {                                      // unsigned: also rejects v < first
+                atomicAdd(acc + 2 * rel, (double)(wt * g.x));
+                atomicAdd(acc + 2 * rel + 1, (double)(wt * g.y));
+            }
+        }
+    }
+    __syncthreads();
+
+    float *out = G + ((size_t)dl.g_off[l] + first) * 2;
+    for (uint32_t i = threadIdx.x; i < count * 2; i += kSlicedBlock) {
+        const float v = (float)acc[i];
+        if (store_direct) out[i] = v;
         else if (v != 0.0f) atomic_add(out + i, v);
     }
 }

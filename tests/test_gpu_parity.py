@@ -54,11 +54,12 @@ def check_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8, name=""):
     return check_close(f"y {name}", y, y_ref, ymag, fp16_out=(w.io_dtype == "f16"))
 
 
-# the three ways the library can run the backward pass: its own choice, and each variant forced
-BWD_PATHS = {"auto": 0, "direct": cngp.BWD_DIRECT, "sliced": cngp.BWD_SLICED}
+# the ways the library can run the backward pass: its own choice, and each variant forced
+BWD_PATHS = {"auto": 0, "direct": cngp.BWD_DIRECT, "sliced": cngp.BWD_SLICED,
+             "sliced_nopre": cngp.BWD_SLICED | cngp.BWD_NO_PREREDUCE}
 
 
-def check_bwd(w, x, D_f, Dhat, dy, name="", paths=("auto", "direct", "sliced")):
+def check_bwd(w, x, D_f, Dhat, dy, name="", paths=("auto", "direct", "sliced", "sliced_nopre")):
     gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
     worst = (0.0, 0.0)
     for path in paths:
@@ -175,7 +176,7 @@ def test_backward_parity_sweep(d, N_p, feat, io):
     check_bwd(w, x, D_f, Dhat, dy)
 
 
-@pytest.mark.parametrize("path", ["direct", "sliced"])
+@pytest.mark.parametrize("path", ["direct", "sliced", "sliced_nopre"])
 def test_backward_accumulates_without_zero_flag(path):
     w = sweep_workload(3, 4, "f32", "f32", N=500)
     x, D_f, Dhat, dy = tables(w)
@@ -191,7 +192,18 @@ def test_sliced_backward_many_chunks_and_slices():
                  feat_dtype="f16", io_dtype="f16")
     x, D_f, Dhat, dy = tables(w)
     D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
-    check_bwd(w, x, D_f, Dhat, dy, paths=("sliced", "auto"))
+    check_bwd(w, x, D_f, Dhat, dy, paths=("sliced", "sliced_nopre", "auto"))
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_sliced_backward_vertex_grids_of_several_slices(d):
+    """Coarse levels whose dense vertex grid spans several LDS slices, next to hashed fine levels."""
+    w = W.custom(cfg=82 + d, d=d, L=6, N_f=2**13, N_c=2**11, N_p=8, N_min=20, N_max=(600 if d == 2 else 90),
+                 N=150000 + 11, feat_dtype="f16", io_dtype="f16", points="uniform")
+    x, D_f, Dhat, dy = tables(w)
+    x[:3] = [[0.0] * d, [1.0] * d, [0.5] * d]
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    check_bwd(w, x, D_f, Dhat, dy, paths=("sliced", "sliced_nopre"))
 
 
 def test_sliced_backward_needs_workspace():
