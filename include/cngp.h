@@ -59,7 +59,8 @@ enum {
     CNGP_BWD_DIRECT = 2u,   /* force the backward variant that adds straight into HBM with global atomics  */
     CNGP_BWD_SLICED = 4u,   /* force the variant that accumulates table slices in LDS (needs workspace)   */
                             /* neither of the two: the library picks by table size and N                   */
-    CNGP_BWD_NO_PREREDUCE = 8u /* LDS variant only: do not pre-reduce coarse levels per grid vertex        */
+    CNGP_BWD_NO_PREREDUCE = 8u, /* LDS variant only: do not pre-reduce coarse levels per grid vertex       */
+    CNGP_FWD_SIMPLE = 16u   /* force the forward variant that reads D_c from memory, not from LDS          */
 };
 
 /* Hyper-parameters of the encoding (Table 1 of the paper, same symbols). */

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libcngp.so")
 
 F32, F16 = 0, 1
 IDX_U8, IDX_PACKED4 = 0, 1
-ZERO_GRADS, BWD_DIRECT, BWD_SLICED, BWD_NO_PREREDUCE = 1, 2, 4, 8
+ZERO_GRADS, BWD_DIRECT, BWD_SLICED, BWD_NO_PREREDUCE, FWD_SIMPLE = 1, 2, 4, 8, 16
 
 OK, ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
 

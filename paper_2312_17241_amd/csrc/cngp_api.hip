@@ -45,7 +45,7 @@ int validate(const cngp_config *c) {
     if (c->io_dtype != CNGP_F32 && c->io_dtype != CNGP_F16) return CNGP_ERR_INVALID;
     if (c->index_format != CNGP_IDX_U8 && c->index_format != CNGP_IDX_PACKED4) return CNGP_ERR_INVALID;
     if (c->index_format == CNGP_IDX_PACKED4 && c->N_c < 2) return CNGP_ERR_INVALID;
-    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE)) return CNGP_ERR_INVALID;
+    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE | CNGP_FWD_SIMPLE)) return CNGP_ERR_INVALID;
     if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & CNGP_BWD_SLICED)) return CNGP_ERR_INVALID;
     if (c->F != 2) return CNGP_ERR_UNSUPPORTED;
     return CNGP_OK;
@@ -126,6 +126,23 @@ int launch_zero(float *ptr, int64_t n, hipStream_t s) {
 template <int D, typename FeatT, typename IoT>
 int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
                const void *D_c, void *y, hipStream_t s) {
+    // tile variant: one level's index codebook and the tile's outputs fit in LDS
+    const bool   packed = c->index_format == CNGP_IDX_PACKED4;
+    const size_t c_stride = packed ? c->N_c / 2 : c->N_c;
+    const size_t lds = ((((size_t)c->N_c + 1) / 2 + 15) & ~(size_t)15) + (size_t)kFwdTile * c->L * 2 * sizeof(IoT);
+    if (lds <= 64 * 1024 && N >= kFwdTile && !(c->flags & CNGP_FWD_SIMPLE)) {
+        const int64_t blocks = (N + kFwdTile - 1) / kFwdTile;
+        if (int rc = check_blocks(blocks)) return rc;
+        const int vec = (c_stride % 16 == 0 && ((uintptr_t)D_c & 15u) == 0) ? 1 : 0;
+        LaunchTimer t(s, K_FWD);
+        if (packed)
+            encode_fwd_tile_kernel<D, FeatT, IoT, true><<<(unsigned)blocks, kFwdTile, lds, s>>>(
+                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec);
+        else
+            encode_fwd_tile_kernel<D, FeatT, IoT, false><<<(unsigned)blocks, kFwdTile, lds, s>>>(
+                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec);
+        return launch_status("encode_fwd_tile_kernel");
+    }
     const int64_t pairs = N * c->L;
     const int64_t blocks = (pairs + kBlock - 1) / kBlock;
     if (int rc = check_blocks(blocks)) return rc;
@@ -286,7 +303,7 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             for (int i = 0; i < c->d; ++i) verts *= (uint64_t)res[l] + 2;
             const uint64_t slices = (verts + kDenseSliceVerts - 1) / kDenseSliceVerts;
             if (verts > kMaxDenseVerts || (N << c->d) < kMinRefsPerVertex * (int64_t)verts) break;
-            if (slices * 3 > per_level && slices > 1) break;
+            if (slices * 2 > per_level && slices > 1) break;
             b.dense.side[l] = res[l] + 2;
             b.dense.verts[l] = (uint32_t)verts;
             b.dense.slices[l] = (uint32_t)slices;

@@ -48,6 +48,94 @@ __global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
     store_pair(y, (size_t)i, y0, y1);
 }
 
+// Tile variant of the forward pass: a workgroup takes kFwdTile consecutive points through all levels.
+// Per level it copies that level's index codebook D_c into LDS (always as packed 4-bit entries, N_c / 2
+// bytes: byte-per-entry input is packed on the way in), so the probe lookups -- half of all random
+// reads of the forward pass -- never reach the memory pipeline; only the D_f gathers do.  Outputs are
+// collected in LDS and leave as one contiguous, fully coalesced block.
+constexpr int kFwdTile = 256;
+
+template <int D, typename FeatT, typename IoT, bool PACKED4>
+__global__ __launch_bounds__(kFwdTile) void encode_fwd_tile_kernel(
+    const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
+    const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t N, const uint32_t c_stride, const int vec)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint8_t *probes = smem;                                                  // D_c of the current level, 4-bit packed
+    const uint32_t lds_c = (p.N_c + 1u) / 2u;                                // bytes of it
+    IoT     *out = reinterpret_cast<IoT *>(smem + ((lds_c + 15u) & ~15u));   // [kFwdTile][L * 2]
+    const int     t = threadIdx.x;
+    const int64_t n0 = (int64_t)blockIdx.x * kFwdTile;
+    const int64_t n = n0 + t;
+    const bool    valid = n < N;
+    float xp[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) xp[j] = valid ? x[n * D + j] : 0.0f;
+
+    for (int l = 0; l < p.L; ++l) {
+        const uint8_t *C_l = D_c + (size_t)l * c_stride;
+        __syncthreads();                                                     // previous level's lookups are done
+        if (PACKED4) {
+            if (vec) {
+                for (uint32_t i = t * 16u; i < c_stride; i += kFwdTile * 16u)
+                    *reinterpret_cast<uint4 *>(probes + i) = *reinterpret_cast<const uint4 *>(C_l + i);
+            } else {
+                for (uint32_t i = t; i < c_stride; i += kFwdTile) probes[i] = C_l[i];
+            }
+        } else if (vec) {                                                    // 16 entries in, 8 bytes out
+            for (uint32_t i = t * 16u; i < c_stride; i += kFwdTile * 16u) {
+                const uint4 w = *reinterpret_cast<const uint4 *>(C_l + i);
+                auto pack = [](uint32_t v) {                                 // 4 entries -> 2 bytes
+                    v &= 0x0F0F0F0Fu;
+                    v = (v | (v >> 4)) & 0x00FF00FFu;
+                    return (v | (v >> 8)) & 0xFFFFu;
+                };
+                *reinterpret_cast<uint2 *>(probes + i / 2) =
+                    make_uint2(pack(w.x) | (pack(w.y) << 16), pack(w.z) | (pack(w.w) << 16));
+            }
+        } else {
+            for (uint32_t i = t; i < lds_c; i += kFwdTile) {
+                const uint32_t lo = C_l[2 * i] & 0xFu, hi = (2 * i + 1 < c_stride) ? (C_l[2 * i + 1] & 0xFu) : 0u;
+                probes[i] = (uint8_t)(lo | (hi << 4));
+            }
+        }
+        __syncthreads();
+
+        Cell<D> cell;
+        cell.locate(xp, p.N_l[l]);
+        const FeatT *F_l = D_f + (size_t)l * p.N_f * 2;
+        uint32_t idx[1 << D];
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c)
+            idx[c] = probe_base(cell.hash1(c), p) + read_probe<true>(probes, cell.hash2(c) & p.c_mask);
+        float2 feat[1 << D];
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) feat[c] = load_pair(F_l, idx[c]);
+        float y0 = 0.0f, y1 = 0.0f;
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) {
+            const float wt = cell.weight(c);
+            y0 = fmaf(wt, feat[c].x, y0);
+            y1 = fmaf(wt, feat[c].y, y1);
+        }
+        store_pair(out, (size_t)t * p.L + l, y0, y1);
+    }
+    __syncthreads();
+
+    // the tile's outputs are one contiguous block of y
+    const int64_t rows = (N - n0 < kFwdTile) ? N - n0 : kFwdTile;
+    const size_t  bytes = (size_t)rows * p.L * 2 * sizeof(IoT);
+    unsigned char *dst = reinterpret_cast<unsigned char *>(y + (size_t)n0 * p.L * 2);
+    const unsigned char *src = reinterpret_cast<const unsigned char *>(out);
+    if (((uintptr_t)dst & 15u) == 0 && bytes % 16 == 0) {
+        for (size_t i = (size_t)t * 16; i < bytes; i += (size_t)kFwdTile * 16)
+            *reinterpret_cast<uint4 *>(dst + i) = *reinterpret_cast<const uint4 *>(src + i);
+    } else {
+        for (size_t i = (size_t)t * sizeof(IoT); i < bytes; i += (size_t)kFwdTile * sizeof(IoT))
+            *reinterpret_cast<IoT *>(dst + i) = *reinterpret_cast<const IoT *>(src + i);
+    }
+}
+
 // ------------------------------------------------------------------ backward (Sec. 3 "Training")
 // Reduction over the NP lanes that share one probe row.
 template <int NP>

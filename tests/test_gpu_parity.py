@@ -27,8 +27,8 @@ def tables(w, n=None):
     return x, W.make_feature_codebook(w), W.make_probe_logits(w), W.make_upstream_grad(w, x.shape[0])
 
 
-def run_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8):
-    cfg = cngp.Config.from_workload(w, index_format=index_format)
+def run_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8, flags=0):
+    cfg = cngp.Config.from_workload(w, index_format=index_format, flags=flags)
     D_c_dev = dev(D_c)
     if index_format == cngp.IDX_PACKED4:
         D_c_dev = cngp.pack4(D_c_dev)
@@ -49,9 +49,13 @@ def run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS, init=None):
 
 
 def check_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8, name=""):
+    """Both forward variants (index codebook staged in LDS; read from memory) against the oracle."""
     y_ref, ymag = oracle.encode_fwd(w, x, D_f, D_c)
-    y = run_fwd(w, x, D_f, D_c, index_format)
-    return check_close(f"y {name}", y, y_ref, ymag, fp16_out=(w.io_dtype == "f16"))
+    worst = 0.0
+    for variant, flags in (("tile", 0), ("simple", cngp.FWD_SIMPLE)):
+        y = run_fwd(w, x, D_f, D_c, index_format, flags)
+        worst = max(worst, check_close(f"y {name} [{variant}]", y, y_ref, ymag, fp16_out=(w.io_dtype == "f16")))
+    return worst
 
 
 # the ways the library can run the backward pass: its own choice, and each variant forced
