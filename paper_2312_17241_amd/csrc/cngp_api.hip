@@ -7,7 +7,6 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
-#include <cstdlib>
 #include <type_traits>
 #include <string>
 #include <vector>
@@ -314,13 +313,7 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             b.dense.count = l + 1;
         }
     }
-    const int Ld = b.dense.count, Lh = c->L - Ld;
     if (b.sliced) choose_geometry(c, N, b);
-#ifdef CNGP_EXPERIMENT
-    if (const char *e = getenv("CNGP_CHUNKS_F")) { int cn = atoi(e); int64_t ch = ((N + cn - 1) / cn + 63) / 64 * 64; b.feat_pts = {(uint32_t)((N + ch - 1) / ch), (uint32_t)ch}; }
-    if (const char *e = getenv("CNGP_CHUNKS_C")) { int cn = atoi(e); int64_t ch = ((N + cn - 1) / cn + 63) / 64 * 64; b.logit_pts = {(uint32_t)((N + ch - 1) / ch), (uint32_t)ch}; }
-    if (const char *e = getenv("CNGP_CHUNKS_G")) { int cn = atoi(e); int64_t ch = ((N + cn - 1) / cn + 63) / 64 * 64; b.grid = {(uint32_t)((N + ch - 1) / ch), (uint32_t)ch}; }
-#endif
     const size_t queues = (size_t)kSlicedWaves * kRingBytes;
     b.lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8 + queues;
     b.lds_c = ((size_t)1 << b.rows_c_log2) * c->N_p * 8 + queues;
