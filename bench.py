@@ -155,6 +155,28 @@ def main():
         "kernel_parts": {k: v["parts"] for k, v in per_kernel.items() if len(v["parts"]) > 1},
     }
 
+    # Applicable roofline: the tables are cache resident, so the forward pass is bound by random gathers
+    # and the backward pass by scatter-add atomics.  Both rates are measured now, on this device.
+    rates = cngp.measure_rates(dev)
+    corners = 1 << w.d
+    t_fwd = per_kernel["encode_fwd"]["ms"] / args.steps * 1e-3
+    gathers = N * w.L * corners                                  # D_f entries the forward must fetch
+    out["applicable_roofline"] = {
+        "measured_rates": {k: round(v, 1) for k, v in rates.items()},
+        "fwd": {"bound": "random 4-byte gathers (D_f entries; the D_c lookups are served from LDS)",
+                "achieved": round(gathers / t_fwd / 1e9, 1), "peak": round(rates["gather4_Gps"], 1),
+                "unit": "G gathers/s", "frac": round(gathers / t_fwd / 1e9 / rates["gather4_Gps"], 3)}}
+    if not fwd_only:
+        t_bwd = (per_kernel["encode_bwd"]["ms"] + per_kernel.get("zero", {"ms": 0.0})["ms"]) / args.steps * 1e-3
+        updates = N * w.L * corners * w.N_p * (3 if w.N_p > 1 else 2)   # scalar += the backward pass defines
+        out["applicable_roofline"]["bwd"] = {
+            "bound": "scatter-add updates (2 feature + 1 logit per candidate) against the fastest atomic of the "
+                     "chip, LDS fp64; as global fp32 atomics they would take 'global_atomic_floor_ms'",
+            "achieved": round(updates / t_bwd / 1e9, 1), "peak": round(rates["lds_atomic_f64_Gps"], 1),
+            "unit": "G updates/s", "frac": round(updates / t_bwd / 1e9 / rates["lds_atomic_f64_Gps"], 3),
+            "global_atomic_floor_ms": round(updates / 16 / rates["global_atomic_Gseg"] / 1e6, 3),
+            "measured_ms": round(t_bwd * 1e3, 3)}
+
     if not args.no_check or not args.no_cpu_baseline:
         import oracle
         sys.path.insert(0, os.path.join(ROOT, "tests"))

@@ -130,6 +130,21 @@ int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const 
                        uint32_t *base, uint32_t *h2, uint8_t *probe, uint32_t *feat_idx,
                        void *stream);
 
+/* Rates of this device that bound the kernels above, measured by short microbenchmarks (about 20 ms):
+ * the codebooks of this method are cache resident, so its forward pass is bound by random gathers and
+ * its backward pass by scatter-add atomics (Sec. 4 "Performance" of the paper: gradient accumulation
+ * must be staged in workgroup-local memory), not by streaming bandwidth.
+ *   scratch  dev, at least 64 MiB, 256-byte aligned; contents are overwritten.
+ * Unlike the other entry points this one waits for its kernels (it returns host-side numbers). */
+typedef struct {
+    double copy_GBps;            /* streaming copy, bytes read + written per second / 1e9            */
+    double gather4_Gps;          /* random 4-byte gathers from a 4 MB table, 1e9 per second          */
+    double row_gather_Gps;       /* random 64-byte rows read by 16 lanes each, 1e9 rows per second   */
+    double global_atomic_Gseg;   /* fp32 atomic adds to random 64-byte rows, 1e9 rows per second     */
+    double lds_atomic_f64_Gps;   /* fp64 atomic adds in LDS (rows of 32), 1e9 adds per second, chip  */
+} cngp_rates;
+int cngp_measure_rates(cngp_rates *out, void *scratch, size_t scratch_bytes, void *stream);
+
 /* Per-kernel timing, off by default.  When enabled every kernel the library launches is bracketed
  * by HIP events on its stream.  cngp_profile_read() waits for those events, adds each kernel's
  * elapsed milliseconds and launch count into the caller's arrays (host, `max_kernels` entries;

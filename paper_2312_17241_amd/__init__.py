@@ -66,6 +66,8 @@ def _load():
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
     lib.cngp_debug_indices.restype = ctypes.c_int
     lib.cngp_debug_indices.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.cngp_measure_rates.restype = ctypes.c_int
+    lib.cngp_measure_rates.argtypes = [vp, vp, sz, vp]
     lib.cngp_profile_enable.restype = ctypes.c_int
     lib.cngp_profile_enable.argtypes = [ctypes.c_int]
     lib.cngp_profile_read.restype = ctypes.c_int
@@ -229,6 +231,20 @@ def debug_indices(cfg: Config, x, D_c):
         ctypes.c_void_p(base.data_ptr()), ctypes.c_void_p(h2.data_ptr()),
         ctypes.c_void_p(probe.data_ptr()), ctypes.c_void_p(fidx.data_ptr()), _stream()))
     return base, h2, probe, fidx
+
+
+class CRates(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("copy_GBps", "gather4_Gps", "row_gather_Gps",
+                                               "global_atomic_Gseg", "lds_atomic_f64_Gps")]
+
+
+def measure_rates(device="cuda") -> dict:
+    """Streaming, gather and atomic rates of the device (see cngp_measure_rates); synchronises."""
+    scratch = torch.zeros(64 << 20, dtype=torch.uint8, device=device)
+    r = CRates()
+    _check(_lib.cngp_measure_rates(ctypes.byref(r), ctypes.c_void_p(scratch.data_ptr()), scratch.numel(), _stream()))
+    torch.cuda.synchronize()
+    return {n: getattr(r, n) for n, _ in CRates._fields_}
 
 
 def profile_enable(on: bool) -> bool:

@@ -3,6 +3,7 @@
 #include "../../include/cngp.h"
 #include "cngp_kernels.h"
 #include "cngp_bwd_sliced.h"
+#include "cngp_rates.h"
 
 #include <cmath>
 #include <cstdio>
@@ -579,6 +580,53 @@ int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const 
     if (cfg->d == 2) { CNGP_DBG(2); } else { CNGP_DBG(3); }
 #undef CNGP_DBG
     return launch_status("debug_indices_kernel");
+}
+
+int cngp_measure_rates(cngp_rates *out, void *scratch, size_t scratch_bytes, void *stream) {
+    if (!out || !scratch) return CNGP_ERR_NULL;
+    const size_t need = (size_t)64 << 20;
+    if (scratch_bytes < need || ((uintptr_t)scratch & 255u)) return CNGP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t  t0, t1;
+    CNGP_HIP(hipEventCreate(&t0));
+    CNGP_HIP(hipEventCreate(&t1));
+    int rc = CNGP_OK;
+    auto timed = [&](auto launch, int reps, double &ms_out) {       // one untimed run, then `reps` timed ones
+        launch();
+        if (hipEventRecord(t0, s) != hipSuccess) rc = CNGP_ERR_HIP;
+        for (int i = 0; i < reps; ++i) launch();
+        if (hipEventRecord(t1, s) != hipSuccess || hipEventSynchronize(t1) != hipSuccess) rc = CNGP_ERR_HIP;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, t0, t1) != hipSuccess) rc = CNGP_ERR_HIP;
+        ms_out = (double)ms / reps;
+    };
+    float *tab = (float *)scratch;
+    float *sink = tab + (need / 4 - 64);                            // last 256 bytes: never inside a table
+    double ms = 0.0;
+    const size_t half = need / 2 - 256;
+    timed([&] { rate_copy_kernel<<<8192, kBlock, 0, s>>>((const float4 *)scratch, (float4 *)((char *)scratch + need / 2), half / 16); }, 3, ms);
+    out->copy_GBps = 2.0 * (double)(half / 16 * 16) / ms / 1e6;
+    const int      blocks = 256 * 32, iters = 16;
+    const double   lane_ops = (double)blocks * kBlock * iters * 8;
+    const uint32_t table_floats = (4u << 20) / 4;                   // 4 MB table: L2 resident
+    timed([&] { rate_rows_kernel<1, false><<<blocks, kBlock, 0, s>>>(tab, table_floats - 1, iters, sink); }, 3, ms);
+    out->gather4_Gps = lane_ops / ms / 1e6;
+    timed([&] { rate_rows_kernel<16, false><<<blocks, kBlock, 0, s>>>(tab, table_floats / 16 - 1, iters, sink); }, 3, ms);
+    out->row_gather_Gps = lane_ops / 16 / ms / 1e6;
+    timed([&] { rate_rows_kernel<16, true><<<blocks, kBlock, 0, s>>>(tab, table_floats / 16 - 1, iters, sink); }, 3, ms);
+    out->global_atomic_Gseg = lane_ops / 16 / ms / 1e6;
+    {
+        auto kernel = rate_lds_atomic_kernel;
+        const size_t lds = 16384 * sizeof(double);
+        if (int r2 = allow_big_lds(kernel, lds)) rc = r2;
+        const int lblocks = 1024, liters = 64;
+        timed([&] { kernel<<<lblocks, 1024, lds, s>>>(liters, sink); }, 3, ms);
+        out->lds_atomic_f64_Gps = (double)lblocks * 1024 * liters * 8 / ms / 1e6;
+    }
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (rc == CNGP_OK) rc = launch_status("cngp_measure_rates");
+    return rc;
 }
 
 int cngp_profile_enable(int on) {

@@ -1,0 +1,62 @@
+// Microbenchmarks of the chip rates that bound the encoding kernels: streaming copy, random
+// gathers, global floating-point atomics and LDS fp64 atomics.  They give the benchmark an
+// "applicable roofline" measured in the same run, on the same device.
+#pragma once
+#include "cngp_device.h"
+
+namespace cngp {
+
+__device__ __forceinline__ uint32_t rate_mix(uint32_t a) {
+    a ^= a >> 16; a *= 0x7feb352dU; a ^= a >> 15; a *= 0x846ca68bU; a ^= a >> 16;
+    return a;
+}
+
+__global__ __launch_bounds__(kBlock) void rate_copy_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst,
+                                                          const size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+// GROUP lanes read (ATOMIC = false) or atomically add to (ATOMIC = true) one random row of GROUP floats
+// of a table of rows_mask + 1 rows; 8 independent rows per lane and iteration.
+template <int GROUP, bool ATOMIC>
+__global__ __launch_bounds__(kBlock) void rate_rows_kernel(float *__restrict__ tab, const uint32_t rows_mask,
+                                                          const int iters, float *__restrict__ sink)
+{
+    const uint32_t gid = blockIdx.x * kBlock + threadIdx.x, grp = gid / GROUP, k = gid % GROUP;
+    uint32_t r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = rate_mix(grp * 8u + j);
+    float acc = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float *q = tab + (size_t)((r[j] + it * 0x9e3779b1u) & rows_mask) * GROUP + k;
+            if (ATOMIC) atomic_add(q, 1.0f);
+            else acc += *q;
+        }
+    }
+    if (acc == 12345.678f) sink[0] = acc;          // keeps the loads alive
+}
+
+// fp64 atomic adds to random rows of 32 consecutive doubles in a 128 KB LDS array.
+__global__ __launch_bounds__(1024) void rate_lds_atomic_kernel(const int iters, float *__restrict__ sink)
+{
+    extern __shared__ double lds[];
+    constexpr uint32_t kDoubles = 16384, kRows = kDoubles / 32;
+    for (uint32_t i = threadIdx.x; i < kDoubles; i += 1024) lds[i] = 0.0;
+    __syncthreads();
+    const uint32_t gid = blockIdx.x * 1024 + threadIdx.x, grp = gid / 32, k = gid % 32;
+    uint32_t r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = rate_mix(grp * 8u + j);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) atomicAdd(lds + ((r[j] + it * 97u) & (kRows - 1)) * 32 + k, 1.0);
+    }
+    __syncthreads();
+    if (lds[threadIdx.x] == -1.0) sink[0] = 1.0f;
+}
+
+}  // namespace cngp
