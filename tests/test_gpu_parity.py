@@ -283,6 +283,44 @@ def test_probe_range_one_matches_unprobed_hash_grid():
     check_bwd(w, x, D_f, Dhat, dy)
 
 
+# ------------------------------------------------------------------ randomised configurations
+
+def _random_workloads(count=24, seed=2024):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        d = int(rng.choice([2, 3]))
+        N_p = int(rng.choice([1, 2, 4, 8, 16]))
+        N_f = int(2 ** rng.integers(max(2, int(np.log2(N_p))), 15))
+        N_c = int(2 ** rng.integers(0, 13))
+        L = int(rng.integers(1, 9))
+        N_min = int(rng.integers(1, 20))
+        N_max = int(N_min * 2 ** rng.integers(0, 7)) if L > 1 else N_min
+        N = int(rng.choice([1, 17, 300, 2500, 9000, 40000]))
+        out.append(W.custom(name=f"rand{i}", cfg=200 + i, d=d, L=L, N_f=max(N_f, N_p), N_c=N_c, N_p=N_p,
+                            N_min=N_min, N_max=N_max, N=N, feat_dtype=str(rng.choice(["f32", "f16"])),
+                            io_dtype=str(rng.choice(["f32", "f16"])),
+                            points=("uniform" if d == 2 else str(rng.choice(["uniform", "nerf_rays", "sdf_shell"])))))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_workloads(), ids=lambda w: f"{w.name}-d{w.d}-L{w.L}-Nf{w.N_f}-Nc{w.N_c}-Np{w.N_p}-N{w.N}")
+def test_random_configurations(w):
+    """Seeded random hyper-parameters and batch sizes: indices, bake, forward and every backward variant."""
+    x, D_f, Dhat, dy = tables(w)
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    D_c = oracle.bake_probes(Dhat)
+    cfg = cngp.Config.from_workload(w)
+    check_exact("D_c", host(cngp.bake_probes(cfg, dev(Dhat))), D_c)
+    got = cngp.debug_indices(cfg, dev(x), dev(D_c))
+    for nm, g, r in zip(("base", "h2", "probe", "feat_idx"), got, oracle.indices(w, x, D_c)):
+        check_exact(nm, host(g).view(r.dtype), r)
+    check_fwd(w, x, D_f, D_c)
+    if w.N_c >= 2:
+        check_fwd(w, x, D_f, D_c, cngp.IDX_PACKED4)
+    check_bwd(w, x, D_f, Dhat, dy)
+
+
 # ------------------------------------------------------------------ full benchmark sizes
 
 @pytest.mark.parametrize("name", ["tiny2d", "nerf3d", "image2d", "sdf3d"])
