@@ -103,25 +103,30 @@ int launch_status(const char *what) {
 }
 
 // ---------------------------------------------------------------- launches
-int launch_zero(float *ptr, int64_t n, hipStream_t s) {
-    if (n <= 0) return CNGP_OK;
-    // the head up to 16-byte alignment and the tail go through the scalar path
-    int64_t head = 0;
-    while (head < n && ((uintptr_t)(ptr + head) & 15u)) ++head;
-    if (head) {
-        LaunchTimer t(s, K_ZERO);
-        zero_kernel<<<1, kBlock, 0, s>>>(nullptr, 0, ptr, (int)head);
+// Collects the arrays one call has to clear and clears them with a single launch.
+struct ZeroList {
+    ZeroSegments seg;
+    int          n = 0;
+    int64_t      largest = 0;
+    void add(float *ptr, int64_t count) {
+        if (count <= 0 || n >= kZeroSegments) return;
+        seg.ptr[n] = ptr;
+        seg.count[n] = count;
+        if (count > largest) largest = count;
+        ++n;
     }
-    const int64_t n4 = (n - head) / 4;
-    const int ntail = (int)((n - head) - n4 * 4);
-    int64_t blocks = (n4 + kBlock - 1) / kBlock;
-    if (blocks > 4096) blocks = 4096;
-    if (blocks < 1) blocks = 1;
-    LaunchTimer t(s, K_ZERO);
-    zero_kernel<<<(unsigned)blocks, kBlock, 0, s>>>(reinterpret_cast<float4 *>(ptr + head), n4,
-                                                     ptr + head + n4 * 4, ntail);
-    return launch_status("zero_kernel");
-}
+    int launch(hipStream_t s) {
+        if (n == 0) return CNGP_OK;
+        int64_t blocks = (largest / 4 + kBlock - 1) / kBlock;
+        if (blocks > 2048) blocks = 2048;
+        if (blocks < 1) blocks = 1;
+        LaunchTimer t(s, K_ZERO);
+        zero_kernel<<<dim3((unsigned)blocks, (unsigned)n), kBlock, 0, s>>>(seg);
+        n = 0;
+        largest = 0;
+        return launch_status("zero_kernel");
+    }
+};
 
 template <int D, typename FeatT, typename IoT>
 int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
@@ -382,8 +387,11 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
     const int Ld = b.dense.count, Lh = c->L - Ld;
     if (Ld > 0) {
         const int direct = b.grid.chunks == 1;
-        if (!direct)
-            if (int rc = launch_zero(G, (int64_t)b.dense_verts * 2, s)) return rc;
+        if (!direct) {
+            ZeroList z;
+            z.add(G, (int64_t)b.dense_verts * 2);
+            if (int rc = z.launch(s)) return rc;
+        }
         auto kernel = bwd_vertex_grid_kernel<D, IoT>;
         const size_t lds = (size_t)kDenseSliceVerts * 2 * sizeof(double);
         if (int rc = allow_big_lds(kernel, lds)) return rc;
@@ -521,15 +529,13 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
         const int64_t per_f = (int64_t)cfg->N_f * cfg->F, per_c = (int64_t)cfg->N_c * cfg->N_p;
         const bool    sl = N > 0 && b.sliced;
         const int     Ld = sl ? b.dense.count : 0, Lh = cfg->L - Ld;
-        if (!(sl && b.feat_vtx.chunks == 1) && Ld > 0)
-            if (int rc = launch_zero(grad_D_f, per_f * Ld, s)) return rc;
-        if (!(sl && b.feat_pts.chunks == 1) && Lh > 0)
-            if (int rc = launch_zero(grad_D_f + per_f * Ld, per_f * Lh, s)) return rc;
+        ZeroList z;
+        if (!(sl && b.feat_vtx.chunks == 1) && Ld > 0) z.add(grad_D_f, per_f * Ld);
+        if (!(sl && b.feat_pts.chunks == 1) && Lh > 0) z.add(grad_D_f + per_f * Ld, per_f * Lh);
         const bool logit = sl && cfg->N_p > 1;
-        if (!(logit && b.logit_vtx.chunks == 1) && Ld > 0)
-            if (int rc = launch_zero(grad_Dhat_c, per_c * Ld, s)) return rc;
-        if (!(logit && b.logit_pts.chunks == 1) && Lh > 0)
-            if (int rc = launch_zero(grad_Dhat_c + per_c * Ld, per_c * Lh, s)) return rc;
+        if (!(logit && b.logit_vtx.chunks == 1) && Ld > 0) z.add(grad_Dhat_c, per_c * Ld);
+        if (!(logit && b.logit_pts.chunks == 1) && Lh > 0) z.add(grad_Dhat_c + per_c * Ld, per_c * Lh);
+        if (int rc = z.launch(s)) return rc;
     }
     if (N == 0) return CNGP_OK;
     const Params p = make_params(cfg);

@@ -262,13 +262,30 @@ __global__ __launch_bounds__(kBlock) void debug_indices_kernel(
 }
 
 // ------------------------------------------------------------------ fill with zeros
-__global__ __launch_bounds__(kBlock) void zero_kernel(float4 *__restrict__ p4, const int64_t n4,
-                                                      float *__restrict__ tail, const int ntail)
+// Clears up to kZeroSegments float arrays in one launch; blockIdx.y selects the array.
+constexpr int kZeroSegments = 6;
+struct ZeroSegments {
+    float  *ptr[kZeroSegments];
+    int64_t count[kZeroSegments];
+};
+
+__global__ __launch_bounds__(kBlock) void zero_kernel(const ZeroSegments seg)
 {
+    float        *p = seg.ptr[blockIdx.y];
+    const int64_t n = seg.count[blockIdx.y];
+    // scalar head up to 16-byte alignment, float4 body, scalar tail
+    int64_t head = (int64_t)(((16u - ((uintptr_t)p & 15u)) & 15u) / 4u);
+    if (head > n) head = n;
+    const int64_t n4 = (n - head) / 4;
+    float4       *p4 = reinterpret_cast<float4 *>(p + head);
     const int64_t stride = (int64_t)gridDim.x * kBlock;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride)
         p4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0.0f;
+    if (blockIdx.x == 0) {
+        if ((int64_t)threadIdx.x < head) p[threadIdx.x] = 0.0f;
+        const int64_t tail0 = head + n4 * 4;
+        if (tail0 + threadIdx.x < n) p[tail0 + threadIdx.x] = 0.0f;
+    }
 }
 
 }  // namespace cngp
