@@ -192,21 +192,25 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
         if (tail - mid >= (uint32_t)kBatch) issue();
     };
 
-    // software prefetch of the next step's point (or vertex) and its upstream gradient
-    auto fetch = [&](const int64_t n, float (&xo)[D], float2 &go) {
-        const bool ok = n < n1;
+    // software prefetch of the next step's point (or vertex) and its upstream gradient; items are
+    // addressed by a 32-bit index relative to the chunk (a chunk holds fewer than 2^32 items)
+    const float   *xc = x + n0 * D;
+    const GradT   *gc = g_l + n0 * 2;
+    const uint32_t items = (uint32_t)(n1 > n0 ? n1 - n0 : 0);
+    auto fetch = [&](const uint32_t i, float (&xo)[D], float2 &go) {
+        const bool ok = i < items;
         if (!VERTEX) {
 #pragma unroll
-            for (int j = 0; j < D; ++j) xo[j] = ok ? x[n * D + j] : 0.0f;
+            for (int j = 0; j < D; ++j) xo[j] = ok ? xc[i * D + j] : 0.0f;
         }
-        go = ok ? load_pair(g_l, (size_t)n) : make_float2(0.f, 0.f);
+        go = ok ? load_pair(gc, i) : make_float2(0.f, 0.f);
     };
-    float   xn[D] = {};
-    float2  gn;
-    int64_t nb = n0 + wave * 64;
+    float    xn[D] = {};
+    float2   gn;
+    uint32_t nb = wave * 64;
     fetch(nb + lane, xn, gn);
-    for (; nb < n1; nb += kSlicedBlock) {
-        const bool valid = nb + lane < n1;
+    for (; nb < items; nb += kSlicedBlock) {
+        const bool valid = nb + lane < items;
         float xp[D];
 #pragma unroll
         for (int j = 0; j < D; ++j) xp[j] = xn[j];
@@ -218,7 +222,7 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
         uint32_t accepted = 0;                                      // corners of this lane's item in the slice
         if (VERTEX) {
             // grid coordinates of vertex number nb + lane; its only corner is itself, weight 1
-            uint32_t rest = (uint32_t)(nb + lane);
+            uint32_t rest = (uint32_t)n0 + nb + lane;
 #pragma unroll
             for (int i = 0; i < D; ++i) {
                 const uint32_t v = (i == D - 1) ? rest : rest % side;
