@@ -197,7 +197,7 @@ struct BwdPlan {
 };
 
 constexpr uint32_t kMaxSlicesPerLevel = 128;   // beyond this the replicated scan costs more than global atomics
-constexpr int64_t  kMinSlicedPoints = 2048;
+constexpr int64_t  kMinSlicedRefs = 1 << 19;    // corner references (N * L * 2^d) below which launch overheads win
 constexpr uint64_t kMaxDenseVerts = 32ull * kDenseSliceVerts;   // largest vertex grid that is pre-reduced
 constexpr int64_t  kMinRefsPerVertex = 4;      // below this reuse the vertex pass saves nothing
 constexpr int64_t  kCus = 256;
@@ -294,7 +294,7 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     const uint32_t per_level = b.slices_f + b.slices_c;
     // a queued reference packs (row inside the slice, row of the other table) into 32 bits
     const bool keys_fit = b.rows_f_log2 + ilog2(c->N_c) <= 32 && b.rows_c_log2 + ilog2(groups) <= 32;
-    b.sliced = per_level <= kMaxSlicesPerLevel && N >= kMinSlicedPoints;
+    b.sliced = per_level <= kMaxSlicesPerLevel && (N << c->d) * c->L >= kMinSlicedRefs;
     if (c->flags & CNGP_BWD_DIRECT) b.sliced = false;
     if ((c->flags & CNGP_BWD_SLICED) && (uint64_t)per_level * 32u * 64u < 0x7fffffffull) b.sliced = true;
     if (!keys_fit) b.sliced = false;
