@@ -117,6 +117,15 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N,
                     float *grad_D_f, float *grad_Dhat_c,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* How cngp_encode_bwd would run for this configuration and N (host only; for tests, tuning and logs).
+ * info (host, CNGP_PLAN_INFO_COUNT entries): [0] 1 = LDS-sliced variant, 0 = global atomics;
+ * [1] number of coarse levels pre-reduced per grid vertex; [2], [3] slices per level of the feature and
+ * of the logit gradient table; [4], [5] point chunks of the feature / logit role on hashed levels;
+ * [6], [7] vertex chunks of the two roles on pre-reduced levels; [8] point chunks and [9] total slices
+ * of the vertex-grid accumulation. */
+enum { CNGP_PLAN_INFO_COUNT = 10 };
+int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info);
+
 /* Bake (Fig. 3; Sec. 3): D_c[l][r] = index of the largest confidence value in row r of D^_c.
  * Ties: lowest index; NaN never wins; an all-NaN row gives 0.  Result always < N_p.
  *   Dhat_c dev float32 [L, N_c, N_p];  D_c dev, written in cfg->index_format. */

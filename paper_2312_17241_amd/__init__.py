@@ -66,6 +66,8 @@ def _load():
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
     lib.cngp_debug_indices.restype = ctypes.c_int
     lib.cngp_debug_indices.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.cngp_bwd_plan_info.restype = ctypes.c_int
+    lib.cngp_bwd_plan_info.argtypes = [cfgp, i64, vp]
     lib.cngp_measure_rates.restype = ctypes.c_int
     lib.cngp_measure_rates.argtypes = [vp, vp, sz, vp]
     lib.cngp_profile_enable.restype = ctypes.c_int
@@ -164,6 +166,16 @@ def level_resolutions(cfg: Config) -> np.ndarray:
 def workspace_bytes(cfg: Config, N: int) -> int:
     c = cfg.c()
     return int(_lib.cngp_workspace_bytes(ctypes.byref(c), N))
+
+
+def bwd_plan_info(cfg: Config, N: int) -> dict:
+    """How encode_bwd would run for (cfg, N): variant, pre-reduced levels, slices and chunk counts."""
+    info = (ctypes.c_int32 * 10)()
+    c = cfg.c()
+    _check(_lib.cngp_bwd_plan_info(ctypes.byref(c), N, info))
+    names = ("sliced", "dense_levels", "slices_f", "slices_c", "chunks_feat_pts", "chunks_logit_pts",
+             "chunks_feat_vtx", "chunks_logit_vtx", "chunks_grid", "grid_slices")
+    return dict(zip(names, list(info)))
 
 
 def alloc_workspace(cfg: Config, N: int, device="cuda"):

@@ -248,7 +248,9 @@ Geom chunks_of(int64_t items, int64_t c) {
 void choose_geometry(const cngp_config *c, int64_t N, BwdPlan &b) {
     const int    Ld = b.dense.count, Lh = c->L - Ld;
     const double corners = (double)(1 << c->d);
-    const double fixed = 12000.0;
+    // fixed cost per workgroup ~ clearing and flushing its slice: 12000 points' worth for a full 128 KB slice
+    const double fixed_f = 1500.0 + 10500.0 * (double)(((size_t)1 << b.rows_f_log2) * c->N_p * 16) / kSliceBytes;
+    const double fixed_c = 1500.0 + 10500.0 * (double)(((size_t)1 << b.rows_c_log2) * c->N_p * 8) / kSliceBytes;
     const double item_f = 1.0 + 2.0 * corners / b.slices_f;                      // per point, feature role
     const double item_c = b.slices_c ? 1.0 + 1.5 * corners / b.slices_c : 0.0;   // per point, logit role
     const double vtx_f = 0.6 + 2.0 / b.slices_f, vtx_c = b.slices_c ? 0.6 + 1.5 / b.slices_c : 0.0;
@@ -258,24 +260,28 @@ void choose_geometry(const cngp_config *c, int64_t N, BwdPlan &b) {
         const int64_t cv = (b.dense_max_verts + 16383) / 16384;                  // vertex chunks of <= 16384
         b.feat_vtx = b.logit_vtx = chunks_of(b.dense_max_verts, cv > 0 ? cv : 1);
     }
+    // small slices are cheap to clear and flush: allow finer chunks there
+    const bool    small = fixed_f + fixed_c < 8000.0;
+    const int64_t min_chunk = small ? 8192 : 16384, cap = small ? 32 : 12;
+    const int64_t cmax = N / min_chunk > 1 ? (N / min_chunk < cap ? N / min_chunk : cap) : 1;
     double best = -1.0;
-    const int64_t cmax = N / 16384 > 1 ? (N / 16384 < 12 ? N / 16384 : 12) : 1;
     for (int64_t cc = 1; cc <= (b.slices_c ? cmax : 1); ++cc)
         for (int64_t cf = 1; cf <= cmax; ++cf) {
             const Geom gc = chunks_of(N, cc), gf = chunks_of(N, cf);
             std::vector<std::pair<int64_t, double>> batches;
             if (Lh > 0 && b.slices_c)
-                batches.push_back({(int64_t)Lh * b.slices_c * gc.chunks, fixed + gc.chunk_items * item_c});
+                batches.push_back({(int64_t)Lh * b.slices_c * gc.chunks, fixed_c + gc.chunk_items * item_c});
             if (Lh > 0)
-                batches.push_back({(int64_t)Lh * b.slices_f * gf.chunks, fixed + gf.chunk_items * item_f});
+                batches.push_back({(int64_t)Lh * b.slices_f * gf.chunks, fixed_f + gf.chunk_items * item_f});
             if (Ld > 0 && b.slices_c)
-                batches.push_back({(int64_t)Ld * b.slices_c * b.logit_vtx.chunks, fixed + b.logit_vtx.chunk_items * vtx_c});
+                batches.push_back({(int64_t)Ld * b.slices_c * b.logit_vtx.chunks, fixed_c + b.logit_vtx.chunk_items * vtx_c});
             if (Ld > 0)
-                batches.push_back({(int64_t)Ld * b.slices_f * b.feat_vtx.chunks, fixed + b.feat_vtx.chunk_items * vtx_f});
+                batches.push_back({(int64_t)Ld * b.slices_f * b.feat_vtx.chunks, fixed_f + b.feat_vtx.chunk_items * vtx_f});
             const double t = simulate_makespan(batches);
             if (best < 0.0 || t < best) { best = t; b.logit_pts = gc; b.feat_pts = gf; }
         }
 }
+
 
 BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     BwdPlan b;
@@ -497,6 +503,19 @@ int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l) {
 size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N) {
     if (validate(cfg) != CNGP_OK || N <= 0) return 0;
     return make_bwd_plan(cfg, N).ws_bytes;
+}
+
+int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info) {
+    if (!info) return CNGP_ERR_NULL;
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    const BwdPlan b = make_bwd_plan(cfg, N);
+    const int32_t v[CNGP_PLAN_INFO_COUNT] = {
+        b.sliced ? 1 : 0, b.dense.count, (int32_t)b.slices_f, (int32_t)b.slices_c,
+        (int32_t)b.feat_pts.chunks, (int32_t)b.logit_pts.chunks, (int32_t)b.feat_vtx.chunks,
+        (int32_t)b.logit_vtx.chunks, (int32_t)b.grid.chunks, (int32_t)b.dense_slices};
+    for (int i = 0; i < CNGP_PLAN_INFO_COUNT; ++i) info[i] = v[i];
+    return CNGP_OK;
 }
 
 int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const void *D_c,

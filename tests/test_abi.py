@@ -108,6 +108,22 @@ def test_null_pointers_and_negative_counts():
     assert lib.cngp_level_resolutions(ctypes.byref(c), None) == cngp.ERR_NULL
 
 
+def test_backward_plan_is_reported_on_the_host():
+    """The plan needs no GPU: benchmark shapes take the LDS-sliced variant with pre-reduced coarse levels,
+    a tiny batch takes global atomics, and the flags override the choice."""
+    w = W.WORKLOADS["nerf3d"]
+    p = cngp.bwd_plan_info(cngp.Config.from_workload(w), w.N)
+    assert p["sliced"] == 1 and p["slices_f"] == 8 and p["slices_c"] == 16 and 1 <= p["dense_levels"] <= 6
+    assert cngp.workspace_bytes(cngp.Config.from_workload(w), w.N) >= 4 * w.L * w.N_c * w.N_p + 2 * w.N * w.L * w.F
+    t = W.WORKLOADS["tiny2d"]
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(t), t.N)["sliced"] == 0
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(t, flags=cngp.BWD_SLICED), t.N)["sliced"] == 1
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_DIRECT), w.N)["sliced"] == 0
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_NO_PREREDUCE), w.N)["dense_levels"] == 0
+    big = W.custom(d=3, L=16, N_f=2**24, N_c=2**24, N_p=2, N_min=16, N_max=2048, N=2**18)
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(big), big.N)["sliced"] == 0     # too many slices
+
+
 def test_binding_rejects_host_tensors_and_wrong_shapes():
     import torch
     cfg = base_cfg()
