@@ -76,11 +76,11 @@ Params make_params(const cngp_config *c) {
 int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INVALID : CNGP_OK; }
 
 // ---------------------------------------------------------------- per-kernel timing
-enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_VERTEX_GRID, K_BWD_SLICED,
+enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_SLICED, K_BWD_SLICED_V,
                 K_BAKE, K_ZERO, K_DEBUG, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_softmax_table",
-                                           "encode_bwd_transpose_dy", "encode_bwd_vertex_grid", "encode_bwd_sliced",
-                                           "bake_probes", "zero", "debug_indices"};
+                                           "encode_bwd_transpose_dy", "encode_bwd_sliced_points_and_grid",
+                                           "encode_bwd_sliced_vertices", "bake_probes", "zero", "debug_indices"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -391,51 +391,53 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
     // per-vertex sums of weight * dL/dy on the dense levels
     float *G = reinterpret_cast<float *>((char *)workspace + b.G_off);
     const int Ld = b.dense.count, Lh = c->L - Ld;
-    if (Ld > 0) {
-        const int direct = b.grid.chunks == 1;
-        if (!direct) {
-            ZeroList z;
-            z.add(G, (int64_t)b.dense_verts * 2);
-            if (int rc = z.launch(s)) return rc;
-        }
-        auto kernel = bwd_vertex_grid_kernel<D, IoT>;
-        const size_t lds = (size_t)kDenseSliceVerts * 2 * sizeof(double);
-        if (int rc = allow_big_lds(kernel, lds)) return rc;
-        LaunchTimer t(s, K_BWD_VERTEX_GRID);
-        kernel<<<b.dense_slices * b.grid.chunks, kSlicedBlock, lds, s>>>(p, b.dense, b.grid.chunks, b.grid.chunk_items,
-                                                                        direct, x, dyT, G, N);
-        if (int rc = launch_status("bwd_vertex_grid_kernel")) return rc;
+    const int grid_direct = b.grid.chunks == 1;
+    if (Ld > 0 && !grid_direct) {
+        ZeroList z;
+        z.add(G, (int64_t)b.dense_verts * 2);
+        if (int rc = z.launch(s)) return rc;
     }
 
-    // feature and logit gradients: hashed levels scan the points, dense levels scan their vertex grid
+    // Launch 1: feature and logit gradients of the hashed levels (scan the points) together with the
+    // vertex-grid accumulation of the dense levels.  Launch 2: the two gradients of the dense levels
+    // (scan the vertex grids, which launch 1 has completed).
     const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
-    BwdRoles roles;
-    std::memset(&roles, 0, sizeof(roles));
-    uint32_t next = 0;
-    auto add_role = [&](int role, bool present, const Geom &g, uint32_t rows_log2, uint32_t slices, int level0,
-                        int nlevels) {
-        SliceParams &sp = roles.sp[role];
-        sp.rows_log2 = rows_log2;
-        sp.slices = slices ? slices : 1;
-        sp.chunks = g.chunks ? g.chunks : 1;
-        sp.chunk_pts = g.chunk_items;
-        sp.store_direct = (g.chunks == 1 && zero_first) ? 1 : 0;     // matches the clearing in cngp_encode_bwd
-        sp.level0 = level0;
-        sp.nlevels = present ? nlevels : 0;
-        roles.first[role] = next;
-        if (present && nlevels > 0)      // 8 equal runs of (level, slice, chunk) units, one per XCD
-            next += (uint32_t)kXcds * (((uint32_t)nlevels * sp.slices * sp.chunks + kXcds - 1) / kXcds);
-    };
-    add_role(ROLE_LOGIT_PTS, NP > 1, b.logit_pts, b.rows_c_log2, b.slices_c, Ld, Lh);
-    add_role(ROLE_FEAT_PTS, true, b.feat_pts, b.rows_f_log2, b.slices_f, Ld, Lh);
-    add_role(ROLE_LOGIT_VTX, NP > 1, b.logit_vtx, b.rows_c_log2, b.slices_c, 0, Ld);
-    add_role(ROLE_FEAT_VTX, true, b.feat_vtx, b.rows_f_log2, b.slices_f, 0, Ld);
-    roles.first[ROLE_COUNT] = next;
-    {
-        auto kernel = bwd_sliced_kernel<D, NP, FeatT, IoT>;
-        const size_t lds = b.lds_f > b.lds_c ? b.lds_f : b.lds_c;
-        if (int rc = allow_big_lds(kernel, lds)) return rc;
-        LaunchTimer t(s, K_BWD_SLICED);
+    auto kernel = bwd_sliced_kernel<D, NP, FeatT, IoT>;
+    size_t lds = b.lds_f > b.lds_c ? b.lds_f : b.lds_c;
+    const size_t lds_grid = (size_t)kDenseSliceVerts * 2 * sizeof(double);
+    if (Ld > 0 && lds_grid > lds) lds = lds_grid;
+    if (int rc = allow_big_lds(kernel, lds)) return rc;
+    for (int launch = 0; launch < 2; ++launch) {
+        BwdRoles roles;
+        std::memset(&roles, 0, sizeof(roles));
+        uint32_t next = 0;
+        auto add_role = [&](int role, bool present, const Geom &g, uint32_t rows_log2, uint32_t slices, int level0,
+                            int nlevels) {
+            SliceParams &sp = roles.sp[role];
+            sp.rows_log2 = rows_log2;
+            sp.slices = slices ? slices : 1;
+            sp.chunks = g.chunks ? g.chunks : 1;
+            sp.chunk_pts = g.chunk_items;
+            sp.store_direct = (g.chunks == 1 && zero_first) ? 1 : 0;     // matches the clearing in cngp_encode_bwd
+            sp.level0 = level0;
+            sp.nlevels = present ? nlevels : 0;
+            roles.first[role] = next;
+            if (present && nlevels > 0)      // 8 equal runs of (level, slice, chunk) units, one per XCD
+                next += (uint32_t)kXcds * (((uint32_t)nlevels * sp.slices * sp.chunks + kXcds - 1) / kXcds);
+        };
+        const bool pts = launch == 0, vtx = launch == 1;
+        add_role(ROLE_LOGIT_PTS, pts && NP > 1, b.logit_pts, b.rows_c_log2, b.slices_c, Ld, Lh);
+        add_role(ROLE_FEAT_PTS, pts, b.feat_pts, b.rows_f_log2, b.slices_f, Ld, Lh);
+        add_role(ROLE_LOGIT_VTX, vtx && NP > 1, b.logit_vtx, b.rows_c_log2, b.slices_c, 0, Ld);
+        add_role(ROLE_FEAT_VTX, vtx, b.feat_vtx, b.rows_f_log2, b.slices_f, 0, Ld);
+        roles.first[ROLE_GRID] = next;
+        roles.sp[ROLE_GRID].chunks = b.grid.chunks ? b.grid.chunks : 1;
+        roles.sp[ROLE_GRID].chunk_pts = b.grid.chunk_items;
+        roles.sp[ROLE_GRID].store_direct = grid_direct;
+        if (pts && Ld > 0) next += b.dense_slices * roles.sp[ROLE_GRID].chunks;
+        roles.first[ROLE_COUNT] = next;
+        if (next == 0) continue;
+        LaunchTimer t(s, pts ? K_BWD_SLICED : K_BWD_SLICED_V);
         kernel<<<next, kSlicedBlock, lds, s>>>(p, roles, b.dense, x, (const FeatT *)D_f, sigma, dyT, G, gD_f, gDhat_c, N);
         if (int rc = launch_status("bwd_sliced_kernel")) return rc;
     }

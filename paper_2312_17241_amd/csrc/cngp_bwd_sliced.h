@@ -407,53 +407,17 @@ __device__ __forceinline__ void bwd_logit_sliced(
     }
 }
 
-// ------------------------------------------------------------------ one launch for all four roles
-// The grid lists, in this order, the workgroups of: logit gradient over points, feature gradient over
-// points (hashed levels), logit gradient over vertices, feature gradient over vertices (dense levels).
-// One launch instead of four keeps all CUs busy across the roles' different run times.
-enum { ROLE_LOGIT_PTS = 0, ROLE_FEAT_PTS, ROLE_LOGIT_VTX, ROLE_FEAT_VTX, ROLE_COUNT };
-struct BwdRoles {
-    uint32_t    first[ROLE_COUNT + 1];      // first workgroup of each role (multiples of 8); [ROLE_COUNT] = grid size
-    SliceParams sp[ROLE_COUNT];
-};
-
-template <int D, int NP, typename FeatT, typename IoT>
-__global__ __launch_bounds__(kSlicedBlock) void bwd_sliced_kernel(
-    const Params p, const BwdRoles roles, const DenseLevels dl, const float *__restrict__ x,
-    const FeatT *__restrict__ D_f, const float *__restrict__ sigma, const IoT *__restrict__ dyT,
-    const float *__restrict__ G, float *__restrict__ gD_f, float *__restrict__ gDhat_c, const int64_t N)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    const uint32_t wg = blockIdx.x;
-    if (wg < roles.first[ROLE_FEAT_PTS]) {
-        if (NP > 1)
-            bwd_logit_sliced<D, NP, false, FeatT, IoT>(p, roles.sp[ROLE_LOGIT_PTS], dl, wg - roles.first[ROLE_LOGIT_PTS],
-                                                       smem, x, D_f, sigma, dyT, gDhat_c, N);
-    } else if (wg < roles.first[ROLE_LOGIT_VTX]) {
-        bwd_feat_sliced<D, NP, false, IoT>(p, roles.sp[ROLE_FEAT_PTS], dl, wg - roles.first[ROLE_FEAT_PTS], smem, x,
-                                           sigma, dyT, gD_f, N);
-    } else if (wg < roles.first[ROLE_FEAT_VTX]) {
-        if (NP > 1)
-            bwd_logit_sliced<D, NP, true, FeatT, float>(p, roles.sp[ROLE_LOGIT_VTX], dl, wg - roles.first[ROLE_LOGIT_VTX],
-                                                        smem, x, D_f, sigma, G, gDhat_c, N);
-    } else {
-        bwd_feat_sliced<D, NP, true, float>(p, roles.sp[ROLE_FEAT_VTX], dl, wg - roles.first[ROLE_FEAT_VTX], smem, x,
-                                            sigma, G, gD_f, N);
-    }
-}
-
 // ------------------------------------------------------------------ per-vertex pre-reduction
 // G[l][v][f] = sum over the corner references to vertex v of level l of weight * dL/dy[n, l, f], for the
 // dense levels.  A workgroup owns kDenseSliceVerts consecutive vertices (row-major: dimension 0 fastest)
 // of one level as fp64 accumulators in LDS and scans a chunk of the points; no hashing is involved.
 template <int D, typename IoT>
-__global__ __launch_bounds__(kSlicedBlock) void bwd_vertex_grid_kernel(
-    const Params p, const DenseLevels dl, const uint32_t chunks, const uint32_t chunk_pts, const int store_direct,
-    const float *__restrict__ x, const IoT *__restrict__ dyT, float *__restrict__ G, const int64_t N)
+__device__ __forceinline__ void bwd_vertex_grid(
+    const Params &p, const DenseLevels &dl, const uint32_t chunks, const uint32_t chunk_pts, const int store_direct,
+    uint32_t wg, unsigned char *smem, const float *__restrict__ x, const IoT *__restrict__ dyT,
+    float *__restrict__ G, const int64_t N)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
     double *acc = reinterpret_cast<double *>(smem);
-    uint32_t wg = blockIdx.x;
     int l = 0;
     while (l < dl.count - 1 && wg >= dl.slices[l] * chunks) { wg -= dl.slices[l] * chunks; ++l; }
     const uint32_t slice = wg / chunks, chunk = wg % chunks;
@@ -508,6 +472,47 @@ __global__ __launch_bounds__(kSlicedBlock) void bwd_vertex_grid_kernel(
         const float v = (float)acc[i];
         if (store_direct) out[i] = v;
         else if (v != 0.0f) atomic_add(out + i, v);
+    }
+}
+
+// ------------------------------------------------------------------ one kernel, five roles
+// The grid lists, in this order, the workgroups of: logit gradient over points, feature gradient over
+// points (hashed levels), logit gradient over vertices, feature gradient over vertices (dense levels),
+// vertex-grid accumulation.  Sharing a launch keeps all CUs busy across the roles' different run times.
+// The host launches it twice: points roles + vertex-grid accumulation (independent of each other), then
+// the two vertex roles, which read the finished grid sums G.
+enum { ROLE_LOGIT_PTS = 0, ROLE_FEAT_PTS, ROLE_LOGIT_VTX, ROLE_FEAT_VTX, ROLE_GRID, ROLE_COUNT };
+struct BwdRoles {
+    uint32_t    first[ROLE_COUNT + 1];      // first workgroup of each role (multiples of 8); [ROLE_COUNT] = grid size
+    SliceParams sp[ROLE_COUNT];             // for ROLE_GRID only chunks, chunk_pts and store_direct are used
+};
+
+template <int D, int NP, typename FeatT, typename IoT>
+__global__ __launch_bounds__(kSlicedBlock) void bwd_sliced_kernel(
+    const Params p, const BwdRoles roles, const DenseLevels dl, const float *__restrict__ x,
+    const FeatT *__restrict__ D_f, const float *__restrict__ sigma, const IoT *__restrict__ dyT,
+    float *__restrict__ G, float *__restrict__ gD_f, float *__restrict__ gDhat_c, const int64_t N)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const uint32_t wg = blockIdx.x;
+    if (wg < roles.first[ROLE_FEAT_PTS]) {
+        if (NP > 1)
+            bwd_logit_sliced<D, NP, false, FeatT, IoT>(p, roles.sp[ROLE_LOGIT_PTS], dl, wg - roles.first[ROLE_LOGIT_PTS],
+                                                       smem, x, D_f, sigma, dyT, gDhat_c, N);
+    } else if (wg < roles.first[ROLE_LOGIT_VTX]) {
+        bwd_feat_sliced<D, NP, false, IoT>(p, roles.sp[ROLE_FEAT_PTS], dl, wg - roles.first[ROLE_FEAT_PTS], smem, x,
+                                           sigma, dyT, gD_f, N);
+    } else if (wg < roles.first[ROLE_FEAT_VTX]) {
+        if (NP > 1)
+            bwd_logit_sliced<D, NP, true, FeatT, float>(p, roles.sp[ROLE_LOGIT_VTX], dl, wg - roles.first[ROLE_LOGIT_VTX],
+                                                        smem, x, D_f, sigma, G, gDhat_c, N);
+    } else if (wg < roles.first[ROLE_GRID]) {
+        bwd_feat_sliced<D, NP, true, float>(p, roles.sp[ROLE_FEAT_VTX], dl, wg - roles.first[ROLE_FEAT_VTX], smem, x,
+                                            sigma, G, gD_f, N);
+    } else {
+        const SliceParams &sp = roles.sp[ROLE_GRID];
+        bwd_vertex_grid<D, IoT>(p, dl, sp.chunks, sp.chunk_pts, sp.store_direct, wg - roles.first[ROLE_GRID], smem, x,
+                                dyT, G, N);
     }
 }
 
