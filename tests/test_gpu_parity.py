@@ -283,6 +283,40 @@ def test_probe_range_one_matches_unprobed_hash_grid():
     check_bwd(w, x, D_f, Dhat, dy)
 
 
+# ------------------------------------------------------------------ adversarial point sets
+
+@pytest.mark.parametrize("kind", ["identical", "axis_line", "two_cells", "corner_of_cube"])
+def test_backward_hot_spots(kind):
+    """Point sets that send every corner reference to a handful of table rows: one workgroup's slice
+    takes all the traffic (its queue fills in every round) and its LDS atomics all collide."""
+    w = W.custom(cfg=90, d=3, L=5, N_f=2**14, N_c=2**12, N_p=16, N_min=16, N_max=512, N=60000 + 3,
+                 feat_dtype="f16", io_dtype="f16")
+    rng = np.random.default_rng(11)
+    if kind == "identical":
+        x = np.tile(np.array([[0.3141, 0.2718, 0.5772]], np.float32), (w.N, 1))
+    elif kind == "axis_line":
+        x = np.zeros((w.N, 3), np.float32); x[:, 0] = rng.random(w.N); x[:, 1] = 0.5; x[:, 2] = 0.25
+    elif kind == "two_cells":
+        x = (np.array([[0.1, 0.1, 0.1]]) + (rng.integers(0, 2, (w.N, 1)) * 0.7) + rng.random((w.N, 3)) * 1e-3).astype(np.float32)
+    else:
+        x = np.ones((w.N, 3), np.float32)
+    _, D_f, Dhat, dy = tables(w)
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    check_fwd(w, x, D_f, oracle.bake_probes(Dhat))
+    check_bwd(w, x, D_f, Dhat, dy)
+
+
+def test_backward_is_reproducible_within_tolerance():
+    """Two runs of the same backward call: atomics reorder the sums, results stay within the bar of each other."""
+    w = W.WORKLOADS["nerf3d"]
+    x, D_f, Dhat, dy = tables(w, 50000)
+    g1 = run_bwd(w, x, D_f, Dhat, dy)
+    g2 = run_bwd(w, x, D_f, Dhat, dy)
+    for a, b in zip(g1, g2):
+        scale = max(float(np.abs(a).max()), 1e-30)
+        assert float(np.abs(a - b).max()) <= 1e-5 * scale
+
+
 # ------------------------------------------------------------------ randomised configurations
 
 def _random_workloads(count=24, seed=2024):
