@@ -131,6 +131,36 @@ int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info);
  *   Dhat_c dev float32 [L, N_c, N_p];  D_c dev, written in cfg->index_format. */
 int cngp_bake_probes(const cngp_config *cfg, const float *Dhat_c, void *D_c, void *stream);
 
+/* Optimiser step fused with the bake (Fig. 3: the bake follows every training step).  The paper
+ * names no optimiser: this entry point ASSUMES Adam (Kingma & Ba 2015) without weight decay.
+ * For every entry of a table, with g = grad * grad_scale and t = step (the number of this step, >= 1):
+ *     m = beta1 * m + (1 - beta1) * g            v = beta2 * v + (1 - beta2) * g * g
+ *     theta -= lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+ * in fp32.  Then D_c[l][r] = argmax of the UPDATED row r of D^_c, with the rule of cngp_bake_probes.
+ * One launch; every array is read once and written once. */
+typedef struct cngp_adam {
+    float   lr, beta1, beta2;   /* lr >= 0; 0 <= beta < 1                                            */
+    float   eps;                /* > 0; with eps >= 1e-15 squares of gradients that underflow fp32
+                                   change the step by less than the tolerance of the parity tests   */
+    float   grad_scale;         /* e.g. 1 / loss scale; must be finite                               */
+    int32_t step;               /* t >= 1                                                            */
+} cngp_adam;
+
+/*   opt_f, opt_c   host; either may be NULL: that table is then left alone (with opt_c == NULL
+ *                  D_c is not written either) and its pointers are ignored
+ *   D_f_master     dev float32 [L, N_f, F]   parameters, updated in place
+ *   D_f            dev: with feat_dtype F16, receives the updated parameters rounded to fp16 (the array
+ *                  the forward and backward passes read); with F32 pass NULL or D_f_master itself
+ *   m_f, v_f       dev float32 [L, N_f, F]   moments, updated in place (zero before the first step)
+ *   grad_D_f       dev float32 [L, N_f, F]   read; set to zero afterwards if cfg->flags has CNGP_ZERO_GRADS
+ *   Dhat_c, m_c, v_c, grad_Dhat_c   dev float32 [L, N_c, N_p], likewise
+ *   D_c            dev, written in cfg->index_format
+ * All float arrays must be 16-byte aligned (D_f with F16: 8-byte), else CNGP_ERR_INVALID. */
+int cngp_adam_step_bake(const cngp_config *cfg, const cngp_adam *opt_f, const cngp_adam *opt_c,
+                        float *D_f_master, void *D_f, float *m_f, float *v_f, float *grad_D_f,
+                        float *Dhat_c, float *m_c, float *v_c, float *grad_Dhat_c, void *D_c,
+                        void *stream);
+
 /* Index dump for parity checks: for every (point, level, corner) the integers of Eq. 6.
  * All outputs dev, shape [N, L, 2^d]; any of them may be NULL.
  *   base      (N_p * hash(v)) mod N_f        h2        hash2(v) mod N_c

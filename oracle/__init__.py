@@ -131,3 +131,14 @@ def bake_probes(Dhat_c) -> np.ndarray:
     out = np.zeros(Dhat_c.shape[:-1], dtype=np.uint8)
     lib().cngp_oracle_bake_probes(_p(Dhat_c), ctypes.c_int64(rows), _u32(N_p), _p(out))
     return out
+
+
+def adam_step(theta, m, v, grad, lr, beta1, beta2, eps, t):
+    """One Adam step (assumed optimiser) in fp64.  Returns new (theta, m, v); inputs are not modified."""
+    theta = _f64(theta).copy(); m = _f64(m).copy(); v = _f64(v).copy(); grad = _f64(grad)
+    assert theta.shape == m.shape == v.shape == grad.shape and t >= 1
+    lib().cngp_oracle_adam_step(ctypes.c_int64(theta.size), ctypes.c_double(lr), ctypes.c_double(beta1),
+                                ctypes.c_double(beta2), ctypes.c_double(eps), ctypes.c_int(t),
+                                _p(theta), _p(m), _p(v), _p(grad))
+    return theta, m, v
+

@@ -246,3 +246,20 @@ void cngp_oracle_bake_probes(const float *Dhat_c, int64_t rows, uint32_t N_p, ui
         D_c[r] = (uint8_t)best;
     }
 }
+
+/* Optimiser step fused with the bake (Fig. 3 caption: the bake follows every training step).
+ * The paper does not name its optimiser; this build ASSUMES Adam (Kingma & Ba 2015: exponential
+ * moving averages m, v of the gradient and its square, bias-corrected by 1 - beta^t, update
+ * theta -= lr * m_hat / (sqrt(v_hat) + eps)), without weight decay, as in the hash-grid encoding the
+ * method builds on.  All arrays have n entries; t >= 1 is the step number; everything in fp64. */
+void cngp_oracle_adam_step(int64_t n, double lr, double beta1, double beta2, double eps, int t,
+                           double *theta, double *m, double *v, const double *grad)
+{
+    const double c1 = 1.0 - pow(beta1, (double)t), c2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        m[i] = beta1 * m[i] + (1.0 - beta1) * grad[i];
+        v[i] = beta2 * v[i] + (1.0 - beta2) * grad[i] * grad[i];
+        theta[i] -= lr * (m[i] / c1) / (sqrt(v[i] / c2) + eps);
+    }
+}
+

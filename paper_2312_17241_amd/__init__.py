@@ -64,6 +64,8 @@ def _load():
     lib.cngp_encode_bwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cngp_bake_probes.restype = ctypes.c_int
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
+    lib.cngp_adam_step_bake.restype = ctypes.c_int
+    lib.cngp_adam_step_bake.argtypes = [cfgp, vp, vp] + [vp] * 10 + [vp]
     lib.cngp_debug_indices.restype = ctypes.c_int
     lib.cngp_debug_indices.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.cngp_bwd_plan_info.restype = ctypes.c_int
@@ -226,6 +228,53 @@ def bake_probes(cfg: Config, Dhat_c, D_c=None):
         ctypes.byref(c), _dev(Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "Dhat_c"),
         _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c"), _stream()))
     return D_c
+
+
+class CAdam(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("grad_scale", ctypes.c_float), ("step", ctypes.c_int32)]
+
+
+@dataclass
+class Adam:
+    """Hyper-parameters of one table's optimiser step (cngp_adam)."""
+    lr: float = 1e-2
+    beta1: float = 0.9
+    beta2: float = 0.99
+    eps: float = 1e-15
+    grad_scale: float = 1.0
+    step: int = 1
+
+    def c(self):
+        return CAdam(self.lr, self.beta1, self.beta2, self.eps, self.grad_scale, self.step)
+
+
+def adam_step_bake(cfg: Config, opt_f, opt_c, features=None, logits=None):
+    """cngp_adam_step_bake.  `features` = (D_f_master, D_f, m_f, v_f, grad_D_f) with D_f None when the
+    codebook is stored as float32; `logits` = (Dhat_c, m_c, v_c, grad_Dhat_c, D_c).  Updates in place."""
+    c = cfg.c()
+    null = ctypes.c_void_p(0)
+    fa = [null] * 5
+    ca = [null] * 5
+    of = oc = None
+    if opt_f is not None:
+        master, D_f, m_f, v_f, g_f = features
+        shp = (cfg.L, cfg.N_f, cfg.F)
+        fa = [_dev(master, torch.float32, shp, "D_f_master"),
+              null if D_f is None else _dev(D_f, _TORCH_DT[cfg.feat_dtype], shp, "D_f"),
+              _dev(m_f, torch.float32, shp, "m_f"), _dev(v_f, torch.float32, shp, "v_f"),
+              _dev(g_f, torch.float32, shp, "grad_D_f")]
+        of = opt_f.c()
+    if opt_c is not None:
+        Dhat_c, m_c, v_c, g_c, D_c = logits
+        shp = (cfg.L, cfg.N_c, cfg.N_p)
+        ca = [_dev(Dhat_c, torch.float32, shp, "Dhat_c"), _dev(m_c, torch.float32, shp, "m_c"),
+              _dev(v_c, torch.float32, shp, "v_c"), _dev(g_c, torch.float32, shp, "grad_Dhat_c"),
+              _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c")]
+        oc = opt_c.c()
+    _check(_lib.cngp_adam_step_bake(
+        ctypes.byref(c), None if of is None else ctypes.cast(ctypes.byref(of), ctypes.c_void_p),
+        None if oc is None else ctypes.cast(ctypes.byref(oc), ctypes.c_void_p), *fa, *ca, _stream()))
 
 
 def debug_indices(cfg: Config, x, D_c):

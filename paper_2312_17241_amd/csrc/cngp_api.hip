@@ -4,6 +4,7 @@
 #include "cngp_kernels.h"
 #include "cngp_bwd_sliced.h"
 #include "cngp_rates.h"
+#include "cngp_optim.h"
 
 #include <cmath>
 #include <cstdio>
@@ -77,10 +78,11 @@ int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INV
 
 // ---------------------------------------------------------------- per-kernel timing
 enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_SLICED, K_BWD_SLICED_V,
-                K_BAKE, K_ZERO, K_DEBUG, K_COUNT };
+                K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_softmax_table",
                                            "encode_bwd_transpose_dy", "encode_bwd_sliced_points_and_grid",
-                                           "encode_bwd_sliced_vertices", "bake_probes", "zero", "debug_indices"};
+                                           "encode_bwd_sliced_vertices", "bake_probes", "zero", "debug_indices",
+                                           "adam_step_bake"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -476,6 +478,24 @@ int dispatch_bwd_np(const cngp_config *c, const Params &p, const BwdPlan &b, con
 }  // namespace
 
 // ==================================================================== exported C ABI
+namespace {
+int adam_coefficients(const cngp_adam *o, AdamCoef *a) {
+    if (!(o->lr >= 0.0f) || !std::isfinite(o->lr)) return CNGP_ERR_INVALID;
+    if (!(o->beta1 >= 0.0f && o->beta1 < 1.0f) || !(o->beta2 >= 0.0f && o->beta2 < 1.0f)) return CNGP_ERR_INVALID;
+    if (!(o->eps > 0.0f) || !std::isfinite(o->eps) || !std::isfinite(o->grad_scale) || o->step < 1) return CNGP_ERR_INVALID;
+    const double c1 = 1.0 - std::pow((double)o->beta1, (double)o->step);
+    const double c2 = 1.0 - std::pow((double)o->beta2, (double)o->step);
+    a->b1 = o->beta1;  a->one_minus_b1 = (float)(1.0 - (double)o->beta1);
+    a->b2 = o->beta2;  a->one_minus_b2 = (float)(1.0 - (double)o->beta2);
+    a->step = (float)((double)o->lr / c1);
+    a->rsqrt_c2 = (float)(1.0 / std::sqrt(c2));
+    a->eps = o->eps;
+    a->grad_scale = o->grad_scale;
+    return CNGP_OK;
+}
+bool aligned(const void *p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+}  // namespace
+
 extern "C" {
 
 int cngp_version(void) { return 100; }
@@ -585,6 +605,60 @@ int cngp_bake_probes(const cngp_config *cfg, const float *Dhat_c, void *D_c, voi
     }
 #undef CNGP_BAKE
     return launch_status("bake_probes_kernel");
+}
+
+int cngp_adam_step_bake(const cngp_config *cfg, const cngp_adam *opt_f, const cngp_adam *opt_c,
+                        float *D_f_master, void *D_f, float *m_f, float *v_f, float *grad_D_f,
+                        float *Dhat_c, float *m_c, float *v_c, float *grad_Dhat_c, void *D_c, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    AdamTable f, c;
+    std::memset(&f, 0, sizeof(f));
+    std::memset(&c, 0, sizeof(c));
+    __half *D_f_half = nullptr;
+    if (opt_f) {
+        if (!D_f_master || !m_f || !v_f || !grad_D_f) return CNGP_ERR_NULL;
+        if (int rc = adam_coefficients(opt_f, &f.a)) return rc;
+        if (cfg->feat_dtype == CNGP_F16) {
+            if (!D_f) return CNGP_ERR_NULL;
+            if (!aligned(D_f, 8)) return CNGP_ERR_INVALID;
+            D_f_half = (__half *)D_f;
+        } else if (D_f && D_f != (void *)D_f_master) {
+            return CNGP_ERR_INVALID;
+        }
+        if (!aligned(D_f_master, 16) || !aligned(m_f, 16) || !aligned(v_f, 16) || !aligned(grad_D_f, 16)) return CNGP_ERR_INVALID;
+        f.theta = D_f_master; f.m = m_f; f.v = v_f; f.grad = grad_D_f;
+        f.n = (int64_t)cfg->L * cfg->N_f * cfg->F;
+    }
+    if (opt_c) {
+        if (!Dhat_c || !m_c || !v_c || !grad_Dhat_c || !D_c) return CNGP_ERR_NULL;
+        if (int rc = adam_coefficients(opt_c, &c.a)) return rc;
+        if (!aligned(Dhat_c, 16) || !aligned(m_c, 16) || !aligned(v_c, 16) || !aligned(grad_Dhat_c, 16)) return CNGP_ERR_INVALID;
+        c.theta = Dhat_c; c.m = m_c; c.v = v_c; c.grad = grad_Dhat_c;
+        c.n = (int64_t)cfg->L * cfg->N_c * cfg->N_p;
+    }
+    const int64_t per_block = (int64_t)kOptBlock * 4;
+    const int64_t blocks_f = (f.n + per_block - 1) / per_block;
+    const int64_t blocks_c = (c.n + per_block - 1) / per_block;
+    if (blocks_f + blocks_c == 0) return CNGP_OK;
+    if (int rc = check_blocks(blocks_f + blocks_c)) return rc;
+    const bool packed = cfg->index_format == CNGP_IDX_PACKED4;
+    const int  clear = (cfg->flags & CNGP_ZERO_GRADS) ? 1 : 0;
+    hipStream_t s = (hipStream_t)stream;
+    LaunchTimer t(s, K_ADAM);
+#define CNGP_ADAM(NP)                                                                                   \
+    if (packed) adam_step_bake_kernel<NP, true><<<(unsigned)(blocks_f + blocks_c), kOptBlock, 0, s>>>(  \
+                    f, c, D_f_half, (uint8_t *)D_c, (uint32_t)blocks_f, clear);                         \
+    else        adam_step_bake_kernel<NP, false><<<(unsigned)(blocks_f + blocks_c), kOptBlock, 0, s>>>( \
+                    f, c, D_f_half, (uint8_t *)D_c, (uint32_t)blocks_f, clear)
+    switch (cfg->N_p) {
+    case 1:  CNGP_ADAM(1); break;
+    case 2:  CNGP_ADAM(2); break;
+    case 4:  CNGP_ADAM(4); break;
+    case 8:  CNGP_ADAM(8); break;
+    default: CNGP_ADAM(16); break;
+    }
+#undef CNGP_ADAM
+    return launch_status("adam_step_bake_kernel");
 }
 
 int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const void *D_c, uint32_t *base,

@@ -108,6 +108,41 @@ def test_null_pointers_and_negative_counts():
     assert lib.cngp_level_resolutions(ctypes.byref(c), None) == cngp.ERR_NULL
 
 
+def test_adam_step_bake_rejects_bad_arguments():
+    """Every check of the optimiser entry point runs on the host before anything is launched."""
+    lib = ctypes.CDLL(cngp.LIB_PATH)
+    c = base_cfg().c()                                   # nerf3d: fp16 feature storage
+    a = ctypes.c_void_p(4096)                            # an aligned, never dereferenced address
+    ok = cngp.Adam().c()
+    feats = [a, a, a, a, a]
+    logits = [a, a, a, a, a]
+
+    def call(cfg, of, oc, f=feats, l=logits):
+        ref = lambda o: None if o is None else ctypes.cast(ctypes.byref(o), ctypes.c_void_p)
+        return lib.cngp_adam_step_bake(ctypes.byref(cfg), ref(of), ref(oc), *f, *l, None)
+
+    assert call(c, None, None) == cngp.OK                # nothing to do
+    for bad in (dict(lr=-1.0), dict(lr=float("nan")), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0),
+                dict(step=0), dict(grad_scale=float("inf"))):
+        assert call(c, cngp.Adam(**bad).c(), None) == cngp.ERR_INVALID, bad
+        assert call(c, None, cngp.Adam(**bad).c()) == cngp.ERR_INVALID, bad
+    for i in range(5):
+        f = list(feats); f[i] = None
+        assert call(c, ok, None, f=f) == cngp.ERR_NULL, i
+        l = list(logits); l[i] = None
+        assert call(c, None, ok, l=l) == cngp.ERR_NULL, i
+    for i in (0, 2, 3, 4):                               # misaligned float arrays
+        f = list(feats); f[i] = ctypes.c_void_p(4100)
+        assert call(c, ok, None, f=f) == cngp.ERR_INVALID, i
+    for i in range(4):
+        l = list(logits); l[i] = ctypes.c_void_p(4104)
+        assert call(c, None, ok, l=l) == cngp.ERR_INVALID, i
+    c32 = base_cfg(feat_dtype=cngp.F32).c()              # fp32 storage: D_f is NULL or the master itself
+    assert call(c32, ok, None, f=[a, ctypes.c_void_p(8192), a, a, a]) == cngp.ERR_INVALID
+    bad_cfg = base_cfg(N_p=3).c()
+    assert call(bad_cfg, ok, ok) == cngp.ERR_INVALID
+
+
 def test_backward_plan_is_reported_on_the_host():
     """The plan needs no GPU: benchmark shapes take the LDS-sliced variant with pre-reduced coarse levels,
     a tiny batch takes global atomics, and the flags override the choice."""

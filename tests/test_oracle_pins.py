@@ -412,6 +412,46 @@ def test_bake_ties_and_nan():
     assert oracle.bake_probes(rows).tolist() == [0, 1, 1, 0, 0, 2]
 
 
+# --------------------------------------------------------------------------- optimiser step (assumed: Adam)
+
+def test_adam_closed_forms():
+    rng = np.random.default_rng(41)
+    g = rng.standard_normal(64); theta = rng.standard_normal(64); z = np.zeros(64)
+    lr, b1, b2, eps = 1e-2, 0.9, 0.99, 1e-8
+    # first step from zero state: m_hat = g, v_hat = g^2, so the step is lr * g / (|g| + eps)
+    t1, m1, v1 = oracle.adam_step(theta, z, z, g, lr, b1, b2, eps, 1)
+    assert np.allclose(t1, theta - lr * g / (np.abs(g) + eps), rtol=0, atol=1e-15)
+    assert np.allclose(m1, (1 - b1) * g) and np.allclose(v1, (1 - b2) * g * g)
+    # constant gradient: bias correction makes every step identical
+    th, m, v = theta, z, z
+    for t in range(1, 8):
+        th, m, v = oracle.adam_step(th, m, v, g, lr, b1, b2, eps, t)
+    assert np.allclose(th, theta - 7 * lr * g / (np.abs(g) + eps), rtol=0, atol=1e-13)
+    # zero gradient, zero state: nothing moves; eps = 0: the step is invariant to the gradient's scale
+    t0, m0, v0 = oracle.adam_step(theta, z, z, np.zeros(64), lr, b1, b2, eps, 3)
+    assert np.array_equal(t0, theta) and not m0.any() and not v0.any()
+    a = oracle.adam_step(theta, z, z, g, lr, b1, b2, 0.0, 1)[0]
+    b = oracle.adam_step(theta, z, z, 1000.0 * g, lr, b1, b2, 0.0, 1)[0]
+    assert np.allclose(a, b, rtol=0, atol=1e-15)
+
+
+def test_adam_matches_library_optimiser():
+    """Several steps with changing gradients against torch.optim.Adam in fp64."""
+    import torch
+    rng = np.random.default_rng(43)
+    theta0 = rng.standard_normal(200)
+    lr, b1, b2, eps = 3e-3, 0.9, 0.99, 1e-15
+    par = torch.nn.Parameter(torch.tensor(theta0, dtype=torch.float64))
+    opt = torch.optim.Adam([par], lr=lr, betas=(b1, b2), eps=eps)
+    th, m, v = theta0, np.zeros(200), np.zeros(200)
+    for t in range(1, 6):
+        g = rng.standard_normal(200) * (10.0 ** rng.integers(-4, 2))
+        par.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        th, m, v = oracle.adam_step(th, m, v, g, lr, b1, b2, eps, t)
+        assert np.allclose(th, par.detach().numpy(), rtol=1e-12, atol=1e-14)
+
+
 # --------------------------------------------------------------------------- storage conventions
 
 def test_model_sizes_consistent_with_table_3():
