@@ -38,6 +38,9 @@ def algorithmic_bytes(w, n):
         "encode_bwd": pts + D_f + Dhat + gD_f + Dhat,
         "bake_probes": Dhat + D_c,
         "zero": gD_f + Dhat,
+        # parameters, two moments and the gradient read, the first three written, for both tables;
+        # plus the storage copy of D_f when that is fp16, plus D_c
+        "adam_step_bake": 7 * (gD_f + Dhat) + (D_f if fb == 2 else 0) + D_c,
     }
 
 
@@ -47,6 +50,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="nerf3d", help="nerf3d (headline) | image2d | sdf3d | tiny2d | infer3d")
+    ap.add_argument("--with-optimizer", action="store_true",
+                    help="a step becomes: Adam step fused with the bake (replaces the bake), forward, backward; "
+                         "the tables then change from step to step.  Not the headline configuration.")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -90,8 +96,26 @@ def main():
         gF = torch.empty((w.L, w.N_f, w.F), dtype=torch.float32, device=dev)
         gC = torch.empty((w.L, w.N_c, w.N_p), dtype=torch.float32, device=dev)
 
+    with_opt = args.with_optimizer and not fwd_only
+    if with_opt:
+        half = w.feat_dtype == "f16"
+        master = D_f.float()
+        D_f_arg = D_f if half else None
+        if not half:
+            D_f = master
+        moments = [torch.zeros_like(master), torch.zeros_like(master), torch.zeros_like(Dhat), torch.zeros_like(Dhat)]
+        gF.zero_(); gC.zero_()
+        cfg_opt = cngp.Config.from_workload(w, index_format=fmt)
+        n_step = [0]
+
     def step():
-        cngp.bake_probes(cfg, Dhat, D_c)
+        if with_opt:
+            n_step[0] += 1
+            opt = cngp.Adam(lr=1e-3, beta1=0.9, beta2=0.99, eps=1e-15, step=n_step[0])
+            cngp.adam_step_bake(cfg_opt, opt, opt, (master, D_f_arg, moments[0], moments[1], gF),
+                                (Dhat, moments[2], moments[3], gC, D_c))
+        else:
+            cngp.bake_probes(cfg, Dhat, D_c)
         cngp.encode_fwd(cfg, x, D_f, D_c, y, workspace=ws)
         if not fwd_only:
             cngp.encode_bwd(cfg, x, D_f, Dhat, dy, gF, gC, workspace=ws)
@@ -149,7 +173,9 @@ def main():
         "config": {"workload": f"{w.name}: d={w.d} L={w.L} F={w.F} N_f={w.N_f} N_c={w.N_c} N_p={w.N_p} "
                                f"N_min={w.N_min} N_max={w.N_max} points={N} ({w.points}) "
                                f"D_f={w.feat_dtype} y/dy={w.io_dtype}",
-                   "step": "bake + fwd" if fwd_only else "bake + fwd + bwd (grads cleared each step)"},
+                   "step": "bake + fwd" if fwd_only else
+                           ("Adam step fused with bake + fwd + bwd (grads cleared each step)" if with_opt else
+                            "bake + fwd + bwd (grads cleared each step)")},
         "roofline": roofline,
         "kernels_us_per_step": {k: round(v["ms"] * 1e3 / args.steps, 2) for k, v in per_kernel.items()},
         "kernel_parts": {k: v["parts"] for k, v in per_kernel.items() if len(v["parts"]) > 1},
@@ -176,6 +202,18 @@ def main():
             "unit": "G updates/s", "frac": round(updates / t_bwd / 1e9 / rates["lds_atomic_f64_Gps"], 3),
             "global_atomic_floor_ms": round(updates / 16 / rates["global_atomic_Gseg"] / 1e6, 3),
             "measured_ms": round(t_bwd * 1e3, 3)}
+
+    if with_opt:
+        t_opt = per_kernel["adam_step_bake"]["ms"] / args.steps * 1e-3
+        out["optimizer_roofline"] = {"bound": "hbm", "kernel": "adam_step_bake",
+                                     "achieved": round(alg["adam_step_bake"] / t_opt / 1e9, 1), "peak": HBM_PEAK_GBS,
+                                     "unit": "GB/s", "frac": round(alg["adam_step_bake"] / t_opt / 1e9 / HBM_PEAK_GBS, 4),
+                                     "algorithmic_bytes_per_launch": alg["adam_step_bake"],
+                                     "avg_launch_us": round(t_opt * 1e6, 2)}
+        # the tables moved: the self-check below compares against the oracle on their final state, which is
+        # the state the last forward and backward pass of the timed loop ran on
+        D_f_h = D_f.cpu().numpy()
+        Dhat_h = Dhat.cpu().numpy()
 
     if not args.no_check or not args.no_cpu_baseline:
         import oracle
