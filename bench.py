@@ -23,13 +23,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
 
-def algorithmic_bytes(w, n):
+def algorithmic_bytes(w, n, index_level_bytes=None):
     """Compulsory HBM bytes per launch of each kernel kind: every input read once, every output
     written once (tables included; random re-reads of cached rows are not algorithmic)."""
     fb = 2 if w.feat_dtype == "f16" else 4
     iob = 2 if w.io_dtype == "f16" else 4
     D_f = w.L * w.N_f * w.F * fb
-    D_c = w.L * w.N_c
+    D_c = w.L * (w.N_c if index_level_bytes is None else index_level_bytes)
     Dhat = w.L * w.N_c * w.N_p * 4
     gD_f = w.L * w.N_f * w.F * 4
     pts = n * (4 * w.d + w.L * w.F * iob)
@@ -49,7 +49,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="nerf3d", help="nerf3d (headline) | image2d | sdf3d | tiny2d | infer3d")
+    ap.add_argument("--workload", default="nerf3d", help="nerf3d (headline) | image2d | sdf3d | tiny2d | infer3d | compact3d")
     ap.add_argument("--with-optimizer", action="store_true",
                     help="a step becomes: Adam step fused with the bake (replaces the bake), forward, backward; "
                          "the tables then change from step to step.  Not the headline configuration.")
@@ -76,8 +76,8 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     w = W.WORKLOADS[args.workload]
-    fwd_only = args.workload == "infer3d"
-    fmt = cngp.IDX_PACKED4 if fwd_only else cngp.IDX_U8
+    fwd_only = args.workload in ("infer3d", "compact3d")
+    fmt = {"infer3d": cngp.IDX_PACKED4, "compact3d": cngp.IDX_BITS}.get(args.workload, cngp.IDX_U8)
     cfg = cngp.Config.from_workload(w, index_format=fmt, flags=cngp.ZERO_GRADS)
 
     x_h = W.make_points(w)
@@ -146,7 +146,7 @@ def main():
     value = N * args.steps / (t1 - t0)
 
     # roofline of the dominant kernel kind
-    alg = algorithmic_bytes(w, N)
+    alg = algorithmic_bytes(w, N, cfg.index_cols)
     per_kernel = {}
     for name, (ms, cnt) in kernels.items():
         kind = "encode_bwd" if name.startswith("encode_bwd") else name
@@ -236,8 +236,11 @@ def main():
                                              + ("" if fwd_only else " + bwd") + f", {t_cpu:.2f} s"}
         if not args.no_check:
             # self-check of the timed configuration against the oracle (same launch configuration)
-            unpack = D_c if fmt == cngp.IDX_U8 else torch.stack([D_c & 0xF, D_c >> 4], dim=-1).reshape(w.L, w.N_c)
-            check_exact("D_c", unpack.cpu().numpy(), D_c_ref)
+            if fmt == cngp.IDX_BITS:
+                check_exact("D_c", D_c.cpu().numpy(), oracle.pack_index_bits(D_c_ref, w.N_p))
+            else:
+                unpack = D_c if fmt == cngp.IDX_U8 else torch.stack([D_c & 0xF, D_c >> 4], dim=-1).reshape(w.L, w.N_c)
+                check_exact("D_c", unpack.cpu().numpy(), D_c_ref)
             e = {"y": check_close("y", y[:n_cpu].cpu().numpy(), y_ref, ymag, fp16_out=(w.io_dtype == "f16"))}
             if not fwd_only and n_cpu == N:
                 e["grad_D_f"] = check_close("grad D_f", gF.cpu().numpy(), g_ref[0], g_ref[2], fp16_out=False)

@@ -50,8 +50,17 @@ typedef enum { CNGP_F32 = 0, CNGP_F16 = 1 } cngp_dtype;
 /* Layout of the baked index codebook D_c.
  *   CNGP_IDX_U8      one byte per entry, [L, N_c]
  *   CNGP_IDX_PACKED4 two entries per byte, [L, N_c / 2]; entry 2i is the low nibble of byte i.
- *                    Needs N_c >= 2 (N_p <= 16 always fits four bits). */
-typedef enum { CNGP_IDX_U8 = 0, CNGP_IDX_PACKED4 = 1 } cngp_index_format;
+ *                    Needs N_c >= 2 (N_p <= 16 always fits four bits).
+ *   CNGP_IDX_BITS    exact width, the storage the model sizes of Tables 3 and 4 imply: with
+ *                    b = log2(N_p), entry r of a level is bits [r * b, (r + 1) * b) of that level's
+ *                    bit string, least significant bit first within little-endian 32-bit words.
+ *                    Every level starts on a 4-byte boundary: consecutive levels are
+ *                    4 * ceil(N_c * b / 32) bytes apart, padding bits are zero when the library writes
+ *                    them and ignored when it reads; the array must be 4-byte aligned.  N_p = 1
+ *                    stores nothing (the pointer may be NULL).  Read by cngp_encode_fwd and
+ *                    cngp_debug_indices, written by cngp_bake_probes; the optimiser step does not
+ *                    take it (CNGP_ERR_UNSUPPORTED): training keeps one of the two formats above. */
+typedef enum { CNGP_IDX_U8 = 0, CNGP_IDX_PACKED4 = 1, CNGP_IDX_BITS = 2 } cngp_index_format;
 
 /* cngp_config.flags */
 enum {
@@ -83,6 +92,10 @@ typedef struct {
  * N_l = floor(N_min * b^l + 1e-6), b = exp(ln(N_max / N_min) / (L - 1)); L == 1 gives N_min.
  * out_N_l: host, L entries.  Runs on the host. */
 int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l);
+
+/* Bytes of the stored model (Tables 3 and 4 count these): D_f in feat_dtype, D_c in index_format
+ * (per level, i.e. the distance between consecutive levels, and in total).  Any output may be NULL.  Host only. */
+int cngp_storage_bytes(const cngp_config *cfg, size_t *D_f_bytes, size_t *D_c_level_bytes, size_t *D_c_bytes);
 
 /* Bytes of device scratch the calls below need for N points (may be 0).  The workspace
  * must be 256-byte aligned; its contents are undefined before and after each call.

@@ -142,3 +142,38 @@ def adam_step(theta, m, v, grad, lr, beta1, beta2, eps, t):
                                 _p(theta), _p(m), _p(v), _p(grad))
     return theta, m, v
 
+
+def pack_index_bits(D_c, N_p):
+    """Exact-width storage of a baked index codebook [L, N_c] (the storage the model sizes of Tables 3 and 4
+    imply: log2(N_p) bits per entry): entry r of a level occupies bits [r b, (r + 1) b) of the level's bit
+    string, least significant bit first; each level is padded with zero bits to a whole number of 32-bit
+    words.  Returns uint8 [L, 4 * ceil(N_c b / 32)]."""
+    D_c = np.asarray(D_c, dtype=np.uint8)
+    L, N_c = D_c.shape
+    b = int(N_p).bit_length() - 1
+    nbytes = 4 * ((N_c * b + 31) // 32)
+    full = np.zeros((L, nbytes * 8), np.uint8)
+    if b:
+        full[:, :N_c * b] = ((D_c[..., None] >> np.arange(b, dtype=np.uint8)) & 1).reshape(L, N_c * b)
+    return np.packbits(full, axis=1, bitorder="little") if nbytes else np.zeros((L, 0), np.uint8)
+
+
+def unpack_index_bits(packed, N_c, N_p):
+    """Inverse of pack_index_bits."""
+    packed = np.asarray(packed, dtype=np.uint8)
+    L = packed.shape[0]
+    b = int(N_p).bit_length() - 1
+    if b == 0:
+        return np.zeros((L, N_c), np.uint8)
+    bits = np.unpackbits(packed, axis=1, bitorder="little")[:, :N_c * b].reshape(L, N_c, b)
+    return (bits.astype(np.uint32) << np.arange(b, dtype=np.uint32)).sum(axis=-1).astype(np.uint8)
+
+
+def storage_bytes(w, index_bits_exact=True):
+    """Bytes of the stored model: F-wide features per entry in the workload's feature type, index codebook
+    at log2(N_p) bits per entry (levels padded to 32-bit words) or one byte per entry."""
+    fb = 2 if w.feat_dtype == "f16" else 4
+    b = int(w.N_p).bit_length() - 1
+    level = 4 * ((w.N_c * b + 31) // 32) if index_bits_exact else w.N_c
+    return {"D_f": w.L * w.N_f * w.F * fb, "D_c_level": level, "D_c": w.L * level}
+

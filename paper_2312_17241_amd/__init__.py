@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcngp.so")
 
 F32, F16 = 0, 1
-IDX_U8, IDX_PACKED4 = 0, 1
+IDX_U8, IDX_PACKED4, IDX_BITS = 0, 1, 2
 ZERO_GRADS, BWD_DIRECT, BWD_SLICED, BWD_NO_PREREDUCE, FWD_SIMPLE = 1, 2, 4, 8, 16
 
 OK, ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
@@ -64,6 +64,8 @@ def _load():
     lib.cngp_encode_bwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cngp_bake_probes.restype = ctypes.c_int
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
+    lib.cngp_storage_bytes.restype = ctypes.c_int
+    lib.cngp_storage_bytes.argtypes = [cfgp, vp, vp, vp]
     lib.cngp_adam_step_bake.restype = ctypes.c_int
     lib.cngp_adam_step_bake.argtypes = [cfgp, vp, vp] + [vp] * 10 + [vp]
     lib.cngp_debug_indices.restype = ctypes.c_int
@@ -117,6 +119,9 @@ class Config:
 
     @property
     def index_cols(self) -> int:
+        """Bytes per level of the index codebook in this configuration's format."""
+        if self.index_format == IDX_BITS:
+            return 4 * ((self.N_c * (self.N_p.bit_length() - 1) + 31) // 32)
         return self.N_c // 2 if self.index_format == IDX_PACKED4 else self.N_c
 
 
@@ -165,6 +170,14 @@ def level_resolutions(cfg: Config) -> np.ndarray:
     return out[:cfg.L]
 
 
+def storage_bytes(cfg: Config) -> dict:
+    """Bytes of the stored model: D_f in feat_dtype, D_c per level and in total in index_format."""
+    a, b, t = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    c = cfg.c()
+    _check(_lib.cngp_storage_bytes(ctypes.byref(c), ctypes.byref(a), ctypes.byref(b), ctypes.byref(t)))
+    return {"D_f": a.value, "D_c_level": b.value, "D_c": t.value}
+
+
 def workspace_bytes(cfg: Config, N: int) -> int:
     c = cfg.c()
     return int(_lib.cngp_workspace_bytes(ctypes.byref(c), N))
@@ -197,7 +210,7 @@ def encode_fwd(cfg: Config, x, D_f, D_c, y=None, workspace=None):
     _check(_lib.cngp_encode_fwd(
         ctypes.byref(c), _dev(x, torch.float32, (N, cfg.d), "x"), N,
         _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"),
-        _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c"),
+        _dc(cfg, D_c),
         _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), wp, wb, _stream()))
     return y
 
@@ -226,7 +239,7 @@ def bake_probes(cfg: Config, Dhat_c, D_c=None):
     c = cfg.c()
     _check(_lib.cngp_bake_probes(
         ctypes.byref(c), _dev(Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "Dhat_c"),
-        _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c"), _stream()))
+        _dc(cfg, D_c), _stream()))
     return D_c
 
 
@@ -288,7 +301,7 @@ def debug_indices(cfg: Config, x, D_c):
     c = cfg.c()
     _check(_lib.cngp_debug_indices(
         ctypes.byref(c), _dev(x, torch.float32, (N, cfg.d), "x"), N,
-        _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c"),
+        _dc(cfg, D_c),
         ctypes.c_void_p(base.data_ptr()), ctypes.c_void_p(h2.data_ptr()),
         ctypes.c_void_p(probe.data_ptr()), ctypes.c_void_p(fidx.data_ptr()), _stream()))
     return base, h2, probe, fidx
@@ -319,6 +332,27 @@ def profile_read() -> dict:
     cnt = (ctypes.c_int64 * n)()
     k = _lib.cngp_profile_read(ms, cnt, n)
     return {_lib.cngp_profile_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(min(k, n)) if cnt[i]}
+
+
+def _dc(cfg, D_c):
+    """Device pointer of an index codebook; the exact-width format of N_p = 1 has no bytes (NULL)."""
+    if cfg.index_format == IDX_BITS and cfg.N_p == 1:
+        return ctypes.c_void_p(0)
+    return _dev(D_c, torch.uint8, (cfg.L, cfg.index_cols), "D_c")
+
+
+def pack_bits(D_c_u8, N_p):
+    """Repack a [L, N_c] uint8 index codebook into the exact-width layout (log2(N_p) bits per entry, least
+    significant bit first, each level padded to whole 32-bit words).  Pure data movement with torch ops."""
+    b = int(N_p).bit_length() - 1
+    L, N_c = D_c_u8.shape
+    nbytes = 4 * ((N_c * b + 31) // 32)
+    if b == 0:
+        return torch.empty((L, 0), dtype=torch.uint8, device=D_c_u8.device)
+    bits = ((D_c_u8.to(torch.int32).unsqueeze(-1) >> torch.arange(b, device=D_c_u8.device)) & 1).reshape(L, N_c * b)
+    pad = torch.zeros((L, nbytes * 8 - N_c * b), dtype=torch.int32, device=D_c_u8.device)
+    bits = torch.cat([bits, pad], dim=1).reshape(L, nbytes, 8)
+    return (bits << torch.arange(8, device=D_c_u8.device)).sum(dim=-1).to(torch.uint8).contiguous()
 
 
 def pack4(D_c_u8):

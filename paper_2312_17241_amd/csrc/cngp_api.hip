@@ -44,7 +44,7 @@ int validate(const cngp_config *c) {
     if (c->N_min > (1u << 24)) return CNGP_ERR_INVALID;
     if (c->feat_dtype != CNGP_F32 && c->feat_dtype != CNGP_F16) return CNGP_ERR_INVALID;
     if (c->io_dtype != CNGP_F32 && c->io_dtype != CNGP_F16) return CNGP_ERR_INVALID;
-    if (c->index_format != CNGP_IDX_U8 && c->index_format != CNGP_IDX_PACKED4) return CNGP_ERR_INVALID;
+    if (c->index_format != CNGP_IDX_U8 && c->index_format != CNGP_IDX_PACKED4 && c->index_format != CNGP_IDX_BITS) return CNGP_ERR_INVALID;
     if (c->index_format == CNGP_IDX_PACKED4 && c->N_c < 2) return CNGP_ERR_INVALID;
     if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE | CNGP_FWD_SIMPLE)) return CNGP_ERR_INVALID;
     if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & CNGP_BWD_SLICED)) return CNGP_ERR_INVALID;
@@ -73,6 +73,15 @@ Params make_params(const cngp_config *c) {
     p.log2_Np = ilog2(c->N_p);
     return p;
 }
+
+// Bytes between the index codebooks of consecutive levels.
+size_t index_level_bytes(const cngp_config *c) {
+    if (c->index_format == CNGP_IDX_PACKED4) return c->N_c / 2;
+    if (c->index_format == CNGP_IDX_BITS) return 4 * (((size_t)c->N_c * ilog2(c->N_p) + 31) / 32);
+    return c->N_c;
+}
+// The exact-width format of a codebook with N_p = 1 has no bytes at all: its pointer may be NULL.
+bool index_codebook_is_empty(const cngp_config *c) { return c->index_format == CNGP_IDX_BITS && c->N_p == 1; }
 
 int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INVALID : CNGP_OK; }
 
@@ -130,36 +139,59 @@ struct ZeroList {
     }
 };
 
+template <typename K>
+int allow_big_lds(K kernel, size_t bytes) {
+    if (bytes <= 64 * 1024) return CNGP_OK;
+    hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    return e == hipSuccess ? CNGP_OK : hip_fail(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+}
+
 template <int D, typename FeatT, typename IoT>
 int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
                const void *D_c, void *y, hipStream_t s) {
     // tile variant: one level's index codebook and the tile's outputs fit in LDS
-    const bool   packed = c->index_format == CNGP_IDX_PACKED4;
-    const size_t c_stride = packed ? c->N_c / 2 : c->N_c;
-    const size_t lds = ((((size_t)c->N_c + 1) / 2 + 15) & ~(size_t)15) + (size_t)kFwdTile * c->L * 2 * sizeof(IoT);
+    const size_t c_stride = index_level_bytes(c);
+    const int    fmt = c->index_format;
+    const size_t lds_probes = (((size_t)c->N_c + 1) / 2 + 15) & ~(size_t)15;
+    const size_t lds = lds_probes + (size_t)kFwdTile * c->L * 2 * sizeof(IoT);
+    const size_t lds_large = lds_probes + (size_t)kFwdTileLarge * c->L * 2 * sizeof(IoT);
     if (lds <= 64 * 1024 && N >= kFwdTile && !(c->flags & CNGP_FWD_SIMPLE)) {
-        const int64_t blocks = (N + kFwdTile - 1) / kFwdTile;
+        // Staging a level's codebook costs c_stride bytes per workgroup; a tile looks up TILE * 2^d entries.
+        // When the staging outweighs the lookups of a small tile and there are points enough to keep every
+        // CU busy with large ones, take the large tile.
+        const bool large = c_stride >= 8192 && lds_large <= 128 * 1024 && N >= (int64_t)kFwdTileLarge * 1024;
+        const int  tile = large ? kFwdTileLarge : kFwdTile;
+        const int64_t blocks = (N + tile - 1) / tile;
         if (int rc = check_blocks(blocks)) return rc;
         const int vec = (c_stride % 16 == 0 && ((uintptr_t)D_c & 15u) == 0) ? 1 : 0;
-        LaunchTimer t(s, K_FWD);
-        if (packed)
-            encode_fwd_tile_kernel<D, FeatT, IoT, true><<<(unsigned)blocks, kFwdTile, lds, s>>>(
-                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec);
-        else
-            encode_fwd_tile_kernel<D, FeatT, IoT, false><<<(unsigned)blocks, kFwdTile, lds, s>>>(
-                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec);
+#define CNGP_FWD_TILE(FMT, TILE, LDS)                                                                   \
+        do {                                                                                            \
+            auto kernel = encode_fwd_tile_kernel<D, FeatT, IoT, FMT, TILE>;                             \
+            if (int rc = allow_big_lds(kernel, LDS)) return rc;                                         \
+            LaunchTimer t(s, K_FWD);                                                                    \
+            kernel<<<(unsigned)blocks, TILE, LDS, s>>>(                                                 \
+                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec);  \
+        } while (0)
+#define CNGP_FWD_TILE_FMT(FMT)                                                                          \
+        if (large) CNGP_FWD_TILE(FMT, kFwdTileLarge, lds_large); else CNGP_FWD_TILE(FMT, kFwdTile, lds)
+        if (fmt == CNGP_IDX_PACKED4) { CNGP_FWD_TILE_FMT(kFmtPacked4); }
+        else if (fmt == CNGP_IDX_BITS) { CNGP_FWD_TILE_FMT(kFmtBits); }
+        else { CNGP_FWD_TILE_FMT(kFmtU8); }
+#undef CNGP_FWD_TILE_FMT
+#undef CNGP_FWD_TILE
         return launch_status("encode_fwd_tile_kernel");
     }
     const int64_t pairs = N * c->L;
     const int64_t blocks = (pairs + kBlock - 1) / kBlock;
     if (int rc = check_blocks(blocks)) return rc;
     LaunchTimer t(s, K_FWD);
-    if (c->index_format == CNGP_IDX_PACKED4)
-        encode_fwd_kernel<D, FeatT, IoT, true><<<(unsigned)blocks, kBlock, 0, s>>>(
-            p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, pairs);
-    else
-        encode_fwd_kernel<D, FeatT, IoT, false><<<(unsigned)blocks, kBlock, 0, s>>>(
-            p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, pairs);
+#define CNGP_FWD_SIMPLE_LAUNCH(FMT)                                                                     \
+    encode_fwd_kernel<D, FeatT, IoT, FMT><<<(unsigned)blocks, kBlock, 0, s>>>(                          \
+        p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, pairs, (uint32_t)c_stride)
+    if (fmt == CNGP_IDX_PACKED4) CNGP_FWD_SIMPLE_LAUNCH(kFmtPacked4);
+    else if (fmt == CNGP_IDX_BITS) CNGP_FWD_SIMPLE_LAUNCH(kFmtBits);
+    else CNGP_FWD_SIMPLE_LAUNCH(kFmtU8);
+#undef CNGP_FWD_SIMPLE_LAUNCH
     return launch_status("encode_fwd_kernel");
 }
 
@@ -372,13 +404,6 @@ int launch_transpose_dy(const cngp_config *c, const void *dy, void *dyT, int64_t
     return launch_status("transpose_dy_kernel");
 }
 
-template <typename K>
-int allow_big_lds(K kernel, size_t bytes) {
-    if (bytes <= 64 * 1024) return CNGP_OK;
-    hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    return e == hipSuccess ? CNGP_OK : hip_fail(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
-}
-
 template <int D, int NP, typename FeatT, typename IoT>
 int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, const float *x, int64_t N,
                       const void *D_f, const float *Dhat_c, const void *dy, float *gD_f, float *gDhat_c,
@@ -545,7 +570,8 @@ int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     if (int rc = validate(cfg)) return rc;
     if (N < 0) return CNGP_ERR_INVALID;
     if (N == 0) return CNGP_OK;
-    if (!x || !D_f || !D_c || !y) return CNGP_ERR_NULL;
+    if (!x || !D_f || !y || (!D_c && !index_codebook_is_empty(cfg))) return CNGP_ERR_NULL;
+    if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
     (void)workspace; (void)workspace_bytes;
     const Params p = make_params(cfg);
     hipStream_t s = (hipStream_t)stream;
@@ -583,15 +609,42 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     CNGP_DISPATCH_TYPES(dispatch_bwd_np, cfg, p, b, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, workspace, s);
 }
 
+int cngp_storage_bytes(const cngp_config *cfg, size_t *D_f_bytes, size_t *D_c_level_bytes, size_t *D_c_bytes) {
+    if (int rc = validate(cfg)) return rc;
+    const size_t level = index_level_bytes(cfg);
+    if (D_f_bytes) *D_f_bytes = (size_t)cfg->L * cfg->N_f * cfg->F * (cfg->feat_dtype == CNGP_F16 ? 2 : 4);
+    if (D_c_level_bytes) *D_c_level_bytes = level;
+    if (D_c_bytes) *D_c_bytes = level * cfg->L;
+    return CNGP_OK;
+}
+
 int cngp_bake_probes(const cngp_config *cfg, const float *Dhat_c, void *D_c, void *stream) {
     if (int rc = validate(cfg)) return rc;
+    if (index_codebook_is_empty(cfg)) return Dhat_c ? CNGP_OK : CNGP_ERR_NULL;       // nothing to write
     if (!Dhat_c || !D_c) return CNGP_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (cfg->index_format == CNGP_IDX_BITS) {
+        if ((uintptr_t)D_c & 3u) return CNGP_ERR_INVALID;
+        const uint32_t wpl = (uint32_t)(index_level_bytes(cfg) / 4);
+        const int64_t  words = (int64_t)cfg->L * wpl;
+        const int64_t  blocks = (words + kBlock - 1) / kBlock;
+        if (int rc = check_blocks(blocks)) return rc;
+        LaunchTimer t(s, K_BAKE);
+#define CNGP_BAKE_BITS(NP) bake_probes_bits_kernel<NP><<<(unsigned)blocks, kBlock, 0, s>>>(Dhat_c, (uint32_t *)D_c, cfg->N_c, wpl, words)
+        switch (cfg->N_p) {
+        case 2:  CNGP_BAKE_BITS(2); break;
+        case 4:  CNGP_BAKE_BITS(4); break;
+        case 8:  CNGP_BAKE_BITS(8); break;
+        default: CNGP_BAKE_BITS(16); break;
+        }
+#undef CNGP_BAKE_BITS
+        return launch_status("bake_probes_bits_kernel");
+    }
     const bool packed = cfg->index_format == CNGP_IDX_PACKED4;
     const int64_t rows = (int64_t)cfg->L * cfg->N_c;
     const int64_t bytes_out = packed ? rows / 2 : rows;
     const int64_t blocks = (bytes_out + kBlock - 1) / kBlock;
     if (int rc = check_blocks(blocks)) return rc;
-    hipStream_t s = (hipStream_t)stream;
     LaunchTimer t(s, K_BAKE);
 #define CNGP_BAKE(NP)                                                                                  \
     if (packed) bake_probes_kernel<NP, true><<<(unsigned)blocks, kBlock, 0, s>>>(Dhat_c, (uint8_t *)D_c, bytes_out); \
@@ -611,6 +664,7 @@ int cngp_adam_step_bake(const cngp_config *cfg, const cngp_adam *opt_f, const cn
                         float *D_f_master, void *D_f, float *m_f, float *v_f, float *grad_D_f,
                         float *Dhat_c, float *m_c, float *v_c, float *grad_Dhat_c, void *D_c, void *stream) {
     if (int rc = validate(cfg)) return rc;
+    if (cfg->index_format == CNGP_IDX_BITS) return CNGP_ERR_UNSUPPORTED;   // training keeps whole-byte or 4-bit entries
     AdamTable f, c;
     std::memset(&f, 0, sizeof(f));
     std::memset(&c, 0, sizeof(c));
@@ -667,18 +721,22 @@ int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const 
     if (N < 0) return CNGP_ERR_INVALID;
     if (N == 0) return CNGP_OK;
     if (!x) return CNGP_ERR_NULL;
-    if (!D_c && (probe || feat_idx)) return CNGP_ERR_NULL;
+    if (!D_c && (probe || feat_idx) && !index_codebook_is_empty(cfg)) return CNGP_ERR_NULL;
     const Params p = make_params(cfg);
     const int64_t pairs = N * cfg->L;
     const int64_t blocks = (pairs + kBlock - 1) / kBlock;
     if (int rc = check_blocks(blocks)) return rc;
     hipStream_t s = (hipStream_t)stream;
-    const bool packed = cfg->index_format == CNGP_IDX_PACKED4;
+    if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
+    const uint32_t c_stride = (uint32_t)index_level_bytes(cfg);
     LaunchTimer t(s, K_DEBUG);
-#define CNGP_DBG(D)                                                                                      \
-    if (packed) debug_indices_kernel<D, true><<<(unsigned)blocks, kBlock, 0, s>>>(p, x, (const uint8_t *)D_c, base, h2, probe, feat_idx, pairs); \
-    else        debug_indices_kernel<D, false><<<(unsigned)blocks, kBlock, 0, s>>>(p, x, (const uint8_t *)D_c, base, h2, probe, feat_idx, pairs)
-    if (cfg->d == 2) { CNGP_DBG(2); } else { CNGP_DBG(3); }
+#define CNGP_DBG(D, FMT) debug_indices_kernel<D, FMT><<<(unsigned)blocks, kBlock, 0, s>>>(p, x, (const uint8_t *)D_c, base, h2, probe, feat_idx, pairs, c_stride)
+#define CNGP_DBG_FMT(D)                                                     \
+    if (cfg->index_format == CNGP_IDX_PACKED4) CNGP_DBG(D, kFmtPacked4);   \
+    else if (cfg->index_format == CNGP_IDX_BITS) CNGP_DBG(D, kFmtBits);    \
+    else CNGP_DBG(D, kFmtU8)
+    if (cfg->d == 2) { CNGP_DBG_FMT(2); } else { CNGP_DBG_FMT(3); }
+#undef CNGP_DBG_FMT
 #undef CNGP_DBG
     return launch_status("debug_indices_kernel");
 }

@@ -77,14 +77,36 @@ __device__ __forceinline__ uint32_t probe_base(uint32_t h1, const Params &p) {
     return (h1 & p.row_mask) << p.log2_Np;
 }
 
-// Baked index codebook readers.
-template <bool PACKED4>
-__device__ __forceinline__ uint32_t read_probe(const uint8_t *D_c_level, uint32_t r) {
-    if (PACKED4) {
+// Baked index codebook readers.  FMT: 0 one byte per entry, 1 two entries per byte, 2 exact width
+// (entry r = bits [r * bits, (r + 1) * bits) of the level's little-endian bit string, read as 32-bit words).
+constexpr int kFmtU8 = 0, kFmtPacked4 = 1, kFmtBits = 2;
+
+template <int FMT>
+__device__ __forceinline__ uint32_t read_probe(const uint8_t *D_c_level, uint32_t r, uint32_t bits = 4) {
+    if (FMT == kFmtPacked4) {
         uint32_t b = D_c_level[r >> 1];
         return (b >> ((r & 1u) * 4u)) & 0xFu;
     }
+    if (FMT == kFmtBits) {
+        if (bits == 0) return 0u;
+        const uint32_t *W = reinterpret_cast<const uint32_t *>(D_c_level);
+        const uint32_t  pos = r * bits, w = pos >> 5, sh = pos & 31u;
+        uint32_t v = W[w] >> sh;
+        if (sh + bits > 32u) v |= W[w + 1] << (32u - sh);          // only 3-bit entries ever straddle a word
+        return v & ((1u << bits) - 1u);
+    }
     return D_c_level[r];
+}
+
+// Exact-width entry from a copy of the level's bit string in LDS.  Only 3-bit entries can straddle two
+// words; they always read the following word as well (the caller keeps 4 readable bytes behind the
+// string; when the entry does not straddle, the funnel shift takes nothing from that word).
+__device__ __forceinline__ uint32_t read_probe_bits_lds(const uint8_t *lds_level, uint32_t r, uint32_t bits) {
+    const uint32_t *W = reinterpret_cast<const uint32_t *>(lds_level);
+    const uint32_t  pos = r * bits, w = pos >> 5, sh = pos & 31u;
+    const uint32_t  lo = W[w];
+    const uint32_t  v = (bits == 3u) ? __funnelshift_r(lo, W[w + 1], sh) : (lo >> sh);
+    return v & ((1u << bits) - 1u);
 }
 
 // Two-feature codebook entry as a pair of floats.

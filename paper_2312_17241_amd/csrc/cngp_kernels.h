@@ -8,10 +8,10 @@ namespace cngp {
 // ------------------------------------------------------------------ forward (Eq. 6 + interpolation)
 // One thread per (point, level) pair, pairs numbered n * L + l, so that the F = 2 outputs
 // of consecutive threads are consecutive in y: every wavefront writes one contiguous run.
-template <int D, typename FeatT, typename IoT, bool PACKED4>
+template <int D, typename FeatT, typename IoT, int FMT>
 __global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
     const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
-    const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t pairs)
+    const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t pairs, const uint32_t c_stride)
 {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= pairs) return;
@@ -25,14 +25,13 @@ __global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
     cell.locate(xp, p.N_l[l]);
 
     const FeatT   *F_l = D_f + (size_t)l * p.N_f * 2;
-    const uint32_t c_stride = PACKED4 ? (p.N_c >> 1) : p.N_c;
     const uint8_t *C_l = D_c + (size_t)l * c_stride;
 
     // issue all probe reads, then all feature reads, so the gathers overlap
     uint32_t idx[1 << D];
 #pragma unroll
     for (int c = 0; c < (1 << D); ++c)
-        idx[c] = read_probe<PACKED4>(C_l, cell.hash2(c) & p.c_mask);
+        idx[c] = read_probe<FMT>(C_l, cell.hash2(c) & p.c_mask, p.log2_Np);
 #pragma unroll
     for (int c = 0; c < (1 << D); ++c) idx[c] += probe_base(cell.hash1(c), p);
     float2 feat[1 << D];
@@ -48,24 +47,25 @@ __global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
     store_pair(y, (size_t)i, y0, y1);
 }
 
-// Tile variant of the forward pass: a workgroup takes kFwdTile consecutive points through all levels.
+// Tile variant of the forward pass: a workgroup of TILE lanes takes TILE consecutive points through all levels.
 // Per level it copies that level's index codebook D_c into LDS (always as packed 4-bit entries, N_c / 2
 // bytes: byte-per-entry input is packed on the way in), so the probe lookups -- half of all random
 // reads of the forward pass -- never reach the memory pipeline; only the D_f gathers do.  Outputs are
 // collected in LDS and leave as one contiguous, fully coalesced block.
-constexpr int kFwdTile = 256;
+constexpr int kFwdTile = 256;        // default; kFwdTileLarge when staging a level's codebook is the larger cost
+constexpr int kFwdTileLarge = 1024;
 
-template <int D, typename FeatT, typename IoT, bool PACKED4>
-__global__ __launch_bounds__(kFwdTile) void encode_fwd_tile_kernel(
+template <int D, typename FeatT, typename IoT, int FMT, int TILE>
+__global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
     const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t N, const uint32_t c_stride, const int vec)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint8_t *probes = smem;                                                  // D_c of the current level, 4-bit packed
+    uint8_t *probes = smem;                                  // D_c of the current level: 4-bit packed, or its exact-width bit string
     const uint32_t lds_c = (p.N_c + 1u) / 2u;                                // bytes of it
-    IoT     *out = reinterpret_cast<IoT *>(smem + ((lds_c + 15u) & ~15u));   // [kFwdTile][L * 2]
+    IoT     *out = reinterpret_cast<IoT *>(smem + ((lds_c + 15u) & ~15u));   // [TILE][L * 2]
     const int     t = threadIdx.x;
-    const int64_t n0 = (int64_t)blockIdx.x * kFwdTile;
+    const int64_t n0 = (int64_t)blockIdx.x * TILE;
     const int64_t n = n0 + t;
     const bool    valid = n < N;
     float xp[D];
@@ -75,15 +75,23 @@ __global__ __launch_bounds__(kFwdTile) void encode_fwd_tile_kernel(
     for (int l = 0; l < p.L; ++l) {
         const uint8_t *C_l = D_c + (size_t)l * c_stride;
         __syncthreads();                                                     // previous level's lookups are done
-        if (PACKED4) {
+        if (FMT == kFmtBits) {                                               // the level's bit string as it is
             if (vec) {
-                for (uint32_t i = t * 16u; i < c_stride; i += kFwdTile * 16u)
+                for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u)
                     *reinterpret_cast<uint4 *>(probes + i) = *reinterpret_cast<const uint4 *>(C_l + i);
             } else {
-                for (uint32_t i = t; i < c_stride; i += kFwdTile) probes[i] = C_l[i];
+                for (uint32_t i = t * 4u; i < c_stride; i += TILE * 4u)
+                    *reinterpret_cast<uint32_t *>(probes + i) = *reinterpret_cast<const uint32_t *>(C_l + i);
+            }
+        } else if (FMT == kFmtPacked4) {
+            if (vec) {
+                for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u)
+                    *reinterpret_cast<uint4 *>(probes + i) = *reinterpret_cast<const uint4 *>(C_l + i);
+            } else {
+                for (uint32_t i = t; i < c_stride; i += TILE) probes[i] = C_l[i];
             }
         } else if (vec) {                                                    // 16 entries in, 8 bytes out
-            for (uint32_t i = t * 16u; i < c_stride; i += kFwdTile * 16u) {
+            for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u) {
                 const uint4 w = *reinterpret_cast<const uint4 *>(C_l + i);
                 auto pack = [](uint32_t v) {                                 // 4 entries -> 2 bytes
                     v &= 0x0F0F0F0Fu;
@@ -94,7 +102,7 @@ __global__ __launch_bounds__(kFwdTile) void encode_fwd_tile_kernel(
                     make_uint2(pack(w.x) | (pack(w.y) << 16), pack(w.z) | (pack(w.w) << 16));
             }
         } else {
-            for (uint32_t i = t; i < lds_c; i += kFwdTile) {
+            for (uint32_t i = t; i < lds_c; i += TILE) {
                 const uint32_t lo = C_l[2 * i] & 0xFu, hi = (2 * i + 1 < c_stride) ? (C_l[2 * i + 1] & 0xFu) : 0u;
                 probes[i] = (uint8_t)(lo | (hi << 4));
             }
@@ -107,7 +115,9 @@ __global__ __launch_bounds__(kFwdTile) void encode_fwd_tile_kernel(
         uint32_t idx[1 << D];
 #pragma unroll
         for (int c = 0; c < (1 << D); ++c)
-            idx[c] = probe_base(cell.hash1(c), p) + read_probe<true>(probes, cell.hash2(c) & p.c_mask);
+            idx[c] = probe_base(cell.hash1(c), p) +
+                     (FMT == kFmtBits ? read_probe_bits_lds(probes, cell.hash2(c) & p.c_mask, p.log2_Np)
+                                      : read_probe<kFmtPacked4>(probes, cell.hash2(c) & p.c_mask));
         float2 feat[1 << D];
 #pragma unroll
         for (int c = 0; c < (1 << D); ++c) feat[c] = load_pair(F_l, idx[c]);
@@ -123,15 +133,15 @@ __global__ __launch_bounds__(kFwdTile) void encode_fwd_tile_kernel(
     __syncthreads();
 
     // the tile's outputs are one contiguous block of y
-    const int64_t rows = (N - n0 < kFwdTile) ? N - n0 : kFwdTile;
+    const int64_t rows = (N - n0 < TILE) ? N - n0 : TILE;
     const size_t  bytes = (size_t)rows * p.L * 2 * sizeof(IoT);
     unsigned char *dst = reinterpret_cast<unsigned char *>(y + (size_t)n0 * p.L * 2);
     const unsigned char *src = reinterpret_cast<const unsigned char *>(out);
     if (((uintptr_t)dst & 15u) == 0 && bytes % 16 == 0) {
-        for (size_t i = (size_t)t * 16; i < bytes; i += (size_t)kFwdTile * 16)
+        for (size_t i = (size_t)t * 16; i < bytes; i += (size_t)TILE * 16)
             *reinterpret_cast<uint4 *>(dst + i) = *reinterpret_cast<const uint4 *>(src + i);
     } else {
-        for (size_t i = (size_t)t * sizeof(IoT); i < bytes; i += (size_t)kFwdTile * sizeof(IoT))
+        for (size_t i = (size_t)t * sizeof(IoT); i < bytes; i += (size_t)TILE * sizeof(IoT))
             *reinterpret_cast<IoT *>(dst + i) = *reinterpret_cast<const IoT *>(src + i);
     }
 }
@@ -231,12 +241,35 @@ __global__ __launch_bounds__(kBlock) void bake_probes_kernel(
     }
 }
 
+// Exact-width output: one thread per 32-bit word of a level's bit string.  An entry that straddles two
+// words (3-bit entries only) is evaluated by both threads.
+template <int NP>
+__global__ __launch_bounds__(kBlock) void bake_probes_bits_kernel(
+    const float *__restrict__ Dhat_c, uint32_t *__restrict__ D_c, const uint32_t N_c,
+    const uint32_t words_per_level, const int64_t words)
+{
+    constexpr uint32_t bits = NP == 16 ? 4u : NP == 8 ? 3u : NP == 4 ? 2u : 1u;
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= words) return;
+    const uint32_t l = (uint32_t)(i / words_per_level), w = (uint32_t)(i % words_per_level);
+    const uint32_t first = (32u * w) / bits;
+    uint32_t last = (32u * w + 31u) / bits;
+    if (last > N_c - 1u) last = N_c - 1u;
+    uint32_t out = 0;
+    for (uint32_t e = first; e <= last; ++e) {
+        const uint32_t v = argmax_row<NP>(Dhat_c + ((size_t)l * N_c + e) * NP);
+        const int pos = (int)(e * bits) - (int)(32u * w);
+        out |= pos >= 0 ? (v << pos) : (v >> (-pos));
+    }
+    D_c[i] = out;
+}
+
 // ------------------------------------------------------------------ index dump (parity checks)
-template <int D, bool PACKED4>
+template <int D, int FMT>
 __global__ __launch_bounds__(kBlock) void debug_indices_kernel(
     const Params p, const float *__restrict__ x, const uint8_t *__restrict__ D_c,
     uint32_t *__restrict__ base_out, uint32_t *__restrict__ h2_out, uint8_t *__restrict__ probe_out,
-    uint32_t *__restrict__ idx_out, const int64_t pairs)
+    uint32_t *__restrict__ idx_out, const int64_t pairs, const uint32_t c_stride)
 {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= pairs) return;
@@ -247,12 +280,11 @@ __global__ __launch_bounds__(kBlock) void debug_indices_kernel(
     for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
     Cell<D> cell;
     cell.locate(xp, p.N_l[l]);
-    const uint32_t c_stride = PACKED4 ? (p.N_c >> 1) : p.N_c;
 #pragma unroll
     for (int c = 0; c < (1 << D); ++c) {
         const uint32_t base = probe_base(cell.hash1(c), p);
         const uint32_t r    = cell.hash2(c) & p.c_mask;
-        const uint32_t pr   = D_c ? read_probe<PACKED4>(D_c + (size_t)l * c_stride, r) : 0u;
+        const uint32_t pr   = D_c ? read_probe<FMT>(D_c + (size_t)l * c_stride, r, p.log2_Np) : 0u;
         const size_t   o    = (size_t)i * (1 << D) + c;
         if (base_out)  base_out[o] = base;
         if (h2_out)    h2_out[o] = r;

@@ -62,7 +62,7 @@ BAD = [
     dict(d=1), dict(d=4), dict(L=0), dict(L=33), dict(F=0),
     dict(N_f=0), dict(N_f=3000), dict(N_c=0), dict(N_c=100), dict(N_p=0), dict(N_p=3), dict(N_p=32),
     dict(N_p=16, N_f=8), dict(N_min=0), dict(N_max=8), dict(N_max=2**25),
-    dict(feat_dtype=2), dict(io_dtype=-1), dict(index_format=2), dict(flags=32), dict(flags=6),
+    dict(feat_dtype=2), dict(io_dtype=-1), dict(index_format=3), dict(flags=32), dict(flags=6),
     dict(index_format=cngp.IDX_PACKED4, N_c=1, N_p=1),
 ]
 
@@ -141,6 +141,20 @@ def test_adam_step_bake_rejects_bad_arguments():
     assert call(c32, ok, None, f=[a, ctypes.c_void_p(8192), a, a, a]) == cngp.ERR_INVALID
     bad_cfg = base_cfg(N_p=3).c()
     assert call(bad_cfg, ok, ok) == cngp.ERR_INVALID
+
+
+def test_storage_bytes_match_the_oracle_arithmetic():
+    import oracle
+    for N_p, N_c, fmt in [(8, 65536, cngp.IDX_BITS), (16, 16384, cngp.IDX_BITS), (2, 4, cngp.IDX_BITS), (1, 64, cngp.IDX_BITS),
+                          (4, 8, cngp.IDX_BITS), (8, 1, cngp.IDX_BITS), (16, 16384, cngp.IDX_U8), (16, 16384, cngp.IDX_PACKED4)]:
+        w = W.custom(d=3, L=16, N_f=256, N_c=N_c, N_p=N_p, N_min=16, N_max=2048, N=16, feat_dtype="f16")
+        got = cngp.storage_bytes(cngp.Config.from_workload(w, index_format=fmt))
+        if fmt == cngp.IDX_PACKED4:
+            want = {"D_f": 16 * 256 * 2 * 2, "D_c_level": N_c // 2, "D_c": 16 * N_c // 2}
+        else:
+            want = oracle.storage_bytes(w, index_bits_exact=(fmt == cngp.IDX_BITS))
+        assert got == want, (N_p, N_c, fmt)
+        assert cngp.Config.from_workload(w, index_format=fmt).index_cols == want["D_c_level"]
 
 
 def test_backward_plan_is_reported_on_the_host():

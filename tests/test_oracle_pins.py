@@ -412,6 +412,38 @@ def test_bake_ties_and_nan():
     assert oracle.bake_probes(rows).tolist() == [0, 1, 1, 0, 0, 2]
 
 
+# --------------------------------------------------------------------------- exact-width index storage
+
+@pytest.mark.parametrize("N_p", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("N_c", [1, 2, 8, 16, 32, 128])
+def test_index_bit_packing_is_the_little_endian_integer(N_p, N_c):
+    """A level's bit string read as one little-endian integer is sum_r D_c[r] * N_p^r (entry r at bit r b)."""
+    rng = np.random.default_rng(N_p * 1000 + N_c)
+    D_c = rng.integers(0, N_p, (3, N_c)).astype(np.uint8)
+    packed = oracle.pack_index_bits(D_c, N_p)
+    b = N_p.bit_length() - 1
+    assert packed.shape == (3, 4 * ((N_c * b + 31) // 32))
+    for l in range(3):
+        assert int.from_bytes(packed[l].tobytes(), "little") == sum(int(v) * N_p ** r for r, v in enumerate(D_c[l]))
+    assert np.array_equal(oracle.unpack_index_bits(packed, N_c, N_p), D_c)
+
+
+def test_storage_bytes_against_table_3():
+    """The model sizes of Table 3 (which also hold an MLP and, apparently, smaller coarse levels) lie a
+    little below the bytes of 16 levels of fp16 features and exact-width indices."""
+    for line in open(os.path.join(GOLDEN, "table3_sizes.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        _, N_f, N_c, N_p, kB = line.split()
+        w = W.custom(d=3, L=16, N_f=int(N_f), N_c=int(N_c), N_p=int(N_p), N_min=16, N_max=2048, N=16, feat_dtype="f16")
+        sb = oracle.storage_bytes(w)
+        total = (sb["D_f"] + sb["D_c"]) / 1000.0
+        assert 0.8 * total <= float(kB) <= total, (line, total)
+    # the paper's row: 2^8 features, 2^16 three-bit indices per level
+    w = W.custom(d=3, L=16, N_f=256, N_c=65536, N_p=8, N_min=16, N_max=2048, N=16, feat_dtype="f16")
+    assert oracle.storage_bytes(w) == {"D_f": 16 * 256 * 2 * 2, "D_c_level": 65536 * 3 // 8, "D_c": 16 * 65536 * 3 // 8}
+
+
 # --------------------------------------------------------------------------- optimiser step (assumed: Adam)
 
 def test_adam_closed_forms():
