@@ -4,7 +4,8 @@ Thin ctypes marshalling around oracle/cngp_oracle.c (plain C, fp64).  Only
 tests, the smoke check and the benchmark's CPU-baseline leg import this
 package; the product package never does, and this package never imports the
 product.  All arithmetic lives in the C file; this file converts arrays and
-threads shapes through.
+threads shapes through; the storage convention of the index codebook and the decoder that
+follows the encoding (oracle/mlp.py) are a few lines of plain numpy.
 """
 import ctypes
 import os
@@ -12,6 +13,7 @@ import os
 import numpy as np
 
 from .build import build as _build
+from .mlp import mlp_bwd, mlp_fwd  # noqa: F401
 
 _lib = None
 

@@ -484,6 +484,49 @@ def test_adam_matches_library_optimiser():
         assert np.allclose(th, par.detach().numpy(), rtol=1e-12, atol=1e-14)
 
 
+# --------------------------------------------------------------------------- decoder (assumed: 2 hidden ReLU layers)
+
+def _mlp_case(seed, N=50, n_in=16, n_out=3):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((N, n_in)), rng.standard_normal((64, n_in)) * 0.3,
+            rng.standard_normal((64, 64)) * 0.2, rng.standard_normal((n_out, 64)) * 0.2,
+            rng.standard_normal((N, n_out)))
+
+
+def test_mlp_matches_library_autograd():
+    import torch
+    y, W1, W2, W3, dout = _mlp_case(0)
+    t = [torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (y, W1, W2, W3)]
+    out = torch.relu(torch.relu(t[0] @ t[1].T) @ t[2].T) @ t[3].T
+    out.backward(torch.tensor(dout))
+    assert np.allclose(oracle.mlp_fwd(y, W1, W2, W3), out.detach().numpy(), rtol=1e-12, atol=1e-13)
+    g, mag, _ = oracle.mlp_bwd(y, W1, W2, W3, dout)
+    for name, ref in zip(("dy", "dW1", "dW2", "dW3"), t):
+        assert np.allclose(g[name], ref.grad.numpy(), rtol=1e-11, atol=1e-12), name
+        assert np.all(mag[name] >= np.abs(g[name]) - 1e-12)
+
+
+def test_mlp_linear_regime_and_finite_differences():
+    rng = np.random.default_rng(1)
+    # all-positive inputs and weights: no unit is ever clipped, the network is the product of its matrices
+    y, W1, W2, W3 = rng.random((20, 8)), rng.random((64, 8)), rng.random((64, 64)), rng.random((3, 64))
+    assert np.allclose(oracle.mlp_fwd(y, W1, W2, W3), y @ (W3 @ W2 @ W1).T, rtol=1e-12)
+    out, mag, _ = oracle.mlp_fwd(y, W1, W2, W3, want_mag=True)
+    assert np.allclose(out, mag)
+    # central differences of L = sum(out * dout) in every argument
+    y, W1, W2, W3, dout = _mlp_case(2, N=6, n_in=8)
+    g, _, _ = oracle.mlp_bwd(y, W1, W2, W3, dout)
+    args = {"dy": y, "dW1": W1, "dW2": W2, "dW3": W3}
+    loss = lambda: float((oracle.mlp_fwd(y, W1, W2, W3) * dout).sum())
+    for name, arr in args.items():
+        for idx in [tuple(rng.integers(0, s) for s in arr.shape) for _ in range(12)]:
+            old = arr[idx]; h = 1e-6
+            arr[idx] = old + h; up = loss()
+            arr[idx] = old - h; dn = loss()
+            arr[idx] = old
+            assert abs((up - dn) / (2 * h) - g[name][idx]) < 1e-6 * max(1.0, abs(g[name][idx])), (name, idx)
+
+
 # --------------------------------------------------------------------------- storage conventions
 
 def test_model_sizes_consistent_with_table_3():
