@@ -174,6 +174,36 @@ int cngp_adam_step_bake(const cngp_config *cfg, const cngp_adam *opt_f, const cn
                         float *Dhat_c, float *m_c, float *v_c, float *grad_Dhat_c, void *D_c,
                         void *stream);
 
+/* Decoder after the encoding (Fig. 3: the interpolated features are fed into an MLP; Table 1: 64 hidden
+ * neurons).  The paper gives the width only; ASSUMED here: two hidden layers, ReLU after each, a linear
+ * output layer, no biases:
+ *     h1 = relu(W1 y)    h2 = relu(W2 h1)    out = W3 h2
+ * Runs on the matrix cores: fp16 operands (y, the weights, h1, h2 and the hidden-layer gradients are
+ * rounded to fp16), fp32 accumulation.
+ *   n_in   columns of y, 1 .. 32 (L * F of the encoding)      n_out  1 .. 16
+ *   W      dev float16: W1 [64, n_in], W2 [64, 64], W3 [n_out, 64], row-major, one after the other
+ *   y      dev io_dtype [N, n_in]          out   dev float32 [N, n_out], written */
+typedef struct cngp_mlp_config {
+    int32_t  n_in, n_out;
+    int32_t  io_dtype;     /* cngp_dtype of y and dL/dy                                            */
+    uint32_t flags;        /* CNGP_ZERO_GRADS: cngp_mlp_bwd clears grad_W before accumulating      */
+} cngp_mlp_config;
+size_t cngp_mlp_weight_count(const cngp_mlp_config *cfg);     /* 64 n_in + 64 * 64 + 64 n_out; 0 if invalid */
+int cngp_mlp_fwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const void *W, float *out, void *stream);
+
+/* Backward pass of the decoder for L = sum(out * dout): recomputes the hidden layers, then
+ *   dy      dev io_dtype [N, n_in]    written: dL/dy, the upstream gradient cngp_encode_bwd takes
+ *   grad_W  dev float32, layout of W  accumulated (+=) with floating-point atomics, or cleared first
+ * relu'(a) = 1 for a > 0, else 0, decided on the fp32 pre-activation the kernel itself computed. */
+int cngp_mlp_bwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const void *W, const float *dout,
+                 void *dy, float *grad_W, void *stream);
+
+/* Adam step (see cngp_adam_step_bake) on one plain array of n parameters, e.g. the decoder's weights:
+ * master, m, v, grad dev float32 [n], 16-byte aligned; half_copy dev float16 [n] (8-byte aligned) receives
+ * the updated parameters rounded to fp16, or NULL; clear_grad != 0 sets grad to zero afterwards. */
+int cngp_adam_step(const cngp_adam *opt, int64_t n, float *master, void *half_copy, float *m, float *v,
+                   float *grad, int clear_grad, void *stream);
+
 /* Index dump for parity checks: for every (point, level, corner) the integers of Eq. 6.
  * All outputs dev, shape [N, L, 2^d]; any of them may be NULL.
  *   base      (N_p * hash(v)) mod N_f        h2        hash2(v) mod N_c

@@ -41,8 +41,12 @@ def mlp_bwd(y, W1, W2, W3, dout):
     dW3 = dout.T @ h2
     dW2 = dh2.T @ h1
     dW1 = dh1.T @ y
-    # magnitudes: the same products with absolute values everywhere (masks kept)
+    # magnitudes: the same chains with absolute values in every factor (masks kept), i.e. what each result
+    # would be if no term cancelled anywhere along the way -- hidden activations included, because their
+    # own rounding error is relative to that sum, not to their value
+    mh1 = (np.abs(y) @ np.abs(W1).T) * (a1 > 0)
+    mh2 = (mh1 @ np.abs(W2).T) * (a2 > 0)
     m2 = (np.abs(dout) @ np.abs(W3)) * (a2 > 0)
     m1 = (m2 @ np.abs(W2)) * (a1 > 0)
-    mag = {"dy": m1 @ np.abs(W1), "dW3": np.abs(dout).T @ h2, "dW2": m2.T @ h1, "dW1": m1.T @ np.abs(y)}
+    mag = {"dy": m1 @ np.abs(W1), "dW3": np.abs(dout).T @ mh2, "dW2": m2.T @ mh1, "dW1": m1.T @ np.abs(y)}
     return {"dy": dy, "dW1": dW1, "dW2": dW2, "dW3": dW3}, mag, (a1, a2)

@@ -64,6 +64,14 @@ def _load():
     lib.cngp_encode_bwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cngp_bake_probes.restype = ctypes.c_int
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
+    lib.cngp_mlp_weight_count.restype = ctypes.c_size_t
+    lib.cngp_mlp_weight_count.argtypes = [vp]
+    lib.cngp_mlp_fwd.restype = ctypes.c_int
+    lib.cngp_mlp_fwd.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib.cngp_mlp_bwd.restype = ctypes.c_int
+    lib.cngp_mlp_bwd.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
+    lib.cngp_adam_step.restype = ctypes.c_int
+    lib.cngp_adam_step.argtypes = [vp, i64, vp, vp, vp, vp, vp, ctypes.c_int, vp]
     lib.cngp_storage_bytes.restype = ctypes.c_int
     lib.cngp_storage_bytes.argtypes = [cfgp, vp, vp, vp]
     lib.cngp_adam_step_bake.restype = ctypes.c_int
@@ -288,6 +296,70 @@ def adam_step_bake(cfg: Config, opt_f, opt_c, features=None, logits=None):
     _check(_lib.cngp_adam_step_bake(
         ctypes.byref(c), None if of is None else ctypes.cast(ctypes.byref(of), ctypes.c_void_p),
         None if oc is None else ctypes.cast(ctypes.byref(oc), ctypes.c_void_p), *fa, *ca, _stream()))
+
+
+def adam_step(opt: Adam, master, half_copy, m, v, grad, clear_grad=False):
+    """cngp_adam_step on one flat float32 parameter array; half_copy (float16, same size) may be None."""
+    n = master.numel()
+    o = opt.c()
+    hc = ctypes.c_void_p(0) if half_copy is None else _dev(half_copy, torch.float16, tuple(master.shape), "half_copy")
+    _check(_lib.cngp_adam_step(ctypes.byref(o), n, _dev(master, torch.float32, tuple(master.shape), "master"), hc,
+                               _dev(m, torch.float32, tuple(master.shape), "m"),
+                               _dev(v, torch.float32, tuple(master.shape), "v"),
+                               _dev(grad, torch.float32, tuple(master.shape), "grad"), int(bool(clear_grad)), _stream()))
+
+
+class CMlpConfig(ctypes.Structure):
+    _fields_ = [("n_in", ctypes.c_int32), ("n_out", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
+
+
+@dataclass(frozen=True)
+class MlpConfig:
+    """Decoder after the encoding (cngp_mlp_config): n_in -> 64 -> 64 -> n_out, ReLU, no biases."""
+    n_in: int
+    n_out: int
+    io_dtype: int = F32
+    flags: int = 0
+
+    def c(self):
+        return CMlpConfig(self.n_in, self.n_out, self.io_dtype, self.flags)
+
+    @property
+    def weight_count(self) -> int:
+        c = self.c()
+        return int(_lib.cngp_mlp_weight_count(ctypes.byref(c)))
+
+    def split(self, W):
+        """Views of a flat weight (or gradient) array as W1 [64, n_in], W2 [64, 64], W3 [n_out, 64]."""
+        a, b = 64 * self.n_in, 64 * self.n_in + 64 * 64
+        return W[:a].view(64, self.n_in), W[a:b].view(64, 64), W[b:].view(self.n_out, 64)
+
+
+def mlp_fwd(cfg: MlpConfig, y, W, out=None):
+    N = y.shape[0]
+    if out is None:
+        out = torch.empty((N, cfg.n_out), dtype=torch.float32, device=y.device)
+    c = cfg.c()
+    _check(_lib.cngp_mlp_fwd(ctypes.byref(c), _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.n_in), "y"), N,
+                             _dev(W, torch.float16, (cfg.weight_count,), "W"),
+                             _dev(out, torch.float32, (N, cfg.n_out), "out"), _stream()))
+    return out
+
+
+def mlp_bwd(cfg: MlpConfig, y, W, dout, dy=None, grad_W=None):
+    N = y.shape[0]
+    if dy is None:
+        dy = torch.empty((N, cfg.n_in), dtype=_TORCH_DT[cfg.io_dtype], device=y.device)
+    if grad_W is None:
+        grad_W = torch.zeros((cfg.weight_count,), dtype=torch.float32, device=y.device)
+    c = cfg.c()
+    _check(_lib.cngp_mlp_bwd(ctypes.byref(c), _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.n_in), "y"), N,
+                             _dev(W, torch.float16, (cfg.weight_count,), "W"),
+                             _dev(dout, torch.float32, (N, cfg.n_out), "dout"),
+                             _dev(dy, _TORCH_DT[cfg.io_dtype], (N, cfg.n_in), "dy"),
+                             _dev(grad_W, torch.float32, (cfg.weight_count,), "grad_W"), _stream()))
+    return dy, grad_W
 
 
 def debug_indices(cfg: Config, x, D_c):

@@ -5,6 +5,7 @@
 #include "cngp_bwd_sliced.h"
 #include "cngp_rates.h"
 #include "cngp_optim.h"
+#include "cngp_mlp.h"
 
 #include <cmath>
 #include <cstdio>
@@ -87,11 +88,11 @@ int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INV
 
 // ---------------------------------------------------------------- per-kernel timing
 enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_SLICED, K_BWD_SLICED_V,
-                K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_COUNT };
+                K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_softmax_table",
                                            "encode_bwd_transpose_dy", "encode_bwd_sliced_points_and_grid",
                                            "encode_bwd_sliced_vertices", "bake_probes", "zero", "debug_indices",
-                                           "adam_step_bake"};
+                                           "adam_step_bake", "mlp_fwd", "mlp_bwd"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -713,6 +714,96 @@ int cngp_adam_step_bake(const cngp_config *cfg, const cngp_adam *opt_f, const cn
     }
 #undef CNGP_ADAM
     return launch_status("adam_step_bake_kernel");
+}
+
+int cngp_adam_step(const cngp_adam *opt, int64_t n, float *master, void *half_copy, float *m, float *v,
+                   float *grad, int clear_grad, void *stream) {
+    if (!opt || !master || !m || !v || !grad) return CNGP_ERR_NULL;
+    if (n < 0) return CNGP_ERR_INVALID;
+    AdamTable f, c;
+    std::memset(&f, 0, sizeof(f));
+    std::memset(&c, 0, sizeof(c));
+    if (int rc = adam_coefficients(opt, &f.a)) return rc;
+    if (!aligned(master, 16) || !aligned(m, 16) || !aligned(v, 16) || !aligned(grad, 16) || !aligned(half_copy, 8)) return CNGP_ERR_INVALID;
+    if (n == 0) return CNGP_OK;
+    f.theta = master; f.m = m; f.v = v; f.grad = grad; f.n = n;
+    const int64_t per_block = (int64_t)kOptBlock * 4;
+    const int64_t blocks = (n + per_block - 1) / per_block;
+    if (int rc = check_blocks(blocks)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    LaunchTimer t(s, K_ADAM);
+    adam_step_bake_kernel<1, false><<<(unsigned)blocks, kOptBlock, 0, s>>>(f, c, (__half *)half_copy, nullptr,
+                                                                           (uint32_t)blocks, clear_grad ? 1 : 0);
+    return launch_status("adam_step_bake_kernel");
+}
+
+namespace {
+int mlp_dims(const cngp_mlp_config *cfg, MlpDims *d) {
+    if (!cfg) return CNGP_ERR_NULL;
+    if (cfg->n_in < 1 || cfg->n_in > kMlpMaxIn || cfg->n_out < 1 || cfg->n_out > kMlpMaxOut) return CNGP_ERR_INVALID;
+    if (cfg->io_dtype != CNGP_F32 && cfg->io_dtype != CNGP_F16) return CNGP_ERR_INVALID;
+    if (cfg->flags & ~(uint32_t)CNGP_ZERO_GRADS) return CNGP_ERR_INVALID;
+    d->n_in = cfg->n_in; d->n_out = cfg->n_out;
+    d->ks1 = (cfg->n_in + 7) / 8; d->ks3 = (cfg->n_out + 7) / 8;
+    return CNGP_OK;
+}
+// A persistent grid: every wavefront walks over tiles of 32 points.
+unsigned mlp_blocks(int64_t tiles, int per_cu) {
+    const int64_t want = (tiles + kMlpBlock / 64 - 1) / (kMlpBlock / 64);
+    const int64_t cap = 256 * (int64_t)per_cu;
+    return (unsigned)(want < cap ? want : cap);
+}
+}  // namespace
+
+size_t cngp_mlp_weight_count(const cngp_mlp_config *cfg) {
+    MlpDims d;
+    if (mlp_dims(cfg, &d)) return 0;
+    return (size_t)kMlpHidden * d.n_in + (size_t)kMlpHidden * kMlpHidden + (size_t)kMlpHidden * d.n_out;
+}
+
+int cngp_mlp_fwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const void *W, float *out, void *stream) {
+    MlpDims d;
+    if (int rc = mlp_dims(cfg, &d)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    if (N == 0) return CNGP_OK;
+    if (!y || !W || !out) return CNGP_ERR_NULL;
+    const int64_t tiles = (N + 31) / 32;
+    hipStream_t s = (hipStream_t)stream;
+    LaunchTimer t(s, K_MLP_FWD);
+    if (cfg->io_dtype == CNGP_F16)
+        mlp_fwd_kernel<__half><<<mlp_blocks(tiles, 8), kMlpBlock, kMlpFwdLds, s>>>(d, (const __half *)y, N, (const __half *)W, out, tiles);
+    else
+        mlp_fwd_kernel<float><<<mlp_blocks(tiles, 8), kMlpBlock, kMlpFwdLds, s>>>(d, (const float *)y, N, (const __half *)W, out, tiles);
+    return launch_status("mlp_fwd_kernel");
+}
+
+int cngp_mlp_bwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const void *W, const float *dout,
+                 void *dy, float *grad_W, void *stream) {
+    MlpDims d;
+    if (int rc = mlp_dims(cfg, &d)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    if (!grad_W) return CNGP_ERR_NULL;
+    if (N > 0 && (!y || !W || !dout || !dy)) return CNGP_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (cfg->flags & CNGP_ZERO_GRADS) {
+        ZeroList z;
+        z.add(grad_W, (int64_t)cngp_mlp_weight_count(cfg));
+        if (int rc = z.launch(s)) return rc;
+    }
+    if (N == 0) return CNGP_OK;
+    const int64_t tiles = (N + 31) / 32;
+    if (cfg->io_dtype == CNGP_F16) {
+        auto kernel = mlp_bwd_kernel<__half>;
+        if (int rc = allow_big_lds(kernel, kMlpBwdLds)) return rc;
+        LaunchTimer t(s, K_MLP_BWD);
+        kernel<<<mlp_blocks(tiles, 1), kMlpBlock, kMlpBwdLds, s>>>(d, (const __half *)y, N, (const __half *)W, dout, (__half *)dy, grad_W, tiles);
+    } else {
+        auto kernel = mlp_bwd_kernel<float>;
+        if (int rc = allow_big_lds(kernel, kMlpBwdLds)) return rc;
+        LaunchTimer t(s, K_MLP_BWD);
+        kernel<<<mlp_blocks(tiles, 1), kMlpBlock, kMlpBwdLds, s>>>(d, (const float *)y, N, (const __half *)W, dout, (float *)dy, grad_W, tiles);
+    }
+    return launch_status("mlp_bwd_kernel");
 }
 
 int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const void *D_c, uint32_t *base,

@@ -1,0 +1,310 @@
+// Decoder after the encoding (Fig. 3: the interpolated features are fed into an MLP; Table 1: 64 hidden
+// neurons).  Assumed, because the paper does not say: two hidden layers, ReLU, linear output, no biases.
+//
+//     h1 = relu(W1 y)   h2 = relu(W2 h1)   out = W3 h2        W1 [64, n_in], W2 [64, 64], W3 [n_out, 64]
+//
+// The only dense contraction of the method, hence the only user of the matrix cores here.  Everything is
+// computed transposed, points along the columns: one wavefront owns 32 points and every layer is
+//     (weights as the A operand, 32 x 8 per instruction) x (activations^T as the B operand, 8 x 32)
+// with v_mfma_f32_32x32x8_f16.  The accumulator layout of that instruction (lane = column, four
+// consecutive rows per register group) IS its B operand layout, so the activations of one layer feed the
+// next straight from registers: after ReLU and rounding to fp16, accumulator registers 4j .. 4j+3 of row
+// tile t are the B operand of K-step 4t + j.  Only the weight gradients, which contract over the points,
+// need a transpose; it goes through a per-wavefront tile in LDS.
+#pragma once
+#include "cngp_bwd_sliced.h"   // wave_lds_fence
+
+namespace cngp {
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float    acc16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kMlpHidden = 64;
+constexpr int kMlpBlock = 256;                 // 4 wavefronts
+constexpr int kMlpMaxIn = 32, kMlpMaxOut = 16;
+
+struct MlpDims {
+    int n_in, n_out;
+    int ks1;                                   // K-steps of layer 1: ceil(n_in / 8)
+    int ks3;                                   // K-steps of the transposed output layer: ceil(n_out / 8)
+};
+
+// Slots of the weight operands in LDS; a slot holds one half4 per lane (512 bytes), ready to be used as
+// the A operand of one instruction.
+enum : int { kOpW1 = 0, kOpW2 = 8, kOpW3 = 24, kOpW3T = 32, kOpW2T = 36, kOpW1T = 52, kOpFwdSlots = 32, kOpAllSlots = 60 };
+
+__device__ __forceinline__ acc16_t mfma(const half4_t a, const half4_t b, const acc16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ acc16_t acc_zero() {
+    acc16_t z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.0f;
+    return z;
+}
+
+// A-operand element (row i, column k) of a matrix stored row-major [rows, cols] (or its transpose).
+__device__ __forceinline__ _Float16 w_at(const __half *W, int rows, int cols, bool transposed, int i, int k) {
+    const int r = transposed ? k : i, c = transposed ? i : k;
+    return (r < rows && c < cols) ? (_Float16)__half2float(W[r * cols + c]) : (_Float16)0.0f;
+}
+
+// Fills `slots` operand slots, the work spread over the workgroup.
+__device__ __forceinline__ void stage_operands(half4_t *ops, const __half *W, const MlpDims d, const int slots) {
+    const __half *W1 = W, *W2 = W + kMlpHidden * d.n_in, *W3 = W2 + kMlpHidden * kMlpHidden;
+    for (int e = threadIdx.x; e < slots * 64; e += kMlpBlock) {
+        const int slot = e >> 6, lane = e & 63, row = lane & 31, k4 = 4 * (lane >> 5);
+        const __half *M;
+        int  rows, cols, t, s;
+        bool tr;
+        if (slot < kOpW2)       { M = W1; rows = kMlpHidden; cols = d.n_in;      tr = false; t = (slot - kOpW1) >> 2;  s = (slot - kOpW1) & 3; }
+        else if (slot < kOpW3)  { M = W2; rows = kMlpHidden; cols = kMlpHidden;  tr = false; t = (slot - kOpW2) >> 3;  s = (slot - kOpW2) & 7; }
+        else if (slot < kOpW3T) { M = W3; rows = d.n_out;    cols = kMlpHidden;  tr = false; t = 0;                    s = slot - kOpW3; }
+        else if (slot < kOpW2T) { M = W3; rows = d.n_out;    cols = kMlpHidden;  tr = true;  t = (slot - kOpW3T) >> 1; s = (slot - kOpW3T) & 1; }
+        else if (slot < kOpW1T) { M = W2; rows = kMlpHidden; cols = kMlpHidden;  tr = true;  t = (slot - kOpW2T) >> 3; s = (slot - kOpW2T) & 7; }
+        else                    { M = W1; rows = kMlpHidden; cols = d.n_in;      tr = true;  t = 0;                    s = slot - kOpW1T; }
+        half4_t v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = w_at(M, rows, cols, tr, 32 * t + row, 8 * s + k4 + j);
+        ops[e] = v;
+    }
+}
+
+template <typename T> __device__ __forceinline__ float to_float(T v);
+template <> __device__ __forceinline__ float to_float<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_float<__half>(__half v) { return __half2float(v); }
+template <typename T> __device__ __forceinline__ T from_float(float v);
+template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <> __device__ __forceinline__ __half from_float<__half>(float v) { return __float2half_rn(v); }
+
+// B operand of K-step s from a row-major [N, cols] array: this lane's point, columns 8s + 4h .. + 3.
+template <typename T>
+__device__ __forceinline__ half4_t load_b(const T *__restrict__ a, const int64_t pt, const int64_t N,
+                                          const int cols, const int k0) {
+    half4_t v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        v[j] = (pt < N && k0 + j < cols) ? (_Float16)to_float<T>(a[pt * cols + k0 + j]) : (_Float16)0.0f;
+    return v;
+}
+
+// ReLU, rounding to fp16, and the re-use of an accumulator tile as B operands of the next layer.
+__device__ __forceinline__ void relu_to_b(const acc16_t a, half4_t (&b)[8], const int t) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        half4_t v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = (_Float16)fmaxf(a[4 * j + q], 0.0f);
+        b[4 * t + j] = v;
+    }
+}
+
+// Same for a gradient tile: entries whose forward pre-activation was not positive are dropped.
+__device__ __forceinline__ void mask_to_b(const acc16_t g, const uint32_t mask, half4_t (&b)[8], const int t) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        half4_t v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = ((mask >> (4 * j + q)) & 1u) ? (_Float16)g[4 * j + q] : (_Float16)0.0f;
+        b[4 * t + j] = v;
+    }
+}
+
+__device__ __forceinline__ uint32_t positive_mask(const acc16_t a) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) m |= (a[r] > 0.0f ? 1u : 0u) << r;
+    return m;
+}
+
+// Layers 1 and 2 for this wavefront's 32 points.
+struct Hidden {
+    half4_t  yb[4], h1[8], h2[8];
+    uint32_t m1[2], m2[2];
+};
+
+template <typename IoT>
+__device__ __forceinline__ void hidden_layers(const half4_t *ops, const MlpDims d, const IoT *__restrict__ y,
+                                              const int64_t pt, const int64_t N, const int lane, Hidden &H) {
+    const int k4 = 4 * (lane >> 5);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) H.yb[s] = load_b(y, pt, N, d.n_in, 8 * s + k4);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        acc16_t a = acc_zero();
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            if (s < d.ks1) a = mfma(ops[(kOpW1 + 4 * t + s) * 64 + lane], H.yb[s], a);
+        H.m1[t] = positive_mask(a);
+        relu_to_b(a, H.h1, t);
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        acc16_t a = acc_zero();
+#pragma unroll
+        for (int s = 0; s < 8; ++s) a = mfma(ops[(kOpW2 + 8 * t + s) * 64 + lane], H.h1[s], a);
+        H.m2[t] = positive_mask(a);
+        relu_to_b(a, H.h2, t);
+    }
+}
+
+// ------------------------------------------------------------------ forward
+template <typename IoT>
+__global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
+    const MlpDims d, const IoT *__restrict__ y, const int64_t N, const __half *__restrict__ W,
+    float *__restrict__ out, const int64_t tiles)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    half4_t *ops = reinterpret_cast<half4_t *>(smem);
+    stage_operands(ops, W, d, kOpFwdSlots);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, k4 = 4 * (lane >> 5);
+    const int64_t waves = (int64_t)gridDim.x * (kMlpBlock / 64);
+    for (int64_t tile = (int64_t)blockIdx.x * (kMlpBlock / 64) + (threadIdx.x >> 6); tile < tiles; tile += waves) {
+        const int64_t pt = tile * 32 + (lane & 31);
+        Hidden H;
+        hidden_layers(ops, d, y, pt, N, lane, H);
+        acc16_t o = acc_zero();
+#pragma unroll
+        for (int s = 0; s < 8; ++s) o = mfma(ops[(kOpW3 + s) * 64 + lane], H.h2[s], o);
+        if (pt < N) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {                       // rows 0 .. 15 of the tile are the outputs
+                const int ch = 8 * (r >> 2) + k4 + (r & 3);
+                if (ch < d.n_out) out[pt * d.n_out + ch] = o[r];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ backward
+// Per-wavefront transpose tile: rows = input dimensions / neurons / output channels, 32 points per row,
+// rows padded to 36 halves so that the 8-byte operand reads of 32 lanes fall into different banks.
+constexpr int kTileStride = 36;
+enum : int { kRowY = 0, kRowH1 = 32, kRowH2 = 96, kRowD1 = 160, kRowD2 = 224, kRowDo = 288, kTileRows = 320 };
+constexpr size_t kMlpBwdLds = (size_t)kOpAllSlots * 64 * sizeof(half4_t) +
+                              (size_t)(kMlpBlock / 64) * kTileRows * kTileStride * sizeof(_Float16);
+constexpr size_t kMlpFwdLds = (size_t)kOpFwdSlots * 64 * sizeof(half4_t);
+
+// B-layout registers (lane = point, K-step s holds rows 8s + 4h .. + 3) written as rows of the tile.
+template <int STEPS>
+__device__ __forceinline__ void put_rows(_Float16 *tile, const int row0, const half4_t (&b)[STEPS], const int lane) {
+    const int p = lane & 31, k4 = 4 * (lane >> 5);
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tile[(row0 + 8 * s + k4 + j) * kTileStride + p] = b[s][j];
+}
+
+// Operand whose K index runs over the 32 points: row 32u + lane % 32, points 8s + 4h .. + 3.
+__device__ __forceinline__ half4_t get_op(const _Float16 *tile, const int row0, const int u, const int s, const int lane) {
+    return *reinterpret_cast<const half4_t *>(tile + (row0 + 32 * u + (lane & 31)) * kTileStride + 8 * s + 4 * (lane >> 5));
+}
+
+template <typename IoT>
+__global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
+    const MlpDims d, const IoT *__restrict__ y, const int64_t N, const __half *__restrict__ W,
+    const float *__restrict__ dout, IoT *__restrict__ dy, float *__restrict__ gW, const int64_t tiles)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    half4_t  *ops = reinterpret_cast<half4_t *>(smem);
+    _Float16 *tile = reinterpret_cast<_Float16 *>(smem + (size_t)kOpAllSlots * 64 * sizeof(half4_t)) +
+                     (size_t)(threadIdx.x >> 6) * kTileRows * kTileStride;
+    stage_operands(ops, W, d, kOpAllSlots);
+    const int lane = threadIdx.x & 63, k4 = 4 * (lane >> 5);
+    for (int i = lane; i < kTileRows * kTileStride; i += 64) tile[i] = (_Float16)0.0f;   // padding rows stay zero
+    __syncthreads();
+
+    acc16_t gW1[2], gW2[2][2], gW3[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        gW1[t] = acc_zero(); gW3[t] = acc_zero();
+        gW2[t][0] = acc_zero(); gW2[t][1] = acc_zero();
+    }
+
+    const int64_t waves = (int64_t)gridDim.x * (kMlpBlock / 64);
+    for (int64_t tl = (int64_t)blockIdx.x * (kMlpBlock / 64) + (threadIdx.x >> 6); tl < tiles; tl += waves) {
+        const int64_t pt = tl * 32 + (lane & 31);
+        Hidden H;
+        hidden_layers(ops, d, y, pt, N, lane, H);
+
+        half4_t db[2], dh2[8], dh1[8];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) db[s] = load_b(dout, pt, N, d.n_out, 8 * s + k4);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {                           // dL/dh2 = W3^T dout, where h2 was active
+            acc16_t g = acc_zero();
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                if (s < d.ks3) g = mfma(ops[(kOpW3T + 2 * t + s) * 64 + lane], db[s], g);
+            mask_to_b(g, H.m2[t], dh2, t);
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {                           // dL/dh1 = W2^T dL/dh2, where h1 was active
+            acc16_t g = acc_zero();
+#pragma unroll
+            for (int s = 0; s < 8; ++s) g = mfma(ops[(kOpW2T + 8 * t + s) * 64 + lane], dh2[s], g);
+            mask_to_b(g, H.m1[t], dh1, t);
+        }
+        {                                                       // dL/dy = W1^T dL/dh1
+            acc16_t g = acc_zero();
+#pragma unroll
+            for (int s = 0; s < 8; ++s) g = mfma(ops[(kOpW1T + s) * 64 + lane], dh1[s], g);
+            if (pt < N) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int i = 8 * (r >> 2) + k4 + (r & 3);
+                    if (i < d.n_in) dy[pt * d.n_in + i] = from_float<IoT>(g[r]);
+                }
+            }
+        }
+
+        // weight gradients contract over the points: transpose through the tile
+        wave_lds_fence();                                       // the previous tile's operand reads are done
+        put_rows<4>(tile, kRowY, H.yb, lane);
+        put_rows<8>(tile, kRowH1, H.h1, lane);
+        put_rows<8>(tile, kRowH2, H.h2, lane);
+        put_rows<8>(tile, kRowD1, dh1, lane);
+        put_rows<8>(tile, kRowD2, dh2, lane);
+        put_rows<2>(tile, kRowDo, db, lane);
+        wave_lds_fence();
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const half4_t yT = get_op(tile, kRowY, 0, s, lane), doT = get_op(tile, kRowDo, 0, s, lane);
+            half4_t h1T[2], h2T[2], d1T[2], d2T[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                h1T[u] = get_op(tile, kRowH1, u, s, lane);
+                h2T[u] = get_op(tile, kRowH2, u, s, lane);
+                d1T[u] = get_op(tile, kRowD1, u, s, lane);
+                d2T[u] = get_op(tile, kRowD2, u, s, lane);
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                gW1[t] = mfma(d1T[t], yT, gW1[t]);              // [hidden 32t.., input dim]
+                gW3[t] = mfma(doT, h2T[t], gW3[t]);             // [channel, hidden 32t..]
+#pragma unroll
+                for (int u = 0; u < 2; ++u) gW2[t][u] = mfma(d2T[t], h1T[u], gW2[t][u]);   // [hidden 32t.., hidden 32u..]
+            }
+        }
+    }
+
+    // this wavefront's partial sums: lane = column, registers = rows 8 (r / 4) + 4 h + r % 4
+    float *g1 = gW, *g2 = gW + kMlpHidden * d.n_in, *g3 = g2 + kMlpHidden * kMlpHidden;
+    const int col = lane & 31;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + k4 + (r & 3);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (col < d.n_in && gW1[t][r] != 0.0f) atomic_add(g1 + (32 * t + row) * d.n_in + col, gW1[t][r]);
+            if (row < d.n_out && gW3[t][r] != 0.0f) atomic_add(g3 + row * kMlpHidden + 32 * t + col, gW3[t][r]);
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                if (gW2[t][u][r] != 0.0f) atomic_add(g2 + (32 * t + row) * kMlpHidden + 32 * u + col, gW2[t][u][r]);
+        }
+    }
+}
+
+}  // namespace cngp

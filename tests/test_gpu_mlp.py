@@ -1,0 +1,140 @@
+"""GPU parity of the decoder kernels (matrix cores, fp16 operands, fp32 accumulation) against the fp64
+oracle.  Bars: |gpu - ref| <= 2e-3 * M with M the sum of the magnitudes of the terms that form the value
+(the oracle returns it): inputs, weights, hidden activations and hidden-layer gradients are each rounded to
+fp16 once (relative 2^-11 = 4.9e-4), three of those roundings stack up along the longest path.
+
+The backward pass decides relu'(a) on the sign of a pre-activation.  That decision is taken by both sides
+in their own arithmetic and can differ where |a| is within rounding error of zero, so the seeded batch is
+filtered with the ORACLE's pre-activations first: points with a hidden unit closer to zero than the
+kernel's own rounding can move it are dropped (about a tenth), which also makes the batch sizes ragged."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2312_17241_amd as cngp
+from parity import TOL_F16
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    return t if dtype is None else t.to(dtype)
+
+
+def make_case(seed, N, n_in, n_out, io):
+    rng = np.random.default_rng(seed)
+    y = rng.standard_normal((N, n_in)) * 0.5
+    y = y.astype(np.float16).astype(np.float64) if io == cngp.F16 else y.astype(np.float32).astype(np.float64)
+    he = lambda rows, cols: (rng.standard_normal((rows, cols)) * np.sqrt(2.0 / cols)).astype(np.float16).astype(np.float64)
+    W1, W2, W3 = he(64, n_in), he(64, 64), he(n_out, 64)
+    dout = rng.standard_normal((N, n_out)).astype(np.float32).astype(np.float64)
+    return y, W1, W2, W3, dout
+
+
+def drop_ambiguous(y, W1, W2, W3, dout, io):
+    """Keep the points whose hidden pre-activations all lie clearly on one side of zero.  The weights are
+    fp16 numbers; y is one too when it is stored as fp16, else the kernel rounds it (2^-11 relative).  The
+    kernel's first pre-activation then differs from the oracle's by that rounding and its fp32 summation
+    (1e-5 of the magnitude sum); the second one also by the rounding of every h1 to fp16."""
+    eps = 2.0 ** -11
+    a1 = y @ W1.T
+    m1 = np.abs(y) @ np.abs(W1).T
+    d1 = ((eps if io == cngp.F32 else 0.0) + 1e-5) * m1
+    h1 = np.maximum(a1, 0)
+    a2 = h1 @ W2.T
+    d2 = (d1 + eps * h1) @ np.abs(W2).T + 2e-5 * (h1 @ np.abs(W2).T)
+    keep = (np.abs(a1) > d1).all(axis=1) & (np.abs(a2) > d2).all(axis=1)
+    return y[keep], dout[keep], float(keep.mean())
+
+
+def check(name, got, ref, mag):
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    assert np.isfinite(got).all(), name
+    err = np.abs(got - ref) / np.maximum(np.maximum(np.abs(ref), mag), 1e-30)
+    worst = np.unravel_index(np.argmax(err), err.shape)
+    assert err[worst] <= TOL_F16, f"{name}: rel err {err[worst]:.3e} at {worst}: got {got[worst]}, ref {ref[worst]}, mag {mag[worst]}"
+    return float(err.max())
+
+
+CASES = [(32, 3, cngp.F16, 5000), (32, 3, cngp.F32, 777), (16, 3, cngp.F32, 2049), (8, 1, cngp.F32, 300),
+         (32, 16, cngp.F16, 1000), (20, 4, cngp.F16, 640), (3, 2, cngp.F32, 31), (32, 4, cngp.F16, 1)]
+
+
+@pytest.mark.parametrize("n_in,n_out,io,N", CASES)
+def test_mlp_forward(n_in, n_out, io, N):
+    y, W1, W2, W3, _ = make_case(n_in * 100 + n_out, N, n_in, n_out, io)
+    cfg = cngp.MlpConfig(n_in, n_out, io)
+    assert cfg.weight_count == 64 * n_in + 64 * 64 + 64 * n_out
+    W = dev(np.concatenate([W1.ravel(), W2.ravel(), W3.ravel()]), torch.float16)
+    out = cngp.mlp_fwd(cfg, dev(y, torch.float16 if io == cngp.F16 else torch.float32), W)
+    torch.cuda.synchronize()
+    ref, mag, _ = oracle.mlp_fwd(y, W1, W2, W3, want_mag=True)
+    check("out", out.cpu().numpy(), ref, mag)
+
+
+@pytest.mark.parametrize("n_in,n_out,io,N", CASES)
+def test_mlp_backward(n_in, n_out, io, N):
+    y, W1, W2, W3, dout = make_case(n_in * 100 + n_out + 7, N, n_in, n_out, io)
+    y, dout, kept = drop_ambiguous(y, W1, W2, W3, dout, io)
+    assert kept > 0.2 or N < 40          # the bounds are worst-case, so the filter is conservative
+    if y.shape[0] == 0:
+        pytest.skip("the only point of this case was ambiguous")
+    cfg = cngp.MlpConfig(n_in, n_out, io, flags=cngp.ZERO_GRADS)
+    W = dev(np.concatenate([W1.ravel(), W2.ravel(), W3.ravel()]), torch.float16)
+    tdt = torch.float16 if io == cngp.F16 else torch.float32
+    gW = torch.full((cfg.weight_count,), float("nan"), device=DEV)
+    dy, gW = cngp.mlp_bwd(cfg, dev(y, tdt), W, dev(dout, torch.float32), grad_W=gW)
+    torch.cuda.synchronize()
+    g, mag, _ = oracle.mlp_bwd(y, W1, W2, W3, dout)
+    check("dy", dy.float().cpu().numpy(), g["dy"], mag["dy"])
+    g1, g2, g3 = (t.cpu().numpy() for t in cfg.split(gW))
+    check("dW1", g1, g["dW1"], mag["dW1"])
+    check("dW2", g2, g["dW2"], mag["dW2"])
+    check("dW3", g3, g["dW3"], mag["dW3"])
+    # without the flag the gradient accumulates
+    cfg2 = cngp.MlpConfig(n_in, n_out, io)
+    _, gW2 = cngp.mlp_bwd(cfg2, dev(y, tdt), W, dev(dout, torch.float32), grad_W=gW.clone())
+    torch.cuda.synchronize()
+    check("2 dW2", cfg.split(gW2)[1].cpu().numpy(), 2 * g["dW2"], 2 * mag["dW2"])
+
+
+def test_mlp_full_size():
+    """The benchmark's batch: 2^18 points, 32 inputs (L * F of the headline workload), RGB output."""
+    N, n_in, n_out = 2**18, 32, 3
+    y, W1, W2, W3, dout = make_case(99, N, n_in, n_out, cngp.F16)
+    y, dout, kept = drop_ambiguous(y, W1, W2, W3, dout, cngp.F16)
+    cfg = cngp.MlpConfig(n_in, n_out, cngp.F16, flags=cngp.ZERO_GRADS)
+    W = dev(np.concatenate([W1.ravel(), W2.ravel(), W3.ravel()]), torch.float16)
+    out = cngp.mlp_fwd(cfg, dev(y, torch.float16), W)
+    dy, gW = cngp.mlp_bwd(cfg, dev(y, torch.float16), W, dev(dout, torch.float32))
+    torch.cuda.synchronize()
+    ref, mag, _ = oracle.mlp_fwd(y, W1, W2, W3, want_mag=True)
+    check("out", out.cpu().numpy(), ref, mag)
+    g, gm, _ = oracle.mlp_bwd(y, W1, W2, W3, dout)
+    check("dy", dy.float().cpu().numpy(), g["dy"], gm["dy"])
+    for name, t in zip(("dW1", "dW2", "dW3"), cfg.split(gW)):
+        check(name, t.cpu().numpy(), g[name], gm[name])
+
+
+def test_adam_step_on_a_plain_array():
+    rng = np.random.default_rng(5)
+    n = 64 * 32 + 64 * 64 + 64 * 3 + 1                      # not a multiple of four
+    theta = rng.standard_normal(n).astype(np.float32)
+    m = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    v = (rng.random(n) * 1e-3).astype(np.float32)
+    g = rng.standard_normal(n).astype(np.float32)
+    opt = cngp.Adam(lr=1e-2, beta1=0.9, beta2=0.99, eps=1e-15, step=4)
+    t = [dev(a) for a in (theta, m, v, g)]
+    half = torch.zeros(n, dtype=torch.float16, device=DEV)
+    cngp.adam_step(opt, t[0], half, t[1], t[2], t[3], clear_grad=True)
+    torch.cuda.synchronize()
+    f = lambda z: float(np.float32(z))
+    th, m1, v1 = oracle.adam_step(theta, m, v, g, f(opt.lr), f(opt.beta1), f(opt.beta2), f(opt.eps), opt.step)
+    assert np.allclose(t[0].cpu().numpy(), th, rtol=1e-5, atol=1e-7)
+    assert np.allclose(t[1].cpu().numpy(), m1, rtol=1e-5, atol=1e-8) and np.allclose(t[2].cpu().numpy(), v1, rtol=1e-5, atol=1e-10)
+    assert np.array_equal(half.cpu().numpy().view(np.uint16), t[0].cpu().numpy().astype(np.float16).view(np.uint16))
+    assert not t[3].any()
