@@ -745,11 +745,15 @@ int mlp_dims(const cngp_mlp_config *cfg, MlpDims *d) {
     if (cfg->flags & ~(uint32_t)CNGP_ZERO_GRADS) return CNGP_ERR_INVALID;
     d->n_in = cfg->n_in; d->n_out = cfg->n_out;
     d->ks1 = (cfg->n_in + 7) / 8; d->ks3 = (cfg->n_out + 7) / 8;
+    d->vec_in = d->vec_out = 0;            // set by the caller once the pointers are known
     return CNGP_OK;
 }
-// A persistent grid: every wavefront walks over tiles of 32 points.
-unsigned mlp_blocks(int64_t tiles, int per_cu) {
-    const int64_t want = (tiles + kMlpBlock / 64 - 1) / (kMlpBlock / 64);
+// A persistent grid: every wavefront walks over tiles of 32 points.  At most `per_cu` workgroups per CU
+// (what fits at once), and no more than gives each wavefront `min_tiles` tiles, so that the staging of the
+// weights, which every workgroup repeats, stays a small part of its work.
+unsigned mlp_blocks(int64_t tiles, int per_cu, int min_tiles) {
+    const int64_t per_block = (int64_t)(kMlpBlock / 64) * min_tiles;
+    const int64_t want = (tiles + per_block - 1) / per_block;
     const int64_t cap = 256 * (int64_t)per_cu;
     return (unsigned)(want < cap ? want : cap);
 }
@@ -769,11 +773,12 @@ int cngp_mlp_fwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const voi
     if (!y || !W || !out) return CNGP_ERR_NULL;
     const int64_t tiles = (N + 31) / 32;
     hipStream_t s = (hipStream_t)stream;
+    d.vec_in = (cfg->n_in % 4 == 0 && aligned(y, 16)) ? 1 : 0;
     LaunchTimer t(s, K_MLP_FWD);
     if (cfg->io_dtype == CNGP_F16)
-        mlp_fwd_kernel<__half><<<mlp_blocks(tiles, 8), kMlpBlock, kMlpFwdLds, s>>>(d, (const __half *)y, N, (const __half *)W, out, tiles);
+        mlp_fwd_kernel<__half><<<mlp_blocks(tiles, 3, 4), kMlpBlock, kMlpFwdLds, s>>>(d, (const __half *)y, N, (const __half *)W, out, tiles);
     else
-        mlp_fwd_kernel<float><<<mlp_blocks(tiles, 8), kMlpBlock, kMlpFwdLds, s>>>(d, (const float *)y, N, (const __half *)W, out, tiles);
+        mlp_fwd_kernel<float><<<mlp_blocks(tiles, 3, 4), kMlpBlock, kMlpFwdLds, s>>>(d, (const float *)y, N, (const __half *)W, out, tiles);
     return launch_status("mlp_fwd_kernel");
 }
 
@@ -792,16 +797,18 @@ int cngp_mlp_bwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const voi
     }
     if (N == 0) return CNGP_OK;
     const int64_t tiles = (N + 31) / 32;
+    d.vec_in = (cfg->n_in % 4 == 0 && aligned(y, 16) && aligned(dy, 16)) ? 1 : 0;
+    d.vec_out = (cfg->n_out % 4 == 0 && aligned(dout, 16)) ? 1 : 0;
     if (cfg->io_dtype == CNGP_F16) {
         auto kernel = mlp_bwd_kernel<__half>;
         if (int rc = allow_big_lds(kernel, kMlpBwdLds)) return rc;
         LaunchTimer t(s, K_MLP_BWD);
-        kernel<<<mlp_blocks(tiles, 1), kMlpBlock, kMlpBwdLds, s>>>(d, (const __half *)y, N, (const __half *)W, dout, (__half *)dy, grad_W, tiles);
+        kernel<<<mlp_blocks(tiles, 1, 4), kMlpBlock, kMlpBwdLds, s>>>(d, (const __half *)y, N, (const __half *)W, dout, (__half *)dy, grad_W, tiles);
     } else {
         auto kernel = mlp_bwd_kernel<float>;
         if (int rc = allow_big_lds(kernel, kMlpBwdLds)) return rc;
         LaunchTimer t(s, K_MLP_BWD);
-        kernel<<<mlp_blocks(tiles, 1), kMlpBlock, kMlpBwdLds, s>>>(d, (const float *)y, N, (const __half *)W, dout, (float *)dy, grad_W, tiles);
+        kernel<<<mlp_blocks(tiles, 1, 4), kMlpBlock, kMlpBwdLds, s>>>(d, (const float *)y, N, (const __half *)W, dout, (float *)dy, grad_W, tiles);
     }
     return launch_status("mlp_bwd_kernel");
 }

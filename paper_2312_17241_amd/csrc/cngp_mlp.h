@@ -27,6 +27,7 @@ struct MlpDims {
     int n_in, n_out;
     int ks1;                                   // K-steps of layer 1: ceil(n_in / 8)
     int ks3;                                   // K-steps of the transposed output layer: ceil(n_out / 8)
+    int vec_in, vec_out;                       // rows of y (and dL/dy) / of dL/dout can be read four values at a time
 };
 
 // Slots of the weight operands in LDS; a slot holds one half4 per lane (512 bytes), ready to be used as
@@ -50,9 +51,23 @@ __device__ __forceinline__ _Float16 w_at(const __half *W, int rows, int cols, bo
     return (r < rows && c < cols) ? (_Float16)__half2float(W[r * cols + c]) : (_Float16)0.0f;
 }
 
-// Fills `slots` operand slots, the work spread over the workgroup.
-__device__ __forceinline__ void stage_operands(half4_t *ops, const __half *W, const MlpDims d, const int slots) {
-    const __half *W1 = W, *W2 = W + kMlpHidden * d.n_in, *W3 = W2 + kMlpHidden * kMlpHidden;
+// Fills `slots` operand slots, the work spread over the workgroup.  The weights first come into LDS as
+// they are, with wide coalesced loads (`raw`: room for weight_count halves, 16-byte aligned, may be reused
+// after the barrier at the end); building the operand layout from global memory element by element is a
+// chain of dependent cache round trips that costs more than the whole forward pass of a small batch.
+__device__ __forceinline__ void stage_operands(half4_t *ops, __half *raw, const __half *W, const MlpDims d,
+                                               const int slots) {
+    const int count = kMlpHidden * d.n_in + kMlpHidden * kMlpHidden + kMlpHidden * d.n_out;
+    if ((reinterpret_cast<uintptr_t>(W) & 15u) == 0) {
+        for (int i = threadIdx.x * 8; i < count; i += kMlpBlock * 8) {
+            if (i + 8 <= count) *reinterpret_cast<uint4 *>(raw + i) = *reinterpret_cast<const uint4 *>(W + i);
+            else for (int j = i; j < count; ++j) raw[j] = W[j];
+        }
+    } else {
+        for (int i = threadIdx.x; i < count; i += kMlpBlock) raw[i] = W[i];
+    }
+    __syncthreads();
+    const __half *W1 = raw, *W2 = raw + kMlpHidden * d.n_in, *W3 = W2 + kMlpHidden * kMlpHidden;
     for (int e = threadIdx.x; e < slots * 64; e += kMlpBlock) {
         const int slot = e >> 6, lane = e & 63, row = lane & 31, k4 = 4 * (lane >> 5);
         const __half *M;
@@ -69,6 +84,7 @@ __device__ __forceinline__ void stage_operands(half4_t *ops, const __half *W, co
         for (int j = 0; j < 4; ++j) v[j] = w_at(M, rows, cols, tr, 32 * t + row, 8 * s + k4 + j);
         ops[e] = v;
     }
+    __syncthreads();
 }
 
 template <typename T> __device__ __forceinline__ float to_float(T v);
@@ -78,15 +94,45 @@ template <typename T> __device__ __forceinline__ T from_float(float v);
 template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
 template <> __device__ __forceinline__ __half from_float<__half>(float v) { return __float2half_rn(v); }
 
-// B operand of K-step s from a row-major [N, cols] array: this lane's point, columns 8s + 4h .. + 3.
-template <typename T>
-__device__ __forceinline__ half4_t load_b(const T *__restrict__ a, const int64_t pt, const int64_t N,
-                                          const int cols, const int k0) {
+// B operand of K-step s from a row-major [N, cols] array: this lane's point, columns k0 .. k0 + 3.
+// `vec`: cols is a multiple of four and the array 16-byte aligned, so the four values are one load.
+__device__ __forceinline__ half4_t load_b(const __half *__restrict__ a, const int64_t pt, const int64_t N,
+                                          const int cols, const int k0, const bool vec) {
     half4_t v;
+    if (vec) {
+        if (pt < N && k0 < cols) return *reinterpret_cast<const half4_t *>(a + pt * cols + k0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (_Float16)0.0f;
+        return v;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-        v[j] = (pt < N && k0 + j < cols) ? (_Float16)to_float<T>(a[pt * cols + k0 + j]) : (_Float16)0.0f;
+        v[j] = (pt < N && k0 + j < cols) ? (_Float16)__half2float(a[pt * cols + k0 + j]) : (_Float16)0.0f;
     return v;
+}
+__device__ __forceinline__ half4_t load_b(const float *__restrict__ a, const int64_t pt, const int64_t N,
+                                          const int cols, const int k0, const bool vec) {
+    half4_t v;
+    float4  f = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (vec) {
+        if (pt < N && k0 < cols) f = *reinterpret_cast<const float4 *>(a + pt * cols + k0);
+    } else {
+        if (pt < N && k0 + 0 < cols) f.x = a[pt * cols + k0 + 0];
+        if (pt < N && k0 + 1 < cols) f.y = a[pt * cols + k0 + 1];
+        if (pt < N && k0 + 2 < cols) f.z = a[pt * cols + k0 + 2];
+        if (pt < N && k0 + 3 < cols) f.w = a[pt * cols + k0 + 3];
+    }
+    v[0] = (_Float16)f.x; v[1] = (_Float16)f.y; v[2] = (_Float16)f.z; v[3] = (_Float16)f.w;
+    return v;
+}
+
+__device__ __forceinline__ void store4(float *p, float a, float b, float c, float e) {
+    *reinterpret_cast<float4 *>(p) = make_float4(a, b, c, e);
+}
+__device__ __forceinline__ void store4(__half *p, float a, float b, float c, float e) {
+    half4_t v;
+    v[0] = (_Float16)a; v[1] = (_Float16)b; v[2] = (_Float16)c; v[3] = (_Float16)e;
+    *reinterpret_cast<half4_t *>(p) = v;
 }
 
 // ReLU, rounding to fp16, and the re-use of an accumulator tile as B operands of the next layer.
@@ -124,12 +170,17 @@ struct Hidden {
     uint32_t m1[2], m2[2];
 };
 
+// This lane's part of the inputs of one tile of 32 points (the B operands of layer 1).
 template <typename IoT>
-__device__ __forceinline__ void hidden_layers(const half4_t *ops, const MlpDims d, const IoT *__restrict__ y,
-                                              const int64_t pt, const int64_t N, const int lane, Hidden &H) {
+__device__ __forceinline__ void load_inputs(const MlpDims d, const IoT *__restrict__ y, const int64_t pt,
+                                            const int64_t N, const int lane, half4_t (&yb)[4]) {
     const int k4 = 4 * (lane >> 5);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) H.yb[s] = load_b(y, pt, N, d.n_in, 8 * s + k4);
+    for (int s = 0; s < 4; ++s) yb[s] = load_b(y, pt, N, d.n_in, 8 * s + k4, d.vec_in != 0);
+}
+
+// H.yb holds the inputs on entry.
+__device__ __forceinline__ void hidden_layers(const half4_t *ops, const MlpDims d, const int lane, Hidden &H) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         acc16_t a = acc_zero();
@@ -149,6 +200,19 @@ __device__ __forceinline__ void hidden_layers(const half4_t *ops, const MlpDims 
     }
 }
 
+// Per-wavefront transpose tile: rows = input dimensions / neurons / output channels, 32 points per row,
+// rows padded to 36 halves so that the 8-byte operand reads of 32 lanes fall into different banks.
+constexpr int kTileStride = 36;
+enum : int { kRowY = 0, kRowH1 = 32, kRowH2 = 96, kRowD1 = 160, kRowD2 = 224, kRowDo = 288, kTileRows = 320 };
+constexpr size_t kMlpBwdLds = (size_t)kOpAllSlots * 64 * sizeof(half4_t) +
+                              (size_t)(kMlpBlock / 64) * kTileRows * kTileStride * sizeof(_Float16);
+constexpr size_t kMlpRawBytes = ((size_t)kMlpHidden * (kMlpMaxIn + kMlpHidden + kMlpMaxOut) * 2 + 15) & ~(size_t)15;
+constexpr size_t kMlpFwdOps = (size_t)kOpFwdSlots * 64 * sizeof(half4_t);
+constexpr size_t kMlpFwdLds = kMlpFwdOps + kMlpRawBytes;
+constexpr size_t kMlpAccBytes = (size_t)8 * 16 * 64 * sizeof(float);        // one wavefront's weight-gradient registers
+static_assert(kMlpRawBytes <= (size_t)(kMlpBlock / 64) * kTileRows * kTileStride * sizeof(_Float16), "raw weights share the tile region");
+static_assert(kMlpAccBytes <= (size_t)(kMlpBlock / 64) * kTileRows * kTileStride * sizeof(_Float16), "the reduction shares the tile region");
+
 // ------------------------------------------------------------------ forward
 template <typename IoT>
 __global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
@@ -157,14 +221,19 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
 {
     extern __shared__ __align__(16) unsigned char smem[];
     half4_t *ops = reinterpret_cast<half4_t *>(smem);
-    stage_operands(ops, W, d, kOpFwdSlots);
-    __syncthreads();
+    stage_operands(ops, reinterpret_cast<__half *>(smem + kMlpFwdOps), W, d, kOpFwdSlots);
     const int lane = threadIdx.x & 63, k4 = 4 * (lane >> 5);
     const int64_t waves = (int64_t)gridDim.x * (kMlpBlock / 64);
-    for (int64_t tile = (int64_t)blockIdx.x * (kMlpBlock / 64) + (threadIdx.x >> 6); tile < tiles; tile += waves) {
+    int64_t tile = (int64_t)blockIdx.x * (kMlpBlock / 64) + (threadIdx.x >> 6);
+    half4_t next[4];
+    load_inputs(d, y, tile * 32 + (lane & 31), N, lane, next);
+    for (; tile < tiles; tile += waves) {
         const int64_t pt = tile * 32 + (lane & 31);
         Hidden H;
-        hidden_layers(ops, d, y, pt, N, lane, H);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) H.yb[s] = next[s];
+        load_inputs(d, y, (tile + waves) * 32 + (lane & 31), N, lane, next);     // next tile, in flight during this one
+        hidden_layers(ops, d, lane, H);
         acc16_t o = acc_zero();
 #pragma unroll
         for (int s = 0; s < 8; ++s) o = mfma(ops[(kOpW3 + s) * 64 + lane], H.h2[s], o);
@@ -179,14 +248,6 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
 }
 
 // ------------------------------------------------------------------ backward
-// Per-wavefront transpose tile: rows = input dimensions / neurons / output channels, 32 points per row,
-// rows padded to 36 halves so that the 8-byte operand reads of 32 lanes fall into different banks.
-constexpr int kTileStride = 36;
-enum : int { kRowY = 0, kRowH1 = 32, kRowH2 = 96, kRowD1 = 160, kRowD2 = 224, kRowDo = 288, kTileRows = 320 };
-constexpr size_t kMlpBwdLds = (size_t)kOpAllSlots * 64 * sizeof(half4_t) +
-                              (size_t)(kMlpBlock / 64) * kTileRows * kTileStride * sizeof(_Float16);
-constexpr size_t kMlpFwdLds = (size_t)kOpFwdSlots * 64 * sizeof(half4_t);
-
 // B-layout registers (lane = point, K-step s holds rows 8s + 4h .. + 3) written as rows of the tile.
 template <int STEPS>
 __device__ __forceinline__ void put_rows(_Float16 *tile, const int row0, const half4_t (&b)[STEPS], const int lane) {
@@ -211,7 +272,7 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
     half4_t  *ops = reinterpret_cast<half4_t *>(smem);
     _Float16 *tile = reinterpret_cast<_Float16 *>(smem + (size_t)kOpAllSlots * 64 * sizeof(half4_t)) +
                      (size_t)(threadIdx.x >> 6) * kTileRows * kTileStride;
-    stage_operands(ops, W, d, kOpAllSlots);
+    stage_operands(ops, reinterpret_cast<__half *>(smem + (size_t)kOpAllSlots * 64 * sizeof(half4_t)), W, d, kOpAllSlots);
     const int lane = threadIdx.x & 63, k4 = 4 * (lane >> 5);
     for (int i = lane; i < kTileRows * kTileStride; i += 64) tile[i] = (_Float16)0.0f;   // padding rows stay zero
     __syncthreads();
@@ -224,14 +285,25 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
     }
 
     const int64_t waves = (int64_t)gridDim.x * (kMlpBlock / 64);
-    for (int64_t tl = (int64_t)blockIdx.x * (kMlpBlock / 64) + (threadIdx.x >> 6); tl < tiles; tl += waves) {
+    int64_t tl = (int64_t)blockIdx.x * (kMlpBlock / 64) + (threadIdx.x >> 6);
+    half4_t next[4], next_db[2];
+    load_inputs(d, y, tl * 32 + (lane & 31), N, lane, next);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) next_db[s] = load_b(dout, tl * 32 + (lane & 31), N, d.n_out, 8 * s + k4, d.vec_out != 0);
+    for (; tl < tiles; tl += waves) {
         const int64_t pt = tl * 32 + (lane & 31);
         Hidden H;
-        hidden_layers(ops, d, y, pt, N, lane, H);
-
         half4_t db[2], dh2[8], dh1[8];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) db[s] = load_b(dout, pt, N, d.n_out, 8 * s + k4);
+        for (int s = 0; s < 4; ++s) H.yb[s] = next[s];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) db[s] = next_db[s];
+        load_inputs(d, y, (tl + waves) * 32 + (lane & 31), N, lane, next);       // next tile, in flight during this one
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+            next_db[s] = load_b(dout, (tl + waves) * 32 + (lane & 31), N, d.n_out, 8 * s + k4, d.vec_out != 0);
+        hidden_layers(ops, d, lane, H);
+
 #pragma unroll
         for (int t = 0; t < 2; ++t) {                           // dL/dh2 = W3^T dout, where h2 was active
             acc16_t g = acc_zero();
@@ -253,9 +325,15 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
             for (int s = 0; s < 8; ++s) g = mfma(ops[(kOpW1T + s) * 64 + lane], dh1[s], g);
             if (pt < N) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int i = 8 * (r >> 2) + k4 + (r & 3);
-                    if (i < d.n_in) dy[pt * d.n_in + i] = from_float<IoT>(g[r]);
+                for (int q = 0; q < 4; ++q) {                   // register group q: input dimensions 8q + 4h .. + 3
+                    const int i = 8 * q + k4;
+                    if (d.vec_in && i < d.n_in) {
+                        store4(dy + pt * d.n_in + i, g[4 * q], g[4 * q + 1], g[4 * q + 2], g[4 * q + 3]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (i + j < d.n_in) dy[pt * d.n_in + i + j] = from_float<IoT>(g[4 * q + j]);
+                    }
                 }
             }
         }
@@ -290,7 +368,33 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
         }
     }
 
-    // this wavefront's partial sums: lane = column, registers = rows 8 (r / 4) + 4 h + r % 4
+    // Sum over the workgroup's wavefronts in LDS (plain read-add-write, one wavefront after the other; the
+    // tile region is free now), then one set of global atomics per workgroup.
+    // Register r of accumulator a, lane l lives at red[(a * 16 + r) * 64 + l].
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(smem + (size_t)kOpAllSlots * 64 * sizeof(half4_t));
+    const int wave = threadIdx.x >> 6;
+    for (int w = 0; w < kMlpBlock / 64 - 1; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    float *p1 = red + ((0 + t) * 16 + r) * 64 + lane, *p3 = red + ((2 + t) * 16 + r) * 64 + lane;
+                    *p1 = (w == 0 ? 0.0f : *p1) + gW1[t][r];
+                    *p3 = (w == 0 ? 0.0f : *p3) + gW3[t][r];
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        float *p2 = red + ((4 + 2 * t + u) * 16 + r) * 64 + lane;
+                        *p2 = (w == 0 ? 0.0f : *p2) + gW2[t][u][r];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (wave != kMlpBlock / 64 - 1) return;
+    // lane = column, registers = rows 8 (r / 4) + 4 h + r % 4
     float *g1 = gW, *g2 = gW + kMlpHidden * d.n_in, *g3 = g2 + kMlpHidden * kMlpHidden;
     const int col = lane & 31;
 #pragma unroll
@@ -298,11 +402,15 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
         const int row = 8 * (r >> 2) + k4 + (r & 3);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            if (col < d.n_in && gW1[t][r] != 0.0f) atomic_add(g1 + (32 * t + row) * d.n_in + col, gW1[t][r]);
-            if (row < d.n_out && gW3[t][r] != 0.0f) atomic_add(g3 + row * kMlpHidden + 32 * t + col, gW3[t][r]);
+            const float v1 = gW1[t][r] + red[((0 + t) * 16 + r) * 64 + lane];
+            const float v3 = gW3[t][r] + red[((2 + t) * 16 + r) * 64 + lane];
+            if (col < d.n_in && v1 != 0.0f) atomic_add(g1 + (32 * t + row) * d.n_in + col, v1);
+            if (row < d.n_out && v3 != 0.0f) atomic_add(g3 + row * kMlpHidden + 32 * t + col, v3);
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
-                if (gW2[t][u][r] != 0.0f) atomic_add(g2 + (32 * t + row) * kMlpHidden + 32 * u + col, gW2[t][u][r]);
+            for (int u = 0; u < 2; ++u) {
+                const float v2 = gW2[t][u][r] + red[((4 + 2 * t + u) * 16 + r) * 64 + lane];
+                if (v2 != 0.0f) atomic_add(g2 + (32 * t + row) * kMlpHidden + 32 * u + col, v2);
+            }
         }
     }
 }

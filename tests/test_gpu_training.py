@@ -108,3 +108,38 @@ def test_module_gradients_match_the_oracle():
     gF, gC, A_f, A_c = oracle.encode_bwd(w, x_h, D_f, Dhat, np.ascontiguousarray(dy))
     check_close("grad D_f", enc.grad_D_f.cpu().numpy(), 2 * gF, 2 * A_f, fp16_out=False)
     check_close("grad Dhat_c", enc.grad_Dhat_c.cpu().numpy(), 2 * gC, 2 * A_c, fp16_out=False)
+
+
+def test_training_with_the_library_decoder():
+    """The same fit with every trained component inside the library: encoding forward / backward, decoder
+    forward / backward on the matrix cores, Adam steps for the codebooks (fused with the bake) and for the
+    decoder's weights.  PyTorch only allocates, draws the batch and forms the residual."""
+    cfg = cngp.Config(d=2, L=8, F=2, N_f=2**8, N_c=2**14, N_p=16, N_min=16, N_max=512,
+                      feat_dtype=cngp.F16, io_dtype=cngp.F16)
+    mcfg = cngp.MlpConfig(cfg.L * cfg.F, 3, cngp.F16, flags=cngp.ZERO_GRADS)
+    enc = Encoding(cfg, DEV, seed=0)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    W1, W2, W3 = (torch.randn((r, c), generator=g) * math.sqrt(2.0 / c) for r, c in ((64, 16), (64, 64), (3, 64)))
+    master = torch.cat([W1.ravel(), W2.ravel(), W3.ravel()]).to(DEV)
+    W = master.half()
+    m, v, gW = torch.zeros_like(master), torch.zeros_like(master), torch.zeros_like(master)
+    gen = torch.Generator(device=DEV).manual_seed(1)
+    steps, scale, losses = 400, 128.0, []
+    ws = cngp.alloc_workspace(cfg, 2**15)
+    for it in range(steps):
+        decay = 0.1 ** (it / steps)
+        x = torch.rand((2**15, 2), device=DEV, generator=gen)
+        y = cngp.encode_fwd(cfg, x, enc.D_f, enc.D_c, workspace=ws)
+        out = cngp.mlp_fwd(mcfg, y, W)
+        resid = out - synthetic_image(x)
+        losses.append((resid ** 2).mean().item())
+        dout = resid * (2.0 * scale / resid.numel())                       # loss scaling keeps fp16 dL/dy in range
+        dy, _ = cngp.mlp_bwd(mcfg, y, W, dout, grad_W=gW)
+        cngp.encode_bwd(cfg, x, enc.D_f, enc.Dhat_c, dy, enc.grad_D_f, enc.grad_Dhat_c, workspace=ws)
+        cngp.adam_step(cngp.Adam(lr=1e-2 * decay, eps=1e-15, grad_scale=1 / scale, step=it + 1), master, W, m, v, gW)
+        enc.step(cngp.Adam(lr=1e-2 * decay, eps=1e-15, grad_scale=1 / scale),
+                 cngp.Adam(lr=1e-1 * decay, eps=1e-15, grad_scale=1 / scale))
+    print(f"loss {np.mean(losses[:5]):.3e} -> {np.mean(losses[-20:]):.3e}")
+    assert np.isfinite(losses).all()
+    assert np.mean(losses[-20:]) < 0.1 * np.mean(losses[:5])
+    assert np.mean(losses[-20:]) < 4e-3          # the PyTorch-decoder run of the same shape ends near 2e-3
