@@ -53,6 +53,10 @@ def main():
     ap.add_argument("--with-optimizer", action="store_true",
                     help="a step becomes: Adam step fused with the bake (replaces the bake), forward, backward; "
                          "the tables then change from step to step.  Not the headline configuration.")
+    ap.add_argument("--with-decoder", action="store_true",
+                    help="adds the 64-wide decoder after the encoding: forward, residual against a fixed random target, "
+                         "backward (its dL/dy feeds the encoding's backward), and with --with-optimizer its Adam step.  "
+                         "Not the headline configuration.")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -108,15 +112,39 @@ def main():
         cfg_opt = cngp.Config.from_workload(w, index_format=fmt)
         n_step = [0]
 
+    with_dec = args.with_decoder and not fwd_only
+    if with_dec:
+        n_out = 3
+        mcfg = cngp.MlpConfig(w.L * w.F, n_out, cngp.F16 if w.io_dtype == "f16" else cngp.F32, flags=cngp.ZERO_GRADS)
+        g = torch.Generator(device="cpu").manual_seed(7)
+        W_master = torch.cat([(torch.randn((r, c), generator=g) * (2.0 / c) ** 0.5).ravel()
+                              for r, c in ((64, w.L * w.F), (64, 64), (n_out, 64))]).to(dev)
+        W_half = W_master.half()
+        W_m, W_v, W_g = torch.zeros_like(W_master), torch.zeros_like(W_master), torch.zeros_like(W_master)
+        target = torch.rand((N, n_out), generator=g).to(dev)
+        out_dec = torch.empty((N, n_out), dtype=torch.float32, device=dev)
+        dout = torch.empty_like(out_dec)
+        loss_scale = 128.0
+
     def step():
+        if with_dec:
+            if with_opt:
+                cngp.adam_step(cngp.Adam(lr=1e-3, eps=1e-15, grad_scale=1 / loss_scale, step=n_step[0] + 1),
+                               W_master, W_half, W_m, W_v, W_g)
         if with_opt:
             n_step[0] += 1
-            opt = cngp.Adam(lr=1e-3, beta1=0.9, beta2=0.99, eps=1e-15, step=n_step[0])
+            opt = cngp.Adam(lr=1e-3, beta1=0.9, beta2=0.99, eps=1e-15, step=n_step[0],
+                            grad_scale=(1 / loss_scale) if with_dec else 1.0)
             cngp.adam_step_bake(cfg_opt, opt, opt, (master, D_f_arg, moments[0], moments[1], gF),
                                 (Dhat, moments[2], moments[3], gC, D_c))
         else:
             cngp.bake_probes(cfg, Dhat, D_c)
         cngp.encode_fwd(cfg, x, D_f, D_c, y, workspace=ws)
+        if with_dec:
+            cngp.mlp_fwd(mcfg, y, W_half, out_dec)
+            torch.sub(out_dec, target, out=dout)                      # residual of an L2 loss: plumbing, two tiny torch kernels
+            dout.mul_(2.0 * loss_scale / dout.numel())
+            cngp.mlp_bwd(mcfg, y, W_half, dout, dy, W_g)              # writes dL/dy for the encoding
         if not fwd_only:
             cngp.encode_bwd(cfg, x, D_f, Dhat, dy, gF, gC, workspace=ws)
 
@@ -174,8 +202,9 @@ def main():
                                f"N_min={w.N_min} N_max={w.N_max} points={N} ({w.points}) "
                                f"D_f={w.feat_dtype} y/dy={w.io_dtype}",
                    "step": "bake + fwd" if fwd_only else
-                           ("Adam step fused with bake + fwd + bwd (grads cleared each step)" if with_opt else
-                            "bake + fwd + bwd (grads cleared each step)")},
+                           (("decoder fwd/bwd + " if with_dec else "") +
+                            ("Adam step fused with bake + fwd + bwd (grads cleared each step)" if with_opt else
+                             "bake + fwd + bwd (grads cleared each step)"))},
         "roofline": roofline,
         "kernels_us_per_step": {k: round(v["ms"] * 1e3 / args.steps, 2) for k, v in per_kernel.items()},
         "kernel_parts": {k: v["parts"] for k, v in per_kernel.items() if len(v["parts"]) > 1},
@@ -205,11 +234,26 @@ def main():
 
     if with_opt:
         t_opt = per_kernel["adam_step_bake"]["ms"] / args.steps * 1e-3
+        if with_dec:                                    # the decoder's Adam launch is counted in the same kernel kind
+            alg["adam_step_bake"] += 30 * W_master.numel()
         out["optimizer_roofline"] = {"bound": "hbm", "kernel": "adam_step_bake",
                                      "achieved": round(alg["adam_step_bake"] / t_opt / 1e9, 1), "peak": HBM_PEAK_GBS,
                                      "unit": "GB/s", "frac": round(alg["adam_step_bake"] / t_opt / 1e9 / HBM_PEAK_GBS, 4),
                                      "algorithmic_bytes_per_launch": alg["adam_step_bake"],
                                      "avg_launch_us": round(t_opt * 1e6, 2)}
+
+    if with_dec:
+        flops = 2.0 * N * (64 * w.L * w.F + 64 * 64 + 64 * n_out)          # one pass through the three products
+        out["decoder_roofline"] = {
+            "bound": "mfma", "peak": 2500.0, "unit": "TFLOP/s",
+            "fwd": {"avg_launch_us": round(per_kernel["mlp_fwd"]["ms"] * 1e3 / args.steps, 2),
+                    "achieved": round(flops / (per_kernel["mlp_fwd"]["ms"] * 1e-3 / args.steps) / 1e12, 1)},
+            "bwd": {"avg_launch_us": round(per_kernel["mlp_bwd"]["ms"] * 1e3 / args.steps, 2),
+                    "achieved": round(3 * flops / (per_kernel["mlp_bwd"]["ms"] * 1e-3 / args.steps) / 1e12, 1)},
+            "note": "useful flops (2 per multiply-add of the unpadded products; backward = recompute + data + weight "
+                    "gradients = 3 passes) over the kernel's average duration"}
+        for k in ("fwd", "bwd"):
+            out["decoder_roofline"][k]["frac"] = round(out["decoder_roofline"][k]["achieved"] / 2500.0, 4)
 
     if not args.no_check or not args.no_cpu_baseline:
         import oracle
@@ -242,7 +286,9 @@ def main():
                 unpack = D_c if fmt == cngp.IDX_U8 else torch.stack([D_c & 0xF, D_c >> 4], dim=-1).reshape(w.L, w.N_c)
                 check_exact("D_c", unpack.cpu().numpy(), D_c_ref)
             e = {"y": check_close("y", y[:n_cpu].cpu().numpy(), y_ref, ymag, fp16_out=(w.io_dtype == "f16"))}
-            if not fwd_only and n_cpu == N:
+            # with the decoder in the loop the upstream gradient is the decoder's output: no oracle input may come
+            # from the kernels, so the gradient check is left to the parity tests in that mode
+            if not fwd_only and n_cpu == N and not with_dec:
                 e["grad_D_f"] = check_close("grad D_f", gF.cpu().numpy(), g_ref[0], g_ref[2], fp16_out=False)
                 e["grad_Dhat_c"] = check_close("grad Dhat_c", gC.cpu().numpy(), g_ref[1], g_ref[3], fp16_out=False)
             out["parity_max_rel_err"] = {k: float(f"{v:.3e}") for k, v in e.items()}
