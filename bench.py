@@ -158,20 +158,30 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # timed region: exactly K steps, every kernel bracketed by HIP events on its launch stream
-    cngp.profile_enable(True)
-    cngp.profile_read()
+    # timed region: exactly K steps, nothing else on the stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kernels = cngp.profile_read()
-    cngp.profile_enable(False)
-
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = N * args.steps / (t1 - t0)
+
+    # The same K steps again, now with every kernel bracketed by HIP events on its launch stream: the
+    # per-kernel durations the roofline is computed from.  The event records themselves cost a few
+    # microseconds per launch (about 6 % of a step), which is why they are kept out of the timed region;
+    # the step time of this pass is reported as "ms_per_step_with_events".
+    cngp.profile_enable(True)
+    cngp.profile_read()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    kernels = cngp.profile_read()
+    cngp.profile_enable(False)
 
     # roofline of the dominant kernel kind
     alg = algorithmic_bytes(w, N, cfg.index_cols)
@@ -196,7 +206,8 @@ def main():
     out = {
         "metric": "encoded points/s fwd+bwd (d=3, L=16)" if not fwd_only else "encoded points/s fwd",
         "value": round(value, 1), "unit": "points/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_with_events": round((t3 - t2) * 1e3 / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: d={w.d} L={w.L} F={w.F} N_f={w.N_f} N_c={w.N_c} N_p={w.N_p} "
                                f"N_min={w.N_min} N_max={w.N_max} points={N} ({w.points}) "
