@@ -69,7 +69,9 @@ enum {
     CNGP_BWD_SLICED = 4u,   /* force the variant that accumulates table slices in LDS (needs workspace)   */
                             /* neither of the two: the library picks by table size and N                   */
     CNGP_BWD_NO_PREREDUCE = 8u, /* LDS variant only: do not pre-reduce coarse levels per grid vertex       */
-    CNGP_FWD_SIMPLE = 16u   /* force the forward variant that reads D_c from memory, not from LDS          */
+    CNGP_FWD_SIMPLE = 16u,  /* force the forward variant that reads D_c from memory, not from LDS          */
+    CNGP_BWD_BINNED = 32u   /* LDS variant: bin the references of the hashed levels by slice first instead */
+                            /* of scanning all points once per slice (more workspace, see plan info)       */
 };
 
 /* Hyper-parameters of the encoding (Table 1 of the paper, same symbols). */
@@ -135,8 +137,9 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N,
  * [1] number of coarse levels pre-reduced per grid vertex; [2], [3] slices per level of the feature and
  * of the logit gradient table; [4], [5] point chunks of the feature / logit role on hashed levels;
  * [6], [7] vertex chunks of the two roles on pre-reduced levels; [8] point chunks and [9] total slices
- * of the vertex-grid accumulation. */
-enum { CNGP_PLAN_INFO_COUNT = 10 };
+ * of the vertex-grid accumulation; [10] 1 = the hashed levels' references are binned by slice first, and then
+ * [11], [12] workgroups that drain one bin of the feature / logit table and [13] point chunks of the binning. */
+enum { CNGP_PLAN_INFO_COUNT = 14 };
 int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info);
 
 /* Bake (Fig. 3; Sec. 3): D_c[l][r] = index of the largest confidence value in row r of D^_c.

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libcngp.so")
 
 F32, F16 = 0, 1
 IDX_U8, IDX_PACKED4, IDX_BITS = 0, 1, 2
-ZERO_GRADS, BWD_DIRECT, BWD_SLICED, BWD_NO_PREREDUCE, FWD_SIMPLE = 1, 2, 4, 8, 16
+ZERO_GRADS, BWD_DIRECT, BWD_SLICED, BWD_NO_PREREDUCE, FWD_SIMPLE, BWD_BINNED = 1, 2, 4, 8, 16, 32
 
 OK, ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
 
@@ -193,11 +193,12 @@ def workspace_bytes(cfg: Config, N: int) -> int:
 
 def bwd_plan_info(cfg: Config, N: int) -> dict:
     """How encode_bwd would run for (cfg, N): variant, pre-reduced levels, slices and chunk counts."""
-    info = (ctypes.c_int32 * 10)()
+    info = (ctypes.c_int32 * 14)()
     c = cfg.c()
     _check(_lib.cngp_bwd_plan_info(ctypes.byref(c), N, info))
     names = ("sliced", "dense_levels", "slices_f", "slices_c", "chunks_feat_pts", "chunks_logit_pts",
-             "chunks_feat_vtx", "chunks_logit_vtx", "chunks_grid", "grid_slices")
+             "chunks_feat_vtx", "chunks_logit_vtx", "chunks_grid", "grid_slices",
+             "binned", "drain_wgs_feat", "drain_wgs_logit", "bin_chunks")
     return dict(zip(names, list(info)))
 
 

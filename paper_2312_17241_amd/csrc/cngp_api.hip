@@ -3,6 +3,7 @@
 #include "../../include/cngp.h"
 #include "cngp_kernels.h"
 #include "cngp_bwd_sliced.h"
+#include "cngp_bwd_binned.h"
 #include "cngp_rates.h"
 #include "cngp_optim.h"
 #include "cngp_mlp.h"
@@ -47,8 +48,8 @@ int validate(const cngp_config *c) {
     if (c->io_dtype != CNGP_F32 && c->io_dtype != CNGP_F16) return CNGP_ERR_INVALID;
     if (c->index_format != CNGP_IDX_U8 && c->index_format != CNGP_IDX_PACKED4 && c->index_format != CNGP_IDX_BITS) return CNGP_ERR_INVALID;
     if (c->index_format == CNGP_IDX_PACKED4 && c->N_c < 2) return CNGP_ERR_INVALID;
-    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE | CNGP_FWD_SIMPLE)) return CNGP_ERR_INVALID;
-    if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & CNGP_BWD_SLICED)) return CNGP_ERR_INVALID;
+    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE | CNGP_FWD_SIMPLE | CNGP_BWD_BINNED)) return CNGP_ERR_INVALID;
+    if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & (CNGP_BWD_SLICED | CNGP_BWD_BINNED))) return CNGP_ERR_INVALID;
     if (c->F != 2) return CNGP_ERR_UNSUPPORTED;
     return CNGP_OK;
 }
@@ -88,11 +89,14 @@ int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INV
 
 // ---------------------------------------------------------------- per-kernel timing
 enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_SLICED, K_BWD_SLICED_V,
-                K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD, K_COUNT };
+                K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD,
+                K_BWD_BIN_COUNT, K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_softmax_table",
                                            "encode_bwd_transpose_dy", "encode_bwd_sliced_points_and_grid",
                                            "encode_bwd_sliced_vertices", "bake_probes", "zero", "debug_indices",
-                                           "adam_step_bake", "mlp_fwd", "mlp_bwd"};
+                                           "adam_step_bake", "mlp_fwd", "mlp_bwd",
+                                           "encode_bwd_bin_count", "encode_bwd_bin_offsets", "encode_bwd_bin_scatter",
+                                           "encode_bwd_bin_drain"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -227,6 +231,10 @@ struct BwdPlan {
     Geom     grid;                      // vertex-grid accumulation: chunks of points
     size_t   lds_f, lds_c;              // dynamic LDS bytes of the two kernels
     size_t   sigma_off, dyT_off, G_off, ws_bytes;
+    bool     binned;                    // hashed levels: references binned by slice first (cngp_bwd_binned.h)
+    uint32_t bin_chunks, bin_chunk_pts; // point chunks of the count / scatter kernels
+    uint32_t subs_f, subs_c;            // drain workgroups per bin
+    size_t   cntF_off, cntC_off, baseF_off, baseC_off, recF_off, recC_off;
     DenseLevels dense;                  // levels pre-reduced per grid vertex (a prefix of the levels)
     uint32_t dense_slices, dense_verts, dense_max_verts;
 };
@@ -295,6 +303,10 @@ void choose_geometry(const cngp_config *c, int64_t N, BwdPlan &b) {
         const int64_t cv = (b.dense_max_verts + 16383) / 16384;                  // vertex chunks of <= 16384
         b.feat_vtx = b.logit_vtx = chunks_of(b.dense_max_verts, cv > 0 ? cv : 1);
     }
+    if (b.binned) {                         // the point roles of the hashed levels are not launched
+        b.logit_pts = b.feat_pts = chunks_of(N, 1);
+        return;
+    }
     // small slices are cheap to clear and flush: allow finer chunks there
     const bool    small = fixed_f + fixed_c < 8000.0;
     const int64_t min_chunk = small ? 8192 : 16384, cap = small ? 32 : 12;
@@ -360,7 +372,35 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             b.dense.count = l + 1;
         }
     }
+    // Binning the references of the hashed levels first: possible whenever the record positions fit 32 bits
+    // and a level's bins can be counted in LDS; it also covers tables with far too many slices for the
+    // replicated scan.
+    const int  Lh = c->L - b.dense.count;
+    const bool bin_ok = keys_fit && Lh > 0 && ((uint64_t)N << c->d) < (1ull << 31) &&
+                        b.slices_f <= 8192 && b.slices_c <= 8192 && N > 0;
+    if ((c->flags & CNGP_BWD_BINNED) && bin_ok) {
+        b.sliced = true;
+        b.binned = true;
+    }
     if (b.sliced) choose_geometry(c, N, b);
+    if (b.binned) {
+        b.bin_chunk_pts = 4096;
+        b.bin_chunks = (uint32_t)((N + b.bin_chunk_pts - 1) / b.bin_chunk_pts);
+        // drain workgroups per bin: about 2^16 records each, and enough workgroups to fill the chip twice
+        const double refs = (double)((uint64_t)N << c->d);
+        auto subs = [&](uint32_t slices) -> uint32_t {
+            if (!slices) return 1;
+            double want = refs / slices / 65536.0;
+            const double fill = 512.0 / ((double)Lh * (b.slices_f + b.slices_c));
+            if (want < fill) want = fill;
+            const double by_size = refs / slices / 8192.0;              // but never less than 8192 records each
+            if (want > by_size) want = by_size;
+            uint32_t r = (uint32_t)(want + 0.5);
+            return r < 1 ? 1 : (r > 64 ? 64 : r);
+        };
+        b.subs_f = subs(b.slices_f);
+        b.subs_c = subs(b.slices_c);
+    }
     const size_t queues = (size_t)kSlicedWaves * kRingBytes;
     b.lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8 + queues;
     b.lds_c = ((size_t)1 << b.rows_c_log2) * c->N_p * 8 + queues;
@@ -370,6 +410,16 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
         b.dyT_off = align256((size_t)c->L * c->N_c * c->N_p * sizeof(float));
         b.G_off = b.dyT_off + align256((size_t)N * c->L * c->F * io);
         b.ws_bytes = b.G_off + align256((size_t)b.dense_verts * 2 * sizeof(float));
+        if (b.binned) {
+            const size_t cap = (size_t)N << c->d;
+            b.cntF_off = b.ws_bytes;
+            b.cntC_off = b.cntF_off + align256((size_t)Lh * b.bin_chunks * b.slices_f * 4);
+            b.baseF_off = b.cntC_off + align256((size_t)Lh * b.bin_chunks * b.slices_c * 4);
+            b.baseC_off = b.baseF_off + align256((size_t)Lh * (b.slices_f + 1) * 4);
+            b.recF_off = b.baseC_off + align256((size_t)Lh * (b.slices_c + 1) * 4);
+            b.recC_off = b.recF_off + align256((size_t)Lh * cap * 16);
+            b.ws_bytes = b.recC_off + (b.slices_c ? align256((size_t)Lh * cap * 16) : 0);
+        }
     }
     return b;
 }
@@ -403,6 +453,68 @@ int launch_transpose_dy(const cngp_config *c, const void *dy, void *dyT, int64_t
     LaunchTimer t(s, K_BWD_TRANSPOSE);
     transpose_dy_kernel<PairT><<<(unsigned)blocks, kBlock, 0, s>>>((const PairT *)dy, (PairT *)dyT, N, c->L);
     return launch_status("transpose_dy_kernel");
+}
+
+// Hashed levels with the references binned by slice: count, offsets, scatter, drain.
+template <int D, int NP, typename FeatT, typename IoT>
+int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, const float *x, int64_t N,
+                      const void *D_f, const float *sigma, const IoT *dyT, float *gD_f, float *gDhat_c,
+                      void *workspace, hipStream_t s) {
+    const int Ld = b.dense.count, Lh = c->L - Ld;
+    if (Lh <= 0) return CNGP_OK;
+    char *ws = (char *)workspace;
+    uint32_t *cntF = (uint32_t *)(ws + b.cntF_off), *cntC = (uint32_t *)(ws + b.cntC_off);
+    uint32_t *baseF = (uint32_t *)(ws + b.baseF_off), *baseC = (uint32_t *)(ws + b.baseC_off);
+    uint4    *recF = (uint4 *)(ws + b.recF_off), *recC = (uint4 *)(ws + b.recC_off);
+    BinParams bp;
+    std::memset(&bp, 0, sizeof(bp));
+    bp.level0 = Ld; bp.nlevels = Lh;
+    bp.rows_f_log2 = b.rows_f_log2; bp.slices_f = b.slices_f;
+    bp.rows_c_log2 = b.rows_c_log2; bp.slices_c = NP > 1 ? b.slices_c : 0;
+    bp.chunks = b.bin_chunks; bp.chunk_pts = b.bin_chunk_pts;
+    bp.cap = (uint32_t)((uint64_t)N << c->d);
+    const int64_t blocks = (int64_t)Lh * bp.chunks;
+    if (int rc = check_blocks(blocks)) return rc;
+    const size_t lds_bins = (size_t)(bp.slices_f + bp.slices_c) * sizeof(uint32_t);
+    {
+        LaunchTimer t(s, K_BWD_BIN_COUNT);
+        bin_count_kernel<D><<<(unsigned)blocks, kBinBlock, lds_bins, s>>>(p, bp, x, N, cntF, cntC);
+        if (int rc = launch_status("bin_count_kernel")) return rc;
+    }
+    {
+        LaunchTimer t(s, K_BWD_BIN_OFFSETS);
+        bin_offsets_kernel<<<(unsigned)(2 * Lh), kBinBlock, 0, s>>>(bp, cntF, cntC, baseF, baseC);
+        if (int rc = launch_status("bin_offsets_kernel")) return rc;
+    }
+    {
+        LaunchTimer t(s, K_BWD_BIN_SCATTER);
+        bin_scatter_kernel<D, IoT><<<(unsigned)blocks, kBinBlock, lds_bins, s>>>(p, bp, x, dyT, N, cntF, cntC, recF, recC);
+        if (int rc = launch_status("bin_scatter_kernel")) return rc;
+    }
+    const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
+    auto role = [&](uint32_t rows_log2, uint32_t slices, uint32_t subs, uint32_t &wgs) {
+        SliceParams sp;
+        std::memset(&sp, 0, sizeof(sp));
+        sp.rows_log2 = rows_log2;
+        sp.slices = slices ? slices : 1;
+        sp.chunks = subs ? subs : 1;
+        sp.store_direct = (sp.chunks == 1 && zero_first) ? 1 : 0;       // matches the clearing in cngp_encode_bwd
+        sp.level0 = Ld;
+        sp.nlevels = slices ? Lh : 0;
+        wgs = slices ? (uint32_t)kXcds * (((uint32_t)Lh * sp.slices * sp.chunks + kXcds - 1) / kXcds) : 0u;
+        return sp;
+    };
+    uint32_t wgs_c = 0, wgs_f = 0;
+    const SliceParams sp_c = role(b.rows_c_log2, NP > 1 ? b.slices_c : 0, b.subs_c, wgs_c);
+    const SliceParams sp_f = role(b.rows_f_log2, b.slices_f, b.subs_f, wgs_f);
+    auto kernel = bin_drain_kernel<NP, FeatT>;
+    const size_t lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8, lds_c = ((size_t)1 << b.rows_c_log2) * c->N_p * 8;
+    const size_t lds = lds_f > lds_c ? lds_f : lds_c;
+    if (int rc = allow_big_lds(kernel, lds)) return rc;
+    LaunchTimer t(s, K_BWD_BIN_DRAIN);
+    kernel<<<wgs_c + wgs_f, kSlicedBlock, lds, s>>>(p, sp_c, sp_f, wgs_c, (const FeatT *)D_f, sigma, recF, recC, baseF,
+                                                    baseC, bp.cap, gD_f, gDhat_c);
+    return launch_status("bin_drain_kernel");
 }
 
 template <int D, int NP, typename FeatT, typename IoT>
@@ -454,8 +566,8 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
                 next += (uint32_t)kXcds * (((uint32_t)nlevels * sp.slices * sp.chunks + kXcds - 1) / kXcds);
         };
         const bool pts = launch == 0, vtx = launch == 1;
-        add_role(ROLE_LOGIT_PTS, pts && NP > 1, b.logit_pts, b.rows_c_log2, b.slices_c, Ld, Lh);
-        add_role(ROLE_FEAT_PTS, pts, b.feat_pts, b.rows_f_log2, b.slices_f, Ld, Lh);
+        add_role(ROLE_LOGIT_PTS, pts && NP > 1 && !b.binned, b.logit_pts, b.rows_c_log2, b.slices_c, Ld, Lh);
+        add_role(ROLE_FEAT_PTS, pts && !b.binned, b.feat_pts, b.rows_f_log2, b.slices_f, Ld, Lh);
         add_role(ROLE_LOGIT_VTX, vtx && NP > 1, b.logit_vtx, b.rows_c_log2, b.slices_c, 0, Ld);
         add_role(ROLE_FEAT_VTX, vtx, b.feat_vtx, b.rows_f_log2, b.slices_f, 0, Ld);
         roles.first[ROLE_GRID] = next;
@@ -469,6 +581,7 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
         kernel<<<next, kSlicedBlock, lds, s>>>(p, roles, b.dense, x, (const FeatT *)D_f, sigma, dyT, G, gD_f, gDhat_c, N);
         if (int rc = launch_status("bwd_sliced_kernel")) return rc;
     }
+    if (b.binned) return launch_bwd_binned<D, NP, FeatT, IoT>(c, p, b, x, N, D_f, sigma, dyT, gD_f, gDhat_c, workspace, s);
     return CNGP_OK;
 }
 
@@ -561,7 +674,8 @@ int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info) {
     const int32_t v[CNGP_PLAN_INFO_COUNT] = {
         b.sliced ? 1 : 0, b.dense.count, (int32_t)b.slices_f, (int32_t)b.slices_c,
         (int32_t)b.feat_pts.chunks, (int32_t)b.logit_pts.chunks, (int32_t)b.feat_vtx.chunks,
-        (int32_t)b.logit_vtx.chunks, (int32_t)b.grid.chunks, (int32_t)b.dense_slices};
+        (int32_t)b.logit_vtx.chunks, (int32_t)b.grid.chunks, (int32_t)b.dense_slices,
+        b.binned ? 1 : 0, (int32_t)b.subs_f, (int32_t)b.subs_c, (int32_t)b.bin_chunks};
     for (int i = 0; i < CNGP_PLAN_INFO_COUNT; ++i) info[i] = v[i];
     return CNGP_OK;
 }
@@ -599,10 +713,11 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
         const int     Ld = sl ? b.dense.count : 0, Lh = cfg->L - Ld;
         ZeroList z;
         if (!(sl && b.feat_vtx.chunks == 1) && Ld > 0) z.add(grad_D_f, per_f * Ld);
-        if (!(sl && b.feat_pts.chunks == 1) && Lh > 0) z.add(grad_D_f + per_f * Ld, per_f * Lh);
+        const uint32_t wg_f = b.binned ? b.subs_f : b.feat_pts.chunks, wg_c = b.binned ? b.subs_c : b.logit_pts.chunks;
+        if (!(sl && wg_f == 1) && Lh > 0) z.add(grad_D_f + per_f * Ld, per_f * Lh);
         const bool logit = sl && cfg->N_p > 1;
         if (!(logit && b.logit_vtx.chunks == 1) && Ld > 0) z.add(grad_Dhat_c, per_c * Ld);
-        if (!(logit && b.logit_pts.chunks == 1) && Lh > 0) z.add(grad_Dhat_c + per_c * Ld, per_c * Lh);
+        if (!(logit && wg_c == 1) && Lh > 0) z.add(grad_Dhat_c + per_c * Ld, per_c * Lh);
         if (int rc = z.launch(s)) return rc;
     }
     if (N == 0) return CNGP_OK;

@@ -1,0 +1,306 @@
+// Backward pass of the hashed levels with the corner references BINNED by table slice first.
+//
+// The LDS-sliced backward pass (cngp_bwd_sliced.h) lets every slice's workgroup scan all points and
+// keep the references that fall into its slice: cheap while a level has a few dozen slices, but the
+// scan is repeated per slice.  Here the references are partitioned once:
+//   1. count    per (level, chunk of points): how many references go to each slice of the feature
+//               table (by hash) and of the confidence table (by hash2); histogram in LDS
+//   2. offsets  exclusive prefix sums: where every (chunk, slice) writes inside the level's record array
+//   3. scatter  the same walk again, every reference written as a 16-byte record
+//               { row inside the slice | row of the other table << rows_log2, weight * dL/dy (2 floats), 0 }
+//               to its slice's bin, positions handed out by LDS counters that start at the offsets
+//   4. drain    a workgroup owns a slice as fp64 accumulators in LDS, as in the sliced variant, but reads
+//               only its own bin, coalesced: record loads two batches ahead, the gathers the records ask for
+//               (softmax row / feature row) one batch ahead of the LDS atomics that consume them
+// Per reference this replaces the replicated hashing and the ring-buffer emission by one 16-byte write
+// and one 16-byte read, which is the better trade from a few dozen slices per level upwards and the
+// only workable one for tables of thousands of slices.
+#pragma once
+#include "cngp_bwd_sliced.h"
+
+namespace cngp {
+
+constexpr int kBinBlock = 256;            // count and scatter kernels
+constexpr int kDrainSteps = 4;            // wavefront instructions per batch of the drain pipeline
+
+struct BinParams {
+    int32_t  level0, nlevels;             // the hashed levels
+    uint32_t rows_f_log2, slices_f;       // feature-gradient slices per level
+    uint32_t rows_c_log2, slices_c;       // logit-gradient slices per level; slices_c = 0 when N_p = 1
+    uint32_t chunks, chunk_pts;           // point chunks of count / scatter
+    uint32_t cap;                         // records per level and role: N * 2^d
+};
+
+// Slice of the feature table (role 0) / confidence table (role 1) a corner's hashes select.
+template <int D>
+__device__ __forceinline__ void corner_rows(const Cell<D> &cell, const Params &p, const int c, uint32_t &h1, uint32_t &h2) {
+    h1 = cell.hash1(c) & p.row_mask;
+    h2 = cell.hash2(c) & p.c_mask;
+}
+
+template <int D>
+__global__ __launch_bounds__(kBinBlock) void bin_count_kernel(
+    const Params p, const BinParams bp, const float *__restrict__ x, const int64_t N,
+    uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC)
+{
+    extern __shared__ uint32_t hist[];                      // [slices_f + slices_c]
+    const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
+    const int      l = bp.level0 + (int)li;
+    const uint32_t bins = bp.slices_f + bp.slices_c;
+    for (uint32_t i = threadIdx.x; i < bins; i += kBinBlock) hist[i] = 0u;
+    __syncthreads();
+    const int64_t n0 = (int64_t)chunk * bp.chunk_pts;
+    const int64_t n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
+    for (int64_t n = n0 + threadIdx.x; n < n1; n += kBinBlock) {
+        float xp[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
+        Cell<D> cell;
+        cell.locate(xp, p.N_l[l]);
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) {
+            uint32_t h1, h2;
+            corner_rows<D>(cell, p, c, h1, h2);
+            atomicAdd(&hist[h1 >> bp.rows_f_log2], 1u);
+            if (bp.slices_c) atomicAdd(&hist[bp.slices_f + (h2 >> bp.rows_c_log2)], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t *rowF = cntF + ((size_t)li * bp.chunks + chunk) * bp.slices_f;
+    for (uint32_t s = threadIdx.x; s < bp.slices_f; s += kBinBlock) rowF[s] = hist[s];
+    if (bp.slices_c) {
+        uint32_t *rowC = cntC + ((size_t)li * bp.chunks + chunk) * bp.slices_c;
+        for (uint32_t s = threadIdx.x; s < bp.slices_c; s += kBinBlock) rowC[s] = hist[bp.slices_f + s];
+    }
+}
+
+// One workgroup per (level, role).  In place: cnt[chunk][slice] becomes the position, inside the level's
+// record array, of the first record that chunk writes to that slice; base[slice] = start of the slice's
+// bin, base[slices] = number of records of the level.
+__global__ __launch_bounds__(kBinBlock) void bin_offsets_kernel(
+    const BinParams bp, uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC,
+    uint32_t *__restrict__ baseF, uint32_t *__restrict__ baseC)
+{
+    __shared__ uint32_t part[kBinBlock];
+    const uint32_t li = blockIdx.x >> 1, role = blockIdx.x & 1u;
+    const uint32_t slices = role ? bp.slices_c : bp.slices_f;
+    if (slices == 0) return;
+    uint32_t *cnt = (role ? cntC : cntF) + (size_t)li * bp.chunks * slices;
+    uint32_t *base = (role ? baseC : baseF) + (size_t)li * (slices + 1);
+    // this thread's contiguous run of slices
+    const uint32_t per = (slices + kBinBlock - 1) / kBinBlock;
+    const uint32_t s0 = threadIdx.x * per, s1 = (s0 + per < slices) ? s0 + per : slices;
+    uint32_t mine = 0;
+    for (uint32_t s = s0; s < s1; ++s) {                    // exclusive prefix over the chunks of one slice
+        uint32_t run = 0;
+        for (uint32_t ch = 0; ch < bp.chunks; ++ch) {
+            const uint32_t v = cnt[(size_t)ch * slices + s];
+            cnt[(size_t)ch * slices + s] = run;
+            run += v;
+        }
+        base[s] = run;                                      // the slice's total, for now
+        mine += run;
+    }
+    part[threadIdx.x] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int t = 0; t < kBinBlock; ++t) { const uint32_t v = part[t]; part[t] = run; run += v; }
+        base[slices] = run;
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x];
+    for (uint32_t s = s0; s < s1; ++s) {
+        const uint32_t total = base[s];
+        base[s] = run;
+        for (uint32_t ch = 0; ch < bp.chunks; ++ch) cnt[(size_t)ch * slices + s] += run;
+        run += total;
+    }
+}
+
+template <int D, typename IoT>
+__global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(
+    const Params p, const BinParams bp, const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
+    const uint32_t *__restrict__ cntF, const uint32_t *__restrict__ cntC,
+    uint4 *__restrict__ recF, uint4 *__restrict__ recC)
+{
+    extern __shared__ uint32_t cursor[];                    // [slices_f + slices_c]
+    const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
+    const int      l = bp.level0 + (int)li;
+    const uint32_t *rowF = cntF + ((size_t)li * bp.chunks + chunk) * bp.slices_f;
+    for (uint32_t s = threadIdx.x; s < bp.slices_f; s += kBinBlock) cursor[s] = rowF[s];
+    if (bp.slices_c) {
+        const uint32_t *rowC = cntC + ((size_t)li * bp.chunks + chunk) * bp.slices_c;
+        for (uint32_t s = threadIdx.x; s < bp.slices_c; s += kBinBlock) cursor[bp.slices_f + s] = rowC[s];
+    }
+    __syncthreads();
+    uint4 *outF = recF + (size_t)li * bp.cap;
+    uint4 *outC = recC + (size_t)li * bp.cap;
+    const IoT     *dy_l = dyT + (size_t)l * N * 2;
+    const uint32_t lo_f = (1u << bp.rows_f_log2) - 1u, lo_c = (1u << bp.rows_c_log2) - 1u;
+    const int64_t  n0 = (int64_t)chunk * bp.chunk_pts;
+    const int64_t  n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
+    for (int64_t n = n0 + threadIdx.x; n < n1; n += kBinBlock) {
+        float xp[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
+        Cell<D> cell;
+        cell.locate(xp, p.N_l[l]);
+        const float2 g = load_pair(dy_l, (size_t)n);
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) {
+            uint32_t h1, h2;
+            corner_rows<D>(cell, p, c, h1, h2);
+            const float    wt = cell.weight(c);
+            const uint32_t gx = __float_as_uint(wt * g.x), gy = __float_as_uint(wt * g.y);
+            const uint32_t posF = atomicAdd(&cursor[h1 >> bp.rows_f_log2], 1u);
+            outF[posF] = make_uint4((h1 & lo_f) | (h2 << bp.rows_f_log2), gx, gy, 0u);
+            if (bp.slices_c) {
+                const uint32_t posC = atomicAdd(&cursor[bp.slices_f + (h2 >> bp.rows_c_log2)], 1u);
+                outC[posC] = make_uint4((h2 & lo_c) | (h1 << bp.rows_c_log2), gx, gy, 0u);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ drain
+// Records [beg, end) of one bin, batches of kDrainSteps * (64 / NP) records handed to the workgroup's
+// wavefronts round-robin.  NP lanes cooperate on a record as in the sliced variant.  Positions past
+// `end` read as a record that adds zero to row 0.
+template <int NP, typename T, typename Load, typename Accum>
+__device__ __forceinline__ void drain_records(const uint4 *__restrict__ rec, const uint32_t beg, const uint32_t end,
+                                              Load load, Accum accum)
+{
+    constexpr uint32_t EPI = 64 / NP;
+    constexpr uint32_t kBatchRecs = kDrainSteps * EPI;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane / NP;
+    const uint32_t stride = kSlicedWaves * kBatchRecs;
+    auto fetch = [&](const uint32_t b, uint4 (&r)[kDrainSteps]) {
+#pragma unroll
+        for (int u = 0; u < kDrainSteps; ++u) {
+            const uint32_t i = b + (uint32_t)u * EPI + sub;
+            r[u] = (b < end && i < end) ? rec[i] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    uint32_t b = beg + wave * kBatchRecs;
+    if (b >= end) return;
+    uint4 cur[kDrainSteps], nxt[kDrainSteps];
+    T     t_cur[kDrainSteps];
+    fetch(b, cur);
+#pragma unroll
+    for (int u = 0; u < kDrainSteps; ++u) t_cur[u] = load(cur[u].x);
+    fetch(b + stride, nxt);
+    for (; b < end; b += stride) {
+        T     t_nxt[kDrainSteps];
+        uint4 far[kDrainSteps];
+#pragma unroll
+        for (int u = 0; u < kDrainSteps; ++u) t_nxt[u] = load(nxt[u].x);     // gathers of the next batch
+        fetch(b + 2 * stride, far);                                           // records of the one after
+#pragma unroll
+        for (int u = 0; u < kDrainSteps; ++u)
+            accum(cur[u].x, make_float2(__uint_as_float(cur[u].y), __uint_as_float(cur[u].z)), t_cur[u]);
+#pragma unroll
+        for (int u = 0; u < kDrainSteps; ++u) { cur[u] = nxt[u]; t_cur[u] = t_nxt[u]; nxt[u] = far[u]; }
+    }
+}
+
+// The records of (level index li, slice, sub) of one role: sub-range `sub` of `subs` equal parts of the bin.
+__device__ __forceinline__ void bin_range(const uint32_t *__restrict__ base, const uint32_t slices, const uint32_t li,
+                                          const uint32_t slice, const uint32_t sub, const uint32_t subs,
+                                          uint32_t &beg, uint32_t &end) {
+    const uint32_t *b = base + (size_t)li * (slices + 1);
+    const uint32_t  b0 = b[slice], n = b[slice + 1] - b0;
+    beg = b0 + (uint32_t)(((uint64_t)n * sub) / subs);
+    end = b0 + (uint32_t)(((uint64_t)n * (sub + 1)) / subs);
+}
+
+// sp: rows_log2, slices, chunks (= drain workgroups per bin), store_direct, level0, nlevels as in the sliced variant.
+template <int NP>
+__device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &sp, const uint32_t wg, unsigned char *smem,
+                                           const float *__restrict__ sigma, const uint4 *__restrict__ recF,
+                                           const uint32_t *__restrict__ baseF, const uint32_t cap, float *__restrict__ gD_f)
+{
+    const uint32_t rows = 1u << sp.rows_log2, plane = rows * NP;
+    double *acc = reinterpret_cast<double *>(smem);
+    const SliceCoord co = slice_coord(sp, wg);
+    if (co.index < 0) return;
+    for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) acc[i] = 0.0;
+    __syncthreads();
+    const float   *sig_l = sigma + (size_t)co.level * p.N_c * NP;
+    const uint32_t k = (threadIdx.x & 63) % NP, row_lo_mask = rows - 1u, rows_log2 = sp.rows_log2;
+    auto load = [&](const uint32_t key) -> float { return NP == 1 ? 1.0f : sig_l[(size_t)(key >> rows_log2) * NP + k]; };
+    auto accum = [&](const uint32_t key, const float2 g, const float s) {
+        double *a = acc + (key & row_lo_mask) * NP + k;
+        atomicAdd(a, (double)(s * g.x));
+        atomicAdd(a + plane, (double)(s * g.y));
+    };
+    uint32_t beg, end;
+    bin_range(baseF, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
+    drain_records<NP, float>(recF + (size_t)co.index * cap, beg, end, load, accum);
+    __syncthreads();
+    float *out = gD_f + (size_t)co.level * p.N_f * 2 + (size_t)co.slice * plane * 2;
+    for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) {     // i = (row * NP + k) * 2 + f
+        const float v = (float)acc[(i & 1u) * plane + (i >> 1)];
+        if (sp.store_direct) out[i] = v;
+        else if (v != 0.0f) atomic_add(out + i, v);
+    }
+}
+
+template <int NP, typename FeatT>
+__device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &sp, const uint32_t wg, unsigned char *smem,
+                                            const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
+                                            const uint4 *__restrict__ recC, const uint32_t *__restrict__ baseC,
+                                            const uint32_t cap, float *__restrict__ gDhat_c)
+{
+    const uint32_t rows = 1u << sp.rows_log2;
+    double *acc = reinterpret_cast<double *>(smem);
+    const SliceCoord co = slice_coord(sp, wg);
+    if (co.index < 0) return;
+    for (uint32_t i = threadIdx.x; i < rows * NP; i += kSlicedBlock) acc[i] = 0.0;
+    __syncthreads();
+    const FeatT   *F_l = D_f + (size_t)co.level * p.N_f * 2;
+    const uint32_t k = (threadIdx.x & 63) % NP, row_lo_mask = rows - 1u, rows_log2 = sp.rows_log2;
+    using Raw = typename RawPair<FeatT>::type;
+    auto load = [&](const uint32_t key) -> Raw { return reinterpret_cast<const Raw *>(F_l)[(size_t)(key >> rows_log2) * NP + k]; };
+    auto accum = [&](const uint32_t key, const float2 g, const Raw raw) {
+        const float2 feat = RawPair<FeatT>::to_float2(raw);
+        atomicAdd(acc + (key & row_lo_mask) * NP + k, (double)fmaf(feat.x, g.x, feat.y * g.y));
+    };
+    uint32_t beg, end;
+    bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
+    drain_records<NP, Raw>(recC + (size_t)co.index * cap, beg, end, load, accum);
+    __syncthreads();
+    // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
+    const size_t row0 = (size_t)co.level * p.N_c + (size_t)co.slice * rows;
+    const float *sig = sigma + row0 * NP;
+    float       *out = gDhat_c + row0 * NP;
+    for (uint32_t i = threadIdx.x; i < rows * NP; i += kSlicedBlock) {
+        const double Q = acc[i];
+        const double s = (double)sig[i];
+        double dot = s * Q;
+#pragma unroll
+        for (int o = NP / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, NP);
+        const float v = (float)(s * (Q - dot));
+        if (sp.store_direct) out[i] = v;
+        else if (v != 0.0f) atomic_add(out + i, v);
+    }
+}
+
+// Workgroups [0, first_feat) drain the confidence-table bins, the rest the feature-table bins.
+template <int NP, typename FeatT>
+__global__ __launch_bounds__(kSlicedBlock) void bin_drain_kernel(
+    const Params p, const SliceParams sp_c, const SliceParams sp_f, const uint32_t first_feat,
+    const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
+    const uint4 *__restrict__ recF, const uint4 *__restrict__ recC,
+    const uint32_t *__restrict__ baseF, const uint32_t *__restrict__ baseC, const uint32_t cap,
+    float *__restrict__ gD_f, float *__restrict__ gDhat_c)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (blockIdx.x < first_feat) {
+        if (NP > 1) drain_logit<NP, FeatT>(p, sp_c, blockIdx.x, smem, D_f, sigma, recC, baseC, cap, gDhat_c);
+    } else {
+        drain_feat<NP>(p, sp_f, blockIdx.x - first_feat, smem, sigma, recF, baseF, cap, gD_f);
+    }
+}
+
+}  // namespace cngp

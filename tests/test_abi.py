@@ -62,7 +62,7 @@ BAD = [
     dict(d=1), dict(d=4), dict(L=0), dict(L=33), dict(F=0),
     dict(N_f=0), dict(N_f=3000), dict(N_c=0), dict(N_c=100), dict(N_p=0), dict(N_p=3), dict(N_p=32),
     dict(N_p=16, N_f=8), dict(N_min=0), dict(N_max=8), dict(N_max=2**25),
-    dict(feat_dtype=2), dict(io_dtype=-1), dict(index_format=3), dict(flags=32), dict(flags=6),
+    dict(feat_dtype=2), dict(io_dtype=-1), dict(index_format=3), dict(flags=64), dict(flags=6), dict(flags=34),
     dict(index_format=cngp.IDX_PACKED4, N_c=1, N_p=1),
 ]
 
@@ -169,6 +169,10 @@ def test_backward_plan_is_reported_on_the_host():
     assert cngp.bwd_plan_info(cngp.Config.from_workload(t, flags=cngp.BWD_SLICED), t.N)["sliced"] == 1
     assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_DIRECT), w.N)["sliced"] == 0
     assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_NO_PREREDUCE), w.N)["dense_levels"] == 0
+    pb = cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), w.N)
+    assert pb["sliced"] == 1 and pb["binned"] == 1 and pb["drain_wgs_feat"] >= 1 and pb["bin_chunks"] == w.N // 4096
+    assert cngp.workspace_bytes(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), w.N) > 2 * (w.L - pb["dense_levels"]) * w.N * 8 * 16
+    assert p["binned"] == 0
     big = W.custom(d=3, L=16, N_f=2**24, N_c=2**24, N_p=2, N_min=16, N_max=2048, N=2**18)
     assert cngp.bwd_plan_info(cngp.Config.from_workload(big), big.N)["sliced"] == 0     # too many slices
 

@@ -60,10 +60,11 @@ def check_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8, name=""):
 
 # the ways the library can run the backward pass: its own choice, and each variant forced
 BWD_PATHS = {"auto": 0, "direct": cngp.BWD_DIRECT, "sliced": cngp.BWD_SLICED,
-             "sliced_nopre": cngp.BWD_SLICED | cngp.BWD_NO_PREREDUCE}
+             "sliced_nopre": cngp.BWD_SLICED | cngp.BWD_NO_PREREDUCE,
+             "binned": cngp.BWD_BINNED, "binned_nopre": cngp.BWD_BINNED | cngp.BWD_NO_PREREDUCE}
 
 
-def check_bwd(w, x, D_f, Dhat, dy, name="", paths=("auto", "direct", "sliced", "sliced_nopre")):
+def check_bwd(w, x, D_f, Dhat, dy, name="", paths=("auto", "direct", "sliced", "sliced_nopre", "binned", "binned_nopre")):
     gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
     worst = (0.0, 0.0)
     for path in paths:
