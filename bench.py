@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="nerf3d", help="nerf3d (headline) | image2d | sdf3d | tiny2d | infer3d | compact3d")
+    ap.add_argument("--bwd", default="auto", choices=["auto", "direct", "sliced", "binned"],
+                    help="force a variant of the backward pass (default: the library's own choice)")
     ap.add_argument("--with-optimizer", action="store_true",
                     help="a step becomes: Adam step fused with the bake (replaces the bake), forward, backward; "
                          "the tables then change from step to step.  Not the headline configuration.")
@@ -82,7 +84,8 @@ def main():
     w = W.WORKLOADS[args.workload]
     fwd_only = args.workload in ("infer3d", "compact3d")
     fmt = {"infer3d": cngp.IDX_PACKED4, "compact3d": cngp.IDX_BITS}.get(args.workload, cngp.IDX_U8)
-    cfg = cngp.Config.from_workload(w, index_format=fmt, flags=cngp.ZERO_GRADS)
+    bwd_flag = {"auto": 0, "direct": cngp.BWD_DIRECT, "sliced": cngp.BWD_SLICED, "binned": cngp.BWD_BINNED}[args.bwd]
+    cfg = cngp.Config.from_workload(w, index_format=fmt, flags=cngp.ZERO_GRADS | bwd_flag)
 
     x_h = W.make_points(w)
     D_f_h = W.make_feature_codebook(w)
@@ -217,6 +220,7 @@ def main():
                             ("Adam step fused with bake + fwd + bwd (grads cleared each step)" if with_opt else
                              "bake + fwd + bwd (grads cleared each step)"))},
         "roofline": roofline,
+        "bwd_plan": None if fwd_only else cngp.bwd_plan_info(cfg, N),
         "kernels_us_per_step": {k: round(v["ms"] * 1e3 / args.steps, 2) for k, v in per_kernel.items()},
         "kernel_parts": {k: v["parts"] for k, v in per_kernel.items() if len(v["parts"]) > 1},
     }

@@ -417,8 +417,8 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             b.baseF_off = b.cntC_off + align256((size_t)Lh * b.bin_chunks * b.slices_c * 4);
             b.baseC_off = b.baseF_off + align256((size_t)Lh * (b.slices_f + 1) * 4);
             b.recF_off = b.baseC_off + align256((size_t)Lh * (b.slices_c + 1) * 4);
-            b.recC_off = b.recF_off + align256((size_t)Lh * cap * 16);
-            b.ws_bytes = b.recC_off + (b.slices_c ? align256((size_t)Lh * cap * 16) : 0);
+            b.recC_off = b.recF_off + align256((size_t)Lh * cap * 8);
+            b.ws_bytes = b.recC_off + (b.slices_c ? align256((size_t)Lh * cap * 8) : 0);
         }
     }
     return b;
@@ -465,7 +465,7 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     char *ws = (char *)workspace;
     uint32_t *cntF = (uint32_t *)(ws + b.cntF_off), *cntC = (uint32_t *)(ws + b.cntC_off);
     uint32_t *baseF = (uint32_t *)(ws + b.baseF_off), *baseC = (uint32_t *)(ws + b.baseC_off);
-    uint4    *recF = (uint4 *)(ws + b.recF_off), *recC = (uint4 *)(ws + b.recC_off);
+    uint2    *recF = (uint2 *)(ws + b.recF_off), *recC = (uint2 *)(ws + b.recC_off);
     BinParams bp;
     std::memset(&bp, 0, sizeof(bp));
     bp.level0 = Ld; bp.nlevels = Lh;
@@ -488,7 +488,7 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     }
     {
         LaunchTimer t(s, K_BWD_BIN_SCATTER);
-        bin_scatter_kernel<D, IoT><<<(unsigned)blocks, kBinBlock, lds_bins, s>>>(p, bp, x, dyT, N, cntF, cntC, recF, recC);
+        bin_scatter_kernel<D><<<(unsigned)blocks, kBinBlock, lds_bins, s>>>(p, bp, x, N, cntF, cntC, recF, recC);
         if (int rc = launch_status("bin_scatter_kernel")) return rc;
     }
     const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
@@ -507,13 +507,13 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     uint32_t wgs_c = 0, wgs_f = 0;
     const SliceParams sp_c = role(b.rows_c_log2, NP > 1 ? b.slices_c : 0, b.subs_c, wgs_c);
     const SliceParams sp_f = role(b.rows_f_log2, b.slices_f, b.subs_f, wgs_f);
-    auto kernel = bin_drain_kernel<NP, FeatT>;
+    auto kernel = bin_drain_kernel<D, NP, FeatT, IoT>;
     const size_t lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8, lds_c = ((size_t)1 << b.rows_c_log2) * c->N_p * 8;
     const size_t lds = lds_f > lds_c ? lds_f : lds_c;
     if (int rc = allow_big_lds(kernel, lds)) return rc;
     LaunchTimer t(s, K_BWD_BIN_DRAIN);
-    kernel<<<wgs_c + wgs_f, kSlicedBlock, lds, s>>>(p, sp_c, sp_f, wgs_c, (const FeatT *)D_f, sigma, recF, recC, baseF,
-                                                    baseC, bp.cap, gD_f, gDhat_c);
+    kernel<<<wgs_c + wgs_f, kSlicedBlock, lds, s>>>(p, sp_c, sp_f, wgs_c, x, dyT, N, (const FeatT *)D_f, sigma, recF, recC,
+                                                    baseF, baseC, bp.cap, gD_f, gDhat_c);
     return launch_status("bin_drain_kernel");
 }
 

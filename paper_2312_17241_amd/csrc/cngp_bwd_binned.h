@@ -6,14 +6,16 @@
 //   1. count    per (level, chunk of points): how many references go to each slice of the feature
 //               table (by hash) and of the confidence table (by hash2); histogram in LDS
 //   2. offsets  exclusive prefix sums: where every (chunk, slice) writes inside the level's record array
-//   3. scatter  the same walk again, every reference written as a 16-byte record
-//               { row inside the slice | row of the other table << rows_log2, weight * dL/dy (2 floats), 0 }
+//   3. scatter  the same walk again, every reference written as an 8-byte record
+//               { row inside the slice | row of the other table << rows_log2,  point index * 2^d + corner }
 //               to its slice's bin, positions handed out by LDS counters that start at the offsets
 //   4. drain    a workgroup owns a slice as fp64 accumulators in LDS, as in the sliced variant, but reads
-//               only its own bin, coalesced: record loads two batches ahead, the gathers the records ask for
-//               (softmax row / feature row) one batch ahead of the LDS atomics that consume them
-// Per reference this replaces the replicated hashing and the ring-buffer emission by one 16-byte write
-// and one 16-byte read, which is the better trade from a few dozen slices per level upwards and the
+//               only its own bin, coalesced, one record per lane: the lane re-derives weight * dL/dy of its
+//               record from the point (a dozen instructions per record, against 8 more bytes written and read
+//               per record otherwise); record loads run two batches ahead, the gathers the records ask
+//               for (softmax row / feature row) one batch ahead of the LDS atomics that consume them
+// Per reference this replaces the replicated hashing and the ring-buffer emission by one 8-byte write
+// and one 8-byte read per table, which is the better trade from a few dozen slices per level upwards and the
 // only workable one for tables of thousands of slices.
 #pragma once
 #include "cngp_bwd_sliced.h"
@@ -21,7 +23,6 @@
 namespace cngp {
 
 constexpr int kBinBlock = 256;            // count and scatter kernels
-constexpr int kDrainSteps = 4;            // wavefront instructions per batch of the drain pipeline
 
 struct BinParams {
     int32_t  level0, nlevels;             // the hashed levels
@@ -118,11 +119,11 @@ __global__ __launch_bounds__(kBinBlock) void bin_offsets_kernel(
     }
 }
 
-template <int D, typename IoT>
+template <int D>
 __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(
-    const Params p, const BinParams bp, const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
+    const Params p, const BinParams bp, const float *__restrict__ x, const int64_t N,
     const uint32_t *__restrict__ cntF, const uint32_t *__restrict__ cntC,
-    uint4 *__restrict__ recF, uint4 *__restrict__ recC)
+    uint2 *__restrict__ recF, uint2 *__restrict__ recC)
 {
     extern __shared__ uint32_t cursor[];                    // [slices_f + slices_c]
     const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
@@ -134,9 +135,8 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(
         for (uint32_t s = threadIdx.x; s < bp.slices_c; s += kBinBlock) cursor[bp.slices_f + s] = rowC[s];
     }
     __syncthreads();
-    uint4 *outF = recF + (size_t)li * bp.cap;
-    uint4 *outC = recC + (size_t)li * bp.cap;
-    const IoT     *dy_l = dyT + (size_t)l * N * 2;
+    uint2 *outF = recF + (size_t)li * bp.cap;
+    uint2 *outC = recC + (size_t)li * bp.cap;
     const uint32_t lo_f = (1u << bp.rows_f_log2) - 1u, lo_c = (1u << bp.rows_c_log2) - 1u;
     const int64_t  n0 = (int64_t)chunk * bp.chunk_pts;
     const int64_t  n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
@@ -146,62 +146,134 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(
         for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
         Cell<D> cell;
         cell.locate(xp, p.N_l[l]);
-        const float2 g = load_pair(dy_l, (size_t)n);
 #pragma unroll
         for (int c = 0; c < (1 << D); ++c) {
             uint32_t h1, h2;
             corner_rows<D>(cell, p, c, h1, h2);
-            const float    wt = cell.weight(c);
-            const uint32_t gx = __float_as_uint(wt * g.x), gy = __float_as_uint(wt * g.y);
+            const uint32_t ref = ((uint32_t)n << D) | (uint32_t)c;
             const uint32_t posF = atomicAdd(&cursor[h1 >> bp.rows_f_log2], 1u);
-            outF[posF] = make_uint4((h1 & lo_f) | (h2 << bp.rows_f_log2), gx, gy, 0u);
+            outF[posF] = make_uint2((h1 & lo_f) | (h2 << bp.rows_f_log2), ref);
             if (bp.slices_c) {
                 const uint32_t posC = atomicAdd(&cursor[bp.slices_f + (h2 >> bp.rows_c_log2)], 1u);
-                outC[posC] = make_uint4((h2 & lo_c) | (h1 << bp.rows_c_log2), gx, gy, 0u);
+                outC[posC] = make_uint2((h2 & lo_c) | (h1 << bp.rows_c_log2), ref);
             }
         }
     }
 }
 
 // ------------------------------------------------------------------ drain
-// Records [beg, end) of one bin, batches of kDrainSteps * (64 / NP) records handed to the workgroup's
-// wavefronts round-robin.  NP lanes cooperate on a record as in the sliced variant.  Positions past
-// `end` read as a record that adds zero to row 0.
-template <int NP, typename T, typename Load, typename Accum>
-__device__ __forceinline__ void drain_records(const uint4 *__restrict__ rec, const uint32_t beg, const uint32_t end,
+// Value of lane `u` of this lane's group of NP lanes.  A group of 16 is a DPP row: one VALU move.
+template <int NP, int U>
+__device__ __forceinline__ uint32_t group_bcast(const uint32_t v) {
+    if (NP == 16) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x150 + U, 0xF, 0xF, false);   // row_newbcast:U
+    if (NP == 1) return v;
+    return (uint32_t)__shfl((int)v, (int)((threadIdx.x & 63u & ~(uint32_t)(NP - 1)) + U), 64);
+}
+
+__device__ __forceinline__ float2 pair_to_float2(const float2 v) { return v; }
+__device__ __forceinline__ float2 pair_to_float2(const uint32_t v) {
+    return __half22float2(*reinterpret_cast<const __half2 *>(&v));
+}
+
+// Step U of a batch: every group reads the key its lane U holds and issues the gather it asks for ...
+template <int NP, int U, typename T, typename Load>
+__device__ __forceinline__ void gather_steps(const uint4 &r, T (&g)[NP], Load load) {
+    if constexpr (U < NP) {
+        g[U] = load(group_bcast<NP, U>(r.x));
+        gather_steps<NP, U + 1>(r, g, load);
+    }
+}
+// ... and, a batch later, accumulates it with what the gather brought.
+template <int NP, int U, typename T, typename Accum>
+__device__ __forceinline__ void accum_steps(const uint4 &r, const T (&g)[NP], Accum accum) {
+    if constexpr (U < NP) {
+        accum(group_bcast<NP, U>(r.x),
+              make_float2(__uint_as_float(group_bcast<NP, U>(r.y)), __uint_as_float(group_bcast<NP, U>(r.z))), g[U]);
+        accum_steps<NP, U + 1>(r, g, accum);
+    }
+}
+
+// Records [beg, end) of one bin.  A wavefront takes batches of 64 records round-robin with the other
+// wavefronts of the workgroup; EVERY LANE LOADS ONE RECORD of a batch (a 16-byte load each: loading a
+// record with all NP lanes that work on it costs NP times the return bandwidth of the memory pipeline,
+// which then bounds the kernel), and the NP lanes of a group pass their NP records around: in step u the
+// group works on the record its lane u holds.
+//
+// Three-stage pipeline over three register buffers, unrolled so that no buffer is ever copied: in the
+// step that accumulates batch i, the gathers of batch i + 1 and the record load of batch i + 2 are issued
+// -- the record first, so that waiting for it next step leaves the younger gathers in flight.  Loads
+// are never predicated: a position past `end` re-reads the bin's last record and its gather result is
+// replaced by zero, so it adds nothing.
+template <int D, int NP, typename T, typename IoT, typename Load, typename Accum>
+__device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, const uint32_t beg, const uint32_t end,
+                                              const float *__restrict__ x, const IoT *__restrict__ dy_l, const float res,
                                               Load load, Accum accum)
 {
-    constexpr uint32_t EPI = 64 / NP;
-    constexpr uint32_t kBatchRecs = kDrainSteps * EPI;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane / NP;
-    const uint32_t stride = kSlicedWaves * kBatchRecs;
-    auto fetch = [&](const uint32_t b, uint4 (&r)[kDrainSteps]) {
-#pragma unroll
-        for (int u = 0; u < kDrainSteps; ++u) {
-            const uint32_t i = b + (uint32_t)u * EPI + sub;
-            r[u] = (b < end && i < end) ? rec[i] : make_uint4(0u, 0u, 0u, 0u);
-        }
-    };
-    uint32_t b = beg + wave * kBatchRecs;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t stride = kSlicedWaves * 64u;
+    uint32_t b = beg + wave * 64u;
     if (b >= end) return;
-    uint4 cur[kDrainSteps], nxt[kDrainSteps];
-    T     t_cur[kDrainSteps];
-    fetch(b, cur);
+    const uint32_t last = end - 1u;
+    using Pair = typename std::conditional<sizeof(IoT) == 2, uint32_t, float2>::type;   // dL/dy of a level as stored
+    // Four stages, a batch apart, over four register buffers (unrolled four times, so no buffer is copied):
+    //   A  this lane's record of a batch                          (coalesced 8-byte load)
+    //   B  the record's point and upstream gradient               (gathers by point index)
+    //   C  weight * dL/dy from those, and the gathers the keys of the batch ask for
+    //   D  accumulate
+    // Each stage consumes what the stage before it loaded one step earlier; within a step the loads are
+    // issued A, B, C, so that a wait for an older stage's data leaves the younger loads in flight.
+    uint2 Q[4];
+    float X[4][D];
+    Pair  Y[4];
+    uint4 R[4];                                              // key, weight * dL/dy (two floats), unused
+    T     G[4][NP];
+    auto stage_a = [&](const uint32_t base, uint2 &q) {
+        const uint32_t i = base + lane;
+        q = rec[i < last ? i : last];
+    };
+    auto stage_b = [&](const uint2 &q, float (&xp)[D], Pair &y) {
+        const uint32_t n = q.y >> D;
 #pragma unroll
-    for (int u = 0; u < kDrainSteps; ++u) t_cur[u] = load(cur[u].x);
-    fetch(b + stride, nxt);
-    for (; b < end; b += stride) {
-        T     t_nxt[kDrainSteps];
-        uint4 far[kDrainSteps];
+        for (int j = 0; j < D; ++j) xp[j] = x[(size_t)n * D + j];
+        y = reinterpret_cast<const Pair *>(dy_l)[n];
+    };
+    auto stage_c = [&](const uint32_t base, const uint2 &q, const float (&xp)[D], const Pair &y, uint4 &r, T (&g)[NP]) {
+        const uint32_t c = q.y & ((1u << D) - 1u);
+        float wt = (base + lane < end) ? 1.0f : 0.0f;        // beyond the bin: contributes nothing
+        {
+#pragma clang fp contract(off)
 #pragma unroll
-        for (int u = 0; u < kDrainSteps; ++u) t_nxt[u] = load(nxt[u].x);     // gathers of the next batch
-        fetch(b + 2 * stride, far);                                           // records of the one after
-#pragma unroll
-        for (int u = 0; u < kDrainSteps; ++u)
-            accum(cur[u].x, make_float2(__uint_as_float(cur[u].y), __uint_as_float(cur[u].z)), t_cur[u]);
-#pragma unroll
-        for (int u = 0; u < kDrainSteps; ++u) { cur[u] = nxt[u]; t_cur[u] = t_nxt[u]; nxt[u] = far[u]; }
+            for (int j = 0; j < D; ++j) {
+                const float pos = xp[j] * res;               // one rounded fp32 multiply
+                const float w = pos - floorf(pos);
+                wt *= ((c >> j) & 1u) ? w : 1.0f - w;
+            }
+        }
+        const float2 gy = pair_to_float2(y);
+        r = make_uint4(q.x, __float_as_uint(wt * gy.x), __float_as_uint(wt * gy.y), 0u);
+        gather_steps<NP, 0>(r, g, load);
+    };
+    // prologue: batches b, b + stride, b + 2 stride enter the pipeline
+    stage_a(b, Q[0]);
+    stage_a(b + stride, Q[1]);
+    stage_a(b + 2 * stride, Q[2]);
+    stage_b(Q[0], X[0], Y[0]);
+    stage_b(Q[1], X[1], Y[1]);
+    stage_c(b, Q[0], X[0], Y[0], R[0], G[0]);
+#define CNGP_DRAIN_STEP(P0, P1, P2, P3)                                                  \
+        stage_a(b + 3 * stride, Q[P3]);                                                  \
+        stage_b(Q[P2], X[P2], Y[P2]);                                                    \
+        stage_c(b + stride, Q[P1], X[P1], Y[P1], R[P1], G[P1]);                          \
+        accum_steps<NP, 0>(R[P0], G[P0], accum);                                         \
+        b += stride;                                                                     \
+        if (b >= end) break;
+    for (;;) {
+        CNGP_DRAIN_STEP(0, 1, 2, 3)
+        CNGP_DRAIN_STEP(1, 2, 3, 0)
+        CNGP_DRAIN_STEP(2, 3, 0, 1)
+        CNGP_DRAIN_STEP(3, 0, 1, 2)
     }
+#undef CNGP_DRAIN_STEP
 }
 
 // The records of (level index li, slice, sub) of one role: sub-range `sub` of `subs` equal parts of the bin.
@@ -215,9 +287,10 @@ __device__ __forceinline__ void bin_range(const uint32_t *__restrict__ base, con
 }
 
 // sp: rows_log2, slices, chunks (= drain workgroups per bin), store_direct, level0, nlevels as in the sliced variant.
-template <int NP>
+template <int D, int NP, typename IoT>
 __device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &sp, const uint32_t wg, unsigned char *smem,
-                                           const float *__restrict__ sigma, const uint4 *__restrict__ recF,
+                                           const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
+                                           const float *__restrict__ sigma, const uint2 *__restrict__ recF,
                                            const uint32_t *__restrict__ baseF, const uint32_t cap, float *__restrict__ gD_f)
 {
     const uint32_t rows = 1u << sp.rows_log2, plane = rows * NP;
@@ -236,7 +309,8 @@ __device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &s
     };
     uint32_t beg, end;
     bin_range(baseF, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<NP, float>(recF + (size_t)co.index * cap, beg, end, load, accum);
+    drain_records<D, NP, float>(recF + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+                                (float)p.N_l[co.level], load, accum);
     __syncthreads();
     float *out = gD_f + (size_t)co.level * p.N_f * 2 + (size_t)co.slice * plane * 2;
     for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) {     // i = (row * NP + k) * 2 + f
@@ -246,10 +320,11 @@ __device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &s
     }
 }
 
-template <int NP, typename FeatT>
+template <int D, int NP, typename FeatT, typename IoT>
 __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &sp, const uint32_t wg, unsigned char *smem,
+                                            const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
                                             const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
-                                            const uint4 *__restrict__ recC, const uint32_t *__restrict__ baseC,
+                                            const uint2 *__restrict__ recC, const uint32_t *__restrict__ baseC,
                                             const uint32_t cap, float *__restrict__ gDhat_c)
 {
     const uint32_t rows = 1u << sp.rows_log2;
@@ -268,7 +343,8 @@ __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &
     };
     uint32_t beg, end;
     bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<NP, Raw>(recC + (size_t)co.index * cap, beg, end, load, accum);
+    drain_records<D, NP, Raw>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+                              (float)p.N_l[co.level], load, accum);
     __syncthreads();
     // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
     const size_t row0 = (size_t)co.level * p.N_c + (size_t)co.slice * rows;
@@ -287,19 +363,20 @@ __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &
 }
 
 // Workgroups [0, first_feat) drain the confidence-table bins, the rest the feature-table bins.
-template <int NP, typename FeatT>
+template <int D, int NP, typename FeatT, typename IoT>
 __global__ __launch_bounds__(kSlicedBlock) void bin_drain_kernel(
     const Params p, const SliceParams sp_c, const SliceParams sp_f, const uint32_t first_feat,
+    const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
     const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
-    const uint4 *__restrict__ recF, const uint4 *__restrict__ recC,
+    const uint2 *__restrict__ recF, const uint2 *__restrict__ recC,
     const uint32_t *__restrict__ baseF, const uint32_t *__restrict__ baseC, const uint32_t cap,
     float *__restrict__ gD_f, float *__restrict__ gDhat_c)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     if (blockIdx.x < first_feat) {
-        if (NP > 1) drain_logit<NP, FeatT>(p, sp_c, blockIdx.x, smem, D_f, sigma, recC, baseC, cap, gDhat_c);
+        if (NP > 1) drain_logit<D, NP, FeatT, IoT>(p, sp_c, blockIdx.x, smem, x, dyT, N, D_f, sigma, recC, baseC, cap, gDhat_c);
     } else {
-        drain_feat<NP>(p, sp_f, blockIdx.x - first_feat, smem, sigma, recF, baseF, cap, gD_f);
+        drain_feat<D, NP, IoT>(p, sp_f, blockIdx.x - first_feat, smem, x, dyT, N, sigma, recF, baseF, cap, gD_f);
     }
 }
 
