@@ -239,6 +239,7 @@ struct BwdPlan {
     uint32_t dense_slices, dense_verts, dense_max_verts;
 };
 
+constexpr uint32_t kMinBinnedSlicesPerLevel = 24; // from here on binning the references beats the replicated scan
 constexpr uint32_t kMaxSlicesPerLevel = 128;   // beyond this the replicated scan costs more than global atomics
 constexpr int64_t  kMinSlicedRefs = 1 << 19;    // corner references (N * L * 2^d) below which launch overheads win
 constexpr uint64_t kMaxDenseVerts = 32ull * kDenseSliceVerts;   // largest vertex grid that is pre-reduced
@@ -347,12 +348,25 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     const uint32_t per_level = b.slices_f + b.slices_c;
     // a queued reference packs (row inside the slice, row of the other table) into 32 bits
     const bool keys_fit = b.rows_f_log2 + ilog2(c->N_c) <= 32 && b.rows_c_log2 + ilog2(groups) <= 32;
-    b.sliced = per_level <= kMaxSlicesPerLevel && (N << c->d) * c->L >= kMinSlicedRefs;
+    const bool enough = (N << c->d) * c->L >= kMinSlicedRefs;
+    b.sliced = per_level <= kMaxSlicesPerLevel && enough;
+    // Binning the references of the hashed levels first (cngp_bwd_binned.h): possible whenever record
+    // positions and byte offsets into a level fit 32 bits and a level's bins can be counted in LDS.  It pays
+    // from about two dozen slices per level (measured: 24 slices 1.15x, 64 slices 1.6x over the replicated
+    // scan; 10 slices 0.75x) and is the only LDS variant for tables of hundreds of slices.
+    const bool bin_ok = keys_fit && N > 0 && ((uint64_t)N << c->d) < (1ull << 31) &&
+                        b.slices_f <= 8192 && b.slices_c <= 8192 &&
+                        (uint64_t)c->N_c * c->N_p <= (1ull << 29) && c->N_f <= (1u << 28);
+    b.binned = bin_ok && enough && per_level >= kMinBinnedSlicesPerLevel;
+    if (c->flags & CNGP_BWD_BINNED) b.binned = bin_ok;
+    if (c->flags & (CNGP_BWD_DIRECT | CNGP_BWD_SLICED)) b.binned = false;
+    if (b.binned) b.sliced = true;
     if (c->flags & CNGP_BWD_DIRECT) b.sliced = false;
     if ((c->flags & CNGP_BWD_SLICED) && (uint64_t)per_level * 32u * 64u < 0x7fffffffull) b.sliced = true;
     if (!keys_fit) b.sliced = false;
     // coarse levels whose dense vertex grid is small, much smaller than the number of references, and
-    // takes clearly fewer slice scans than the level's hashed tables
+    // takes clearly fewer slice scans than the level's hashed tables.  With binning a hashed level costs
+    // no replicated scan, and pre-reduction only pays for grids of a few slices.
     if (b.sliced && !(c->flags & CNGP_BWD_NO_PREREDUCE)) {
         uint32_t res[kMaxLevels];
         level_table(c, res);
@@ -362,6 +376,7 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             const uint64_t slices = (verts + kDenseSliceVerts - 1) / kDenseSliceVerts;
             if (verts > kMaxDenseVerts || (N << c->d) < kMinRefsPerVertex * (int64_t)verts) break;
             if (slices * 2 > per_level && slices > 1) break;
+            if (b.binned && l == c->L - 1) break;                        // (at least one level stays hashed)
             b.dense.side[l] = res[l] + 2;
             b.dense.verts[l] = (uint32_t)verts;
             b.dense.slices[l] = (uint32_t)slices;
@@ -372,20 +387,14 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             b.dense.count = l + 1;
         }
     }
-    // Binning the references of the hashed levels first: possible whenever the record positions fit 32 bits
-    // and a level's bins can be counted in LDS; it also covers tables with far too many slices for the
-    // replicated scan.
-    const int  Lh = c->L - b.dense.count;
-    const bool bin_ok = keys_fit && Lh > 0 && ((uint64_t)N << c->d) < (1ull << 31) &&
-                        b.slices_f <= 8192 && b.slices_c <= 8192 && N > 0;
-    if ((c->flags & CNGP_BWD_BINNED) && bin_ok) {
-        b.sliced = true;
-        b.binned = true;
-    }
+    const int Lh = c->L - b.dense.count;
     if (b.sliced) choose_geometry(c, N, b);
     if (b.binned) {
-        b.bin_chunk_pts = 4096;
-        b.bin_chunks = (uint32_t)((N + b.bin_chunk_pts - 1) / b.bin_chunk_pts);
+        // chunks of at least 1024 points, at most 256 of them
+        int64_t cp = ((N + 255) / 256 + 63) / 64 * 64;
+        if (cp < 1024) cp = 1024;
+        b.bin_chunk_pts = (uint32_t)cp;
+        b.bin_chunks = (uint32_t)((N + cp - 1) / cp);
         // drain workgroups per bin: about 2^16 records each, and enough workgroups to fill the chip twice
         const double refs = (double)((uint64_t)N << c->d);
         auto subs = [&](uint32_t slices) -> uint32_t {
@@ -455,17 +464,18 @@ int launch_transpose_dy(const cngp_config *c, const void *dy, void *dyT, int64_t
     return launch_status("transpose_dy_kernel");
 }
 
-// Hashed levels with the references binned by slice: count, offsets, scatter, drain.
+// Binned variant: count, offsets, scatter (+ vertex-grid accumulation of the dense levels), drain
+// (+ the two roles of the dense levels, which scan the finished vertex grids).
 template <int D, int NP, typename FeatT, typename IoT>
 int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, const float *x, int64_t N,
-                      const void *D_f, const float *sigma, const IoT *dyT, float *gD_f, float *gDhat_c,
+                      const void *D_f, const float *sigma, const IoT *dyT, float *G, float *gD_f, float *gDhat_c,
                       void *workspace, hipStream_t s) {
     const int Ld = b.dense.count, Lh = c->L - Ld;
-    if (Lh <= 0) return CNGP_OK;
     char *ws = (char *)workspace;
     uint32_t *cntF = (uint32_t *)(ws + b.cntF_off), *cntC = (uint32_t *)(ws + b.cntC_off);
     uint32_t *baseF = (uint32_t *)(ws + b.baseF_off), *baseC = (uint32_t *)(ws + b.baseC_off);
     uint2    *recF = (uint2 *)(ws + b.recF_off), *recC = (uint2 *)(ws + b.recC_off);
+    const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
     BinParams bp;
     std::memset(&bp, 0, sizeof(bp));
     bp.level0 = Ld; bp.nlevels = Lh;
@@ -476,44 +486,76 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     const int64_t blocks = (int64_t)Lh * bp.chunks;
     if (int rc = check_blocks(blocks)) return rc;
     const size_t lds_bins = (size_t)(bp.slices_f + bp.slices_c) * sizeof(uint32_t);
-    {
-        LaunchTimer t(s, K_BWD_BIN_COUNT);
-        bin_count_kernel<D><<<(unsigned)blocks, kBinBlock, lds_bins, s>>>(p, bp, x, N, cntF, cntC);
-        if (int rc = launch_status("bin_count_kernel")) return rc;
-    }
-    {
+    // One wavefront per chunk keeps a bin's records in the order of the points, which the drain's gathers
+    // like (measured: drain 7 % faster); with many bins a lone wavefront fills its cache lines too slowly
+    // for the memory system to merge the 8-byte writes, and four wavefronts sharing the cursors write
+    // 1.7 times faster (measured at 64 bins per level).
+    const unsigned bin_block = bp.slices_f + bp.slices_c >= 48 ? 256u : (unsigned)kBinBlock;
+    if (Lh > 0) {
+        {
+            LaunchTimer t(s, K_BWD_BIN_COUNT);
+            bin_count_kernel<D><<<(unsigned)blocks, bin_block, lds_bins, s>>>(p, bp, x, N, cntF, cntC);
+            if (int rc = launch_status("bin_count_kernel")) return rc;
+        }
         LaunchTimer t(s, K_BWD_BIN_OFFSETS);
-        bin_offsets_kernel<<<(unsigned)(2 * Lh), kBinBlock, 0, s>>>(bp, cntF, cntC, baseF, baseC);
+        const uint32_t big = bp.slices_f > bp.slices_c ? bp.slices_f : bp.slices_c;
+        const uint32_t words = (uint64_t)bp.chunks * big <= 36864 ? bp.chunks * big : 0u;    // up to 144 KB of LDS
+        if (int rc = allow_big_lds(bin_offsets_kernel, (size_t)words * 4)) return rc;
+        bin_offsets_kernel<<<(unsigned)(2 * Lh), kOffsetsBlock, (size_t)words * 4, s>>>(bp, cntF, cntC, baseF, baseC, words);
         if (int rc = launch_status("bin_offsets_kernel")) return rc;
     }
-    {
+    if (Lh > 0) {
         LaunchTimer t(s, K_BWD_BIN_SCATTER);
-        bin_scatter_kernel<D><<<(unsigned)blocks, kBinBlock, lds_bins, s>>>(p, bp, x, N, cntF, cntC, recF, recC);
+        bin_scatter_kernel<D><<<(unsigned)blocks, bin_block, lds_bins, s>>>(p, bp, x, N, cntF, cntC, recF, recC);
         if (int rc = launch_status("bin_scatter_kernel")) return rc;
     }
-    const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
-    auto role = [&](uint32_t rows_log2, uint32_t slices, uint32_t subs, uint32_t &wgs) {
+    if (Ld > 0) {   // vertex-grid accumulation of the dense levels: the sliced kernel with that role alone
+        BwdRoles roles;
+        std::memset(&roles, 0, sizeof(roles));
+        for (int r = 0; r < ROLE_COUNT; ++r) roles.sp[r].slices = roles.sp[r].chunks = 1;
+        roles.sp[ROLE_GRID].chunks = b.grid.chunks ? b.grid.chunks : 1;
+        roles.sp[ROLE_GRID].chunk_pts = b.grid.chunk_items;
+        roles.sp[ROLE_GRID].store_direct = b.grid.chunks == 1;
+        const uint32_t n_grid = b.dense_slices * roles.sp[ROLE_GRID].chunks;
+        roles.first[ROLE_COUNT] = n_grid;                   // every other role is empty: first[] = 0
+        auto kernel = bwd_sliced_kernel<D, NP, FeatT, IoT>;
+        const size_t lds_grid = (size_t)kDenseSliceVerts * 2 * sizeof(double);
+        if (int rc = allow_big_lds(kernel, lds_grid)) return rc;
+        LaunchTimer t(s, K_BWD_SLICED);
+        kernel<<<n_grid, kSlicedBlock, lds_grid, s>>>(p, roles, b.dense, x, (const FeatT *)D_f, sigma, dyT, G, gD_f, gDhat_c, N);
+        if (int rc = launch_status("bwd_sliced_kernel")) return rc;
+    }
+    auto role = [&](uint32_t rows_log2, uint32_t slices, const Geom &g, int level0, int nlevels, uint32_t &wgs) {
         SliceParams sp;
         std::memset(&sp, 0, sizeof(sp));
         sp.rows_log2 = rows_log2;
         sp.slices = slices ? slices : 1;
-        sp.chunks = subs ? subs : 1;
+        sp.chunks = g.chunks ? g.chunks : 1;
+        sp.chunk_pts = g.chunk_items;
         sp.store_direct = (sp.chunks == 1 && zero_first) ? 1 : 0;       // matches the clearing in cngp_encode_bwd
-        sp.level0 = Ld;
-        sp.nlevels = slices ? Lh : 0;
-        wgs = slices ? (uint32_t)kXcds * (((uint32_t)Lh * sp.slices * sp.chunks + kXcds - 1) / kXcds) : 0u;
+        sp.level0 = level0;
+        sp.nlevels = slices ? nlevels : 0;
+        wgs = (slices && nlevels > 0) ? (uint32_t)kXcds * (((uint32_t)nlevels * sp.slices * sp.chunks + kXcds - 1) / kXcds) : 0u;
         return sp;
     };
-    uint32_t wgs_c = 0, wgs_f = 0;
-    const SliceParams sp_c = role(b.rows_c_log2, NP > 1 ? b.slices_c : 0, b.subs_c, wgs_c);
-    const SliceParams sp_f = role(b.rows_f_log2, b.slices_f, b.subs_f, wgs_f);
+    uint32_t wgs_c = 0, wgs_f = 0, wgs_cv = 0, wgs_fv = 0;
+    const uint32_t slices_c = NP > 1 ? b.slices_c : 0;
+    const SliceParams sp_c = role(b.rows_c_log2, slices_c, Geom{b.subs_c, 0}, Ld, Lh, wgs_c);
+    const SliceParams sp_f = role(b.rows_f_log2, b.slices_f, Geom{b.subs_f, 0}, Ld, Lh, wgs_f);
+    BwdRoles vtx;
+    std::memset(&vtx, 0, sizeof(vtx));
+    vtx.sp[ROLE_LOGIT_VTX] = role(b.rows_c_log2, slices_c, b.logit_vtx, 0, Ld, wgs_cv);
+    vtx.sp[ROLE_FEAT_VTX] = role(b.rows_f_log2, b.slices_f, b.feat_vtx, 0, Ld, wgs_fv);
+    vtx.first[ROLE_LOGIT_VTX] = 0;
+    vtx.first[ROLE_FEAT_VTX] = wgs_cv;
     auto kernel = bin_drain_kernel<D, NP, FeatT, IoT>;
-    const size_t lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8, lds_c = ((size_t)1 << b.rows_c_log2) * c->N_p * 8;
-    const size_t lds = lds_f > lds_c ? lds_f : lds_c;
+    size_t lds = b.lds_f > b.lds_c ? b.lds_f : b.lds_c;                 // slice + the vertex roles' ring buffers
     if (int rc = allow_big_lds(kernel, lds)) return rc;
+    const uint32_t total = wgs_c + wgs_f + wgs_cv + wgs_fv;
+    if (total == 0) return CNGP_OK;
     LaunchTimer t(s, K_BWD_BIN_DRAIN);
-    kernel<<<wgs_c + wgs_f, kSlicedBlock, lds, s>>>(p, sp_c, sp_f, wgs_c, x, dyT, N, (const FeatT *)D_f, sigma, recF, recC,
-                                                    baseF, baseC, bp.cap, gD_f, gDhat_c);
+    kernel<<<total, kSlicedBlock, lds, s>>>(p, sp_c, sp_f, wgs_c, wgs_c + wgs_f, x, dyT, N, (const FeatT *)D_f, sigma, recF, recC,
+                                            baseF, baseC, bp.cap, vtx, b.dense, G, gD_f, gDhat_c);
     return launch_status("bin_drain_kernel");
 }
 
@@ -537,6 +579,9 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
         z.add(G, (int64_t)b.dense_verts * 2);
         if (int rc = z.launch(s)) return rc;
     }
+
+    if (b.binned)
+        return launch_bwd_binned<D, NP, FeatT, IoT>(c, p, b, x, N, D_f, sigma, dyT, G, gD_f, gDhat_c, workspace, s);
 
     // Launch 1: feature and logit gradients of the hashed levels (scan the points) together with the
     // vertex-grid accumulation of the dense levels.  Launch 2: the two gradients of the dense levels
@@ -566,8 +611,8 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
                 next += (uint32_t)kXcds * (((uint32_t)nlevels * sp.slices * sp.chunks + kXcds - 1) / kXcds);
         };
         const bool pts = launch == 0, vtx = launch == 1;
-        add_role(ROLE_LOGIT_PTS, pts && NP > 1 && !b.binned, b.logit_pts, b.rows_c_log2, b.slices_c, Ld, Lh);
-        add_role(ROLE_FEAT_PTS, pts && !b.binned, b.feat_pts, b.rows_f_log2, b.slices_f, Ld, Lh);
+        add_role(ROLE_LOGIT_PTS, pts && NP > 1, b.logit_pts, b.rows_c_log2, b.slices_c, Ld, Lh);
+        add_role(ROLE_FEAT_PTS, pts, b.feat_pts, b.rows_f_log2, b.slices_f, Ld, Lh);
         add_role(ROLE_LOGIT_VTX, vtx && NP > 1, b.logit_vtx, b.rows_c_log2, b.slices_c, 0, Ld);
         add_role(ROLE_FEAT_VTX, vtx, b.feat_vtx, b.rows_f_log2, b.slices_f, 0, Ld);
         roles.first[ROLE_GRID] = next;
@@ -581,7 +626,6 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
         kernel<<<next, kSlicedBlock, lds, s>>>(p, roles, b.dense, x, (const FeatT *)D_f, sigma, dyT, G, gD_f, gDhat_c, N);
         if (int rc = launch_status("bwd_sliced_kernel")) return rc;
     }
-    if (b.binned) return launch_bwd_binned<D, NP, FeatT, IoT>(c, p, b, x, N, D_f, sigma, dyT, gD_f, gDhat_c, workspace, s);
     return CNGP_OK;
 }
 

@@ -22,7 +22,11 @@
 
 namespace cngp {
 
-constexpr int kBinBlock = 256;            // count and scatter kernels
+// Count and scatter run one workgroup per chunk of points.  With a single wavefront (the default block size)
+// the records a chunk adds to a bin follow the order of the points, so the drain's gathers of a batch of
+// records (the points and their upstream gradients) fall into a few cache lines instead of one line per
+// record; the host launches 256 lanes instead when there are many bins.
+constexpr int kBinBlock = 64;
 
 struct BinParams {
     int32_t  level0, nlevels;             // the hashed levels
@@ -40,7 +44,7 @@ __device__ __forceinline__ void corner_rows(const Cell<D> &cell, const Params &p
 }
 
 template <int D>
-__global__ __launch_bounds__(kBinBlock) void bin_count_kernel(
+__global__ __launch_bounds__(256) void bin_count_kernel(
     const Params p, const BinParams bp, const float *__restrict__ x, const int64_t N,
     uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC)
 {
@@ -48,11 +52,11 @@ __global__ __launch_bounds__(kBinBlock) void bin_count_kernel(
     const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
     const int      l = bp.level0 + (int)li;
     const uint32_t bins = bp.slices_f + bp.slices_c;
-    for (uint32_t i = threadIdx.x; i < bins; i += kBinBlock) hist[i] = 0u;
+    for (uint32_t i = threadIdx.x; i < bins; i += blockDim.x) hist[i] = 0u;
     __syncthreads();
     const int64_t n0 = (int64_t)chunk * bp.chunk_pts;
     const int64_t n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
-    for (int64_t n = n0 + threadIdx.x; n < n1; n += kBinBlock) {
+    for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
         float xp[D];
 #pragma unroll
         for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
@@ -68,59 +72,86 @@ __global__ __launch_bounds__(kBinBlock) void bin_count_kernel(
     }
     __syncthreads();
     uint32_t *rowF = cntF + ((size_t)li * bp.chunks + chunk) * bp.slices_f;
-    for (uint32_t s = threadIdx.x; s < bp.slices_f; s += kBinBlock) rowF[s] = hist[s];
+    for (uint32_t s = threadIdx.x; s < bp.slices_f; s += blockDim.x) rowF[s] = hist[s];
     if (bp.slices_c) {
         uint32_t *rowC = cntC + ((size_t)li * bp.chunks + chunk) * bp.slices_c;
-        for (uint32_t s = threadIdx.x; s < bp.slices_c; s += kBinBlock) rowC[s] = hist[bp.slices_f + s];
+        for (uint32_t s = threadIdx.x; s < bp.slices_c; s += blockDim.x) rowC[s] = hist[bp.slices_f + s];
     }
 }
 
+constexpr int kOffsetsBlock = 256;
+
 // One workgroup per (level, role).  In place: cnt[chunk][slice] becomes the position, inside the level's
 // record array, of the first record that chunk writes to that slice; base[slice] = start of the slice's
-// bin, base[slices] = number of records of the level.
-__global__ __launch_bounds__(kBinBlock) void bin_offsets_kernel(
+// bin, base[slices] = number of records of the level.  `lds_words` words of dynamic LDS hold the whole
+// matrix when it fits (the scans then run in LDS; through memory they are chains of dependent loads).
+// Threads form a [segment][slice] array: a thread owns one slice's counts of a run of chunks.
+__global__ __launch_bounds__(kOffsetsBlock) void bin_offsets_kernel(
     const BinParams bp, uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC,
-    uint32_t *__restrict__ baseF, uint32_t *__restrict__ baseC)
+    uint32_t *__restrict__ baseF, uint32_t *__restrict__ baseC, const uint32_t lds_words)
 {
-    __shared__ uint32_t part[kBinBlock];
+    extern __shared__ uint32_t mat[];
+    __shared__ uint32_t part[kOffsetsBlock];                // [segment][slice lane]: sum of the thread's run
+    __shared__ uint32_t carry;                              // records of the slices handled in earlier rounds
     const uint32_t li = blockIdx.x >> 1, role = blockIdx.x & 1u;
     const uint32_t slices = role ? bp.slices_c : bp.slices_f;
     if (slices == 0) return;
-    uint32_t *cnt = (role ? cntC : cntF) + (size_t)li * bp.chunks * slices;
+    uint32_t *gcnt = (role ? cntC : cntF) + (size_t)li * bp.chunks * slices;
     uint32_t *base = (role ? baseC : baseF) + (size_t)li * (slices + 1);
-    // this thread's contiguous run of slices
-    const uint32_t per = (slices + kBinBlock - 1) / kBinBlock;
-    const uint32_t s0 = threadIdx.x * per, s1 = (s0 + per < slices) ? s0 + per : slices;
-    uint32_t mine = 0;
-    for (uint32_t s = s0; s < s1; ++s) {                    // exclusive prefix over the chunks of one slice
-        uint32_t run = 0;
-        for (uint32_t ch = 0; ch < bp.chunks; ++ch) {
+    const uint32_t elems = bp.chunks * slices;
+    const bool     in_lds = elems <= lds_words;
+    uint32_t      *cnt = in_lds ? mat : gcnt;
+    if (in_lds)
+        for (uint32_t i = threadIdx.x; i < elems; i += kOffsetsBlock) mat[i] = gcnt[i];
+    if (threadIdx.x == 0) carry = 0u;
+    __syncthreads();
+    const uint32_t width = slices < (uint32_t)kOffsetsBlock ? slices : (uint32_t)kOffsetsBlock;   // slices per round
+    const uint32_t segs = kOffsetsBlock / width;                                                // width is a power of two
+    const uint32_t lane_s = threadIdx.x % width, seg = threadIdx.x / width;
+    const uint32_t per = (bp.chunks + segs - 1) / segs;
+    const uint32_t c0 = seg * per, c1 = (c0 + per < bp.chunks) ? c0 + per : bp.chunks;
+    for (uint32_t s_round = 0; s_round < slices; s_round += width) {
+        const uint32_t s = s_round + lane_s;                // < slices: both are powers of two
+        uint32_t sum = 0;
+        for (uint32_t ch = c0; ch < c1; ++ch) sum += cnt[(size_t)ch * slices + s];
+        part[threadIdx.x] = sum;
+        __syncthreads();
+        uint32_t before = 0, total = 0;                     // this slice: records of earlier segments, of all
+        for (uint32_t g = 0; g < segs; ++g) {
+            const uint32_t v = part[g * width + lane_s];
+            before += g < seg ? v : 0u;
+            total += v;
+        }
+        __syncthreads();
+        if (seg == 0) part[lane_s] = total;
+        __syncthreads();
+        uint32_t start = carry;                             // exclusive prefix of the totals over the slices
+        for (uint32_t j = 0; j < lane_s; ++j) start += part[j];
+        if (seg == 0) base[s] = start;
+        uint32_t run = start + before;
+        for (uint32_t ch = c0; ch < c1; ++ch) {
             const uint32_t v = cnt[(size_t)ch * slices + s];
             cnt[(size_t)ch * slices + s] = run;
             run += v;
         }
-        base[s] = run;                                      // the slice's total, for now
-        mine += run;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t all = carry;
+            for (uint32_t j = 0; j < width; ++j) all += part[j];
+            carry = all;
+        }
+        __syncthreads();
     }
-    part[threadIdx.x] = mine;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int t = 0; t < kBinBlock; ++t) { const uint32_t v = part[t]; part[t] = run; run += v; }
-        base[slices] = run;
-    }
-    __syncthreads();
-    uint32_t run = part[threadIdx.x];
-    for (uint32_t s = s0; s < s1; ++s) {
-        const uint32_t total = base[s];
-        base[s] = run;
-        for (uint32_t ch = 0; ch < bp.chunks; ++ch) cnt[(size_t)ch * slices + s] += run;
-        run += total;
+    if (threadIdx.x == 0) base[slices] = carry;
+    if (in_lds) {
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < elems; i += kOffsetsBlock) gcnt[i] = mat[i];
     }
 }
 
+// Scatter, one workgroup per (level, chunk).
 template <int D>
-__global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(
+__global__ __launch_bounds__(256) void bin_scatter_kernel(
     const Params p, const BinParams bp, const float *__restrict__ x, const int64_t N,
     const uint32_t *__restrict__ cntF, const uint32_t *__restrict__ cntC,
     uint2 *__restrict__ recF, uint2 *__restrict__ recC)
@@ -129,10 +160,10 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(
     const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
     const int      l = bp.level0 + (int)li;
     const uint32_t *rowF = cntF + ((size_t)li * bp.chunks + chunk) * bp.slices_f;
-    for (uint32_t s = threadIdx.x; s < bp.slices_f; s += kBinBlock) cursor[s] = rowF[s];
+    for (uint32_t s = threadIdx.x; s < bp.slices_f; s += blockDim.x) cursor[s] = rowF[s];
     if (bp.slices_c) {
         const uint32_t *rowC = cntC + ((size_t)li * bp.chunks + chunk) * bp.slices_c;
-        for (uint32_t s = threadIdx.x; s < bp.slices_c; s += kBinBlock) cursor[bp.slices_f + s] = rowC[s];
+        for (uint32_t s = threadIdx.x; s < bp.slices_c; s += blockDim.x) cursor[bp.slices_f + s] = rowC[s];
     }
     __syncthreads();
     uint2 *outF = recF + (size_t)li * bp.cap;
@@ -140,7 +171,7 @@ __global__ __launch_bounds__(kBinBlock) void bin_scatter_kernel(
     const uint32_t lo_f = (1u << bp.rows_f_log2) - 1u, lo_c = (1u << bp.rows_c_log2) - 1u;
     const int64_t  n0 = (int64_t)chunk * bp.chunk_pts;
     const int64_t  n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
-    for (int64_t n = n0 + threadIdx.x; n < n1; n += kBinBlock) {
+    for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
         float xp[D];
 #pragma unroll
         for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
@@ -187,7 +218,7 @@ __device__ __forceinline__ void gather_steps(const uint4 &r, T (&g)[NP], Load lo
 template <int NP, int U, typename T, typename Accum>
 __device__ __forceinline__ void accum_steps(const uint4 &r, const T (&g)[NP], Accum accum) {
     if constexpr (U < NP) {
-        accum(group_bcast<NP, U>(r.x),
+        accum(group_bcast<NP, U>(r.w),
               make_float2(__uint_as_float(group_bcast<NP, U>(r.y)), __uint_as_float(group_bcast<NP, U>(r.z))), g[U]);
         accum_steps<NP, U + 1>(r, g, accum);
     }
@@ -207,8 +238,9 @@ __device__ __forceinline__ void accum_steps(const uint4 &r, const T (&g)[NP], Ac
 template <int D, int NP, typename T, typename IoT, typename Load, typename Accum>
 __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, const uint32_t beg, const uint32_t end,
                                               const float *__restrict__ x, const IoT *__restrict__ dy_l, const float res,
-                                              Load load, Accum accum)
+                                              const uint32_t rows_log2, Load load, Accum accum)
 {
+    const uint32_t row_lo_mask = (1u << rows_log2) - 1u;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t stride = kSlicedWaves * 64u;
     uint32_t b = beg + wave * 64u;
@@ -225,7 +257,7 @@ __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, con
     uint2 Q[4];
     float X[4][D];
     Pair  Y[4];
-    uint4 R[4];                                              // key, weight * dL/dy (two floats), unused
+    uint4 R[4];                                              // gather offset, weight * dL/dy (two floats), LDS offset
     T     G[4][NP];
     auto stage_a = [&](const uint32_t base, uint2 &q) {
         const uint32_t i = base + lane;
@@ -250,7 +282,10 @@ __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, con
             }
         }
         const float2 gy = pair_to_float2(y);
-        r = make_uint4(q.x, __float_as_uint(wt * gy.x), __float_as_uint(wt * gy.y), 0u);
+        // the key, decoded once per record: byte offset of the row the gather reads (candidate 0), and
+        // byte offset of the accumulator row in LDS; the lanes of the group add their candidate's share
+        r = make_uint4((q.x >> rows_log2) * (uint32_t)(NP * sizeof(T)), __float_as_uint(wt * gy.x),
+                       __float_as_uint(wt * gy.y), (q.x & row_lo_mask) * (uint32_t)(NP * sizeof(double)));
         gather_steps<NP, 0>(r, g, load);
     };
     // prologue: batches b, b + stride, b + 2 stride enter the pipeline
@@ -300,17 +335,21 @@ __device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &s
     for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) acc[i] = 0.0;
     __syncthreads();
     const float   *sig_l = sigma + (size_t)co.level * p.N_c * NP;
-    const uint32_t k = (threadIdx.x & 63) % NP, row_lo_mask = rows - 1u, rows_log2 = sp.rows_log2;
-    auto load = [&](const uint32_t key) -> float { return NP == 1 ? 1.0f : sig_l[(size_t)(key >> rows_log2) * NP + k]; };
-    auto accum = [&](const uint32_t key, const float2 g, const float s) {
-        double *a = acc + (key & row_lo_mask) * NP + k;
+    const uint32_t k = (threadIdx.x & 63) % NP;
+    const char    *sig_k = reinterpret_cast<const char *>(sig_l + k);          // this lane's candidate
+    char          *acc_k = reinterpret_cast<char *>(acc + k);
+    auto load = [&](const uint32_t off) -> float {           // off: byte offset of the softmax row
+        return NP == 1 ? 1.0f : *reinterpret_cast<const float *>(sig_k + off);
+    };
+    auto accum = [&](const uint32_t off, const float2 g, const float s) {      // off: byte offset of the accumulator row
+        double *a = reinterpret_cast<double *>(acc_k + off);
         atomicAdd(a, (double)(s * g.x));
         atomicAdd(a + plane, (double)(s * g.y));
     };
     uint32_t beg, end;
     bin_range(baseF, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
     drain_records<D, NP, float>(recF + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
-                                (float)p.N_l[co.level], load, accum);
+                                (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     float *out = gD_f + (size_t)co.level * p.N_f * 2 + (size_t)co.slice * plane * 2;
     for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) {     // i = (row * NP + k) * 2 + f
@@ -334,17 +373,19 @@ __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &
     for (uint32_t i = threadIdx.x; i < rows * NP; i += kSlicedBlock) acc[i] = 0.0;
     __syncthreads();
     const FeatT   *F_l = D_f + (size_t)co.level * p.N_f * 2;
-    const uint32_t k = (threadIdx.x & 63) % NP, row_lo_mask = rows - 1u, rows_log2 = sp.rows_log2;
+    const uint32_t k = (threadIdx.x & 63) % NP;
     using Raw = typename RawPair<FeatT>::type;
-    auto load = [&](const uint32_t key) -> Raw { return reinterpret_cast<const Raw *>(F_l)[(size_t)(key >> rows_log2) * NP + k]; };
-    auto accum = [&](const uint32_t key, const float2 g, const Raw raw) {
+    const char *feat_k = reinterpret_cast<const char *>(reinterpret_cast<const Raw *>(F_l) + k);   // this lane's candidate
+    char       *acc_k = reinterpret_cast<char *>(acc + k);
+    auto load = [&](const uint32_t off) -> Raw { return *reinterpret_cast<const Raw *>(feat_k + off); };
+    auto accum = [&](const uint32_t off, const float2 g, const Raw raw) {
         const float2 feat = RawPair<FeatT>::to_float2(raw);
-        atomicAdd(acc + (key & row_lo_mask) * NP + k, (double)fmaf(feat.x, g.x, feat.y * g.y));
+        atomicAdd(reinterpret_cast<double *>(acc_k + off), (double)fmaf(feat.x, g.x, feat.y * g.y));
     };
     uint32_t beg, end;
     bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
     drain_records<D, NP, Raw>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
-                              (float)p.N_l[co.level], load, accum);
+                              (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
     const size_t row0 = (size_t)co.level * p.N_c + (size_t)co.slice * rows;
@@ -362,21 +403,34 @@ __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &
     }
 }
 
-// Workgroups [0, first_feat) drain the confidence-table bins, the rest the feature-table bins.
+// Workgroups [0, first_feat) drain the confidence-table bins, [first_feat, first_vtx) the feature-table
+// bins; the rest are the two roles of the pre-reduced coarse levels (cngp_bwd_sliced.h: they scan the
+// vertex grids that the launch before this one has completed), sharing the launch so that the CUs stay busy.
 template <int D, int NP, typename FeatT, typename IoT>
 __global__ __launch_bounds__(kSlicedBlock) void bin_drain_kernel(
-    const Params p, const SliceParams sp_c, const SliceParams sp_f, const uint32_t first_feat,
+    const Params p, const SliceParams sp_c, const SliceParams sp_f, const uint32_t first_feat, const uint32_t first_vtx,
     const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
     const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
     const uint2 *__restrict__ recF, const uint2 *__restrict__ recC,
     const uint32_t *__restrict__ baseF, const uint32_t *__restrict__ baseC, const uint32_t cap,
+    const BwdRoles vtx, const DenseLevels dl, const float *__restrict__ G,
     float *__restrict__ gD_f, float *__restrict__ gDhat_c)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     if (blockIdx.x < first_feat) {
         if (NP > 1) drain_logit<D, NP, FeatT, IoT>(p, sp_c, blockIdx.x, smem, x, dyT, N, D_f, sigma, recC, baseC, cap, gDhat_c);
-    } else {
+    } else if (blockIdx.x < first_vtx) {
         drain_feat<D, NP, IoT>(p, sp_f, blockIdx.x - first_feat, smem, x, dyT, N, sigma, recF, baseF, cap, gD_f);
+    } else {
+        const uint32_t wg = blockIdx.x - first_vtx;
+        if (wg < vtx.first[ROLE_FEAT_VTX]) {
+            if (NP > 1)
+                bwd_logit_sliced<D, NP, true, FeatT, float>(p, vtx.sp[ROLE_LOGIT_VTX], dl, wg - vtx.first[ROLE_LOGIT_VTX], smem,
+                                                            x, D_f, sigma, G, gDhat_c, N);
+        } else {
+            bwd_feat_sliced<D, NP, true, float>(p, vtx.sp[ROLE_FEAT_VTX], dl, wg - vtx.first[ROLE_FEAT_VTX], smem, x, sigma,
+                                                G, gD_f, N);
+        }
     }
 }
 

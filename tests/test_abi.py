@@ -170,9 +170,12 @@ def test_backward_plan_is_reported_on_the_host():
     assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_DIRECT), w.N)["sliced"] == 0
     assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_NO_PREREDUCE), w.N)["dense_levels"] == 0
     pb = cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), w.N)
-    assert pb["sliced"] == 1 and pb["binned"] == 1 and pb["drain_wgs_feat"] >= 1 and pb["bin_chunks"] == w.N // 4096
+    assert pb["sliced"] == 1 and pb["binned"] == 1 and pb["drain_wgs_feat"] >= 1 and pb["bin_chunks"] == 256
     assert cngp.workspace_bytes(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), w.N) > 2 * (w.L - pb["dense_levels"]) * w.N * 8 * 8
-    assert p["binned"] == 0
+    assert p["binned"] == 1                               # two dozen slices per level: the library bins by itself
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_SLICED), w.N)["binned"] == 0
+    im = W.WORKLOADS["image2d"]
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(im), im.N)["binned"] == 0      # ten slices: replicated scan
     big = W.custom(d=3, L=16, N_f=2**24, N_c=2**24, N_p=2, N_min=16, N_max=2048, N=2**18)
     assert cngp.bwd_plan_info(cngp.Config.from_workload(big), big.N)["sliced"] == 0     # too many slices
 
