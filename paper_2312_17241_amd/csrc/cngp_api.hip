@@ -235,6 +235,8 @@ struct BwdPlan {
     uint32_t bin_chunks, bin_chunk_pts; // point chunks of the count / scatter kernels
     uint32_t subs_f, subs_c;            // drain workgroups per bin
     size_t   cntF_off, cntC_off, baseF_off, baseC_off, recF_off, recC_off;
+    size_t   cntG_off, baseG_off, recG_off;          // pre-reduced levels binned by slice of their vertex grid
+    GridDrainPlan grid_drain;
     DenseLevels dense;                  // levels pre-reduced per grid vertex (a prefix of the levels)
     uint32_t dense_slices, dense_verts, dense_max_verts;
 };
@@ -427,7 +429,22 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             b.baseC_off = b.baseF_off + align256((size_t)Lh * (b.slices_f + 1) * 4);
             b.recF_off = b.baseC_off + align256((size_t)Lh * (b.slices_c + 1) * 4);
             b.recC_off = b.recF_off + align256((size_t)Lh * cap * 8);
-            b.ws_bytes = b.recC_off + (b.slices_c ? align256((size_t)Lh * cap * 8) : 0);
+            b.cntG_off = b.recC_off + (b.slices_c ? align256((size_t)Lh * cap * 8) : 0);
+            const size_t Ld = (size_t)b.dense.count;
+            b.baseG_off = b.cntG_off + align256(Ld * b.bin_chunks * kGridBins * 4);
+            b.recG_off = b.baseG_off + align256(Ld * (kGridBins + 1) * 4);
+            b.ws_bytes = b.recG_off + align256(Ld * cap * 8);
+            // workgroups per slice of a level's grid: about 2^15 references each
+            uint32_t next = 0;
+            for (int l = 0; l < b.dense.count; ++l) {
+                uint64_t subs = (cap / b.dense.slices[l] + 32767) / 32768;
+                if (subs < 1) subs = 1;
+                if (subs > 256) subs = 256;
+                b.grid_drain.first[l] = next;
+                b.grid_drain.subs[l] = (uint32_t)subs;
+                next += b.dense.slices[l] * (uint32_t)subs;
+            }
+            b.grid_drain.first[b.dense.count] = next;
         }
     }
     return b;
@@ -475,6 +492,8 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     uint32_t *cntF = (uint32_t *)(ws + b.cntF_off), *cntC = (uint32_t *)(ws + b.cntC_off);
     uint32_t *baseF = (uint32_t *)(ws + b.baseF_off), *baseC = (uint32_t *)(ws + b.baseC_off);
     uint2    *recF = (uint2 *)(ws + b.recF_off), *recC = (uint2 *)(ws + b.recC_off);
+    uint32_t *cntG = (uint32_t *)(ws + b.cntG_off), *baseG = (uint32_t *)(ws + b.baseG_off);
+    uint2    *recG = (uint2 *)(ws + b.recG_off);
     const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
     BinParams bp;
     std::memset(&bp, 0, sizeof(bp));
@@ -483,47 +502,43 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     bp.rows_c_log2 = b.rows_c_log2; bp.slices_c = NP > 1 ? b.slices_c : 0;
     bp.chunks = b.bin_chunks; bp.chunk_pts = b.bin_chunk_pts;
     bp.cap = (uint32_t)((uint64_t)N << c->d);
-    const int64_t blocks = (int64_t)Lh * bp.chunks;
+    bp.dense_bins = Ld > 0 ? 1 : 0;
+    const int64_t blocks = (int64_t)(Lh + Ld) * bp.chunks;
     if (int rc = check_blocks(blocks)) return rc;
-    const size_t lds_bins = (size_t)(bp.slices_f + bp.slices_c) * sizeof(uint32_t);
+    const uint32_t most_bins = bp.slices_f + bp.slices_c > kGridBins ? bp.slices_f + bp.slices_c : kGridBins;
+    const size_t lds_bins = (size_t)most_bins * sizeof(uint32_t);
     // One wavefront per chunk keeps a bin's records in the order of the points, which the drain's gathers
     // like (measured: drain 7 % faster); with many bins a lone wavefront fills its cache lines too slowly
     // for the memory system to merge the 8-byte writes, and four wavefronts sharing the cursors write
     // 1.7 times faster (measured at 64 bins per level).
     const unsigned bin_block = bp.slices_f + bp.slices_c >= 48 ? 256u : (unsigned)kBinBlock;
-    if (Lh > 0) {
+    {
         {
             LaunchTimer t(s, K_BWD_BIN_COUNT);
-            bin_count_kernel<D><<<(unsigned)blocks, bin_block, lds_bins, s>>>(p, bp, x, N, cntF, cntC);
+            bin_count_kernel<D><<<(unsigned)blocks, bin_block, lds_bins, s>>>(p, bp, b.dense, x, N, cntF, cntC, cntG);
             if (int rc = launch_status("bin_count_kernel")) return rc;
         }
         LaunchTimer t(s, K_BWD_BIN_OFFSETS);
-        const uint32_t big = bp.slices_f > bp.slices_c ? bp.slices_f : bp.slices_c;
+        uint32_t big = bp.slices_f > bp.slices_c ? bp.slices_f : bp.slices_c;
+        if (Ld > 0 && big < kGridBins) big = kGridBins;
         const uint32_t words = (uint64_t)bp.chunks * big <= 36864 ? bp.chunks * big : 0u;    // up to 144 KB of LDS
         if (int rc = allow_big_lds(bin_offsets_kernel, (size_t)words * 4)) return rc;
-        bin_offsets_kernel<<<(unsigned)(2 * Lh), kOffsetsBlock, (size_t)words * 4, s>>>(bp, cntF, cntC, baseF, baseC, words);
+        bin_offsets_kernel<<<(unsigned)(2 * Lh + Ld), kOffsetsBlock, (size_t)words * 4, s>>>(bp, cntF, cntC, cntG, baseF, baseC,
+                                                                                            baseG, words);
         if (int rc = launch_status("bin_offsets_kernel")) return rc;
     }
-    if (Lh > 0) {
+    {
         LaunchTimer t(s, K_BWD_BIN_SCATTER);
-        bin_scatter_kernel<D><<<(unsigned)blocks, bin_block, lds_bins, s>>>(p, bp, x, N, cntF, cntC, recF, recC);
+        bin_scatter_kernel<D><<<(unsigned)blocks, bin_block, lds_bins, s>>>(p, bp, b.dense, x, N, cntF, cntC, cntG, recF, recC, recG);
         if (int rc = launch_status("bin_scatter_kernel")) return rc;
     }
-    if (Ld > 0) {   // vertex-grid accumulation of the dense levels: the sliced kernel with that role alone
-        BwdRoles roles;
-        std::memset(&roles, 0, sizeof(roles));
-        for (int r = 0; r < ROLE_COUNT; ++r) roles.sp[r].slices = roles.sp[r].chunks = 1;
-        roles.sp[ROLE_GRID].chunks = b.grid.chunks ? b.grid.chunks : 1;
-        roles.sp[ROLE_GRID].chunk_pts = b.grid.chunk_items;
-        roles.sp[ROLE_GRID].store_direct = b.grid.chunks == 1;
-        const uint32_t n_grid = b.dense_slices * roles.sp[ROLE_GRID].chunks;
-        roles.first[ROLE_COUNT] = n_grid;                   // every other role is empty: first[] = 0
-        auto kernel = bwd_sliced_kernel<D, NP, FeatT, IoT>;
+    if (Ld > 0) {   // vertex-grid sums of the pre-reduced levels from their bins
+        auto kernel = bin_grid_drain_kernel<D, IoT>;
         const size_t lds_grid = (size_t)kDenseSliceVerts * 2 * sizeof(double);
         if (int rc = allow_big_lds(kernel, lds_grid)) return rc;
         LaunchTimer t(s, K_BWD_SLICED);
-        kernel<<<n_grid, kSlicedBlock, lds_grid, s>>>(p, roles, b.dense, x, (const FeatT *)D_f, sigma, dyT, G, gD_f, gDhat_c, N);
-        if (int rc = launch_status("bwd_sliced_kernel")) return rc;
+        kernel<<<b.grid_drain.first[Ld], kSlicedBlock, lds_grid, s>>>(p, b.dense, b.grid_drain, x, dyT, N, recG, baseG, bp.cap, G);
+        if (int rc = launch_status("bin_grid_drain_kernel")) return rc;
     }
     auto role = [&](uint32_t rows_log2, uint32_t slices, const Geom &g, int level0, int nlevels, uint32_t &wgs) {
         SliceParams sp;
@@ -573,7 +588,11 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
     // per-vertex sums of weight * dL/dy on the dense levels
     float *G = reinterpret_cast<float *>((char *)workspace + b.G_off);
     const int Ld = b.dense.count, Lh = c->L - Ld;
-    const int grid_direct = b.grid.chunks == 1;
+    bool grid_direct = b.grid.chunks == 1;
+    if (b.binned) {
+        grid_direct = true;
+        for (int l = 0; l < Ld; ++l) grid_direct = grid_direct && b.grid_drain.subs[l] == 1;
+    }
     if (Ld > 0 && !grid_direct) {
         ZeroList z;
         z.add(G, (int64_t)b.dense_verts * 2);

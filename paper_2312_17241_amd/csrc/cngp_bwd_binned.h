@@ -34,7 +34,41 @@ struct BinParams {
     uint32_t rows_c_log2, slices_c;       // logit-gradient slices per level; slices_c = 0 when N_p = 1
     uint32_t chunks, chunk_pts;           // point chunks of count / scatter
     uint32_t cap;                         // records per level and role: N * 2^d
+    int32_t  dense_bins;                  // 1: the pre-reduced coarse levels are binned too, by slice of their vertex grid
 };
+
+// Bins of a pre-reduced level: slices of kDenseSliceVerts vertices of its dense grid; every level is given
+// kGridBins of them (the largest grid that is pre-reduced has that many).
+constexpr uint32_t kGridBins = 32;
+
+// Bin of a vertex; the clamp only matters for coordinates outside [0,1]^d, which are invalid input but must not fault.
+__device__ __forceinline__ uint32_t grid_bin(const uint32_t v) {
+    const uint32_t s = v / kDenseSliceVerts;
+    return s < kGridBins ? s : kGridBins - 1u;
+}
+
+// Vertex numbers (dimension 0 fastest) of the 2^d corners of the cell x lies in, on a grid of `side` vertices per axis.
+template <int D>
+__device__ __forceinline__ void corner_vertices(const float (&xp)[D], const float res, const uint32_t side, uint32_t (&v)[1 << D]) {
+    uint32_t base = 0, stride = 1, step[D];
+    {
+#pragma clang fp contract(off)
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            const float pos = xp[i] * res;                  // one rounded fp32 multiply
+            base += (uint32_t)floorf(pos) * stride;
+            step[i] = stride;
+            stride *= side;
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < (1 << D); ++c) {
+        uint32_t t = base;
+#pragma unroll
+        for (int i = 0; i < D; ++i) t += ((c >> i) & 1) ? step[i] : 0u;
+        v[c] = t;
+    }
+}
 
 // Slice of the feature table (role 0) / confidence table (role 1) a corner's hashes select.
 template <int D>
@@ -43,19 +77,39 @@ __device__ __forceinline__ void corner_rows(const Cell<D> &cell, const Params &p
     h2 = cell.hash2(c) & p.c_mask;
 }
 
+// Workgroups [0, nlevels * chunks) count the hashed levels; with dense_bins the next level0 * chunks ones
+// count the pre-reduced levels 0 .. level0 - 1 by slice of their vertex grid.
 template <int D>
 __global__ __launch_bounds__(256) void bin_count_kernel(
-    const Params p, const BinParams bp, const float *__restrict__ x, const int64_t N,
-    uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC)
+    const Params p, const BinParams bp, const DenseLevels dl, const float *__restrict__ x, const int64_t N,
+    uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC, uint32_t *__restrict__ cntG)
 {
-    extern __shared__ uint32_t hist[];                      // [slices_f + slices_c]
+    extern __shared__ uint32_t hist[];                      // [max(slices_f + slices_c, kGridBins)]
     const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
+    const int64_t n0 = (int64_t)chunk * bp.chunk_pts;
+    const int64_t n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
+    if (li >= (uint32_t)bp.nlevels) {                       // a pre-reduced level
+        const uint32_t ld = li - (uint32_t)bp.nlevels;
+        for (uint32_t i = threadIdx.x; i < kGridBins; i += blockDim.x) hist[i] = 0u;
+        __syncthreads();
+        for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
+            float xp[D];
+#pragma unroll
+            for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
+            uint32_t v[1 << D];
+            corner_vertices<D>(xp, (float)p.N_l[ld], dl.side[ld], v);
+#pragma unroll
+            for (int c = 0; c < (1 << D); ++c) atomicAdd(&hist[grid_bin(v[c])], 1u);
+        }
+        __syncthreads();
+        uint32_t *rowG = cntG + ((size_t)ld * bp.chunks + chunk) * kGridBins;
+        for (uint32_t s = threadIdx.x; s < kGridBins; s += blockDim.x) rowG[s] = hist[s];
+        return;
+    }
     const int      l = bp.level0 + (int)li;
     const uint32_t bins = bp.slices_f + bp.slices_c;
     for (uint32_t i = threadIdx.x; i < bins; i += blockDim.x) hist[i] = 0u;
     __syncthreads();
-    const int64_t n0 = (int64_t)chunk * bp.chunk_pts;
-    const int64_t n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
     for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
         float xp[D];
 #pragma unroll
@@ -87,17 +141,19 @@ constexpr int kOffsetsBlock = 256;
 // matrix when it fits (the scans then run in LDS; through memory they are chains of dependent loads).
 // Threads form a [segment][slice] array: a thread owns one slice's counts of a run of chunks.
 __global__ __launch_bounds__(kOffsetsBlock) void bin_offsets_kernel(
-    const BinParams bp, uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC,
-    uint32_t *__restrict__ baseF, uint32_t *__restrict__ baseC, const uint32_t lds_words)
+    const BinParams bp, uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC, uint32_t *__restrict__ cntG,
+    uint32_t *__restrict__ baseF, uint32_t *__restrict__ baseC, uint32_t *__restrict__ baseG, const uint32_t lds_words)
 {
     extern __shared__ uint32_t mat[];
     __shared__ uint32_t part[kOffsetsBlock];                // [segment][slice lane]: sum of the thread's run
     __shared__ uint32_t carry;                              // records of the slices handled in earlier rounds
-    const uint32_t li = blockIdx.x >> 1, role = blockIdx.x & 1u;
-    const uint32_t slices = role ? bp.slices_c : bp.slices_f;
+    // workgroups 0 .. 2 nlevels - 1: (hashed level, table); then one per pre-reduced level
+    const bool     dense = blockIdx.x >= 2u * (uint32_t)bp.nlevels;
+    const uint32_t li = dense ? blockIdx.x - 2u * (uint32_t)bp.nlevels : blockIdx.x >> 1, role = blockIdx.x & 1u;
+    const uint32_t slices = dense ? kGridBins : role ? bp.slices_c : bp.slices_f;
     if (slices == 0) return;
-    uint32_t *gcnt = (role ? cntC : cntF) + (size_t)li * bp.chunks * slices;
-    uint32_t *base = (role ? baseC : baseF) + (size_t)li * (slices + 1);
+    uint32_t *gcnt = (dense ? cntG : role ? cntC : cntF) + (size_t)li * bp.chunks * slices;
+    uint32_t *base = (dense ? baseG : role ? baseC : baseF) + (size_t)li * (slices + 1);
     const uint32_t elems = bp.chunks * slices;
     const bool     in_lds = elems <= lds_words;
     uint32_t      *cnt = in_lds ? mat : gcnt;
@@ -152,12 +208,34 @@ __global__ __launch_bounds__(kOffsetsBlock) void bin_offsets_kernel(
 // Scatter, one workgroup per (level, chunk).
 template <int D>
 __global__ __launch_bounds__(256) void bin_scatter_kernel(
-    const Params p, const BinParams bp, const float *__restrict__ x, const int64_t N,
-    const uint32_t *__restrict__ cntF, const uint32_t *__restrict__ cntC,
-    uint2 *__restrict__ recF, uint2 *__restrict__ recC)
+    const Params p, const BinParams bp, const DenseLevels dl, const float *__restrict__ x, const int64_t N,
+    const uint32_t *__restrict__ cntF, const uint32_t *__restrict__ cntC, const uint32_t *__restrict__ cntG,
+    uint2 *__restrict__ recF, uint2 *__restrict__ recC, uint2 *__restrict__ recG)
 {
-    extern __shared__ uint32_t cursor[];                    // [slices_f + slices_c]
+    extern __shared__ uint32_t cursor[];                    // [max(slices_f + slices_c, kGridBins)]
     const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
+    if (li >= (uint32_t)bp.nlevels) {                       // a pre-reduced level: record = { vertex inside its slice, reference }
+        const uint32_t ld = li - (uint32_t)bp.nlevels;
+        const uint32_t *rowG = cntG + ((size_t)ld * bp.chunks + chunk) * kGridBins;
+        for (uint32_t s = threadIdx.x; s < kGridBins; s += blockDim.x) cursor[s] = rowG[s];
+        __syncthreads();
+        uint2 *outG = recG + (size_t)ld * bp.cap;
+        const int64_t m0 = (int64_t)chunk * bp.chunk_pts;
+        const int64_t m1 = (m0 + bp.chunk_pts < N) ? m0 + bp.chunk_pts : N;
+        for (int64_t n = m0 + threadIdx.x; n < m1; n += blockDim.x) {
+            float xp[D];
+#pragma unroll
+            for (int j = 0; j < D; ++j) xp[j] = x[n * D + j];
+            uint32_t v[1 << D];
+            corner_vertices<D>(xp, (float)p.N_l[ld], dl.side[ld], v);
+#pragma unroll
+            for (int c = 0; c < (1 << D); ++c) {
+                const uint32_t pos = atomicAdd(&cursor[grid_bin(v[c])], 1u);
+                outG[pos] = make_uint2(v[c] % kDenseSliceVerts, ((uint32_t)n << D) | (uint32_t)c);
+            }
+        }
+        return;
+    }
     const int      l = bp.level0 + (int)li;
     const uint32_t *rowF = cntF + ((size_t)li * bp.chunks + chunk) * bp.slices_f;
     for (uint32_t s = threadIdx.x; s < bp.slices_f; s += blockDim.x) cursor[s] = rowF[s];
@@ -319,6 +397,84 @@ __device__ __forceinline__ void bin_range(const uint32_t *__restrict__ base, con
     const uint32_t  b0 = b[slice], n = b[slice + 1] - b0;
     beg = b0 + (uint32_t)(((uint64_t)n * sub) / subs);
     end = b0 + (uint32_t)(((uint64_t)n * (sub + 1)) / subs);
+}
+
+// ------------------------------------------------------------------ vertex-grid sums from binned references
+// G[l][v][f] = sum over the corner references to vertex v of pre-reduced level l of weight * dL/dy (what
+// bwd_vertex_grid computes by scanning all points once per slice of the grid).  A workgroup owns the slice
+// of one level's grid as fp64 accumulators in LDS and part `sub` of the slice's bin; every lane works on
+// a record of its own: no gathers of table rows here, two LDS atomics per reference.
+struct GridDrainPlan {
+    uint32_t first[kMaxDense + 1];        // first workgroup of each pre-reduced level; [count] = grid size
+    uint32_t subs[kMaxDense];             // workgroups per slice of the level's grid
+};
+
+template <int D, typename IoT>
+__global__ __launch_bounds__(kSlicedBlock) void bin_grid_drain_kernel(
+    const Params p, const DenseLevels dl, const GridDrainPlan gp, const float *__restrict__ x,
+    const IoT *__restrict__ dyT, const int64_t N, const uint2 *__restrict__ recG,
+    const uint32_t *__restrict__ baseG, const uint32_t cap, float *__restrict__ G)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *acc = reinterpret_cast<double *>(smem);
+    int ld = 0;
+    while (ld < dl.count - 1 && blockIdx.x >= gp.first[ld + 1]) ++ld;
+    const uint32_t wg = blockIdx.x - gp.first[ld], subs = gp.subs[ld];
+    const uint32_t slice = wg / subs, sub = wg % subs;
+    const uint32_t first = slice * kDenseSliceVerts;
+    const uint32_t count = dl.verts[ld] - first < kDenseSliceVerts ? dl.verts[ld] - first : kDenseSliceVerts;
+    for (uint32_t i = threadIdx.x; i < count * 2; i += kSlicedBlock) acc[i] = 0.0;
+    __syncthreads();
+
+    uint32_t beg, end;
+    bin_range(baseG, kGridBins, (uint32_t)ld, slice, sub, subs, beg, end);
+    if (beg < end) {
+        using Pair = typename std::conditional<sizeof(IoT) == 2, uint32_t, float2>::type;
+        const uint2   *rec = recG + (size_t)ld * cap;
+        const Pair    *dy_l = reinterpret_cast<const Pair *>(dyT + (size_t)ld * N * 2);
+        const float    res = (float)p.N_l[ld];
+        const uint32_t last = end - 1u;
+        struct Point { float xp[D]; Pair y; };
+        auto record = [&](const uint32_t i) { return rec[i < last ? i : last]; };
+        auto point = [&](const uint2 q) {
+            Point pt;
+            const uint32_t n = q.y >> D;
+#pragma unroll
+            for (int j = 0; j < D; ++j) pt.xp[j] = x[(size_t)n * D + j];
+            pt.y = dy_l[n];
+            return pt;
+        };
+        // record loads run two steps ahead, the point and gradient they name one step ahead
+        uint32_t i = beg + threadIdx.x;
+        uint2 q0 = record(i), q1 = record(i + kSlicedBlock);
+        Point p0 = point(q0);
+        for (; i < end; i += kSlicedBlock) {
+            const uint2 q2 = record(i + 2 * kSlicedBlock);
+            const Point p1 = point(q1);
+            const uint32_t c = q0.y & ((1u << D) - 1u);
+            float wt = 1.0f;
+            {
+#pragma clang fp contract(off)
+#pragma unroll
+                for (int j = 0; j < D; ++j) {
+                    const float pos = p0.xp[j] * res;       // one rounded fp32 multiply
+                    const float w = pos - floorf(pos);
+                    wt *= ((c >> j) & 1u) ? w : 1.0f - w;
+                }
+            }
+            const float2 g = pair_to_float2(p0.y);
+            atomicAdd(acc + 2 * q0.x, (double)(wt * g.x));
+            atomicAdd(acc + 2 * q0.x + 1, (double)(wt * g.y));
+            q0 = q1; q1 = q2; p0 = p1;
+        }
+    }
+    __syncthreads();
+    float *out = G + ((size_t)dl.g_off[ld] + first) * 2;
+    for (uint32_t i = threadIdx.x; i < count * 2; i += kSlicedBlock) {
+        const float v = (float)acc[i];
+        if (subs == 1) out[i] = v;
+        else if (v != 0.0f) atomic_add(out + i, v);
+    }
 }
 
 // sp: rows_log2, slices, chunks (= drain workgroups per bin), store_direct, level0, nlevels as in the sliced variant.
