@@ -181,7 +181,7 @@ def test_backward_parity_sweep(d, N_p, feat, io):
     check_bwd(w, x, D_f, Dhat, dy)
 
 
-@pytest.mark.parametrize("path", ["direct", "sliced", "sliced_nopre"])
+@pytest.mark.parametrize("path", ["direct", "sliced", "sliced_nopre", "binned", "binned_nopre"])
 def test_backward_accumulates_without_zero_flag(path):
     w = sweep_workload(3, 4, "f32", "f32", N=500)
     x, D_f, Dhat, dy = tables(w)
@@ -197,7 +197,21 @@ def test_sliced_backward_many_chunks_and_slices():
                  feat_dtype="f16", io_dtype="f16")
     x, D_f, Dhat, dy = tables(w)
     D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
-    check_bwd(w, x, D_f, Dhat, dy, paths=("sliced", "sliced_nopre", "auto"))
+    check_bwd(w, x, D_f, Dhat, dy, paths=("sliced", "sliced_nopre", "auto", "binned", "binned_nopre"))
+
+
+def test_binned_backward_tables_of_a_thousand_slices():
+    """An index codebook of 2^20 rows per level (the upper end of the paper's N_c sweeps) makes 1024 slices of the
+    logit gradient: far too many to scan the points once per slice, so the library bins by itself; several point
+    chunks, several drain workgroups per bin of the (single-slice) feature table, two pre-reduced levels."""
+    w = W.custom(cfg=83, d=2, L=3, N_f=2**10, N_c=2**20, N_p=16, N_min=16, N_max=2048, N=300000 + 19,
+                 feat_dtype="f16", io_dtype="f16")
+    cfg = cngp.Config.from_workload(w)
+    plan = cngp.bwd_plan_info(cfg, w.N)
+    assert plan["binned"] == 1 and plan["slices_c"] == 1024 and plan["bin_chunks"] > 1 and plan["drain_wgs_feat"] > 1
+    x, D_f, Dhat, dy = tables(w)
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    check_bwd(w, x, D_f, Dhat, dy, paths=("auto", "binned_nopre"))
 
 
 @pytest.mark.parametrize("d", [2, 3])
