@@ -1,0 +1,57 @@
+"""The entry points only enqueue work on the caller's stream (no synchronisation, no allocation, no memset
+nodes), so a caller can capture a whole step into a HIP graph.  Captured here through torch.cuda.CUDAGraph
+and replayed several times with eager work and synchronisation in between; every replay is held against
+the oracle like an eager call."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2312_17241_amd as cngp
+import workloads as W
+from parity import check_close, check_exact
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+@pytest.mark.parametrize("flags,n", [(0, 40000 + 3), (cngp.BWD_BINNED, 40000 + 3), (cngp.BWD_DIRECT, 5000)])
+def test_graph_replay_matches_the_oracle(flags, n):
+    w = W.custom(cfg=91, d=3, L=6, N_f=2**13, N_c=2**11, N_p=8, N_min=8, N_max=256, N=n, feat_dtype="f16", io_dtype="f16")
+    cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS | flags)
+    x_h, D_f_h, Dhat_h, dy_h = W.make_points(w), W.make_feature_codebook(w), W.make_probe_logits(w), W.make_upstream_grad(w)
+    D_f_h = (D_f_h.astype(np.float64) * 1e4).astype(D_f_h.dtype)
+    x, D_f, Dhat, dy = (torch.from_numpy(a).to(DEV) for a in (x_h, D_f_h, Dhat_h, dy_h))
+    D_c = torch.empty((w.L, cfg.index_cols), dtype=torch.uint8, device=DEV)
+    y = torch.empty((n, w.L * w.F), dtype=torch.float16, device=DEV)
+    gF = torch.empty((w.L, w.N_f, w.F), device=DEV)
+    gC = torch.empty((w.L, w.N_c, w.N_p), device=DEV)
+    ws = cngp.alloc_workspace(cfg, n, DEV)
+
+    def step():
+        cngp.bake_probes(cfg, Dhat, D_c)
+        cngp.encode_fwd(cfg, x, D_f, D_c, y, workspace=ws)
+        cngp.encode_bwd(cfg, x, D_f, Dhat, dy, gF, gC, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                              # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+
+    D_c_ref = oracle.bake_probes(Dhat_h)
+    y_ref, ymag = oracle.encode_fwd(w, x_h, D_f_h, D_c_ref)
+    gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x_h, D_f_h, Dhat_h, dy_h)
+    for replay in range(3):
+        D_c.fill_(0xEE); y.fill_(float("nan")); gF.fill_(float("nan")); gC.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        check_exact(f"D_c, replay {replay}", D_c.cpu().numpy(), D_c_ref)
+        check_close(f"y, replay {replay}", y.float().cpu().numpy(), y_ref, ymag, fp16_out=True)
+        check_close(f"grad D_f, replay {replay}", gF.cpu().numpy(), gF_ref, A_f, fp16_out=False)
+        check_close(f"grad Dhat_c, replay {replay}", gC.cpu().numpy(), gC_ref, A_c, fp16_out=False)
+        step()                                              # eager work between the replays
+        (gF.sum() + gC.sum()).item()
