@@ -19,8 +19,8 @@
 //
 // Coarse levels are pre-reduced per grid vertex.  The backward pass is linear in g = weight * dL/dy
 // of a corner reference, and both hashes depend on the vertex only, so all references to one vertex
-// can be summed first: a third kernel accumulates G[v] = sum of g over the references to vertex v
-// into the level's dense vertex grid (LDS slices again, no hashing), and the two kernels above then
+// can be summed first: a further role accumulates G[v] = sum of g over the references to vertex v
+// into the level's dense vertex grid (LDS slices again, no hashing), and the two roles above then
 // scan the grid's vertices (one "corner" of weight 1 with g = G[v]) instead of the points.  A level
 // with few vertices and many points (2M references onto 5832 vertices on the coarsest NeRF level)
 // costs almost nothing this way.
