@@ -515,7 +515,8 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     {
         {
             LaunchTimer t(s, K_BWD_BIN_COUNT);
-            bin_count_kernel<D><<<(unsigned)blocks, bin_block, lds_bins, s>>>(p, bp, b.dense, x, N, cntF, cntC, cntG);
+            const uint32_t reps = most_bins <= 64 ? 16u : most_bins <= 512 ? 4u : 1u;      // copies of the histogram
+            bin_count_kernel<D><<<(unsigned)blocks, bin_block, lds_bins * reps, s>>>(p, bp, b.dense, x, N, cntF, cntC, cntG, reps);
             if (int rc = launch_status("bin_count_kernel")) return rc;
         }
         LaunchTimer t(s, K_BWD_BIN_OFFSETS);

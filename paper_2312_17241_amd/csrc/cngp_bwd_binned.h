@@ -82,15 +82,16 @@ __device__ __forceinline__ void corner_rows(const Cell<D> &cell, const Params &p
 template <int D>
 __global__ __launch_bounds__(256) void bin_count_kernel(
     const Params p, const BinParams bp, const DenseLevels dl, const float *__restrict__ x, const int64_t N,
-    uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC, uint32_t *__restrict__ cntG)
+    uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC, uint32_t *__restrict__ cntG, const uint32_t hist_replicas)
 {
-    extern __shared__ uint32_t hist[];                      // [max(slices_f + slices_c, kGridBins)]
+    extern __shared__ uint32_t hist[];                      // [hist_replicas][max(slices_f + slices_c, kGridBins)]
     const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
     const int64_t n0 = (int64_t)chunk * bp.chunk_pts;
     const int64_t n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
     if (li >= (uint32_t)bp.nlevels) {                       // a pre-reduced level
         const uint32_t ld = li - (uint32_t)bp.nlevels;
-        for (uint32_t i = threadIdx.x; i < kGridBins; i += blockDim.x) hist[i] = 0u;
+        uint32_t *own = hist + (threadIdx.x % hist_replicas) * kGridBins;
+        for (uint32_t i = threadIdx.x; i < kGridBins * hist_replicas; i += blockDim.x) hist[i] = 0u;
         __syncthreads();
         for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
             float xp[D];
@@ -99,16 +100,24 @@ __global__ __launch_bounds__(256) void bin_count_kernel(
             uint32_t v[1 << D];
             corner_vertices<D>(xp, (float)p.N_l[ld], dl.side[ld], v);
 #pragma unroll
-            for (int c = 0; c < (1 << D); ++c) atomicAdd(&hist[grid_bin(v[c])], 1u);
+            for (int c = 0; c < (1 << D); ++c) atomicAdd(&own[grid_bin(v[c])], 1u);
         }
         __syncthreads();
         uint32_t *rowG = cntG + ((size_t)ld * bp.chunks + chunk) * kGridBins;
-        for (uint32_t s = threadIdx.x; s < kGridBins; s += blockDim.x) rowG[s] = hist[s];
+        for (uint32_t s = threadIdx.x; s < kGridBins; s += blockDim.x) {
+            uint32_t total = 0;
+            for (uint32_t r = 0; r < hist_replicas; ++r) total += hist[r * kGridBins + s];
+            rowG[s] = total;
+        }
         return;
     }
     const int      l = bp.level0 + (int)li;
     const uint32_t bins = bp.slices_f + bp.slices_c;
-    for (uint32_t i = threadIdx.x; i < bins; i += blockDim.x) hist[i] = 0u;
+    // `reps` copies of the histogram, picked by lane: 64 lanes adding to a handful of counters would
+    // otherwise serialise on the same LDS addresses (the atomics were the whole cost of this kernel)
+    const uint32_t reps = hist_replicas;
+    uint32_t *mine = hist + (threadIdx.x % reps) * bins;
+    for (uint32_t i = threadIdx.x; i < bins * reps; i += blockDim.x) hist[i] = 0u;
     __syncthreads();
     for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
         float xp[D];
@@ -120,16 +129,18 @@ __global__ __launch_bounds__(256) void bin_count_kernel(
         for (int c = 0; c < (1 << D); ++c) {
             uint32_t h1, h2;
             corner_rows<D>(cell, p, c, h1, h2);
-            atomicAdd(&hist[h1 >> bp.rows_f_log2], 1u);
-            if (bp.slices_c) atomicAdd(&hist[bp.slices_f + (h2 >> bp.rows_c_log2)], 1u);
+            atomicAdd(&mine[h1 >> bp.rows_f_log2], 1u);
+            if (bp.slices_c) atomicAdd(&mine[bp.slices_f + (h2 >> bp.rows_c_log2)], 1u);
         }
     }
     __syncthreads();
     uint32_t *rowF = cntF + ((size_t)li * bp.chunks + chunk) * bp.slices_f;
-    for (uint32_t s = threadIdx.x; s < bp.slices_f; s += blockDim.x) rowF[s] = hist[s];
-    if (bp.slices_c) {
-        uint32_t *rowC = cntC + ((size_t)li * bp.chunks + chunk) * bp.slices_c;
-        for (uint32_t s = threadIdx.x; s < bp.slices_c; s += blockDim.x) rowC[s] = hist[bp.slices_f + s];
+    uint32_t *rowC = cntC + ((size_t)li * bp.chunks + chunk) * bp.slices_c;
+    for (uint32_t s = threadIdx.x; s < bins; s += blockDim.x) {
+        uint32_t total = 0;
+        for (uint32_t r = 0; r < reps; ++r) total += hist[r * bins + s];
+        if (s < bp.slices_f) rowF[s] = total;
+        else rowC[s - bp.slices_f] = total;
     }
 }
 
