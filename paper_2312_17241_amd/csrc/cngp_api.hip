@@ -88,12 +88,12 @@ bool index_codebook_is_empty(const cngp_config *c) { return c->index_format == C
 int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INVALID : CNGP_OK; }
 
 // ---------------------------------------------------------------- per-kernel timing
-enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_SOFTMAX, K_BWD_TRANSPOSE, K_BWD_SLICED, K_BWD_SLICED_V,
+enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_PREP, K_BWD_SLICED, K_BWD_SLICED_V, K_BWD_GRID_DRAIN,
                 K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD,
                 K_BWD_BIN_COUNT, K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_COUNT };
-const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_softmax_table",
-                                           "encode_bwd_transpose_dy", "encode_bwd_sliced_points_and_grid",
-                                           "encode_bwd_sliced_vertices", "bake_probes", "zero", "debug_indices",
+const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_prepare",
+                                           "encode_bwd_sliced_points_and_grid", "encode_bwd_sliced_vertices",
+                                           "encode_bwd_bin_grid_sums", "bake_probes", "zero", "debug_indices",
                                            "adam_step_bake", "mlp_fwd", "mlp_bwd",
                                            "encode_bwd_bin_count", "encode_bwd_bin_offsets", "encode_bwd_bin_scatter",
                                            "encode_bwd_bin_drain"};
@@ -462,25 +462,6 @@ BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
     return last_plan;
 }
 
-template <int NP>
-int launch_softmax_table(const cngp_config *c, const float *Dhat_c, float *sigma, hipStream_t s) {
-    const int64_t elems = (int64_t)c->L * c->N_c * NP;
-    const int64_t blocks = (elems + kBlock - 1) / kBlock;
-    if (int rc = check_blocks(blocks)) return rc;
-    LaunchTimer t(s, K_BWD_SOFTMAX);
-    softmax_table_kernel<NP><<<(unsigned)blocks, kBlock, 0, s>>>(Dhat_c, sigma, elems);
-    return launch_status("softmax_table_kernel");
-}
-
-template <typename PairT>
-int launch_transpose_dy(const cngp_config *c, const void *dy, void *dyT, int64_t N, hipStream_t s) {
-    const int64_t blocks = (N + kBlock - 1) / kBlock;
-    if (int rc = check_blocks(blocks)) return rc;
-    LaunchTimer t(s, K_BWD_TRANSPOSE);
-    transpose_dy_kernel<PairT><<<(unsigned)blocks, kBlock, 0, s>>>((const PairT *)dy, (PairT *)dyT, N, c->L);
-    return launch_status("transpose_dy_kernel");
-}
-
 // Binned variant: count, offsets, scatter (+ vertex-grid accumulation of the dense levels), drain
 // (+ the two roles of the dense levels, which scan the finished vertex grids).
 template <int D, int NP, typename FeatT, typename IoT>
@@ -537,7 +518,7 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
         auto kernel = bin_grid_drain_kernel<D, IoT>;
         const size_t lds_grid = (size_t)kDenseSliceVerts * 2 * sizeof(double);
         if (int rc = allow_big_lds(kernel, lds_grid)) return rc;
-        LaunchTimer t(s, K_BWD_SLICED);
+        LaunchTimer t(s, K_BWD_GRID_DRAIN);
         kernel<<<b.grid_drain.first[Ld], kSlicedBlock, lds_grid, s>>>(p, b.dense, b.grid_drain, x, dyT, N, recG, baseG, bp.cap, G);
         if (int rc = launch_status("bin_grid_drain_kernel")) return rc;
     }
@@ -578,14 +559,9 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
 template <int D, int NP, typename FeatT, typename IoT>
 int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, const float *x, int64_t N,
                       const void *D_f, const float *Dhat_c, const void *dy, float *gD_f, float *gDhat_c,
-                      void *workspace, hipStream_t s) {
+                      void *workspace, ZeroList &zero, hipStream_t s) {
     float *sigma = reinterpret_cast<float *>((char *)workspace + b.sigma_off);
     IoT   *dyT = reinterpret_cast<IoT *>((char *)workspace + b.dyT_off);
-    if (NP > 1)
-        if (int rc = launch_softmax_table<NP>(c, Dhat_c, sigma, s)) return rc;
-    using PairT = typename std::conditional<sizeof(IoT) == 2, uint32_t, float2>::type;
-    if (int rc = launch_transpose_dy<PairT>(c, dy, dyT, N, s)) return rc;
-
     // per-vertex sums of weight * dL/dy on the dense levels
     float *G = reinterpret_cast<float *>((char *)workspace + b.G_off);
     const int Ld = b.dense.count, Lh = c->L - Ld;
@@ -594,10 +570,24 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
         grid_direct = true;
         for (int l = 0; l < Ld; ++l) grid_direct = grid_direct && b.grid_drain.subs[l] == 1;
     }
-    if (Ld > 0 && !grid_direct) {
-        ZeroList z;
-        z.add(G, (int64_t)b.dense_verts * 2);
-        if (int rc = z.launch(s)) return rc;
+    if (Ld > 0 && !grid_direct) zero.add(G, (int64_t)b.dense_verts * 2);
+    {   // one launch: clear what is accumulated with atomics, softmax table, level-major dL/dy
+        using PairT = typename std::conditional<sizeof(IoT) == 2, uint32_t, float2>::type;
+        const int64_t elems = NP > 1 ? (int64_t)c->L * c->N_c * NP : 0;
+        const int64_t softmax_blocks = (elems + kBlock - 1) / kBlock;
+        const int64_t transpose_blocks = (N + kBlock - 1) / kBlock;
+        int64_t zero_blocks = (zero.largest / 4 + kBlock - 1) / kBlock;
+        if (zero_blocks > 1024) zero_blocks = 1024;
+        if (zero_blocks < 1) zero_blocks = 1;
+        const int64_t blocks = (int64_t)zero.n * zero_blocks + softmax_blocks + transpose_blocks;
+        if (int rc = check_blocks(blocks)) return rc;
+        LaunchTimer t(s, K_BWD_PREP);
+        bwd_prep_kernel<NP, PairT><<<(unsigned)blocks, kBlock, 0, s>>>(
+            zero.seg, (uint32_t)zero.n, (uint32_t)zero_blocks, Dhat_c, sigma, elems, (uint32_t)softmax_blocks,
+            (const PairT *)dy, (PairT *)dyT, N, c->L);
+        zero.n = 0;
+        zero.largest = 0;
+        if (int rc = launch_status("bwd_prep_kernel")) return rc;
     }
 
     if (b.binned)
@@ -652,10 +642,11 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
 template <int D, typename FeatT, typename IoT>
 int dispatch_bwd_np(const cngp_config *c, const Params &p, const BwdPlan &b, const float *x, int64_t N,
                     const void *D_f, const float *Dhat_c, const void *dy, float *gD_f, float *gDhat_c,
-                    void *workspace, hipStream_t s) {
+                    void *workspace, ZeroList &zero, hipStream_t s) {
 #define CNGP_BWD_CASE(NP)                                                                                        \
-    return b.sliced ? launch_bwd_sliced<D, NP, FeatT, IoT>(c, p, b, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, workspace, s) \
-                    : launch_bwd_direct<D, NP, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s)
+    if (b.sliced) return launch_bwd_sliced<D, NP, FeatT, IoT>(c, p, b, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, workspace, zero, s); \
+    if (int rc = zero.launch(s)) return rc;                                                                         \
+    return launch_bwd_direct<D, NP, FeatT, IoT>(c, p, 0, c->L, x, N, D_f, Dhat_c, dy, gD_f, gDhat_c, s)
     switch (c->N_p) {
     case 1:  CNGP_BWD_CASE(1);
     case 2:  CNGP_BWD_CASE(2);
@@ -771,22 +762,22 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     }
     // A sliced launch with a single chunk writes every gradient entry of its levels itself; the other
     // level ranges (dense levels 0 .. Ld-1, hashed levels Ld .. L-1) are cleared here.
+    ZeroList z;
     if (cfg->flags & CNGP_ZERO_GRADS) {
         const int64_t per_f = (int64_t)cfg->N_f * cfg->F, per_c = (int64_t)cfg->N_c * cfg->N_p;
         const bool    sl = N > 0 && b.sliced;
         const int     Ld = sl ? b.dense.count : 0, Lh = cfg->L - Ld;
-        ZeroList z;
         if (!(sl && b.feat_vtx.chunks == 1) && Ld > 0) z.add(grad_D_f, per_f * Ld);
         const uint32_t wg_f = b.binned ? b.subs_f : b.feat_pts.chunks, wg_c = b.binned ? b.subs_c : b.logit_pts.chunks;
         if (!(sl && wg_f == 1) && Lh > 0) z.add(grad_D_f + per_f * Ld, per_f * Lh);
         const bool logit = sl && cfg->N_p > 1;
         if (!(logit && b.logit_vtx.chunks == 1) && Ld > 0) z.add(grad_Dhat_c, per_c * Ld);
         if (!(logit && wg_c == 1) && Lh > 0) z.add(grad_Dhat_c + per_c * Ld, per_c * Lh);
-        if (int rc = z.launch(s)) return rc;
     }
-    if (N == 0) return CNGP_OK;
+    if (N == 0) return z.launch(s);
     const Params p = make_params(cfg);
-    CNGP_DISPATCH_TYPES(dispatch_bwd_np, cfg, p, b, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, workspace, s);
+    // the LDS variants clear these ranges in their preparation launch, the direct one with a launch of its own
+    CNGP_DISPATCH_TYPES(dispatch_bwd_np, cfg, p, b, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, workspace, z, s);
 }
 
 int cngp_storage_bytes(const cngp_config *cfg, size_t *D_f_bytes, size_t *D_c_level_bytes, size_t *D_c_bytes) {

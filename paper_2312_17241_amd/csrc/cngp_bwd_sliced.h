@@ -14,8 +14,8 @@
 //   logit gradient    Q[h2][k] += <D_f[base + k], g>, then per row          slice = range of D^_c rows
 //                     grad_Dhat_c[h2][k] += sigma_k * (Q_k - sum_j sigma_j Q_j)
 // (the softmax Jacobian is linear in Q, so it is applied once per row when the slice is flushed).
-// Both read a softmax table sigma = softmax(D^_c) and a level-major copy of dL/dy that two
-// small kernels prepare in the workspace.
+// Both read a softmax table sigma = softmax(D^_c) and a level-major copy of dL/dy that a
+// preparation launch writes into the workspace.
 //
 // Coarse levels are pre-reduced per grid vertex.  The backward pass is linear in g = weight * dL/dy
 // of a corner reference, and both hashes depend on the vertex only, so all references to one vertex
@@ -103,13 +103,13 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_wave_barrier();
 }
 
-// ------------------------------------------------------------------ preparation kernels
+// ------------------------------------------------------------------ preparation
 // sigma[r][k] = softmax(D^_c[r][:])_k, one lane per element, NP lanes per row.
 template <int NP>
-__global__ __launch_bounds__(kBlock) void softmax_table_kernel(const float *__restrict__ Dhat_c,
-                                                              float *__restrict__ sigma, const int64_t elems)
+__device__ __forceinline__ void softmax_rows(const float *__restrict__ Dhat_c, float *__restrict__ sigma,
+                                             const int64_t elems, const uint32_t block)
 {
-    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t i = (int64_t)block * kBlock + threadIdx.x;
     if (i >= elems) return;                       // elems is a multiple of NP: whole rows leave together
     const float v = Dhat_c[i];
     const float m = group_max<NP>(v);
@@ -119,12 +119,34 @@ __global__ __launch_bounds__(kBlock) void softmax_table_kernel(const float *__re
 
 // dyT[l][n] = dy[n][l] for the F = 2 pair of each level (PairT: 4 bytes for fp16, 8 for fp32).
 template <typename PairT>
-__global__ __launch_bounds__(kBlock) void transpose_dy_kernel(const PairT *__restrict__ dy, PairT *__restrict__ dyT,
-                                                             const int64_t N, const int L)
+__device__ __forceinline__ void transpose_rows(const PairT *__restrict__ dy, PairT *__restrict__ dyT,
+                                               const int64_t N, const int L, const uint32_t block)
 {
-    const int64_t n = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t n = (int64_t)block * kBlock + threadIdx.x;
     if (n >= N) return;
     for (int l = 0; l < L; ++l) dyT[(size_t)l * N + n] = dy[(size_t)n * L + l];
+}
+
+// Everything the accumulation kernels need first, in one launch: the gradient (and vertex-grid) ranges
+// that are accumulated with atomics are cleared, the softmax table and the level-major copy of dL/dy are
+// written.  Blocks [0, seg_count * zero_blocks) clear, the next softmax_blocks tabulate, the rest transpose.
+template <int NP, typename PairT>
+__global__ __launch_bounds__(kBlock) void bwd_prep_kernel(
+    const ZeroSegments seg, const uint32_t seg_count, const uint32_t zero_blocks,
+    const float *__restrict__ Dhat_c, float *__restrict__ sigma, const int64_t elems, const uint32_t softmax_blocks,
+    const PairT *__restrict__ dy, PairT *__restrict__ dyT, const int64_t N, const int L)
+{
+    uint32_t b = blockIdx.x;
+    if (b < seg_count * zero_blocks) {
+        zero_segment(seg, (int)(b / zero_blocks), b % zero_blocks, zero_blocks);
+        return;
+    }
+    b -= seg_count * zero_blocks;
+    if (b < softmax_blocks) {
+        softmax_rows<NP>(Dhat_c, sigma, elems, b);
+        return;
+    }
+    transpose_rows<PairT>(dy, dyT, N, L, b - softmax_blocks);
 }
 
 // ------------------------------------------------------------------ shared scan loop

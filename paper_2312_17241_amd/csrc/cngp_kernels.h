@@ -301,23 +301,29 @@ struct ZeroSegments {
     int64_t count[kZeroSegments];
 };
 
-__global__ __launch_bounds__(kBlock) void zero_kernel(const ZeroSegments seg)
+// Block `block` of `nblocks` clearing segment `which`.
+__device__ __forceinline__ void zero_segment(const ZeroSegments &seg, const int which, const uint32_t block, const uint32_t nblocks)
 {
-    float        *p = seg.ptr[blockIdx.y];
-    const int64_t n = seg.count[blockIdx.y];
+    float        *p = seg.ptr[which];
+    const int64_t n = seg.count[which];
     // scalar head up to 16-byte alignment, float4 body, scalar tail
     int64_t head = (int64_t)(((16u - ((uintptr_t)p & 15u)) & 15u) / 4u);
     if (head > n) head = n;
     const int64_t n4 = (n - head) / 4;
     float4       *p4 = reinterpret_cast<float4 *>(p + head);
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride)
+    const int64_t stride = (int64_t)nblocks * kBlock;
+    for (int64_t i = (int64_t)block * kBlock + threadIdx.x; i < n4; i += stride)
         p4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (blockIdx.x == 0) {
+    if (block == 0) {
         if ((int64_t)threadIdx.x < head) p[threadIdx.x] = 0.0f;
         const int64_t tail0 = head + n4 * 4;
         if (tail0 + threadIdx.x < n) p[tail0 + threadIdx.x] = 0.0f;
     }
+}
+
+__global__ __launch_bounds__(kBlock) void zero_kernel(const ZeroSegments seg)
+{
+    zero_segment(seg, (int)blockIdx.y, blockIdx.x, gridDim.x);
 }
 
 }  // namespace cngp
