@@ -241,6 +241,7 @@ struct BwdPlan {
     uint32_t dense_slices, dense_verts, dense_max_verts;
 };
 
+constexpr uint64_t kMaxAutoBinBytes = 8ull << 30;   // workspace the library asks for on its own initiative
 constexpr uint32_t kMinBinnedSlicesPerLevel = 24; // from here on binning the references beats the replicated scan
 constexpr uint32_t kMaxSlicesPerLevel = 128;   // beyond this the replicated scan costs more than global atomics
 constexpr int64_t  kMinSlicedRefs = 1 << 19;    // corner references (N * L * 2^d) below which launch overheads win
@@ -359,7 +360,9 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     const bool bin_ok = keys_fit && N > 0 && ((uint64_t)N << c->d) < (1ull << 31) &&
                         b.slices_f <= 8192 && b.slices_c <= 8192 &&
                         (uint64_t)c->N_c * c->N_p <= (1ull << 29) && c->N_f <= (1u << 28);
-    b.binned = bin_ok && enough && per_level >= kMinBinnedSlicesPerLevel;
+    // (the bins take 8 bytes per reference, level and table: not chosen unasked beyond kMaxAutoBinBytes)
+    const uint64_t bin_bytes = ((uint64_t)N << c->d) * 8u * (uint64_t)c->L * (c->N_p > 1 ? 2u : 1u);
+    b.binned = bin_ok && enough && per_level >= kMinBinnedSlicesPerLevel && bin_bytes <= kMaxAutoBinBytes;
     if (c->flags & CNGP_BWD_BINNED) b.binned = bin_ok;
     if (c->flags & (CNGP_BWD_DIRECT | CNGP_BWD_SLICED)) b.binned = false;
     if (b.binned) b.sliced = true;

@@ -176,6 +176,9 @@ def test_backward_plan_is_reported_on_the_host():
     assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_SLICED), w.N)["binned"] == 0
     im = W.WORKLOADS["image2d"]
     assert cngp.bwd_plan_info(cngp.Config.from_workload(im), im.N)["binned"] == 0      # ten slices: replicated scan
+    huge = cngp.Config.from_workload(w)                   # 2^25 points: the bins would take 64 GiB, so only on request
+    assert cngp.bwd_plan_info(huge, 2**25)["binned"] == 0 and cngp.workspace_bytes(huge, 2**25) < 8 << 30
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), 2**25)["binned"] == 1
     big = W.custom(d=3, L=16, N_f=2**24, N_c=2**24, N_p=2, N_min=16, N_max=2048, N=2**18)
     assert cngp.bwd_plan_info(cngp.Config.from_workload(big), big.N)["sliced"] == 0     # too many slices
 
