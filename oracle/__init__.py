@@ -97,6 +97,19 @@ def encode_fwd(w, x, D_f, D_c, res=None):
     return y, ymag
 
 
+def encode_bwd_input(w, x, D_f, D_c, dy, res=None):
+    """Gradient of the hard forward with respect to the points.  Returns (dL/dx, magnitude), float64 [N, d]."""
+    x = _x(w, x); res = _res(w, res)
+    N = x.shape[0]
+    D_f = _f64(D_f); assert D_f.shape == (w.L, w.N_f, w.F)
+    D_c = np.ascontiguousarray(D_c, dtype=np.uint8); assert D_c.shape == (w.L, w.N_c)
+    dy = _f64(dy); assert dy.shape == (N, w.L * w.F)
+    gx = np.zeros((N, w.d)); gmag = np.zeros((N, w.d))
+    lib().cngp_oracle_encode_bwd_input(w.d, w.L, w.F, _u32(w.N_f), _u32(w.N_c), _u32(w.N_p), _p(res),
+                                       _p(x), ctypes.c_int64(N), _p(D_f), _p(D_c), _p(dy), _p(gx), _p(gmag))
+    return gx, gmag
+
+
 def encode_soft_fwd(w, x, D_f, Dhat_c, res=None):
     """Softmax-relaxed forward (test helper): float64 [N, L*F]."""
     x = _x(w, x); res = _res(w, res)

@@ -263,3 +263,48 @@ void cngp_oracle_adam_step(int64_t n, double lr, double beta1, double beta2, dou
     }
 }
 
+/* Gradient of the hard forward with respect to the query points (the paper does not use it; it is what
+ * a caller needs for normals of a signed distance field or other losses on spatial derivatives).
+ * Inside a cell the feature index of Eq. 6 does not depend on x, so the derivative acts on the d-linear
+ * weights only: with frac_i = x_i N_l - floor(x_i N_l) and the corner offsets delta_i(c),
+ *     d weight_c / d x_j = N_l * (delta_j ? +1 : -1) * prod_{i != j} (delta_i ? frac_i : 1 - frac_i)
+ *     dL/dx_j[n] = sum_l sum_c  d weight_c / d x_j * < D_f[l][base_c + D_c[l][h2_c]], dL/dy[n, l, :] >
+ * (one-sided on a cell face: the cell is the one floor() selects).  gx, gmag are [N, d]; gmag sums the
+ * magnitudes of the terms. */
+void cngp_oracle_encode_bwd_input(int d, int L, int F, uint32_t N_f, uint32_t N_c, uint32_t N_p,
+                                  const uint32_t *N_l, const float *x, int64_t N,
+                                  const double *D_f, const uint8_t *D_c, const double *dy,
+                                  double *gx, double *gmag)
+{
+    const int C = 1 << d;
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int j = 0; j < d; ++j) { gx[n * d + j] = 0.0; if (gmag) gmag[n * d + j] = 0.0; }
+        for (int l = 0; l < L; ++l) {
+            double frac[8];
+            for (int i = 0; i < d; ++i) {
+                float pos = x[n * d + i] * (float)N_l[l];      /* R2: one fp32 multiply */
+                frac[i] = (double)(pos - floorf(pos));
+            }
+            for (int c = 0; c < C; ++c) {
+                corner_t k = corner_of(x + n * d, d, N_l[l], c, N_f, N_c, N_p);
+                uint32_t p = D_c[(int64_t)l * N_c + k.h2];
+                double t = 0.0, tm = 0.0;
+                for (int f = 0; f < F; ++f) {
+                    double feat = D_f[((int64_t)l * N_f + k.base + p) * F + f];
+                    double g = dy[n * (int64_t)(L * F) + l * F + f];
+                    t += feat * g;
+                    tm += fabs(feat * g);
+                }
+                for (int j = 0; j < d; ++j) {
+                    double dw = ((c >> j) & 1) ? 1.0 : -1.0;
+                    for (int i = 0; i < d; ++i)
+                        if (i != j) dw *= ((c >> i) & 1) ? frac[i] : 1.0 - frac[i];
+                    gx[n * d + j] += (double)N_l[l] * dw * t;
+                    if (gmag) gmag[n * d + j] += (double)N_l[l] * fabs(dw) * tm;
+                }
+            }
+        }
+    }
+}
+

@@ -484,6 +484,58 @@ def test_adam_matches_library_optimiser():
         assert np.allclose(th, par.detach().numpy(), rtol=1e-12, atol=1e-14)
 
 
+# --------------------------------------------------------------------------- gradient with respect to the points
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_input_gradient_is_the_derivative_of_the_pinned_forward(d):
+    """Central differences of the hard forward (pinned above by brute force) at points well inside their
+    cells on every level: the forward is d-linear there, so a small step stays exact up to rounding."""
+    w = small(d=d, L=3, N_min=3, N_max=19, N=400, N_f=256, N_c=64, N_p=8)
+    rng = np.random.default_rng(11)
+    x, D_f, Dhat, dy = random_tables(w, seed=5)
+    D_c = oracle.bake_probes(Dhat)
+    res = oracle.level_resolutions(w.N_min, w.N_max, w.L).astype(np.float64)
+    h = 1e-4
+    frac = (x[:, None, :].astype(np.float64) * res[None, :, None]) % 1.0
+    inside = ((frac > 0.05) & (frac < 0.95)).all(axis=(1, 2))
+    assert inside.sum() > 50
+    x = x[inside]
+    gx, gmag = oracle.encode_bwd_input(w, x, D_f, D_c, dy[inside])
+    for j in range(d):
+        e = np.zeros(d, np.float64); e[j] = h
+        up, _ = oracle.encode_fwd(w, (x.astype(np.float64) + e).astype(np.float32), D_f, D_c)
+        dn, _ = oracle.encode_fwd(w, (x.astype(np.float64) - e).astype(np.float32), D_f, D_c)
+        step = ((x.astype(np.float64) + e).astype(np.float32).astype(np.float64)
+                - (x.astype(np.float64) - e).astype(np.float32).astype(np.float64))[:, j]
+        fd = ((up - dn) * dy[inside]).sum(axis=1) / step
+        assert np.allclose(fd, gx[:, j], rtol=0, atol=2e-3 * gmag[:, j].max()), j
+    assert np.all(gmag >= np.abs(gx) - 1e-9)
+
+
+def test_input_gradient_closed_forms():
+    w = small(d=3, L=2, N_min=4, N_max=16, N=100)
+    x, D_f, Dhat, dy = random_tables(w, seed=8)
+    D_c = oracle.bake_probes(Dhat)
+    # a constant codebook interpolates to a constant: no gradient (the weights' derivatives sum to zero)
+    gx, _ = oracle.encode_bwd_input(w, x, np.full_like(D_f, 0.7), D_c, dy)
+    assert np.allclose(gx, 0.0, atol=1e-9)
+    # linear in dL/dy and in the features
+    g1, _ = oracle.encode_bwd_input(w, x, D_f, D_c, dy)
+    g2, _ = oracle.encode_bwd_input(w, x, 3.0 * D_f, D_c, -2.0 * dy)
+    assert np.allclose(g2, -6.0 * g1, rtol=1e-12, atol=1e-12)
+    # one level, d = 2, one output: the x-derivative is N_l * ((1 - fy) (f10 - f00) + fy (f11 - f01))
+    w1 = small(d=2, L=1, N_min=8, N_max=8, N=50)
+    x, D_f, Dhat, dy = random_tables(w1, seed=9)
+    D_c = oracle.bake_probes(Dhat)
+    dy[:, 1] = 0.0
+    *_, fidx = oracle.indices(w1, x, D_c)
+    f = D_f[0, fidx[:, 0, :], 0]                      # [N, 4 corners], corner c = (c & 1) + 2 * (c >> 1 & 1)
+    fy = (x[:, 1].astype(np.float32) * np.float32(8)).astype(np.float64) % 1.0
+    want = 8.0 * ((1 - fy) * (f[:, 1] - f[:, 0]) + fy * (f[:, 3] - f[:, 2])) * dy[:, 0]
+    got, _ = oracle.encode_bwd_input(w1, x, D_f, D_c, dy)
+    assert np.allclose(got[:, 0], want, rtol=1e-10, atol=1e-12)
+
+
 # --------------------------------------------------------------------------- decoder (assumed: 2 hidden ReLU layers)
 
 def _mlp_case(seed, N=50, n_in=16, n_out=3):
