@@ -132,6 +132,15 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N,
                     float *grad_D_f, float *grad_Dhat_c,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* Gradient with respect to the query points (not used by the paper; for losses on spatial derivatives such
+ * as the normals of a signed distance field).  Inside a cell the feature index of Eq. 6 is constant, so
+ * the derivative of the forward pass acts on the d-linear weights only:
+ *     grad_x[n][j] = sum_l N_l sum_c (+1 | -1)_j(c) prod_{i != j} w_i(c) <D_f[l][base_c + D_c[l][h2_c]], dL/dy[n, l, :]>
+ * one-sided on a cell face (the cell floor() selects).  Uses the baked D_c like the forward pass.
+ *   dy dev io_dtype [N, L*F];  grad_x dev float32 [N, d], written. */
+int cngp_encode_bwd_input(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const void *D_c,
+                          const void *dy, float *grad_x, void *stream);
+
 /* How cngp_encode_bwd would run for this configuration and N (host only; for tests, tuning and logs).
  * info (host, CNGP_PLAN_INFO_COUNT entries): [0] 1 = LDS-sliced variant, 0 = global atomics;
  * [1] number of coarse levels pre-reduced per grid vertex; [2], [3] slices per level of the feature and

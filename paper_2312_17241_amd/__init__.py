@@ -64,6 +64,8 @@ def _load():
     lib.cngp_encode_bwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cngp_bake_probes.restype = ctypes.c_int
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
+    lib.cngp_encode_bwd_input.restype = ctypes.c_int
+    lib.cngp_encode_bwd_input.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp]
     lib.cngp_mlp_weight_count.restype = ctypes.c_size_t
     lib.cngp_mlp_weight_count.argtypes = [vp]
     lib.cngp_mlp_fwd.restype = ctypes.c_int
@@ -240,6 +242,20 @@ def encode_bwd(cfg: Config, x, D_f, Dhat_c, dy, grad_D_f=None, grad_Dhat_c=None,
         _dev(grad_D_f, torch.float32, (cfg.L, cfg.N_f, cfg.F), "grad_D_f"),
         _dev(grad_Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "grad_Dhat_c"), wp, wb, _stream()))
     return grad_D_f, grad_Dhat_c
+
+
+def encode_bwd_input(cfg: Config, x, D_f, D_c, dy, grad_x=None):
+    """dL/dx of the forward pass: float32 [N, d]."""
+    N = x.shape[0]
+    if grad_x is None:
+        grad_x = torch.empty((N, cfg.d), dtype=torch.float32, device=x.device)
+    c = cfg.c()
+    _check(_lib.cngp_encode_bwd_input(
+        ctypes.byref(c), _dev(x, torch.float32, (N, cfg.d), "x"), N,
+        _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"), _dc(cfg, D_c),
+        _dev(dy, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "dy"),
+        _dev(grad_x, torch.float32, (N, cfg.d), "grad_x"), _stream()))
+    return grad_x
 
 
 def bake_probes(cfg: Config, Dhat_c, D_c=None):

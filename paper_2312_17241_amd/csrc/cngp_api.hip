@@ -90,13 +90,13 @@ int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INV
 // ---------------------------------------------------------------- per-kernel timing
 enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_PREP, K_BWD_SLICED, K_BWD_SLICED_V, K_BWD_GRID_DRAIN,
                 K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD,
-                K_BWD_BIN_COUNT, K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_COUNT };
+                K_BWD_BIN_COUNT, K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_prepare",
                                            "encode_bwd_sliced_points_and_grid", "encode_bwd_sliced_vertices",
                                            "encode_bwd_bin_grid_sums", "bake_probes", "zero", "debug_indices",
                                            "adam_step_bake", "mlp_fwd", "mlp_bwd",
                                            "encode_bwd_bin_count", "encode_bwd_bin_offsets", "encode_bwd_bin_scatter",
-                                           "encode_bwd_bin_drain"};
+                                           "encode_bwd_bin_drain", "encode_bwd_input"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -198,6 +198,34 @@ int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N,
     else CNGP_FWD_SIMPLE_LAUNCH(kFmtU8);
 #undef CNGP_FWD_SIMPLE_LAUNCH
     return launch_status("encode_fwd_kernel");
+}
+
+template <int D, typename FeatT, typename IoT>
+int launch_bwd_input(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
+                     const void *D_c, const void *dy, float *grad_x, hipStream_t s) {
+    const size_t c_stride = index_level_bytes(c);
+    const int    fmt = c->index_format;
+    const size_t lds = (((size_t)c->N_c + 1) / 2 + 15) & ~(size_t)15;
+    const bool   staged = lds <= 64 * 1024 && N >= kFwdTile;
+    const bool   large = staged && c_stride >= 8192 && N >= (int64_t)kFwdTileLarge * 1024;
+    const int    tile = large ? kFwdTileLarge : kFwdTile;
+    const int64_t blocks = (N + tile - 1) / tile;
+    if (int rc = check_blocks(blocks)) return rc;
+    const int vec = (c_stride % 16 == 0 && ((uintptr_t)D_c & 15u) == 0) ? 1 : 0;
+    LaunchTimer t(s, K_BWD_INPUT);
+#define CNGP_BWD_INPUT(FMT, TILE, STAGED)                                                                   \
+    encode_bwd_input_kernel<D, FeatT, IoT, FMT, TILE, STAGED><<<(unsigned)blocks, TILE, STAGED ? lds : 0, s>>>( \
+        p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (const IoT *)dy, grad_x, N, (uint32_t)c_stride, vec)
+#define CNGP_BWD_INPUT_FMT(FMT)                                                                             \
+    if (!staged) CNGP_BWD_INPUT(FMT, kFwdTile, false);                                                      \
+    else if (large) CNGP_BWD_INPUT(FMT, kFwdTileLarge, true);                                               \
+    else CNGP_BWD_INPUT(FMT, kFwdTile, true)
+    if (fmt == CNGP_IDX_PACKED4) { CNGP_BWD_INPUT_FMT(kFmtPacked4); }
+    else if (fmt == CNGP_IDX_BITS) { CNGP_BWD_INPUT_FMT(kFmtBits); }
+    else { CNGP_BWD_INPUT_FMT(kFmtU8); }
+#undef CNGP_BWD_INPUT_FMT
+#undef CNGP_BWD_INPUT
+    return launch_status("encode_bwd_input_kernel");
 }
 
 template <int D, int NP, typename FeatT, typename IoT>
@@ -781,6 +809,18 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     const Params p = make_params(cfg);
     // the LDS variants clear these ranges in their preparation launch, the direct one with a launch of its own
     CNGP_DISPATCH_TYPES(dispatch_bwd_np, cfg, p, b, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, workspace, z, s);
+}
+
+int cngp_encode_bwd_input(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const void *D_c,
+                          const void *dy, float *grad_x, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    if (N == 0) return CNGP_OK;
+    if (!x || !D_f || !dy || !grad_x || (!D_c && !index_codebook_is_empty(cfg))) return CNGP_ERR_NULL;
+    if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
+    const Params p = make_params(cfg);
+    hipStream_t s = (hipStream_t)stream;
+    CNGP_DISPATCH_TYPES(launch_bwd_input, cfg, p, x, N, D_f, D_c, dy, grad_x, s);
 }
 
 int cngp_storage_bytes(const cngp_config *cfg, size_t *D_f_bytes, size_t *D_c_level_bytes, size_t *D_c_bytes) {

@@ -55,6 +55,46 @@ __global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
 constexpr int kFwdTile = 256;        // default; kFwdTileLarge when staging a level's codebook is the larger cost
 constexpr int kFwdTileLarge = 1024;
 
+// One level's index codebook into LDS, by the whole workgroup: the bit string of the exact-width format as it
+// is, everything else as packed 4-bit entries (byte-per-entry input is packed on the way in).
+template <int FMT, int TILE>
+__device__ __forceinline__ void stage_probes(uint8_t *probes, const uint8_t *__restrict__ C_l, const uint32_t c_stride,
+                                             const uint32_t lds_c, const int vec, const int t)
+{
+    if (FMT == kFmtBits) {                                               // the level's bit string as it is
+        if (vec) {
+            for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u)
+                *reinterpret_cast<uint4 *>(probes + i) = *reinterpret_cast<const uint4 *>(C_l + i);
+        } else {
+            for (uint32_t i = t * 4u; i < c_stride; i += TILE * 4u)
+                *reinterpret_cast<uint32_t *>(probes + i) = *reinterpret_cast<const uint32_t *>(C_l + i);
+        }
+    } else if (FMT == kFmtPacked4) {
+        if (vec) {
+            for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u)
+                *reinterpret_cast<uint4 *>(probes + i) = *reinterpret_cast<const uint4 *>(C_l + i);
+        } else {
+            for (uint32_t i = t; i < c_stride; i += TILE) probes[i] = C_l[i];
+        }
+    } else if (vec) {                                                    // 16 entries in, 8 bytes out
+        for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(C_l + i);
+            auto pack = [](uint32_t v) {                                 // 4 entries -> 2 bytes
+                v &= 0x0F0F0F0Fu;
+                v = (v | (v >> 4)) & 0x00FF00FFu;
+                return (v | (v >> 8)) & 0xFFFFu;
+            };
+            *reinterpret_cast<uint2 *>(probes + i / 2) =
+                make_uint2(pack(w.x) | (pack(w.y) << 16), pack(w.z) | (pack(w.w) << 16));
+        }
+    } else {
+        for (uint32_t i = t; i < lds_c; i += TILE) {
+            const uint32_t lo = C_l[2 * i] & 0xFu, hi = (2 * i + 1 < c_stride) ? (C_l[2 * i + 1] & 0xFu) : 0u;
+            probes[i] = (uint8_t)(lo | (hi << 4));
+        }
+    }
+}
+
 template <int D, typename FeatT, typename IoT, int FMT, int TILE>
 __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
@@ -75,38 +115,7 @@ __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     for (int l = 0; l < p.L; ++l) {
         const uint8_t *C_l = D_c + (size_t)l * c_stride;
         __syncthreads();                                                     // previous level's lookups are done
-        if (FMT == kFmtBits) {                                               // the level's bit string as it is
-            if (vec) {
-                for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u)
-                    *reinterpret_cast<uint4 *>(probes + i) = *reinterpret_cast<const uint4 *>(C_l + i);
-            } else {
-                for (uint32_t i = t * 4u; i < c_stride; i += TILE * 4u)
-                    *reinterpret_cast<uint32_t *>(probes + i) = *reinterpret_cast<const uint32_t *>(C_l + i);
-            }
-        } else if (FMT == kFmtPacked4) {
-            if (vec) {
-                for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u)
-                    *reinterpret_cast<uint4 *>(probes + i) = *reinterpret_cast<const uint4 *>(C_l + i);
-            } else {
-                for (uint32_t i = t; i < c_stride; i += TILE) probes[i] = C_l[i];
-            }
-        } else if (vec) {                                                    // 16 entries in, 8 bytes out
-            for (uint32_t i = t * 16u; i < c_stride; i += TILE * 16u) {
-                const uint4 w = *reinterpret_cast<const uint4 *>(C_l + i);
-                auto pack = [](uint32_t v) {                                 // 4 entries -> 2 bytes
-                    v &= 0x0F0F0F0Fu;
-                    v = (v | (v >> 4)) & 0x00FF00FFu;
-                    return (v | (v >> 8)) & 0xFFFFu;
-                };
-                *reinterpret_cast<uint2 *>(probes + i / 2) =
-                    make_uint2(pack(w.x) | (pack(w.y) << 16), pack(w.z) | (pack(w.w) << 16));
-            }
-        } else {
-            for (uint32_t i = t; i < lds_c; i += TILE) {
-                const uint32_t lo = C_l[2 * i] & 0xFu, hi = (2 * i + 1 < c_stride) ? (C_l[2 * i + 1] & 0xFu) : 0u;
-                probes[i] = (uint8_t)(lo | (hi << 4));
-            }
-        }
+        stage_probes<FMT, TILE>(probes, C_l, c_stride, lds_c, vec, t);
         __syncthreads();
 
         Cell<D> cell;
@@ -143,6 +152,68 @@ __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     } else {
         for (size_t i = (size_t)t * sizeof(IoT); i < bytes; i += (size_t)TILE * sizeof(IoT))
             *reinterpret_cast<IoT *>(dst + i) = *reinterpret_cast<const IoT *>(src + i);
+    }
+}
+
+// ------------------------------------------------------------------ gradient with respect to the points
+// dL/dx of the forward pass above (the index of Eq. 6 is constant inside a cell, so the derivative acts on
+// the d-linear weights):  dL/dx_j = sum_l N_l sum_c (+-1)_j prod_{i != j} w_i(c) <D_f[l][idx_c], dL/dy[n, l]>.
+// Same tile structure as the forward pass: the level's index codebook staged in LDS, one lane per point.
+template <int D, typename FeatT, typename IoT, int FMT, int TILE, bool STAGED>
+__global__ __launch_bounds__(TILE) void encode_bwd_input_kernel(
+    const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f, const uint8_t *__restrict__ D_c,
+    const IoT *__restrict__ dy, float *__restrict__ grad_x, const int64_t N, const uint32_t c_stride, const int vec)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint8_t *probes = smem;
+    const uint32_t lds_c = (p.N_c + 1u) / 2u;
+    const int     t = threadIdx.x;
+    const int64_t n = (int64_t)blockIdx.x * TILE + t;
+    const bool    valid = n < N;
+    float xp[D], gx[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) { xp[j] = valid ? x[n * D + j] : 0.0f; gx[j] = 0.0f; }
+
+    for (int l = 0; l < p.L; ++l) {
+        const uint8_t *C_l = D_c + (size_t)l * c_stride;
+        if (STAGED) {
+            __syncthreads();                                                 // previous level's lookups are done
+            stage_probes<FMT, TILE>(probes, C_l, c_stride, lds_c, vec, t);
+            __syncthreads();
+        }
+        Cell<D> cell;
+        cell.locate(xp, p.N_l[l]);
+        const FeatT *F_l = D_f + (size_t)l * p.N_f * 2;
+        uint32_t idx[1 << D];
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) {
+            const uint32_t r = cell.hash2(c) & p.c_mask;
+            const uint32_t probe = !STAGED ? read_probe<FMT>(C_l, r, p.log2_Np)
+                                 : FMT == kFmtBits ? read_probe_bits_lds(probes, r, p.log2_Np)
+                                                   : read_probe<kFmtPacked4>(probes, r);
+            idx[c] = probe_base(cell.hash1(c), p) + probe;
+        }
+        float2 feat[1 << D];
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) feat[c] = load_pair(F_l, idx[c]);
+        const float2 g = valid ? load_pair(dy, (size_t)n * p.L + l) : make_float2(0.f, 0.f);
+        const float  res = (float)p.N_l[l];
+#pragma unroll
+        for (int c = 0; c < (1 << D); ++c) {
+            const float tc = res * fmaf(feat[c].x, g.x, feat[c].y * g.y);
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                float dw = ((c >> j) & 1) ? tc : -tc;
+#pragma unroll
+                for (int i = 0; i < D; ++i)
+                    if (i != j) dw *= ((c >> i) & 1) ? cell.w[i] : 1.0f - cell.w[i];
+                gx[j] += dw;
+            }
+        }
+    }
+    if (valid) {
+#pragma unroll
+        for (int j = 0; j < D; ++j) grad_x[n * D + j] = gx[j];
     }
 }
 

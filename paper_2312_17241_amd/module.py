@@ -13,7 +13,7 @@ first bake picks an arbitrary one); the optimiser is Adam.
 import torch
 
 from . import (Adam, Config, ZERO_GRADS, _TORCH_DT, F16, adam_step_bake, alloc_workspace, bake_probes,
-               encode_bwd, encode_fwd, workspace_bytes)
+               encode_bwd, encode_bwd_input, encode_fwd, workspace_bytes)
 
 
 class _Encode(torch.autograd.Function):
@@ -30,7 +30,8 @@ class _Encode(torch.autograd.Function):
         dy = dy.contiguous().to(_TORCH_DT[enc.cfg.io_dtype])
         encode_bwd(enc.cfg, x, enc.D_f, enc.Dhat_c, dy, enc.grad_D_f, enc.grad_Dhat_c,
                    workspace=enc._workspace(x.shape[0]))          # accumulates (+=)
-        return None, torch.zeros((), dtype=torch.float32, device=dy.device), None
+        grad_x = encode_bwd_input(enc.cfg, x, enc.D_f, enc.D_c, dy) if ctx.needs_input_grad[0] else None
+        return grad_x, torch.zeros((), dtype=torch.float32, device=dy.device), None
 
 
 class Encoding(torch.nn.Module):

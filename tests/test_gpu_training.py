@@ -108,6 +108,11 @@ def test_module_gradients_match_the_oracle():
     gF, gC, A_f, A_c = oracle.encode_bwd(w, x_h, D_f, Dhat, np.ascontiguousarray(dy))
     check_close("grad D_f", enc.grad_D_f.cpu().numpy(), 2 * gF, 2 * A_f, fp16_out=False)
     check_close("grad Dhat_c", enc.grad_Dhat_c.cpu().numpy(), 2 * gC, 2 * A_c, fp16_out=False)
+    # points that require a gradient get dL/dx through the same bridge
+    xg = x.clone().requires_grad_(True)
+    (enc(xg) * coef).sum().backward()
+    gx_ref, gx_mag = oracle.encode_bwd_input(w, x_h, D_f, enc.D_c.cpu().numpy(), np.ascontiguousarray(dy))
+    check_close("grad x", xg.grad.cpu().numpy(), gx_ref, gx_mag, fp16_out=False)
 
 
 def test_training_with_the_library_decoder():
