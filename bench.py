@@ -35,6 +35,8 @@ def algorithmic_bytes(w, n, index_level_bytes=None):
     pts = n * (4 * w.d + w.L * w.F * iob)
     return {
         "encode_fwd": pts + D_f + D_c,
+        # inference in one kernel: the points in, three fp32 outputs per point out, tables and decoder weights once
+        "encode_mlp_fwd": n * (4 * w.d + 3 * 4) + D_f + D_c + 2 * (64 * w.L * w.F + 64 * 64 + 64 * 3),
         "encode_bwd": pts + D_f + Dhat + gD_f + Dhat,
         "bake_probes": Dhat + D_c,
         "zero": gD_f + Dhat,
@@ -115,6 +117,13 @@ def main():
         cfg_opt = cngp.Config.from_workload(w, index_format=fmt)
         n_step = [0]
 
+    fused_dec = args.with_decoder and fwd_only              # inference: encoding + decoder in one kernel
+    if fused_dec:
+        mcfg = cngp.MlpConfig(w.L * w.F, 3, cngp.F16 if w.io_dtype == "f16" else cngp.F32)
+        g = torch.Generator(device="cpu").manual_seed(7)
+        W_half = torch.cat([(torch.randn((r, c), generator=g) * (2.0 / c) ** 0.5).ravel()
+                            for r, c in ((64, w.L * w.F), (64, 64), (3, 64))]).to(dev).half()
+        out_dec = torch.empty((N, 3), dtype=torch.float32, device=dev)
     with_dec = args.with_decoder and not fwd_only
     if with_dec:
         n_out = 3
@@ -142,6 +151,9 @@ def main():
                                 (Dhat, moments[2], moments[3], gC, D_c))
         else:
             cngp.bake_probes(cfg, Dhat, D_c)
+        if fused_dec:
+            cngp.encode_mlp_fwd(cfg, mcfg, x, D_f, D_c, W_half, out_dec)
+            return
         cngp.encode_fwd(cfg, x, D_f, D_c, y, workspace=ws)
         if with_dec:
             cngp.mlp_fwd(mcfg, y, W_half, out_dec)
@@ -215,7 +227,7 @@ def main():
         "config": {"workload": f"{w.name}: d={w.d} L={w.L} F={w.F} N_f={w.N_f} N_c={w.N_c} N_p={w.N_p} "
                                f"N_min={w.N_min} N_max={w.N_max} points={N} ({w.points}) "
                                f"D_f={w.feat_dtype} y/dy={w.io_dtype}",
-                   "step": "bake + fwd" if fwd_only else
+                   "step": ("bake + encoding and decoder forward in one kernel" if fused_dec else "bake + fwd") if fwd_only else
                            (("decoder fwd/bwd + " if with_dec else "") +
                             ("Adam step fused with bake + fwd + bwd (grads cleared each step)" if with_opt else
                              "bake + fwd + bwd (grads cleared each step)"))},
@@ -229,7 +241,7 @@ def main():
     # and the backward pass by scatter-add atomics.  Both rates are measured now, on this device.
     rates = cngp.measure_rates(dev)
     corners = 1 << w.d
-    t_fwd = per_kernel["encode_fwd"]["ms"] / args.steps * 1e-3
+    t_fwd = per_kernel["encode_mlp_fwd" if fused_dec else "encode_fwd"]["ms"] / args.steps * 1e-3
     gathers = N * w.L * corners                                  # D_f entries the forward must fetch
     out["applicable_roofline"] = {
         "measured_rates": {k: round(v, 1) for k, v in rates.items()},
@@ -285,6 +297,10 @@ def main():
         t0 = time.perf_counter()
         D_c_ref = oracle.bake_probes(Dhat_h)
         y_ref, ymag = oracle.encode_fwd(w, xs, D_f_h, D_c_ref)
+        if fused_dec:
+            Wh = W_half.float().cpu().numpy().astype(np.float64)
+            a, b = 64 * w.L * w.F, 64 * w.L * w.F + 64 * 64
+            dec_ref, dec_mag, _ = oracle.mlp_fwd(y_ref, Wh[:a].reshape(64, -1), Wh[a:b].reshape(64, 64), Wh[b:].reshape(3, 64), want_mag=True)
         if not fwd_only:
             g_ref = oracle.encode_bwd(w, xs, D_f_h, Dhat_h, dy_h[:n_cpu], want_abs=not args.no_check)
         t_cpu = time.perf_counter() - t0
@@ -300,7 +316,12 @@ def main():
             else:
                 unpack = D_c if fmt == cngp.IDX_U8 else torch.stack([D_c & 0xF, D_c >> 4], dim=-1).reshape(w.L, w.N_c)
                 check_exact("D_c", unpack.cpu().numpy(), D_c_ref)
-            e = {"y": check_close("y", y[:n_cpu].cpu().numpy(), y_ref, ymag, fp16_out=(w.io_dtype == "f16"))}
+            if fused_dec:
+                err = np.abs(out_dec[:n_cpu].cpu().numpy() - dec_ref) / np.maximum(np.maximum(np.abs(dec_ref), dec_mag), 1e-30)
+                assert err.max() <= 2e-3, f"decoder(encode(x)): rel err {err.max():.3e}"
+                e = {"decoder_out": float(err.max())}
+            else:
+                e = {"y": check_close("y", y[:n_cpu].cpu().numpy(), y_ref, ymag, fp16_out=(w.io_dtype == "f16"))}
             # with the decoder in the loop the upstream gradient is the decoder's output: no oracle input may come
             # from the kernels, so the gradient check is left to the parity tests in that mode
             if not fwd_only and n_cpu == N and not with_dec:

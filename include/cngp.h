@@ -203,6 +203,13 @@ typedef struct cngp_mlp_config {
 size_t cngp_mlp_weight_count(const cngp_mlp_config *cfg);     /* 64 n_in + 64 * 64 + 64 n_out; 0 if invalid */
 int cngp_mlp_fwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const void *W, float *out, void *stream);
 
+/* Encoding and decoder in one kernel, for inference: out = decoder(encode(x)) without the encoded features
+ * going to memory.  Equal to cngp_encode_fwd followed by cngp_mlp_fwd (the features pass as fp16 either way).
+ * Needs mlp->n_in == cfg->L * cfg->F and an index codebook whose level fits in LDS (N_c <= 2^17 entries);
+ * otherwise CNGP_ERR_UNSUPPORTED: make the two calls instead.  mlp->io_dtype and flags are ignored. */
+int cngp_encode_mlp_fwd(const cngp_config *cfg, const cngp_mlp_config *mlp, const float *x, int64_t N,
+                        const void *D_f, const void *D_c, const void *W, float *out, void *stream);
+
 /* Backward pass of the decoder for L = sum(out * dout): recomputes the hidden layers, then
  *   dy      dev io_dtype [N, n_in]    written: dL/dy, the upstream gradient cngp_encode_bwd takes
  *   grad_W  dev float32, layout of W  accumulated (+=) with floating-point atomics, or cleared first

@@ -70,6 +70,8 @@ def _load():
     lib.cngp_mlp_weight_count.argtypes = [vp]
     lib.cngp_mlp_fwd.restype = ctypes.c_int
     lib.cngp_mlp_fwd.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib.cngp_encode_mlp_fwd.restype = ctypes.c_int
+    lib.cngp_encode_mlp_fwd.argtypes = [cfgp, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.cngp_mlp_bwd.restype = ctypes.c_int
     lib.cngp_mlp_bwd.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
     lib.cngp_adam_step.restype = ctypes.c_int
@@ -364,6 +366,19 @@ def mlp_fwd(cfg: MlpConfig, y, W, out=None):
     return out
 
 
+def encode_mlp_fwd(cfg: Config, mcfg: MlpConfig, x, D_f, D_c, W, out=None):
+    """cngp_encode_mlp_fwd: decoder(encode(x)) in one kernel; float32 [N, n_out]."""
+    N = x.shape[0]
+    if out is None:
+        out = torch.empty((N, mcfg.n_out), dtype=torch.float32, device=x.device)
+    c, m = cfg.c(), mcfg.c()
+    _check(_lib.cngp_encode_mlp_fwd(
+        ctypes.byref(c), ctypes.cast(ctypes.byref(m), ctypes.c_void_p), _dev(x, torch.float32, (N, cfg.d), "x"), N,
+        _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"), _dc(cfg, D_c),
+        _dev(W, torch.float16, (mcfg.weight_count,), "W"), _dev(out, torch.float32, (N, mcfg.n_out), "out"), _stream()))
+    return out
+
+
 def mlp_bwd(cfg: MlpConfig, y, W, dout, dy=None, grad_W=None):
     N = y.shape[0]
     if dy is None:
@@ -416,7 +431,7 @@ def profile_enable(on: bool) -> bool:
 
 def profile_read() -> dict:
     """{kernel name: (total ms, launches)} since the last read; waits for the recorded events."""
-    n = 16
+    n = 64                                   # more than the library has kernel kinds
     ms = (ctypes.c_double * n)()
     cnt = (ctypes.c_int64 * n)()
     k = _lib.cngp_profile_read(ms, cnt, n)

@@ -90,13 +90,13 @@ int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INV
 // ---------------------------------------------------------------- per-kernel timing
 enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_PREP, K_BWD_SLICED, K_BWD_SLICED_V, K_BWD_GRID_DRAIN,
                 K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD,
-                K_BWD_BIN_COUNT, K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_COUNT };
+                K_BWD_BIN_COUNT, K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_FUSED_FWD, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_prepare",
                                            "encode_bwd_sliced_points_and_grid", "encode_bwd_sliced_vertices",
                                            "encode_bwd_bin_grid_sums", "bake_probes", "zero", "debug_indices",
                                            "adam_step_bake", "mlp_fwd", "mlp_bwd",
                                            "encode_bwd_bin_count", "encode_bwd_bin_offsets", "encode_bwd_bin_scatter",
-                                           "encode_bwd_bin_drain", "encode_bwd_input"};
+                                           "encode_bwd_bin_drain", "encode_bwd_input", "encode_mlp_fwd"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -704,6 +704,37 @@ int dispatch_bwd_np(const cngp_config *c, const Params &p, const BwdPlan &b, con
 
 // ==================================================================== exported C ABI
 namespace {
+template <int D, typename FeatT, typename IoT>
+int launch_fused_fwd(const cngp_config *c, const Params &p, const MlpDims &d, const float *x, int64_t N, const void *D_f,
+                     const void *D_c, const void *W, float *out, hipStream_t s) {
+    const size_t c_stride = index_level_bytes(c);
+    size_t rest = (((size_t)c->N_c + 1) / 2 + 15) & ~(size_t)15;
+    if (rest < kMlpRawBytes) rest = kMlpRawBytes;
+    const size_t lds = kMlpFwdOps + (size_t)kFusedTile * kFusedStride * sizeof(_Float16) + rest;
+    if (lds > 128 * 1024) return CNGP_ERR_UNSUPPORTED;
+    const int64_t tiles = (N + kFusedTile - 1) / kFusedTile;
+    int64_t per_cu = (int64_t)(160 * 1024 / lds);            // workgroups that fit a CU at once: LDS, and three
+    if (per_cu > 3) per_cu = 3;                              // wavefronts per SIMD by registers
+    if (per_cu < 1) per_cu = 1;
+    const int64_t blocks = tiles < 256 * per_cu ? tiles : 256 * per_cu;
+    const int vec = (c_stride % 16 == 0 && ((uintptr_t)D_c & 15u) == 0) ? 1 : 0;
+#define CNGP_FUSED(FMT)                                                                                   \
+    do {                                                                                                  \
+        auto kernel = encode_mlp_fwd_kernel<D, FeatT, FMT>;                                               \
+        if (int rc = allow_big_lds(kernel, lds)) return rc;                                               \
+        LaunchTimer t(s, K_FUSED_FWD);                                                                    \
+        kernel<<<(unsigned)blocks, kFusedTile, lds, s>>>(p, d, x, (const FeatT *)D_f, (const uint8_t *)D_c, \
+                                                         (const __half *)W, out, N, tiles, (uint32_t)c_stride, vec); \
+    } while (0)
+    if (c->index_format == CNGP_IDX_PACKED4) CNGP_FUSED(kFmtPacked4);
+    else if (c->index_format == CNGP_IDX_BITS) CNGP_FUSED(kFmtBits);
+    else CNGP_FUSED(kFmtU8);
+#undef CNGP_FUSED
+    return launch_status("encode_mlp_fwd_kernel");
+}
+}  // namespace
+
+namespace {
 int adam_coefficients(const cngp_adam *o, AdamCoef *a) {
     if (!(o->lr >= 0.0f) || !std::isfinite(o->lr)) return CNGP_ERR_INVALID;
     if (!(o->beta1 >= 0.0f && o->beta1 < 1.0f) || !(o->beta2 >= 0.0f && o->beta2 < 1.0f)) return CNGP_ERR_INVALID;
@@ -993,6 +1024,21 @@ int cngp_mlp_fwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const voi
     else
         mlp_fwd_kernel<float><<<mlp_blocks(tiles, 3, 4), kMlpBlock, kMlpFwdLds, s>>>(d, (const float *)y, N, (const __half *)W, out, tiles);
     return launch_status("mlp_fwd_kernel");
+}
+
+int cngp_encode_mlp_fwd(const cngp_config *cfg, const cngp_mlp_config *mlp, const float *x, int64_t N,
+                        const void *D_f, const void *D_c, const void *W, float *out, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    MlpDims d;
+    if (int rc = mlp_dims(mlp, &d)) return rc;
+    if (d.n_in != cfg->L * cfg->F) return CNGP_ERR_INVALID;
+    if (N < 0) return CNGP_ERR_INVALID;
+    if (N == 0) return CNGP_OK;
+    if (!x || !D_f || !W || !out || (!D_c && !index_codebook_is_empty(cfg))) return CNGP_ERR_NULL;
+    if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
+    const Params p = make_params(cfg);
+    hipStream_t s = (hipStream_t)stream;
+    CNGP_DISPATCH_TYPES(launch_fused_fwd, cfg, p, d, x, N, D_f, D_c, W, out, s);
 }
 
 int cngp_mlp_bwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const void *W, const float *dout,

@@ -247,6 +247,95 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
     }
 }
 
+// ------------------------------------------------------------------ encoding + decoder in one kernel (inference)
+// The forward tile kernel of the encoding (cngp_kernels.h: 256 points per workgroup through all levels,
+// the level's index codebook staged in LDS) with the decoder applied to the tile while it is still in LDS:
+// the encoded features never go to memory.  y is kept as fp16, the value the decoder's matrix
+// instructions would read from a stored y of either type, so the result equals the two separate calls.
+// Row stride of the tile: 36 halves (the operand reads of 32 lanes then fall into different banks);
+// columns from 2 L on are zero, which is what the K-steps beyond n_in need.
+constexpr int kFusedTile = 256;
+constexpr int kFusedStride = 36;
+
+template <int D, typename FeatT, int FMT>
+__global__ __launch_bounds__(kFusedTile) void encode_mlp_fwd_kernel(
+    const Params p, const MlpDims d, const float *__restrict__ x, const FeatT *__restrict__ D_f,
+    const uint8_t *__restrict__ D_c, const __half *__restrict__ W, float *__restrict__ out, const int64_t N,
+    const int64_t tiles, const uint32_t c_stride, const int vec)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    half4_t  *ops = reinterpret_cast<half4_t *>(smem);
+    _Float16 *ytile = reinterpret_cast<_Float16 *>(smem + kMlpFwdOps);                      // [kFusedTile][kFusedStride]
+    unsigned char *rest = smem + kMlpFwdOps + (size_t)kFusedTile * kFusedStride * sizeof(_Float16);
+    uint8_t  *probes = rest;                                 // the raw weights first, then each level's index codebook
+    const uint32_t lds_c = (p.N_c + 1u) / 2u;
+    stage_operands(ops, reinterpret_cast<__half *>(rest), W, d, kOpFwdSlots);
+    const int t = threadIdx.x;
+    for (int i = t; i < kFusedTile * kFusedStride; i += kFusedTile) ytile[i] = (_Float16)0.0f;
+    const int lane = t & 63, k4 = 4 * (lane >> 5);
+
+    // persistent: a workgroup stages the decoder's weights once and then walks over tiles of points
+    for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const int64_t n0 = tile * kFusedTile;
+        const int64_t n = n0 + t;
+        const bool    valid = n < N;
+        float xp[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) xp[j] = valid ? x[n * D + j] : 0.0f;
+
+        for (int l = 0; l < p.L; ++l) {
+            const uint8_t *C_l = D_c + (size_t)l * c_stride;
+            __syncthreads();                                 // previous lookups, previous tile's decoder reads, the clearing above
+            stage_probes<FMT, kFusedTile>(probes, C_l, c_stride, lds_c, vec, t);
+            __syncthreads();
+            Cell<D> cell;
+            cell.locate(xp, p.N_l[l]);
+            const FeatT *F_l = D_f + (size_t)l * p.N_f * 2;
+            uint32_t idx[1 << D];
+#pragma unroll
+            for (int c = 0; c < (1 << D); ++c)
+                idx[c] = probe_base(cell.hash1(c), p) +
+                         (FMT == kFmtBits ? read_probe_bits_lds(probes, cell.hash2(c) & p.c_mask, p.log2_Np)
+                                          : read_probe<kFmtPacked4>(probes, cell.hash2(c) & p.c_mask));
+            float2 feat[1 << D];
+#pragma unroll
+            for (int c = 0; c < (1 << D); ++c) feat[c] = load_pair(F_l, idx[c]);
+            float y0 = 0.0f, y1 = 0.0f;
+#pragma unroll
+            for (int c = 0; c < (1 << D); ++c) {
+                const float wt = cell.weight(c);
+                y0 = fmaf(wt, feat[c].x, y0);
+                y1 = fmaf(wt, feat[c].y, y1);
+            }
+            ytile[t * kFusedStride + 2 * l] = (_Float16)y0;
+            ytile[t * kFusedStride + 2 * l + 1] = (_Float16)y1;
+        }
+        wave_lds_fence();                                    // a wavefront decodes the rows it wrote itself
+
+        // decoder: every wavefront takes its own 64 points as two tiles of 32
+#pragma unroll 1
+        for (int half = 0; half < 2; ++half) {
+            const int row = (t & ~63) + 32 * half + (lane & 31);
+            Hidden H;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                H.yb[s] = *reinterpret_cast<const half4_t *>(ytile + row * kFusedStride + 8 * s + k4);
+            hidden_layers(ops, d, lane, H);
+            acc16_t o = acc_zero();
+#pragma unroll
+            for (int s = 0; s < 8; ++s) o = mfma(ops[(kOpW3 + s) * 64 + lane], H.h2[s], o);
+            const int64_t pt = n0 + row;
+            if (pt < N) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const int ch = 8 * (r >> 2) + k4 + (r & 3);
+                    if (ch < d.n_out) out[pt * d.n_out + ch] = o[r];
+                }
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ backward
 // B-layout registers (lane = point, K-step s holds rows 8s + 4h .. + 3) written as rows of the tile.
 template <int STEPS>

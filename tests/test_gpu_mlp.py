@@ -138,3 +138,50 @@ def test_adam_step_on_a_plain_array():
     assert np.allclose(t[1].cpu().numpy(), m1, rtol=1e-5, atol=1e-8) and np.allclose(t[2].cpu().numpy(), v1, rtol=1e-5, atol=1e-10)
     assert np.array_equal(half.cpu().numpy().view(np.uint16), t[0].cpu().numpy().astype(np.float16).view(np.uint16))
     assert not t[3].any()
+
+
+@pytest.mark.parametrize("fmt", [cngp.IDX_U8, cngp.IDX_PACKED4, cngp.IDX_BITS])
+@pytest.mark.parametrize("d,L,N_p,N_c,feat,io,n_out,N", [(3, 16, 16, 2**14, "f16", "f16", 3, 5000 + 77),
+                                                         (2, 8, 8, 2**12, "f32", "f32", 1, 1000 + 3),
+                                                         (3, 5, 4, 2**9, "f16", "f32", 16, 256),
+                                                         (3, 16, 8, 2**16, "f16", "f16", 4, 40000)])
+def test_fused_encode_and_decoder(fmt, d, L, N_p, N_c, feat, io, n_out, N):
+    """cngp_encode_mlp_fwd equals the two separate calls bit for bit (the encoded features pass as fp16 either
+    way) and agrees with the oracle chain within the decoder's bar."""
+    import workloads as W
+    w = W.custom(cfg=95, d=d, L=L, N_f=2**12, N_c=N_c, N_p=N_p, N_min=8, N_max=512, N=N, feat_dtype=feat, io_dtype=io)
+    x_h = W.make_points(w)
+    D_f_h = W.make_feature_codebook(w)
+    D_f_h = (D_f_h.astype(np.float64) * 1e4).astype(D_f_h.dtype)
+    D_c_h = oracle.bake_probes(W.make_probe_logits(w))
+    rng = np.random.default_rng(3)
+    he = lambda rows, cols: (rng.standard_normal((rows, cols)) * np.sqrt(2.0 / cols)).astype(np.float16).astype(np.float64)
+    W1, W2, W3 = he(64, 2 * L), he(64, 64), he(n_out, 64)
+    Wd = dev(np.concatenate([W1.ravel(), W2.ravel(), W3.ravel()]), torch.float16)
+    cfg = cngp.Config.from_workload(w, index_format=fmt)
+    mcfg = cngp.MlpConfig(2 * L, n_out, cngp.F16 if io == "f16" else cngp.F32)
+    D_c = {cngp.IDX_U8: lambda: dev(D_c_h), cngp.IDX_PACKED4: lambda: cngp.pack4(dev(D_c_h)),
+           cngp.IDX_BITS: lambda: dev(oracle.pack_index_bits(D_c_h, N_p))}[fmt]()
+    fused = cngp.encode_mlp_fwd(cfg, mcfg, dev(x_h), dev(D_f_h), D_c, Wd)
+    y = cngp.encode_fwd(cfg, dev(x_h), dev(D_f_h), D_c)
+    two = cngp.mlp_fwd(mcfg, y, Wd)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, two)
+    y_ref, _ = oracle.encode_fwd(w, x_h, D_f_h, D_c_h)
+    ref, mag, _ = oracle.mlp_fwd(y_ref, W1, W2, W3, want_mag=True)
+    check("decoder(encode(x))", fused.cpu().numpy(), ref, mag)
+
+
+def test_fused_encode_and_decoder_refuses_what_it_cannot_do():
+    import workloads as W
+    w = W.custom(cfg=96, d=3, L=4, N_f=2**10, N_c=2**19, N_p=2, N_min=8, N_max=64, N=300)     # index codebook too large for LDS
+    cfg = cngp.Config.from_workload(w)
+    z = lambda shape, dt: torch.zeros(shape, dtype=dt, device=DEV)
+    with pytest.raises(cngp.CngpError) as e:
+        cngp.encode_mlp_fwd(cfg, cngp.MlpConfig(8, 3), z((300, 3), torch.float32), z((4, 2**10, 2), torch.float32),
+                            z((4, 2**19), torch.uint8), z((cngp.MlpConfig(8, 3).weight_count,), torch.float16))
+    assert e.value.status == cngp.ERR_UNSUPPORTED
+    with pytest.raises(cngp.CngpError) as e:                   # decoder input width must be L * F
+        cngp.encode_mlp_fwd(cfg, cngp.MlpConfig(16, 3), z((300, 3), torch.float32), z((4, 2**10, 2), torch.float32),
+                            z((4, 2**19), torch.uint8), z((cngp.MlpConfig(16, 3).weight_count,), torch.float16))
+    assert e.value.status == cngp.ERR_INVALID
