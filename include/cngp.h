@@ -115,6 +115,14 @@ int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N,
                     const void *D_f, const void *D_c, void *y,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* Forward encoding from a partially loaded model (Sec. 1, Sec. 5: level-of-detail streaming, partial results
+ * in bandwidth-constrained settings): only levels 0 .. levels_loaded - 1 of D_f and D_c need to be present
+ * (the arrays keep their full layout; the rest is never read); the columns of the other levels are written
+ * as zero.  levels_loaded = L is cngp_encode_fwd; 0 writes zeros and reads no table. */
+int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const float *x, int64_t N,
+                            const void *D_f, const void *D_c, void *y,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
 /* Backward pass (Sec. 3 "Training"; Fig. 3: straight-through estimator).  The gradient of the
  * forward pass with the hard maximum replaced by a softmax over each row of D^_c: for every
  * enclosing vertex, with g = weight * dL/dy, sigma = softmax(D^_c[l][hash2(v)]) and

@@ -97,6 +97,21 @@ def encode_fwd(w, x, D_f, D_c, res=None):
     return y, ymag
 
 
+def encode_fwd_partial(w, levels_loaded, x, D_f, D_c):
+    """Forward from a partially loaded model (level-of-detail streaming): the first `levels_loaded` levels
+    of the full model's level table are evaluated, the remaining columns are zero."""
+    import dataclasses
+    res = level_resolutions(w.N_min, w.N_max, w.L)
+    N = np.asarray(x).shape[0]
+    y = np.zeros((N, w.L * w.F)); ymag = np.zeros((N, w.L * w.F))
+    if levels_loaded > 0:
+        sub = dataclasses.replace(w, L=levels_loaded)
+        ys, ms = encode_fwd(sub, x, np.asarray(D_f)[:levels_loaded], np.asarray(D_c)[:levels_loaded], res=res[:levels_loaded])
+        y[:, :levels_loaded * w.F] = ys
+        ymag[:, :levels_loaded * w.F] = ms
+    return y, ymag
+
+
 def encode_bwd_input(w, x, D_f, D_c, dy, res=None):
     """Gradient of the hard forward with respect to the points.  Returns (dL/dx, magnitude), float64 [N, d]."""
     x = _x(w, x); res = _res(w, res)

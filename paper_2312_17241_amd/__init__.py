@@ -61,6 +61,8 @@ def _load():
     lib.cngp_encode_fwd.restype = ctypes.c_int
     lib.cngp_encode_fwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.cngp_encode_bwd.restype = ctypes.c_int
+    lib.cngp_encode_fwd_partial.restype = ctypes.c_int
+    lib.cngp_encode_fwd_partial.argtypes = [cfgp, ctypes.c_int32, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.cngp_encode_bwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cngp_bake_probes.restype = ctypes.c_int
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
@@ -225,6 +227,19 @@ def encode_fwd(cfg: Config, x, D_f, D_c, y=None, workspace=None):
         _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"),
         _dc(cfg, D_c),
         _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), wp, wb, _stream()))
+    return y
+
+
+def encode_fwd_partial(cfg: Config, levels_loaded, x, D_f, D_c, y=None):
+    """cngp_encode_fwd_partial: only the first `levels_loaded` levels are read, the others encode to zero."""
+    N = x.shape[0]
+    if y is None:
+        y = torch.empty((N, cfg.L * cfg.F), dtype=_TORCH_DT[cfg.io_dtype], device=x.device)
+    c = cfg.c()
+    _check(_lib.cngp_encode_fwd_partial(
+        ctypes.byref(c), int(levels_loaded), _dev(x, torch.float32, (N, cfg.d), "x"), N,
+        _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"), _dc(cfg, D_c),
+        _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), ctypes.c_void_p(0), 0, _stream()))
     return y
 
 

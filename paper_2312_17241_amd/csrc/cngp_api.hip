@@ -68,6 +68,7 @@ Params make_params(const cngp_config *c) {
     std::memset(&p, 0, sizeof(p));
     level_table(c, p.N_l);
     p.L = c->L;
+    p.L_loaded = c->L;
     p.N_f = c->N_f;
     p.N_c = c->N_c;
     p.row_mask = c->N_f / c->N_p - 1;
@@ -806,6 +807,21 @@ int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
     (void)workspace; (void)workspace_bytes;
     const Params p = make_params(cfg);
+    hipStream_t s = (hipStream_t)stream;
+    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s);
+}
+
+int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const float *x, int64_t N, const void *D_f,
+                            const void *D_c, void *y, void *workspace, size_t workspace_bytes, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0 || levels_loaded < 0 || levels_loaded > cfg->L) return CNGP_ERR_INVALID;
+    if (N == 0) return CNGP_OK;
+    if (!x || !y) return CNGP_ERR_NULL;
+    if (levels_loaded > 0 && (!D_f || (!D_c && !index_codebook_is_empty(cfg)))) return CNGP_ERR_NULL;
+    if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
+    (void)workspace; (void)workspace_bytes;
+    Params p = make_params(cfg);
+    p.L_loaded = levels_loaded;
     hipStream_t s = (hipStream_t)stream;
     CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s);
 }

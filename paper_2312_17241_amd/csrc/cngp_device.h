@@ -19,6 +19,7 @@ __device__ constexpr uint32_t kPi2[3] = {1580030173u, 1367130559u, 3037000507u};
 struct Params {
     uint32_t N_l[kMaxLevels];   // grid resolution per level
     int32_t  L;
+    int32_t  L_loaded;          // forward only: levels from here on are not loaded and encode to zero (level-of-detail streaming)
     uint32_t N_f, N_c;
     uint32_t row_mask;          // N_f / N_p - 1 : hashed most significant bits of the index
     uint32_t c_mask;            // N_c - 1

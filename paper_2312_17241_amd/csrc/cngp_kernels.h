@@ -17,6 +17,10 @@ __global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
     if (i >= pairs) return;
     const int64_t n = i / p.L;
     const int     l = (int)(i - n * p.L);
+    if (l >= p.L_loaded) {                        // level not loaded
+        store_pair(y, (size_t)i, 0.0f, 0.0f);
+        return;
+    }
 
     float xp[D];
 #pragma unroll
@@ -112,7 +116,8 @@ __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
 #pragma unroll
     for (int j = 0; j < D; ++j) xp[j] = valid ? x[n * D + j] : 0.0f;
 
-    for (int l = 0; l < p.L; ++l) {
+    for (int l = p.L_loaded; l < p.L; ++l) store_pair(out, (size_t)t * p.L + l, 0.0f, 0.0f);    // levels that are not loaded
+    for (int l = 0; l < p.L_loaded; ++l) {
         const uint8_t *C_l = D_c + (size_t)l * c_stride;
         __syncthreads();                                                     // previous level's lookups are done
         stage_probes<FMT, TILE>(probes, C_l, c_stride, lds_c, vec, t);

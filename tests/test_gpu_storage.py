@@ -99,3 +99,28 @@ def test_large_tile_forward(fmt):
     pick = np.r_[0:4096, n - 4096:n]
     y_ref, ymag = oracle.encode_fwd(w, x[pick], D_f, D_c)
     check_close("y", y.float().cpu().numpy()[pick], y_ref, ymag, fp16_out=True)
+
+
+@pytest.mark.parametrize("levels", [0, 1, 5, 11, 12])
+@pytest.mark.parametrize("flags", [0, cngp.FWD_SIMPLE])
+def test_forward_from_a_partially_loaded_model(levels, flags):
+    """Level-of-detail streaming: only the first levels are read (the rest of the arrays is poisoned with
+    NaN features and out-of-range indices here), the other columns are zero."""
+    w = W.custom(cfg=97, d=3, L=12, N_f=2**11, N_c=2**10, N_p=8, N_min=8, N_max=1024, N=2000 + 9, feat_dtype="f16", io_dtype="f16")
+    x = W.make_points(w)
+    D_f = W.make_feature_codebook(w)
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    D_c = oracle.bake_probes(W.make_probe_logits(w))
+    y_ref, ymag = oracle.encode_fwd_partial(w, levels, x, D_f, D_c)
+    if levels == w.L:
+        full, _ = oracle.encode_fwd(w, x, D_f, D_c)
+        assert np.array_equal(full, y_ref)
+    D_f_p, D_c_p = D_f.copy(), D_c.copy()
+    D_f_p[levels:] = np.nan
+    D_c_p[levels:] = 255
+    cfg = cngp.Config.from_workload(w, flags=flags)
+    y = cngp.encode_fwd_partial(cfg, levels, dev(x), dev(D_f_p), dev(D_c_p))
+    torch.cuda.synchronize()
+    got = y.float().cpu().numpy()
+    check_close("y", got, y_ref, ymag, fp16_out=True)
+    assert not got[:, levels * w.F:].any()
