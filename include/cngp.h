@@ -88,6 +88,9 @@ typedef struct {
     int32_t  io_dtype;     /* cngp_dtype of y and dL/dy                                        */
     int32_t  index_format; /* cngp_index_format of D_c                                         */
     uint32_t flags;        /* bitwise OR of the CNGP_* flags above                             */
+    uint64_t bin_bytes_max; /* most workspace cngp_encode_bwd spends on binned references (8 bytes per
+                              corner reference, level and gradient table); 0 = 8 GiB.  A larger batch
+                              is taken in several passes inside the one call                      */
 } cngp_config;
 
 /* Grid resolution of every level (Table 1: N_min, N_max, L; geometric growth):
@@ -134,7 +137,9 @@ int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const
  *   dy           dev io_dtype [N, L*F]
  *   grad_D_f     dev float32 [L, N_f, F]      accumulated (+=), or cleared first with CNGP_ZERO_GRADS
  *   grad_Dhat_c  dev float32 [L, N_c, N_p]    same
- * Sums are formed with floating-point atomics: their order, hence the last bits, vary run to run. */
+ * Sums are formed with floating-point atomics: their order, hence the last bits, vary run to run.
+ * A batch whose binned references would pass cfg->bin_bytes_max is taken in several passes over runs of
+ * points, each adding onto the one before, inside the one call (cngp_bwd_plan_info reports how many). */
 int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N,
                     const void *D_f, const float *Dhat_c, const void *dy,
                     float *grad_D_f, float *grad_Dhat_c,
@@ -155,8 +160,10 @@ int cngp_encode_bwd_input(const cngp_config *cfg, const float *x, int64_t N, con
  * of the logit gradient table; [4], [5] point chunks of the feature / logit role on hashed levels;
  * [6], [7] vertex chunks of the two roles on pre-reduced levels; [8] point chunks and [9] total slices
  * of the vertex-grid accumulation; [10] 1 = the hashed levels' references are binned by slice first, and then
- * [11], [12] workgroups that drain one bin of the feature / logit table and [13] point chunks of the binning. */
-enum { CNGP_PLAN_INFO_COUNT = 14 };
+ * [11], [12] workgroups that drain one bin of the feature / logit table and [13] point chunks of the binning;
+ * [14] passes over runs of points (1 unless the batch is split to bound the scratch; [0] .. [13] then
+ * describe the first pass). */
+enum { CNGP_PLAN_INFO_COUNT = 15 };
 int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info);
 
 /* Bake (Fig. 3; Sec. 3): D_c[l][r] = index of the largest confidence value in row r of D^_c.

@@ -32,7 +32,8 @@ class CConfig(ctypes.Structure):
                 ("N_f", ctypes.c_uint32), ("N_c", ctypes.c_uint32), ("N_p", ctypes.c_uint32),
                 ("N_min", ctypes.c_uint32), ("N_max", ctypes.c_uint32),
                 ("feat_dtype", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
-                ("index_format", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("index_format", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("bin_bytes_max", ctypes.c_uint64)]
 
 
 class CngpError(RuntimeError):
@@ -118,6 +119,7 @@ class Config:
     io_dtype: int = F32
     index_format: int = IDX_U8
     flags: int = 0
+    bin_bytes_max: int = 0      # 0 = the library's 8 GiB
 
     @staticmethod
     def from_workload(w, index_format=IDX_U8, flags=0, **over):
@@ -129,7 +131,7 @@ class Config:
 
     def c(self) -> CConfig:
         return CConfig(self.d, self.L, self.F, self.N_f, self.N_c, self.N_p, self.N_min, self.N_max,
-                       self.feat_dtype, self.io_dtype, self.index_format, self.flags)
+                       self.feat_dtype, self.io_dtype, self.index_format, self.flags, self.bin_bytes_max)
 
     @property
     def index_cols(self) -> int:
@@ -199,12 +201,12 @@ def workspace_bytes(cfg: Config, N: int) -> int:
 
 def bwd_plan_info(cfg: Config, N: int) -> dict:
     """How encode_bwd would run for (cfg, N): variant, pre-reduced levels, slices and chunk counts."""
-    info = (ctypes.c_int32 * 14)()
+    info = (ctypes.c_int32 * 15)()
     c = cfg.c()
     _check(_lib.cngp_bwd_plan_info(ctypes.byref(c), N, info))
     names = ("sliced", "dense_levels", "slices_f", "slices_c", "chunks_feat_pts", "chunks_logit_pts",
              "chunks_feat_vtx", "chunks_logit_vtx", "chunks_grid", "grid_slices",
-             "binned", "drain_wgs_feat", "drain_wgs_logit", "bin_chunks")
+             "binned", "drain_wgs_feat", "drain_wgs_logit", "bin_chunks", "passes")
     return dict(zip(names, list(info)))
 
 

@@ -391,7 +391,8 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
                         (uint64_t)c->N_c * c->N_p <= (1ull << 29) && c->N_f <= (1u << 28);
     // (the bins take 8 bytes per reference, level and table: not chosen unasked beyond kMaxAutoBinBytes)
     const uint64_t bin_bytes = ((uint64_t)N << c->d) * 8u * (uint64_t)c->L * (c->N_p > 1 ? 2u : 1u);
-    b.binned = bin_ok && enough && per_level >= kMinBinnedSlicesPerLevel && bin_bytes <= kMaxAutoBinBytes;
+    const uint64_t bin_bytes_max = c->bin_bytes_max ? c->bin_bytes_max : kMaxAutoBinBytes;
+    b.binned = bin_ok && enough && per_level >= kMinBinnedSlicesPerLevel && bin_bytes <= bin_bytes_max;
     if (c->flags & CNGP_BWD_BINNED) b.binned = bin_ok;
     if (c->flags & (CNGP_BWD_DIRECT | CNGP_BWD_SLICED)) b.binned = false;
     if (b.binned) b.sliced = true;
@@ -492,6 +493,24 @@ BwdPlan make_bwd_plan(const cngp_config *c, int64_t N) {
     last_cfg = *c;
     last_N = N;
     return last_plan;
+}
+
+// Points per pass of cngp_encode_bwd.  A batch whose bins would pass the configured limit (or whose references
+// would not fit the 31-bit record positions) is taken in equal passes, each a complete backward over a run
+// of points that accumulates onto the one before, when a pass of that size is binned; otherwise N.
+int64_t bwd_pass_points(const cngp_config *c, int64_t N) {
+    if (N <= 0 || (c->flags & (CNGP_BWD_DIRECT | CNGP_BWD_SLICED))) return N;
+    int64_t most = (((int64_t)1 << 31) - 1) >> c->d;
+    if (!(c->flags & CNGP_BWD_BINNED) || c->bin_bytes_max) {
+        const int64_t per_point = ((int64_t)8 << c->d) * c->L * (c->N_p > 1 ? 2 : 1);
+        const int64_t by_bytes = (int64_t)((c->bin_bytes_max ? c->bin_bytes_max : kMaxAutoBinBytes) / (uint64_t)per_point);
+        if (by_bytes < most) most = by_bytes;
+    }
+    most = most >= 65536 ? most / 65536 * 65536 : most / 1024 * 1024;
+    if (N <= most || most <= 0) return N;
+    const int64_t passes = (N + most - 1) / most;
+    const int64_t per = ((N + passes - 1) / passes + 63) / 64 * 64;
+    return make_bwd_plan_uncached(c, per).binned ? per : N;
 }
 
 // Binned variant: count, offsets, scatter (+ vertex-grid accumulation of the dense levels), drain
@@ -781,19 +800,25 @@ int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l) {
 
 size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N) {
     if (validate(cfg) != CNGP_OK || N <= 0) return 0;
-    return make_bwd_plan(cfg, N).ws_bytes;
+    const int64_t per = bwd_pass_points(cfg, N);
+    if (per >= N) return make_bwd_plan(cfg, N).ws_bytes;
+    const size_t  most = make_bwd_plan_uncached(cfg, per).ws_bytes;          // the last pass is the shorter one
+    const size_t  last = make_bwd_plan_uncached(cfg, N - (N - 1) / per * per).ws_bytes;
+    return most > last ? most : last;
 }
 
 int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info) {
     if (!info) return CNGP_ERR_NULL;
     if (int rc = validate(cfg)) return rc;
     if (N < 0) return CNGP_ERR_INVALID;
-    const BwdPlan b = make_bwd_plan(cfg, N);
+    const int64_t per = bwd_pass_points(cfg, N);
+    const BwdPlan b = make_bwd_plan(cfg, per < N ? per : N);
     const int32_t v[CNGP_PLAN_INFO_COUNT] = {
         b.sliced ? 1 : 0, b.dense.count, (int32_t)b.slices_f, (int32_t)b.slices_c,
         (int32_t)b.feat_pts.chunks, (int32_t)b.logit_pts.chunks, (int32_t)b.feat_vtx.chunks,
         (int32_t)b.logit_vtx.chunks, (int32_t)b.grid.chunks, (int32_t)b.dense_slices,
-        b.binned ? 1 : 0, (int32_t)b.subs_f, (int32_t)b.subs_c, (int32_t)b.bin_chunks};
+        b.binned ? 1 : 0, (int32_t)b.subs_f, (int32_t)b.subs_c, (int32_t)b.bin_chunks,
+        (int32_t)(N > 0 ? (N + per - 1) / per : 1)};
     for (int i = 0; i < CNGP_PLAN_INFO_COUNT; ++i) info[i] = v[i];
     return CNGP_OK;
 }
@@ -834,6 +859,22 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     if (!grad_D_f || !grad_Dhat_c) return CNGP_ERR_NULL;
     if (N > 0 && (!x || !D_f || !Dhat_c || !dy)) return CNGP_ERR_NULL;
     hipStream_t s = (hipStream_t)stream;
+    const int64_t per = bwd_pass_points(cfg, N);
+    if (per < N) {      // several passes over runs of points; the first one clears if asked, the rest accumulate
+        if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < cngp_workspace_bytes(cfg, N))
+            return CNGP_ERR_WORKSPACE;
+        cngp_config   pass = *cfg;
+        const size_t  io = cfg->io_dtype == CNGP_F16 ? 2 : 4;
+        for (int64_t first = 0; first < N; first += per) {
+            const int64_t n = N - first < per ? N - first : per;
+            const int rc = cngp_encode_bwd(&pass, x + first * cfg->d, n, D_f, Dhat_c,
+                                           (const char *)dy + (size_t)first * cfg->L * cfg->F * io, grad_D_f, grad_Dhat_c,
+                                           workspace, workspace_bytes, stream);
+            if (rc) return rc;
+            pass.flags &= ~(uint32_t)CNGP_ZERO_GRADS;
+        }
+        return CNGP_OK;
+    }
     const BwdPlan b = make_bwd_plan(cfg, N);
     if (N > 0 && b.sliced) {
         if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < b.ws_bytes) return CNGP_ERR_WORKSPACE;

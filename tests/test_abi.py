@@ -176,9 +176,17 @@ def test_backward_plan_is_reported_on_the_host():
     assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_SLICED), w.N)["binned"] == 0
     im = W.WORKLOADS["image2d"]
     assert cngp.bwd_plan_info(cngp.Config.from_workload(im), im.N)["binned"] == 0      # ten slices: replicated scan
-    huge = cngp.Config.from_workload(w)                   # 2^25 points: the bins would take 64 GiB, so only on request
-    assert cngp.bwd_plan_info(huge, 2**25)["binned"] == 0 and cngp.workspace_bytes(huge, 2**25) < 8 << 30
-    assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), 2**25)["binned"] == 1
+    huge = cngp.Config.from_workload(w)                   # 2^25 points: the bins would take 64 GiB: 8 passes of 8 GiB
+    ph = cngp.bwd_plan_info(huge, 2**25)
+    assert ph["binned"] == 1 and ph["passes"] == 8 and cngp.workspace_bytes(huge, 2**25) < 10 << 30
+    assert cngp.workspace_bytes(huge, 2**25) == cngp.workspace_bytes(huge, 2**22)
+    pf = cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), 2**25)   # on request: in one pass
+    assert pf["binned"] == 1 and pf["passes"] == 1
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), 2**29)["passes"] == 3   # 2^31 references at most
+    small = cngp.Config.from_workload(w, bin_bytes_max=1 << 30)
+    assert cngp.bwd_plan_info(small, w.N)["passes"] == 1 and cngp.bwd_plan_info(small, 2**22)["passes"] == 8
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(w, bin_bytes_max=1 << 20), w.N)["binned"] == 0    # too small to bin
+    assert p["passes"] == 1 and cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_SLICED), 2**25)["passes"] == 1
     big = W.custom(d=3, L=16, N_f=2**24, N_c=2**24, N_p=2, N_min=16, N_max=2048, N=2**18)
     assert cngp.bwd_plan_info(cngp.Config.from_workload(big), big.N)["sliced"] == 0     # too many slices
 

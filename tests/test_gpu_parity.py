@@ -38,8 +38,8 @@ def run_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8, flags=0):
     return host(y)
 
 
-def run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS, init=None):
-    cfg = cngp.Config.from_workload(w, flags=flags)
+def run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS, init=None, **over):
+    cfg = cngp.Config.from_workload(w, flags=flags, **over)
     gF = torch.full((w.L, w.N_f, w.F), float("nan") if init is None else init, device=DEV)
     gC = torch.full((w.L, w.N_c, w.N_p), float("nan") if init is None else init, device=DEV)
     ws = cngp.alloc_workspace(cfg, x.shape[0])
@@ -212,6 +212,30 @@ def test_binned_backward_tables_of_a_thousand_slices():
     x, D_f, Dhat, dy = tables(w)
     D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
     check_bwd(w, x, D_f, Dhat, dy, paths=("auto", "binned_nopre"))
+
+
+@pytest.mark.parametrize("zero", [True, False])
+@pytest.mark.parametrize("forced", [True, False])
+def test_binned_backward_in_several_passes(zero, forced):
+    """A bound on the bytes of binned references splits the batch into runs of points taken one after the other
+    inside the one call: the first pass clears (if asked), the others add; the last run is shorter."""
+    w = W.custom(cfg=84, d=3, L=8, N_f=2**16, N_c=2**14, N_p=16, N_min=16, N_max=1024, N=150000 + 7,
+                 feat_dtype="f16", io_dtype="f16")
+    per_point = 8 * 2**w.d * w.L * 2
+    limit = 40000 * per_point                       # 39 * 1024 points per pass
+    flags = (cngp.ZERO_GRADS if zero else 0) | (cngp.BWD_BINNED if forced else 0)
+    cfg = cngp.Config.from_workload(w, flags=flags, bin_bytes_max=limit)
+    plan = cngp.bwd_plan_info(cfg, w.N)
+    assert plan["binned"] == 1 and plan["passes"] == 4
+    assert cngp.workspace_bytes(cfg, w.N) < cngp.workspace_bytes(cngp.Config.from_workload(w, flags=flags), w.N) / 3
+    x, D_f, Dhat, dy = tables(w)
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    init = None if zero else 0.25
+    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=flags, init=init, bin_bytes_max=limit)
+    off = 0.0 if zero else 0.25
+    check_close("grad D_f (passes)", gF, gF_ref + off, A_f + off, fp16_out=False)
+    check_close("grad Dhat_c (passes)", gC, gC_ref + off, A_c + off, fp16_out=False)
 
 
 @pytest.mark.parametrize("d", [2, 3])
