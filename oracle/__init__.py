@@ -125,20 +125,22 @@ def encode_bwd_input(w, x, D_f, D_c, dy, res=None):
     return gx, gmag
 
 
-def encode_soft_fwd(w, x, D_f, Dhat_c, res=None):
-    """Softmax-relaxed forward (test helper): float64 [N, L*F]."""
+def encode_soft_fwd(w, x, D_f, Dhat_c, res=None, top_k=0):
+    """Softmax-relaxed forward (test helper): float64 [N, L*F].  top_k > 0: only the top_k largest confidence
+    values of a row keep (softmax) weight."""
     x = _x(w, x); res = _res(w, res)
     N = x.shape[0]
     D_f = _f64(D_f); assert D_f.shape == (w.L, w.N_f, w.F)
     Dhat_c = _f64(Dhat_c); assert Dhat_c.shape == (w.L, w.N_c, w.N_p)
     y = np.zeros((N, w.L * w.F))
     lib().cngp_oracle_encode_soft_fwd(w.d, w.L, w.F, _u32(w.N_f), _u32(w.N_c), _u32(w.N_p), _p(res),
-                                      _p(x), ctypes.c_int64(N), _p(D_f), _p(Dhat_c), _p(y))
+                                      _p(x), ctypes.c_int64(N), _p(D_f), _p(Dhat_c), _u32(top_k), _p(y))
     return y
 
 
-def encode_bwd(w, x, D_f, Dhat_c, dy, res=None, want_abs=True):
-    """Backward.  Returns (gD_f, gDhat_c, A_f, A_c) in float64 (A_* None if not asked)."""
+def encode_bwd(w, x, D_f, Dhat_c, dy, res=None, want_abs=True, top_k=0):
+    """Backward.  Returns (gD_f, gDhat_c, A_f, A_c) in float64 (A_* None if not asked).  top_k > 0: the sparse
+    variant, gradient through the top_k largest confidence values of a row only."""
     x = _x(w, x); res = _res(w, res)
     N = x.shape[0]
     D_f = _f64(D_f); assert D_f.shape == (w.L, w.N_f, w.F)
@@ -148,7 +150,7 @@ def encode_bwd(w, x, D_f, Dhat_c, dy, res=None, want_abs=True):
     Af = np.zeros_like(D_f) if want_abs else None
     Ac = np.zeros_like(Dhat_c) if want_abs else None
     lib().cngp_oracle_encode_bwd(w.d, w.L, w.F, _u32(w.N_f), _u32(w.N_c), _u32(w.N_p), _p(res),
-                                 _p(x), ctypes.c_int64(N), _p(D_f), _p(Dhat_c), _p(dy),
+                                 _p(x), ctypes.c_int64(N), _p(D_f), _p(Dhat_c), _p(dy), _u32(top_k),
                                  _p(gDf), _p(gDc), _p(Af), _p(Ac))
     return gDf, gDc, Af, Ac
 

@@ -154,13 +154,41 @@ static void softmax_row(const double *row, uint32_t N_p, double *sigma)
     for (uint32_t k = 0; k < N_p; ++k) sigma[k] /= s;
 }
 
+/* Weights of the candidates of one row.  top_k == 0 or >= N_p: the softmax of the paper.  Otherwise
+ * the sparse variant (Sec. 5, alternatives to the straight-through softmax; the choice of top-k is this
+ * build's, the paper names the direction only): the top_k largest confidence values, equal values by
+ * lowest index first, a NaN after every number, keep the softmax among themselves; the others get 0. */
+static void candidate_weights(const double *row, uint32_t N_p, uint32_t top_k, double *sigma)
+{
+    if (top_k == 0 || top_k >= N_p) { softmax_row(row, N_p, sigma); return; }
+    int      chosen[64] = {0};
+    double   kept[64];
+    uint32_t at[64];
+    for (uint32_t j = 0; j < top_k; ++j) {
+        int best = -1;
+        for (uint32_t k = 0; k < N_p; ++k) {
+            if (chosen[k]) continue;
+            if (best < 0) { best = (int)k; continue; }
+            const double a = row[k], b = row[best];
+            if ((b != b && a == a) || a > b) best = (int)k;      /* a number beats a NaN; ties keep the lower index */
+        }
+        chosen[best] = 1;
+        kept[j] = row[best];
+        at[j] = (uint32_t)best;
+    }
+    double part[64];
+    softmax_row(kept, top_k, part);
+    for (uint32_t k = 0; k < N_p; ++k) sigma[k] = 0.0;
+    for (uint32_t j = 0; j < top_k; ++j) sigma[at[j]] = part[j];
+}
+
 /* Softmax-relaxed forward: the function whose gradient the backward pass is
  * (Fig. 3 caption: gradients propagate as if the index codebook used a softmax).
  * Test helper; the product has no such entry point. */
 void cngp_oracle_encode_soft_fwd(int d, int L, int F, uint32_t N_f, uint32_t N_c, uint32_t N_p,
                                  const uint32_t *N_l, const float *x, int64_t N,
                                  const double *D_f, const double *Dhat_c /* [L, N_c, N_p] */,
-                                 double *y)
+                                 uint32_t top_k, double *y)
 {
     const int C = 1 << d;
     #pragma omp parallel for schedule(static)
@@ -171,7 +199,7 @@ void cngp_oracle_encode_soft_fwd(int d, int L, int F, uint32_t N_f, uint32_t N_c
                 double acc = 0.0;
                 for (int c = 0; c < C; ++c) {
                     corner_t k = corner_of(x + n * d, d, N_l[l], c, N_f, N_c, N_p);
-                    softmax_row(Dhat_c + ((int64_t)l * N_c + k.h2) * N_p, N_p, sigma);
+                    candidate_weights(Dhat_c + ((int64_t)l * N_c + k.h2) * N_p, N_p, top_k, sigma);
                     double mix = 0.0;
                     for (uint32_t j = 0; j < N_p; ++j)
                         mix += sigma[j] * D_f[((int64_t)l * N_f + k.base + j) * F + f];
@@ -184,7 +212,7 @@ void cngp_oracle_encode_soft_fwd(int d, int L, int F, uint32_t N_f, uint32_t N_c
 
 /* Backward (Sec. 3 "Training"; Fig. 3 caption).  For every corner reference:
  *   g[f]   = weight * dy[n, l*F + f]
- *   sigma  = softmax(D^_c[l][h2][:])
+ *   sigma  = softmax(D^_c[l][h2][:])      (top_k > 0: candidate_weights above, the kept set held fixed)
  *   q_k    = <D_f[l][base + k], g>,  qbar = sum_j sigma_j q_j
  *   gD_f[l][base + k][f] += sigma_k * g[f]
  *   gD^_c[l][h2][k]      += sigma_k * (q_k - qbar)
@@ -194,7 +222,7 @@ void cngp_oracle_encode_soft_fwd(int d, int L, int F, uint32_t N_f, uint32_t N_c
  * the scale that rounding errors of any summation order are proportional to. */
 void cngp_oracle_encode_bwd(int d, int L, int F, uint32_t N_f, uint32_t N_c, uint32_t N_p,
                             const uint32_t *N_l, const float *x, int64_t N,
-                            const double *D_f, const double *Dhat_c, const double *dy,
+                            const double *D_f, const double *Dhat_c, const double *dy, uint32_t top_k,
                             double *gD_f, double *gDhat_c, double *A_f, double *A_c)
 {
     const int C = 1 << d;
@@ -204,7 +232,7 @@ void cngp_oracle_encode_bwd(int d, int L, int F, uint32_t N_f, uint32_t N_c, uin
         for (int64_t n = 0; n < N; ++n)
             for (int c = 0; c < C; ++c) {
                 corner_t k = corner_of(x + n * d, d, N_l[l], c, N_f, N_c, N_p);
-                softmax_row(Dhat_c + ((int64_t)l * N_c + k.h2) * N_p, N_p, sigma);
+                candidate_weights(Dhat_c + ((int64_t)l * N_c + k.h2) * N_p, N_p, top_k, sigma);
                 for (int f = 0; f < F; ++f)
                     g[f] = k.weight * dy[n * (int64_t)(L * F) + l * F + f];
                 double qbar = 0.0, qabar = 0.0;

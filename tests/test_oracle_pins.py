@@ -389,6 +389,98 @@ def test_probe_range_one_backward_is_hash_grid_backward():
     assert np.allclose(gDf, want, rtol=0, atol=1e-13)
 
 
+# --------------------------------------------------------------------------- sparse (top-k) variant
+
+def kept_sets(Dhat, k):
+    """The k largest entries of each row, equal values by lowest index: numpy's stable sort of the negated row."""
+    order = np.argsort(-Dhat.astype(np.float64), axis=-1, kind="stable")[..., :k]
+    keep = np.zeros(Dhat.shape, bool)
+    np.put_along_axis(keep, order, True, axis=-1)
+    return keep
+
+
+@pytest.mark.parametrize("top_k", [1, 2, 4])
+def test_top_k_forward_is_softmax_over_the_kept_set(top_k):
+    """With N_c = 1 the relaxed forward is the mix of the hard forwards of the kept candidates, weighted by the
+    softmax among them (written out here with numpy); rows with equal values keep the lower indices."""
+    w = small(d=2, N_c=1, N_p=8, L=2)
+    x, D_f, Dhat, _ = random_tables(w, seed=41)
+    Dhat = Dhat.copy()
+    Dhat[1, 0, 5] = Dhat[1, 0, 2] = Dhat[1, 0].max() + 1.0          # a tie for the first place on level 1
+    keep = kept_sets(Dhat, top_k)
+    assert keep[1, 0, 2] and (top_k > 1) == bool(keep[1, 0, 5])
+    ys = oracle.encode_soft_fwd(w, x, D_f, Dhat, top_k=top_k)
+    mix = np.zeros_like(ys)
+    for l in range(w.L):
+        e = np.where(keep[l, 0], np.exp(Dhat[l, 0].astype(np.float64)), 0.0); s = e / e.sum()
+        for k in range(w.N_p):
+            D_c = np.zeros((w.L, 1), np.uint8); D_c[l, 0] = k
+            yk, _ = oracle.encode_fwd(w, x, D_f, D_c)
+            mix[:, l * w.F:(l + 1) * w.F] += s[k] * yk[:, l * w.F:(l + 1) * w.F]
+    assert np.allclose(ys, mix, rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("d,top_k", [(2, 2), (3, 4), (3, 3)])
+def test_top_k_backward_matches_finite_differences_and_invariants(d, top_k):
+    """Gradient of the top-k relaxed forward with the kept sets held fixed (small steps do not change them for
+    generic values), zero outside the kept sets, and the invariants of the dense variant."""
+    w = small(d=d, N=120)
+    x, D_f, Dhat, dy = random_tables(w, seed=43)
+    Dh64 = Dhat.astype(np.float64)
+    gDf, gDc, Af, Ac = oracle.encode_bwd(w, x, D_f, Dhat, dy, top_k=top_k)
+    keep = kept_sets(Dhat, top_k)
+    assert np.all(gDc[~keep] == 0.0) and np.all(Ac[~keep] == 0.0)
+    assert np.count_nonzero(gDc) > 0.5 * np.count_nonzero(oracle.encode_bwd(w, x, D_f, Dhat, dy)[1]) * top_k / w.N_p
+    assert np.allclose(gDc.sum(axis=2), 0.0, rtol=0, atol=1e-12)
+    assert np.allclose(gDf.sum(axis=1), dy.reshape(w.N, w.L, w.F).sum(axis=0), rtol=0, atol=1e-11)
+    lhs = float(np.sum(oracle.encode_soft_fwd(w, x, D_f, Dhat, top_k=top_k) * dy))
+    assert abs(lhs - float(np.sum(D_f * gDf))) <= 1e-12 * max(1.0, abs(lhs))
+
+    def loss(Df, Dh):
+        return float(np.sum(oracle.encode_soft_fwd(w, x, Df, Dh, top_k=top_k) * dy))
+    rng = np.random.default_rng(2)
+    for idx in np.argsort(-np.abs(gDf).ravel())[:5].tolist() + rng.integers(0, gDf.size, 4).tolist():
+        i = np.unravel_index(idx, gDf.shape)
+        Dp = D_f.copy(); Dp[i] += 1e-3
+        Dm = D_f.copy(); Dm[i] -= 1e-3
+        fd = (loss(Dp, Dh64) - loss(Dm, Dh64)) / 2e-3
+        assert abs(fd - gDf[i]) <= 1e-8 * max(1.0, abs(gDf[i]))
+    for idx in np.argsort(-np.abs(gDc).ravel())[:8].tolist() + rng.integers(0, gDc.size, 6).tolist():
+        i = np.unravel_index(idx, gDc.shape)
+        row = np.sort(Dh64[i[0], i[1]])
+        if np.min(np.diff(row)) < 1e-3:
+            continue                                              # a step could reorder this row
+        Dp = Dh64.copy(); Dp[i] += 1e-5
+        Dm = Dh64.copy(); Dm[i] -= 1e-5
+        fd = (loss(D_f, Dp) - loss(D_f, Dm)) / 2e-5
+        assert abs(fd - gDc[i]) <= 1e-6 * max(1.0, abs(gDc[i]))
+
+
+def test_top_k_limits():
+    """top_k = N_p (or 0) is the paper's softmax; top_k = 1 is training of the hard forward: no logit gradient, the
+    feature gradient of the baked codebook; a NaN confidence is never kept while a number is left."""
+    w = small(d=3)
+    x, D_f, Dhat, dy = random_tables(w, seed=47)
+    full = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    for k in (0, w.N_p, w.N_p + 3):
+        g = oracle.encode_bwd(w, x, D_f, Dhat, dy, top_k=k)
+        assert all(np.array_equal(a, b) for a, b in zip(g, full))
+    g1 = oracle.encode_bwd(w, x, D_f, Dhat, dy, top_k=1)
+    assert np.all(g1[1] == 0.0)
+    D_c = oracle.bake_probes(Dhat)
+    yh, _ = oracle.encode_fwd(w, x, D_f, D_c)
+    assert np.allclose(oracle.encode_soft_fwd(w, x, D_f, Dhat, top_k=1), yh, rtol=0, atol=1e-15)
+    for idx in np.argsort(-np.abs(g1[0]).ravel())[:6]:
+        i = np.unravel_index(idx, g1[0].shape)
+        Dp = D_f.copy(); Dp[i] += 1.0
+        fd = float(np.sum((oracle.encode_fwd(w, x, Dp, D_c)[0] - yh) * dy))
+        assert abs(fd - g1[0][i]) <= 1e-10 * max(1.0, abs(fd))
+    bad = Dhat.astype(np.float64).copy()
+    bad[:, :, 0] = np.nan                                         # candidate 0 is never among the kept two
+    g2 = oracle.encode_bwd(w, x, D_f, bad, dy, top_k=2)
+    assert np.all(np.isfinite(g2[0])) and np.all(g2[1][:, :, 0] == 0.0) and np.all(g2[0].reshape(w.L, -1, w.N_p, w.F)[:, :, 0] == 0.0)
+
+
 # --------------------------------------------------------------------------- bake
 
 def test_bake_properties():
