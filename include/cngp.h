@@ -91,6 +91,13 @@ typedef struct {
     uint64_t bin_bytes_max; /* most workspace cngp_encode_bwd spends on binned references (8 bytes per
                               corner reference, level and gradient table); 0 = 8 GiB.  A larger batch
                               is taken in several passes inside the one call                      */
+    uint32_t top_k;        /* cngp_encode_bwd only.  0 or N_p: the paper's backward (softmax over all N_p
+                              candidates of a row).  1 .. N_p - 1: sparse variant (Sec. 5 names sparse
+                              alternatives to the dense softmax as future work; top-k is this library's
+                              choice): per row of D^_c only the top_k largest confidence values, equal
+                              values by lowest index first and any number before a NaN, keep the softmax
+                              among themselves; the other candidates get weight 0, hence no gradient    */
+    uint32_t reserved;     /* must be 0                                                                 */
 } cngp_config;
 
 /* Grid resolution of every level (Table 1: N_min, N_max, L; geometric growth):
@@ -132,6 +139,8 @@ int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const
  * q_k = <D_f[l][base + k], g>,
  *     grad_D_f[l][base + k][f]       += sigma_k * g[f]                    for all k < N_p
  *     grad_Dhat_c[l][hash2(v)][k]    += sigma_k * (q_k - sum_j sigma_j q_j)
+ * With cfg->top_k in 1 .. N_p - 1, sigma is the sparse weight vector described at cngp_config.top_k
+ * (the kept set is treated as constant).
  * Uses D^_c only, never D_c.  No gradient with respect to x.
  *   Dhat_c       dev float32 [L, N_c, N_p]
  *   dy           dev io_dtype [N, L*F]

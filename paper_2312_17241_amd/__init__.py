@@ -33,7 +33,7 @@ class CConfig(ctypes.Structure):
                 ("N_min", ctypes.c_uint32), ("N_max", ctypes.c_uint32),
                 ("feat_dtype", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
                 ("index_format", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("bin_bytes_max", ctypes.c_uint64)]
+                ("bin_bytes_max", ctypes.c_uint64), ("top_k", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class CngpError(RuntimeError):
@@ -120,6 +120,7 @@ class Config:
     index_format: int = IDX_U8
     flags: int = 0
     bin_bytes_max: int = 0      # 0 = the library's 8 GiB
+    top_k: int = 0              # backward: 0 = softmax over all N_p candidates; else over the top_k largest only
 
     @staticmethod
     def from_workload(w, index_format=IDX_U8, flags=0, **over):
@@ -131,7 +132,7 @@ class Config:
 
     def c(self) -> CConfig:
         return CConfig(self.d, self.L, self.F, self.N_f, self.N_c, self.N_p, self.N_min, self.N_max,
-                       self.feat_dtype, self.io_dtype, self.index_format, self.flags, self.bin_bytes_max)
+                       self.feat_dtype, self.io_dtype, self.index_format, self.flags, self.bin_bytes_max, self.top_k, 0)
 
     @property
     def index_cols(self) -> int:

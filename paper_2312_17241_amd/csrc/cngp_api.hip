@@ -50,6 +50,7 @@ int validate(const cngp_config *c) {
     if (c->index_format == CNGP_IDX_PACKED4 && c->N_c < 2) return CNGP_ERR_INVALID;
     if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE | CNGP_FWD_SIMPLE | CNGP_BWD_BINNED)) return CNGP_ERR_INVALID;
     if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & (CNGP_BWD_SLICED | CNGP_BWD_BINNED))) return CNGP_ERR_INVALID;
+    if (c->top_k > c->N_p || c->reserved != 0) return CNGP_ERR_INVALID;
     if (c->F != 2) return CNGP_ERR_UNSUPPORTED;
     return CNGP_OK;
 }
@@ -74,6 +75,7 @@ Params make_params(const cngp_config *c) {
     p.row_mask = c->N_f / c->N_p - 1;
     p.c_mask = c->N_c - 1;
     p.log2_Np = ilog2(c->N_p);
+    p.top_k = (c->top_k && c->top_k < c->N_p) ? c->top_k : 0;
     return p;
 }
 
@@ -635,7 +637,7 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
         LaunchTimer t(s, K_BWD_PREP);
         bwd_prep_kernel<NP, PairT><<<(unsigned)blocks, kBlock, 0, s>>>(
             zero.seg, (uint32_t)zero.n, (uint32_t)zero_blocks, Dhat_c, sigma, elems, (uint32_t)softmax_blocks,
-            (const PairT *)dy, (PairT *)dyT, N, c->L);
+            (const PairT *)dy, (PairT *)dyT, N, c->L, p.top_k);
         zero.n = 0;
         zero.largest = 0;
         if (int rc = launch_status("bwd_prep_kernel")) return rc;

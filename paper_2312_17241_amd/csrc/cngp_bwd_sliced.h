@@ -104,14 +104,15 @@ __device__ __forceinline__ void wave_lds_fence() {
 }
 
 // ------------------------------------------------------------------ preparation
-// sigma[r][k] = softmax(D^_c[r][:])_k, one lane per element, NP lanes per row.
+// sigma[r][k] = softmax(D^_c[r][:])_k, one lane per element, NP lanes per row (top_k > 0: over the kept
+// candidates only, 0 for the others).
 template <int NP>
 __device__ __forceinline__ void softmax_rows(const float *__restrict__ Dhat_c, float *__restrict__ sigma,
-                                             const int64_t elems, const uint32_t block)
+                                             const int64_t elems, const uint32_t block, const uint32_t top_k)
 {
     const int64_t i = (int64_t)block * kBlock + threadIdx.x;
     if (i >= elems) return;                       // elems is a multiple of NP: whole rows leave together
-    const float v = Dhat_c[i];
+    const float v = keep_top_k<NP>(Dhat_c[i], (int)(threadIdx.x % NP), top_k);
     const float m = group_max<NP>(v);
     const float e = expf(v - m);
     sigma[i] = e / group_sum<NP>(e);
@@ -134,7 +135,7 @@ template <int NP, typename PairT>
 __global__ __launch_bounds__(kBlock) void bwd_prep_kernel(
     const ZeroSegments seg, const uint32_t seg_count, const uint32_t zero_blocks,
     const float *__restrict__ Dhat_c, float *__restrict__ sigma, const int64_t elems, const uint32_t softmax_blocks,
-    const PairT *__restrict__ dy, PairT *__restrict__ dyT, const int64_t N, const int L)
+    const PairT *__restrict__ dy, PairT *__restrict__ dyT, const int64_t N, const int L, const uint32_t top_k)
 {
     uint32_t b = blockIdx.x;
     if (b < seg_count * zero_blocks) {
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(kBlock) void bwd_prep_kernel(
     }
     b -= seg_count * zero_blocks;
     if (b < softmax_blocks) {
-        softmax_rows<NP>(Dhat_c, sigma, elems, b);
+        softmax_rows<NP>(Dhat_c, sigma, elems, b, top_k);
         return;
     }
     transpose_rows<PairT>(dy, dyT, N, L, b - softmax_blocks);

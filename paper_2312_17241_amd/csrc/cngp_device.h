@@ -24,6 +24,7 @@ struct Params {
     uint32_t row_mask;          // N_f / N_p - 1 : hashed most significant bits of the index
     uint32_t c_mask;            // N_c - 1
     uint32_t log2_Np;
+    uint32_t top_k;             // backward only: 0 = every candidate of a row keeps weight, else the top_k largest
 };
 
 // The cell of one level that contains a point: lower vertex, fractional position and the

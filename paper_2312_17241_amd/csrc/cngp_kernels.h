@@ -237,6 +237,24 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
+// Sparse variant of the backward: the confidence value of candidate k as the softmax should see it --
+// itself when it is among the top_k largest of its row (equal values: lowest index first; a NaN after
+// every number), minus infinity otherwise, which gives it weight exactly 0.  The NP lanes of a row call
+// this together.
+template <int NP>
+__device__ __forceinline__ float keep_top_k(const float v, const int k, const uint32_t top_k) {
+    if (NP == 1 || top_k == 0 || top_k >= (uint32_t)NP) return v;
+    uint32_t ahead = 0;                            // candidates ranked before this one
+    const int first = (int)(threadIdx.x & 63u) - k;
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+        const float o = __shfl(v, first + j, 64);
+        const bool  o_num = o == o, v_num = v == v;
+        ahead += ((o_num && !v_num) || (o_num == v_num && (o > v || ((o == v || !v_num) && j < k)))) ? 1u : 0u;
+    }
+    return ahead < top_k ? v : -INFINITY;
+}
+
 // Direct backward: NP adjacent lanes own one (point, level) pair and walk its 2^d corners;
 // lane k is candidate k of the probing range, so the NP lanes read and update one contiguous
 // row of D^_c / grad D^_c and one contiguous run of D_f / grad D_f per corner.
@@ -269,7 +287,7 @@ __global__ __launch_bounds__(kBlock) void encode_bwd_direct_kernel(
     for (int c = 0; c < (1 << D); ++c) {
         const uint32_t entry = probe_base(cell.hash1(c), p) + k;
         const uint32_t slot  = (cell.hash2(c) & p.c_mask) * NP + k;
-        const float    logit = C_l[slot];
+        const float    logit = keep_top_k<NP>(C_l[slot], k, p.top_k);
         const float2   feat  = load_pair(F_l, entry);
         const float    wt = cell.weight(c);
         const float    g0 = wt * g_up.x, g1 = wt * g_up.y;

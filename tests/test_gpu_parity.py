@@ -64,11 +64,12 @@ BWD_PATHS = {"auto": 0, "direct": cngp.BWD_DIRECT, "sliced": cngp.BWD_SLICED,
              "binned": cngp.BWD_BINNED, "binned_nopre": cngp.BWD_BINNED | cngp.BWD_NO_PREREDUCE}
 
 
-def check_bwd(w, x, D_f, Dhat, dy, name="", paths=("auto", "direct", "sliced", "sliced_nopre", "binned", "binned_nopre")):
-    gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+def check_bwd(w, x, D_f, Dhat, dy, name="", paths=("auto", "direct", "sliced", "sliced_nopre", "binned", "binned_nopre"),
+              top_k=0):
+    gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy, top_k=top_k)
     worst = (0.0, 0.0)
     for path in paths:
-        gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS | BWD_PATHS[path])
+        gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS | BWD_PATHS[path], top_k=top_k)
         e1 = check_close(f"grad D_f {name} [{path}]", gF, gF_ref, A_f, fp16_out=False)
         e2 = check_close(f"grad Dhat_c {name} [{path}]", gC, gC_ref, A_c, fp16_out=False)
         worst = (max(worst[0], e1), max(worst[1], e2))
@@ -212,6 +213,30 @@ def test_binned_backward_tables_of_a_thousand_slices():
     x, D_f, Dhat, dy = tables(w)
     D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
     check_bwd(w, x, D_f, Dhat, dy, paths=("auto", "binned_nopre"))
+
+
+@pytest.mark.parametrize("d,N_p,top_k", [(3, 16, 1), (3, 16, 2), (3, 16, 4), (3, 16, 5), (3, 16, 8), (3, 16, 16),
+                                         (2, 8, 1), (2, 8, 2), (2, 8, 4), (3, 4, 2), (2, 2, 1), (3, 4, 3)])
+def test_sparse_backward_parity(d, N_p, top_k):
+    """The sparse variant (softmax over the top_k largest confidence values of a row) in every way the library can
+    run the backward.  Half of the rows hold values from a coarse lattice, so equal values are common and
+    the rule for them (lowest index first) decides the kept set."""
+    w = sweep_workload(d, N_p, "f16", "f16")
+    x, D_f, Dhat, dy = tables(w)
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    Dhat = Dhat.copy()
+    Dhat[:, ::2] = np.round(Dhat[:, ::2] * 2.0) / 2.0             # values k / 2: many ties
+    assert np.mean(np.sort(Dhat[:, ::2], axis=-1)[..., 1:] == np.sort(Dhat[:, ::2], axis=-1)[..., :-1]) > 0.05
+    check_bwd(w, x, D_f, Dhat, dy, top_k=top_k)
+
+
+def test_sparse_backward_never_keeps_a_nan_before_a_number():
+    w = sweep_workload(3, 8, "f32", "f32", N=2000)
+    x, D_f, Dhat, dy = tables(w)
+    Dhat = Dhat.copy()
+    Dhat[:, :, 3] = np.nan
+    Dhat[:, ::3, 6] = np.nan
+    check_bwd(w, x, D_f, Dhat, dy, top_k=4)
 
 
 @pytest.mark.parametrize("zero", [True, False])
