@@ -61,6 +61,9 @@ def main():
                     help="adds the 64-wide decoder after the encoding: forward, residual against a fixed random target, "
                          "backward (its dL/dy feeds the encoding's backward), and with --with-optimizer its Adam step.  "
                          "Not the headline configuration.")
+    ap.add_argument("--top-k", type=int, default=0, metavar="K",
+                    help="backward: softmax over the K largest confidence values of a row only (the sparse variant; "
+                         "0 = the paper's dense softmax, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -87,7 +90,7 @@ def main():
     fwd_only = args.workload in ("infer3d", "compact3d")
     fmt = {"infer3d": cngp.IDX_PACKED4, "compact3d": cngp.IDX_BITS}.get(args.workload, cngp.IDX_U8)
     bwd_flag = {"auto": 0, "direct": cngp.BWD_DIRECT, "sliced": cngp.BWD_SLICED, "binned": cngp.BWD_BINNED}[args.bwd]
-    cfg = cngp.Config.from_workload(w, index_format=fmt, flags=cngp.ZERO_GRADS | bwd_flag)
+    cfg = cngp.Config.from_workload(w, index_format=fmt, flags=cngp.ZERO_GRADS | bwd_flag, top_k=args.top_k)
 
     x_h = W.make_points(w)
     D_f_h = W.make_feature_codebook(w)
@@ -230,7 +233,8 @@ def main():
                    "step": ("bake + encoding and decoder forward in one kernel" if fused_dec else "bake + fwd") if fwd_only else
                            (("decoder fwd/bwd + " if with_dec else "") +
                             ("Adam step fused with bake + fwd + bwd (grads cleared each step)" if with_opt else
-                             "bake + fwd + bwd (grads cleared each step)"))},
+                             "bake + fwd + bwd (grads cleared each step)") +
+                            (f"; sparse backward, top_k = {args.top_k}" if args.top_k else ""))},
         "roofline": roofline,
         "bwd_plan": None if fwd_only else cngp.bwd_plan_info(cfg, N),
         "kernels_us_per_step": {k: round(v["ms"] * 1e3 / args.steps, 2) for k, v in per_kernel.items()},
@@ -302,7 +306,7 @@ def main():
             a, b = 64 * w.L * w.F, 64 * w.L * w.F + 64 * 64
             dec_ref, dec_mag, _ = oracle.mlp_fwd(y_ref, Wh[:a].reshape(64, -1), Wh[a:b].reshape(64, 64), Wh[b:].reshape(3, 64), want_mag=True)
         if not fwd_only:
-            g_ref = oracle.encode_bwd(w, xs, D_f_h, Dhat_h, dy_h[:n_cpu], want_abs=not args.no_check)
+            g_ref = oracle.encode_bwd(w, xs, D_f_h, Dhat_h, dy_h[:n_cpu], want_abs=not args.no_check, top_k=args.top_k)
         t_cpu = time.perf_counter() - t0
         if not args.no_cpu_baseline:
             out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 1), "unit": "points/s",

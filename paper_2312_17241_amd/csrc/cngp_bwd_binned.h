@@ -282,12 +282,20 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
 }
 
 // ------------------------------------------------------------------ drain
-// Value of lane `u` of this lane's group of NP lanes.  A group of 16 is a DPP row: one VALU move.
+// Value of lane `u` of this lane's group of NP lanes.  Groups of 16 (a DPP row), 4 and 2 (inside a quad): one VALU move.
 template <int NP, int U>
 __device__ __forceinline__ uint32_t group_bcast(const uint32_t v) {
-    if (NP == 16) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x150 + U, 0xF, 0xF, false);   // row_newbcast:U
-    if (NP == 1) return v;
-    return (uint32_t)__shfl((int)v, (int)((threadIdx.x & 63u & ~(uint32_t)(NP - 1)) + U), 64);
+    if constexpr (NP == 16) {                                             // row_newbcast:U
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x150 + U, 0xF, 0xF, false);
+    } else if constexpr (NP == 4) {                                       // quad_perm:[U,U,U,U]
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, U * 0x55, 0xF, 0xF, false);
+    } else if constexpr (NP == 2) {                                       // quad_perm:[U,U,U+2,U+2]
+        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, U * 0x05 + (U + 2) * 0x50, 0xF, 0xF, false);
+    } else if constexpr (NP == 1) {
+        return v;
+    } else {
+        return (uint32_t)__shfl((int)v, (int)((threadIdx.x & 63u & ~(uint32_t)(NP - 1)) + U), 64);
+    }
 }
 
 __device__ __forceinline__ float2 pair_to_float2(const float2 v) { return v; }

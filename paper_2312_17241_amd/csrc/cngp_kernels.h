@@ -237,14 +237,12 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
-// Sparse variant of the backward: the confidence value of candidate k as the softmax should see it --
-// itself when it is among the top_k largest of its row (equal values: lowest index first; a NaN after
-// every number), minus infinity otherwise, which gives it weight exactly 0.  The NP lanes of a row call
-// this together.
+// Sparse variant of the backward: how many candidates of its row are ranked before candidate k, which
+// holds confidence value v (larger first; equal values: lowest index first; a NaN after every number).
+// The NP lanes of a row call this together.
 template <int NP>
-__device__ __forceinline__ float keep_top_k(const float v, const int k, const uint32_t top_k) {
-    if (NP == 1 || top_k == 0 || top_k >= (uint32_t)NP) return v;
-    uint32_t ahead = 0;                            // candidates ranked before this one
+__device__ __forceinline__ uint32_t rank_in_row(const float v, const int k) {
+    uint32_t ahead = 0;
     const int first = (int)(threadIdx.x & 63u) - k;
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
@@ -252,7 +250,14 @@ __device__ __forceinline__ float keep_top_k(const float v, const int k, const ui
         const bool  o_num = o == o, v_num = v == v;
         ahead += ((o_num && !v_num) || (o_num == v_num && (o > v || ((o == v || !v_num) && j < k)))) ? 1u : 0u;
     }
-    return ahead < top_k ? v : -INFINITY;
+    return ahead;
+}
+// The confidence value as the softmax should see it: itself when it is among the top_k largest of its
+// row, minus infinity otherwise, which gives the candidate weight exactly 0.
+template <int NP>
+__device__ __forceinline__ float keep_top_k(const float v, const int k, const uint32_t top_k) {
+    if (NP == 1 || top_k == 0 || top_k >= (uint32_t)NP) return v;
+    return rank_in_row<NP>(v, k) < top_k ? v : -INFINITY;
 }
 
 // Direct backward: NP adjacent lanes own one (point, level) pair and walk its 2^d corners;
