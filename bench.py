@@ -51,7 +51,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="nerf3d", help="nerf3d (headline) | image2d | sdf3d | tiny2d | infer3d | compact3d")
+    ap.add_argument("--workload", default="nerf3d", help="nerf3d (headline) | image2d | sdf3d | tiny2d | infer3d | infer3d_plain | compact3d")
     ap.add_argument("--bwd", default="auto", choices=["auto", "direct", "sliced", "binned"],
                     help="force a variant of the backward pass (default: the library's own choice)")
     ap.add_argument("--with-optimizer", action="store_true",
@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--top-k", type=int, default=0, metavar="K",
                     help="backward: softmax over the K largest confidence values of a row only (the sparse variant; "
                          "0 = the paper's dense softmax, the headline)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measurements reported beside the headline: per-step median / min, cold caches, "
+                         "Morton-ordered points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -87,7 +90,7 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     w = W.WORKLOADS[args.workload]
-    fwd_only = args.workload in ("infer3d", "compact3d")
+    fwd_only = args.workload in ("infer3d", "infer3d_plain", "compact3d")
     fmt = {"infer3d": cngp.IDX_PACKED4, "compact3d": cngp.IDX_BITS}.get(args.workload, cngp.IDX_U8)
     bwd_flag = {"auto": 0, "direct": cngp.BWD_DIRECT, "sliced": cngp.BWD_SLICED, "binned": cngp.BWD_BINNED}[args.bwd]
     cfg = cngp.Config.from_workload(w, index_format=fmt, flags=cngp.ZERO_GRADS | bwd_flag, top_k=args.top_k)
@@ -201,6 +204,77 @@ def main():
     kernels = cngp.profile_read()
     cngp.profile_enable(False)
 
+    # Beside the headline (never part of `value`): the spread of single steps, the same step with cold caches,
+    # and the same batch in Morton order.
+    extras = {}
+    if not args.no_extras:
+        def steps_with_events(k, before=None):
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k)]
+            for a, b in ev:
+                if before is not None:
+                    before()
+                a.record()
+                step()
+                b.record()
+            torch.cuda.synchronize()
+            return sorted(a.elapsed_time(b) for a, b in ev)
+
+        t = steps_with_events(min(args.steps, 50))
+        extras["single_steps_ms"] = {"median": round(t[len(t) // 2], 4), "min": round(t[0], 4), "n": len(t),
+                                     "note": "each step bracketed by its own pair of events on the launch stream"}
+        # cold: 512 MiB written between steps pushes tables, points and workspace out of L2 and the 256 MB memory-side cache
+        scrub = torch.empty(1 << 29, dtype=torch.uint8, device=dev)
+        t = steps_with_events(10, before=lambda: scrub.fill_(1))
+        del scrub
+        extras["cold_cache"] = {"ms_per_step_median": round(t[len(t) // 2], 4), "ms_per_step_min": round(t[0], 4), "n": len(t),
+                                "value": round(N / (t[len(t) // 2] * 1e-3), 1), "unit": "points/s",
+                                "note": "512 MiB scrub buffer written before every step"}
+        if not with_opt and not args.with_decoder:
+            # Morton order: points sorted by the interleaved bits of their coordinates (10 bits per axis in 3D, 16 in 2D)
+            bits = 10 if w.d == 3 else 16
+
+            def interleave(q):                                   # q: integer coordinates [N, d], int64 (numpy or torch)
+                code = q[:, 0] * 0
+                for b in range(bits):
+                    for j in range(w.d):
+                        code |= ((q[:, j] >> b) & 1) << (b * w.d + j)
+                return code
+            t0 = time.perf_counter()
+            q_h = np.clip(x_h.astype(np.float32) * np.float32(1 << bits), 0, (1 << bits) - 1).astype(np.int64)
+            perm_h = np.argsort(interleave(q_h), kind="stable")
+            sort_host = time.perf_counter() - t0
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for attempt in range(2):                             # the first pass pays torch's one-time set-up; the second is timed
+                e0.record()
+                q = (x * float(1 << bits)).clamp_(0, (1 << bits) - 1).to(torch.int64)
+                perm = torch.sort(interleave(q), stable=True).indices
+                x_sorted = x.index_select(0, perm)
+                dy_sorted = None if fwd_only else dy.index_select(0, perm)
+                e1.record()
+                torch.cuda.synchronize()
+            assert np.array_equal(perm.cpu().numpy(), perm_h)
+            x_nat, x = x, x_sorted
+            if not fwd_only:
+                dy_nat, dy = dy, dy_sorted
+            for _ in range(args.warmup):
+                step()
+            torch.cuda.synchronize()
+            m0 = time.perf_counter()
+            for _ in range(args.steps):
+                step()
+            torch.cuda.synchronize()
+            m1 = time.perf_counter()
+            x = x_nat
+            if not fwd_only:
+                dy = dy_nat
+            step()                                               # y and the gradients of the natural order again, for the check
+            torch.cuda.synchronize()
+            extras["morton_order"] = {"value": round(N * args.steps / (m1 - m0), 1), "unit": "points/s",
+                                      "ms_per_step": round((m1 - m0) * 1e3 / args.steps, 4),
+                                      "sort_ms_gpu": round(e0.elapsed_time(e1), 3), "sort_ms_host_numpy": round(sort_host * 1e3, 1),
+                                      "note": "same batch, points (and their dL/dy rows) sorted by Morton code first; the sort "
+                                              "(torch: codes, stable sort, two row gathers) is not part of the step"}
+
     # roofline of the dominant kernel kind
     alg = algorithmic_bytes(w, N, cfg.index_cols)
     per_kernel = {}
@@ -236,6 +310,7 @@ def main():
                              "bake + fwd + bwd (grads cleared each step)") +
                             (f"; sparse backward, top_k = {args.top_k}" if args.top_k else ""))},
         "roofline": roofline,
+        "beside_the_headline": extras or None,
         "bwd_plan": None if fwd_only else cngp.bwd_plan_info(cfg, N),
         "kernels_us_per_step": {k: round(v["ms"] * 1e3 / args.steps, 2) for k, v in per_kernel.items()},
         "kernel_parts": {k: v["parts"] for k, v in per_kernel.items() if len(v["parts"]) > 1},
@@ -296,7 +371,7 @@ def main():
         sys.path.insert(0, os.path.join(ROOT, "tests"))
         from parity import check_close, check_exact
         # bounded sample of the same workload for the CPU leg: the first n_cpu points
-        n_cpu = min(N, 1 << 18)
+        n_cpu = min(N, 1 << 22 if fwd_only else 1 << 18)
         xs = x_h[:n_cpu]
         t0 = time.perf_counter()
         D_c_ref = oracle.bake_probes(Dhat_h)

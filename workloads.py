@@ -55,6 +55,10 @@ WORKLOADS = {
     # Inference-only 3D: forward with the baked, 4-bit packed index codebook.
     "infer3d": Workload("infer3d", 5, 3, 16, 2, 2**16, 2**14, 16, 16, 2048, 2**24,
                         "f16", "f16", "uniform"),
+    # The same inference with plain hashing at the same feature codebook size (N_p = 1: no index codebook): what the
+    # learned probes cost at inference time (Sec. 4 compares against this baseline encoding).
+    "infer3d_plain": Workload("infer3d_plain", 5, 3, 16, 2, 2**16, 1, 1, 16, 2048, 2**24,
+                              "f16", "f16", "uniform"),
     # Inference from the compressed model of the paper's Table 3 row (N_f = 2^8, N_c = 2^16, N_p = 2^3):
     # forward with the index codebook stored at exactly 3 bits per entry.
     "compact3d": Workload("compact3d", 6, 3, 16, 2, 2**8, 2**16, 8, 16, 2048, 2**22,
