@@ -93,12 +93,12 @@ int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INV
 // ---------------------------------------------------------------- per-kernel timing
 enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_PREP, K_BWD_SLICED, K_BWD_SLICED_V, K_BWD_GRID_DRAIN,
                 K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD,
-                K_BWD_BIN_COUNT, K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_FUSED_FWD, K_COUNT };
+                K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_FUSED_FWD, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_prepare",
                                            "encode_bwd_sliced_points_and_grid", "encode_bwd_sliced_vertices",
                                            "encode_bwd_bin_grid_sums", "bake_probes", "zero", "debug_indices",
                                            "adam_step_bake", "mlp_fwd", "mlp_bwd",
-                                           "encode_bwd_bin_count", "encode_bwd_bin_offsets", "encode_bwd_bin_scatter",
+                                           "encode_bwd_bin_offsets", "encode_bwd_bin_scatter",
                                            "encode_bwd_bin_drain", "encode_bwd_input", "encode_mlp_fwd"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
@@ -515,7 +515,24 @@ int64_t bwd_pass_points(const cngp_config *c, int64_t N) {
     return make_bwd_plan_uncached(c, per).binned ? per : N;
 }
 
-// Binned variant: count, offsets, scatter (+ vertex-grid accumulation of the dense levels), drain
+template <int NP>
+BinParams make_bin_params(const cngp_config *c, const BwdPlan &b, int64_t N) {
+    BinParams bp;
+    std::memset(&bp, 0, sizeof(bp));
+    bp.level0 = b.dense.count;
+    bp.nlevels = c->L - b.dense.count;
+    bp.rows_f_log2 = b.rows_f_log2; bp.slices_f = b.slices_f;
+    bp.rows_c_log2 = b.rows_c_log2; bp.slices_c = NP > 1 ? b.slices_c : 0;
+    bp.chunks = b.bin_chunks; bp.chunk_pts = b.bin_chunk_pts;
+    bp.cap = (uint32_t)((uint64_t)N << c->d);
+    bp.dense_bins = b.dense.count > 0 ? 1 : 0;
+    return bp;
+}
+// Bins of the level with the most of them, and the copies of the histogram the count keeps in LDS.
+uint32_t most_bins_of(const BinParams &bp) { return bp.slices_f + bp.slices_c > kGridBins ? bp.slices_f + bp.slices_c : kGridBins; }
+uint32_t hist_replicas_of(uint32_t most_bins) { return most_bins <= 64 ? 16u : most_bins <= 512 ? 4u : 1u; }
+
+// Binned variant: (the count has run with the preparation launch) offsets, scatter (+ vertex-grid accumulation of the dense levels), drain
 // (+ the two roles of the dense levels, which scan the finished vertex grids).
 template <int D, int NP, typename FeatT, typename IoT>
 int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, const float *x, int64_t N,
@@ -529,30 +546,16 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     uint32_t *cntG = (uint32_t *)(ws + b.cntG_off), *baseG = (uint32_t *)(ws + b.baseG_off);
     uint2    *recG = (uint2 *)(ws + b.recG_off);
     const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
-    BinParams bp;
-    std::memset(&bp, 0, sizeof(bp));
-    bp.level0 = Ld; bp.nlevels = Lh;
-    bp.rows_f_log2 = b.rows_f_log2; bp.slices_f = b.slices_f;
-    bp.rows_c_log2 = b.rows_c_log2; bp.slices_c = NP > 1 ? b.slices_c : 0;
-    bp.chunks = b.bin_chunks; bp.chunk_pts = b.bin_chunk_pts;
-    bp.cap = (uint32_t)((uint64_t)N << c->d);
-    bp.dense_bins = Ld > 0 ? 1 : 0;
+    const BinParams bp = make_bin_params<NP>(c, b, N);
     const int64_t blocks = (int64_t)(Lh + Ld) * bp.chunks;
     if (int rc = check_blocks(blocks)) return rc;
-    const uint32_t most_bins = bp.slices_f + bp.slices_c > kGridBins ? bp.slices_f + bp.slices_c : kGridBins;
-    const size_t lds_bins = (size_t)most_bins * sizeof(uint32_t);
+    const size_t lds_bins = (size_t)most_bins_of(bp) * sizeof(uint32_t);
     // One wavefront per chunk keeps a bin's records in the order of the points, which the drain's gathers
     // like (measured: drain 7 % faster); with many bins a lone wavefront fills its cache lines too slowly
     // for the memory system to merge the 8-byte writes, and four wavefronts sharing the cursors write
     // 1.7 times faster (measured at 64 bins per level).
     const unsigned bin_block = bp.slices_f + bp.slices_c >= 48 ? 256u : (unsigned)kBinBlock;
     {
-        {
-            LaunchTimer t(s, K_BWD_BIN_COUNT);
-            const uint32_t reps = most_bins <= 64 ? 16u : most_bins <= 512 ? 4u : 1u;      // copies of the histogram
-            bin_count_kernel<D><<<(unsigned)blocks, bin_block, lds_bins * reps, s>>>(p, bp, b.dense, x, N, cntF, cntC, cntG, reps);
-            if (int rc = launch_status("bin_count_kernel")) return rc;
-        }
         LaunchTimer t(s, K_BWD_BIN_OFFSETS);
         uint32_t big = bp.slices_f > bp.slices_c ? bp.slices_f : bp.slices_c;
         if (Ld > 0 && big < kGridBins) big = kGridBins;
@@ -634,10 +637,23 @@ int launch_bwd_sliced(const cngp_config *c, const Params &p, const BwdPlan &b, c
         if (zero_blocks < 1) zero_blocks = 1;
         const int64_t blocks = (int64_t)zero.n * zero_blocks + softmax_blocks + transpose_blocks;
         if (int rc = check_blocks(blocks)) return rc;
+        PrepArgs a;
+        a.seg = zero.seg; a.seg_count = (uint32_t)zero.n; a.zero_blocks = (uint32_t)zero_blocks;
+        a.Dhat_c = Dhat_c; a.sigma = sigma; a.elems = elems; a.softmax_blocks = (uint32_t)softmax_blocks;
+        a.dy = dy; a.dyT = dyT; a.N = N; a.L = c->L; a.top_k = p.top_k;
         LaunchTimer t(s, K_BWD_PREP);
-        bwd_prep_kernel<NP, PairT><<<(unsigned)blocks, kBlock, 0, s>>>(
-            zero.seg, (uint32_t)zero.n, (uint32_t)zero_blocks, Dhat_c, sigma, elems, (uint32_t)softmax_blocks,
-            (const PairT *)dy, (PairT *)dyT, N, c->L, p.top_k);
+        if (b.binned) {          // the count of the binned variant rides along: it needs nothing this launch writes
+            const BinParams bp = make_bin_params<NP>(c, b, N);
+            const int64_t   count_blocks = (int64_t)c->L * bp.chunks;
+            if (int rc = check_blocks(blocks + count_blocks)) return rc;
+            const uint32_t most = most_bins_of(bp), reps = hist_replicas_of(most);
+            char *ws = (char *)workspace;
+            bwd_prep_count_kernel<D, NP, PairT><<<(unsigned)(blocks + count_blocks), kBlock, (size_t)most * reps * sizeof(uint32_t), s>>>(
+                a, p, bp, b.dense, x, (uint32_t *)(ws + b.cntF_off), (uint32_t *)(ws + b.cntC_off), (uint32_t *)(ws + b.cntG_off),
+                reps, (uint32_t)count_blocks);
+        } else {
+            bwd_prep_kernel<NP, PairT><<<(unsigned)blocks, kBlock, 0, s>>>(a);
+        }
         zero.n = 0;
         zero.largest = 0;
         if (int rc = launch_status("bwd_prep_kernel")) return rc;

@@ -80,12 +80,13 @@ __device__ __forceinline__ void corner_rows(const Cell<D> &cell, const Params &p
 // Workgroups [0, nlevels * chunks) count the hashed levels; with dense_bins the next level0 * chunks ones
 // count the pre-reduced levels 0 .. level0 - 1 by slice of their vertex grid.
 template <int D>
-__global__ __launch_bounds__(256) void bin_count_kernel(
-    const Params p, const BinParams bp, const DenseLevels dl, const float *__restrict__ x, const int64_t N,
-    uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC, uint32_t *__restrict__ cntG, const uint32_t hist_replicas)
+__device__ __forceinline__ void bin_count_block(
+    const Params &p, const BinParams &bp, const DenseLevels &dl, const float *__restrict__ x, const int64_t N,
+    uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC, uint32_t *__restrict__ cntG, const uint32_t hist_replicas,
+    const uint32_t block)
 {
     extern __shared__ uint32_t hist[];                      // [hist_replicas][max(slices_f + slices_c, kGridBins)]
-    const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
+    const uint32_t li = block / bp.chunks, chunk = block % bp.chunks;
     const int64_t n0 = (int64_t)chunk * bp.chunk_pts;
     const int64_t n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
     if (li >= (uint32_t)bp.nlevels) {                       // a pre-reduced level
@@ -142,6 +143,19 @@ __global__ __launch_bounds__(256) void bin_count_kernel(
         if (s < bp.slices_f) rowF[s] = total;
         else rowC[s - bp.slices_f] = total;
     }
+}
+
+// The count shares its launch with the preparation of cngp_bwd_sliced.h (clearing, softmax table, level-major
+// dL/dy): neither needs the other's results, one is bound by hashing and LDS atomics, the other by memory.
+// Workgroups [0, count_blocks) count, the rest prepare (alternating the two kinds over the grid was slower).
+template <int D, int NP, typename PairT>
+__global__ __launch_bounds__(kBlock) void bwd_prep_count_kernel(
+    const PrepArgs a, const Params p, const BinParams bp, const DenseLevels dl, const float *__restrict__ x,
+    uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC, uint32_t *__restrict__ cntG, const uint32_t hist_replicas,
+    const uint32_t count_blocks)
+{
+    if (blockIdx.x < count_blocks) bin_count_block<D>(p, bp, dl, x, a.N, cntF, cntC, cntG, hist_replicas, blockIdx.x);
+    else bwd_prep_block<NP, PairT>(a, blockIdx.x - count_blocks);
 }
 
 constexpr int kOffsetsBlock = 256;

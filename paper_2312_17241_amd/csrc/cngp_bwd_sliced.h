@@ -131,23 +131,39 @@ __device__ __forceinline__ void transpose_rows(const PairT *__restrict__ dy, Pai
 // Everything the accumulation kernels need first, in one launch: the gradient (and vertex-grid) ranges
 // that are accumulated with atomics are cleared, the softmax table and the level-major copy of dL/dy are
 // written.  Blocks [0, seg_count * zero_blocks) clear, the next softmax_blocks tabulate, the rest transpose.
+struct PrepArgs {
+    ZeroSegments seg;
+    uint32_t     seg_count, zero_blocks;
+    const float *Dhat_c;
+    float       *sigma;
+    int64_t      elems;
+    uint32_t     softmax_blocks;
+    const void  *dy;
+    void        *dyT;
+    int64_t      N;
+    int32_t      L;
+    uint32_t     top_k;
+};
+
 template <int NP, typename PairT>
-__global__ __launch_bounds__(kBlock) void bwd_prep_kernel(
-    const ZeroSegments seg, const uint32_t seg_count, const uint32_t zero_blocks,
-    const float *__restrict__ Dhat_c, float *__restrict__ sigma, const int64_t elems, const uint32_t softmax_blocks,
-    const PairT *__restrict__ dy, PairT *__restrict__ dyT, const int64_t N, const int L, const uint32_t top_k)
+__device__ __forceinline__ void bwd_prep_block(const PrepArgs &a, uint32_t b)
 {
-    uint32_t b = blockIdx.x;
-    if (b < seg_count * zero_blocks) {
-        zero_segment(seg, (int)(b / zero_blocks), b % zero_blocks, zero_blocks);
+    if (b < a.seg_count * a.zero_blocks) {
+        zero_segment(a.seg, (int)(b / a.zero_blocks), b % a.zero_blocks, a.zero_blocks);
         return;
     }
-    b -= seg_count * zero_blocks;
-    if (b < softmax_blocks) {
-        softmax_rows<NP>(Dhat_c, sigma, elems, b, top_k);
+    b -= a.seg_count * a.zero_blocks;
+    if (b < a.softmax_blocks) {
+        softmax_rows<NP>(a.Dhat_c, a.sigma, a.elems, b, a.top_k);
         return;
     }
-    transpose_rows<PairT>(dy, dyT, N, L, b - softmax_blocks);
+    transpose_rows<PairT>(reinterpret_cast<const PairT *>(a.dy), reinterpret_cast<PairT *>(a.dyT), a.N, a.L, b - a.softmax_blocks);
+}
+
+template <int NP, typename PairT>
+__global__ __launch_bounds__(kBlock) void bwd_prep_kernel(const PrepArgs a)
+{
+    bwd_prep_block<NP, PairT>(a, blockIdx.x);
 }
 
 // ------------------------------------------------------------------ shared scan loop
