@@ -63,7 +63,7 @@ BAD = [
     dict(N_f=0), dict(N_f=3000), dict(N_c=0), dict(N_c=100), dict(N_p=0), dict(N_p=3), dict(N_p=32),
     dict(N_p=16, N_f=8), dict(N_min=0), dict(N_max=8), dict(N_max=2**25),
     dict(feat_dtype=2), dict(io_dtype=-1), dict(index_format=3), dict(flags=64), dict(flags=6), dict(flags=34),
-    dict(index_format=cngp.IDX_PACKED4, N_c=1, N_p=1),
+    dict(index_format=cngp.IDX_PACKED4, N_c=1, N_p=1), dict(top_k=17), dict(N_p=4, top_k=5),
 ]
 
 
@@ -77,6 +77,14 @@ def test_invalid_configs_are_rejected_on_the_host(over):
     assert lib.cngp_bake_probes(ctypes.byref(c), one, one, None) == cngp.ERR_INVALID
     assert lib.cngp_debug_indices(ctypes.byref(c), one, 8, one, one, one, one, one, None) == cngp.ERR_INVALID
     assert cngp.workspace_bytes(base_cfg(**over), 8) == 0
+
+
+def test_reserved_field_must_be_zero_and_top_k_up_to_the_probing_range_is_valid():
+    c = base_cfg().c()
+    c.reserved = 1
+    assert cngp._lib.cngp_bake_probes(ctypes.byref(c), ctypes.c_void_p(256), ctypes.c_void_p(256), None) == cngp.ERR_INVALID
+    for k in (0, 1, base_cfg().N_p):
+        assert cngp.workspace_bytes(base_cfg(top_k=k, flags=cngp.BWD_SLICED), 1 << 16) > 0
 
 
 def test_unsupported_feature_width():
