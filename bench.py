@@ -207,6 +207,7 @@ def main():
     # Beside the headline (never part of `value`): the spread of single steps, the same step with cold caches,
     # and the same batch in Morton order.
     extras = {}
+    morton_perm = None
     if not args.no_extras:
         def steps_with_events(k, before=None):
             ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k)]
@@ -230,50 +231,52 @@ def main():
                                 "value": round(N / (t[len(t) // 2] * 1e-3), 1), "unit": "points/s",
                                 "note": "512 MiB scrub buffer written before every step"}
         if not with_opt and not args.with_decoder:
-            # Morton order: points sorted by the interleaved bits of their coordinates (10 bits per axis in 3D, 16 in 2D)
-            bits = 10 if w.d == 3 else 16
-
-            def interleave(q):                                   # q: integer coordinates [N, d], int64 (numpy or torch)
-                code = q[:, 0] * 0
-                for b in range(bits):
-                    for j in range(w.d):
-                        code |= ((q[:, j] >> b) & 1) << (b * w.d + j)
-                return code
-            t0 = time.perf_counter()
-            q_h = np.clip(x_h.astype(np.float32) * np.float32(1 << bits), 0, (1 << bits) - 1).astype(np.int64)
-            perm_h = np.argsort(interleave(q_h), kind="stable")
-            sort_host = time.perf_counter() - t0
+            # Morton order (cngp_morton_sort): the same batch with its points sorted along the Z-order curve
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            for attempt in range(2):                             # the first pass pays torch's one-time set-up; the second is timed
+            sort_ws = torch.empty(int(cngp._lib.cngp_morton_sort_workspace_bytes(w.d, N)), dtype=torch.uint8, device=dev)
+            for attempt in range(3):                             # the last of three is the one reported
                 e0.record()
-                q = (x * float(1 << bits)).clamp_(0, (1 << bits) - 1).to(torch.int64)
-                perm = torch.sort(interleave(q), stable=True).indices
-                x_sorted = x.index_select(0, perm)
-                dy_sorted = None if fwd_only else dy.index_select(0, perm)
+                perm, x_sorted = cngp.morton_sort(x, workspace=sort_ws)
                 e1.record()
                 torch.cuda.synchronize()
-            assert np.array_equal(perm.cpu().numpy(), perm_h)
-            x_nat, x = x, x_sorted
-            if not fwd_only:
-                dy_nat, dy = dy, dy_sorted
-            for _ in range(args.warmup):
-                step()
-            torch.cuda.synchronize()
-            m0 = time.perf_counter()
-            for _ in range(args.steps):
-                step()
-            torch.cuda.synchronize()
-            m1 = time.perf_counter()
-            x = x_nat
-            if not fwd_only:
-                dy = dy_nat
-            step()                                               # y and the gradients of the natural order again, for the check
-            torch.cuda.synchronize()
+            sort_ms = e0.elapsed_time(e1)
+            morton_perm = perm.cpu().numpy()                     # compared with the oracle's order in the check below
+            note = "the sort is the library's (cngp_morton_sort) and is not part of these steps"
+            if fwd_only and not fused_dec:
+                # inference: the whole pipeline -- sort, then the forward pass that writes y in the caller's order
+                def sorted_step():
+                    cngp.bake_probes(cfg, Dhat, D_c)
+                    p_, xs_ = cngp.morton_sort(x, workspace=sort_ws)
+                    cngp.encode_fwd_permuted(cfg, xs_, p_, D_f, D_c, y)
+                y_plain = y.clone()
+                for _ in range(args.warmup):
+                    sorted_step()
+                torch.cuda.synchronize()
+                m0 = time.perf_counter()
+                for _ in range(args.steps):
+                    sorted_step()
+                torch.cuda.synchronize()
+                m1 = time.perf_counter()
+                assert torch.equal(y.view(torch.int16), y_plain.view(torch.int16)), "permuted forward differs from the plain one"
+                note = "every step = bake + cngp_morton_sort + cngp_encode_fwd_permuted (y in the caller's order, identical bits)"
+            else:
+                x_nat, x = x, x_sorted
+                dy_nat, dy = dy, dy.index_select(0, perm.long())
+                for _ in range(args.warmup):
+                    step()
+                torch.cuda.synchronize()
+                m0 = time.perf_counter()
+                for _ in range(args.steps):
+                    step()
+                torch.cuda.synchronize()
+                m1 = time.perf_counter()
+                x, dy = x_nat, dy_nat
+                step()                                           # y and the gradients of the natural order again, for the check
+                torch.cuda.synchronize()
+            del sort_ws
             extras["morton_order"] = {"value": round(N * args.steps / (m1 - m0), 1), "unit": "points/s",
                                       "ms_per_step": round((m1 - m0) * 1e3 / args.steps, 4),
-                                      "sort_ms_gpu": round(e0.elapsed_time(e1), 3), "sort_ms_host_numpy": round(sort_host * 1e3, 1),
-                                      "note": "same batch, points (and their dL/dy rows) sorted by Morton code first; the sort "
-                                              "(torch: codes, stable sort, two row gathers) is not part of the step"}
+                                      "sort_ms_gpu": round(sort_ms, 3), "note": note}
 
     # roofline of the dominant kernel kind
     alg = algorithmic_bytes(w, N, cfg.index_cols)
@@ -406,6 +409,11 @@ def main():
             if not fwd_only and n_cpu == N and not with_dec:
                 e["grad_D_f"] = check_close("grad D_f", gF.cpu().numpy(), g_ref[0], g_ref[2], fp16_out=False)
                 e["grad_Dhat_c"] = check_close("grad Dhat_c", gC.cpu().numpy(), g_ref[1], g_ref[3], fp16_out=False)
+            if morton_perm is not None:
+                t0 = time.perf_counter()
+                perm_ref, _ = oracle.morton_order(x_h)
+                extras["morton_order"]["sort_ms_host_oracle"] = round((time.perf_counter() - t0) * 1e3, 1)
+                check_exact("morton perm", morton_perm, perm_ref)
             out["parity_max_rel_err"] = {k: float(f"{v:.3e}") for k, v in e.items()}
 
     print(json.dumps(out))

@@ -65,6 +65,12 @@ def _load():
     lib.cngp_encode_fwd_partial.restype = ctypes.c_int
     lib.cngp_encode_fwd_partial.argtypes = [cfgp, ctypes.c_int32, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.cngp_encode_bwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cngp_morton_sort_workspace_bytes.restype = sz
+    lib.cngp_morton_sort_workspace_bytes.argtypes = [ctypes.c_int32, i64]
+    lib.cngp_morton_sort.restype = ctypes.c_int
+    lib.cngp_morton_sort.argtypes = [ctypes.c_int32, vp, i64, vp, vp, vp, sz, vp]
+    lib.cngp_encode_fwd_permuted.restype = ctypes.c_int
+    lib.cngp_encode_fwd_permuted.argtypes = [cfgp, vp, vp, i64, vp, vp, vp, vp]
     lib.cngp_bake_probes.restype = ctypes.c_int
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
     lib.cngp_encode_bwd_input.restype = ctypes.c_int
@@ -230,6 +236,37 @@ def encode_fwd(cfg: Config, x, D_f, D_c, y=None, workspace=None):
         _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"),
         _dc(cfg, D_c),
         _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), wp, wb, _stream()))
+    return y
+
+
+def morton_sort(x, workspace=None):
+    """cngp_morton_sort: (perm, x_sorted) with x_sorted[i] = x[perm[i]] in Morton order (stable); perm is int32."""
+    N, d = x.shape
+    perm = torch.empty((N,), dtype=torch.int32, device=x.device)
+    x_sorted = torch.empty_like(x)
+    if N == 0:
+        return perm, x_sorted
+    need = int(_lib.cngp_morton_sort_workspace_bytes(d, N))
+    if need == 0:
+        raise CngpError(ERR_INVALID, "morton_sort: d must be 2 or 3 and N below 2^31 (and a device present)")
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    wp, wb = _ws(workspace)
+    _check(_lib.cngp_morton_sort(d, _dev(x, torch.float32, (N, d), "x"), N, _dev(perm, torch.int32, (N,), "perm"),
+                                 _dev(x_sorted, torch.float32, (N, d), "x_sorted"), wp, wb, _stream()))
+    return perm, x_sorted
+
+
+def encode_fwd_permuted(cfg: Config, x_sorted, perm, D_f, D_c, y=None):
+    """cngp_encode_fwd_permuted: row perm[i] of y = encoding of x_sorted[i] (y in the order of the original points)."""
+    N = x_sorted.shape[0]
+    if y is None:
+        y = torch.empty((N, cfg.L * cfg.F), dtype=_TORCH_DT[cfg.io_dtype], device=x_sorted.device)
+    c = cfg.c()
+    _check(_lib.cngp_encode_fwd_permuted(
+        ctypes.byref(c), _dev(x_sorted, torch.float32, (N, cfg.d), "x_sorted"), _dev(perm, torch.int32, (N,), "perm"), N,
+        _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"), _dc(cfg, D_c),
+        _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), _stream()))
     return y
 
 

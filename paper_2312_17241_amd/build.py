@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcngp.so")
-SOURCES = ["cngp_api.hip"]
+SOURCES = ["cngp_api.hip", "cngp_sort.hip"]
 HEADERS = ["cngp_device.h", "cngp_kernels.h", "cngp_bwd_sliced.h", "cngp_bwd_binned.h", "cngp_optim.h", "cngp_mlp.h", "cngp_rates.h", os.path.join("..", "..", "include", "cngp.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-munsafe-fp-atomics",

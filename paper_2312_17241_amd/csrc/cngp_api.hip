@@ -30,6 +30,12 @@ int hip_fail(hipError_t e, const char *what) {
     g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
     return CNGP_ERR_HIP;
 }
+}  // namespace
+
+// for the other translation unit of the library (cngp_sort.hip): same record as cngp_last_hip_error() reads
+namespace cngp { int record_hip_failure(hipError_t e, const char *what) { return hip_fail(e, what); } }
+
+namespace {
 #define CNGP_HIP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return hip_fail(e_, #call); } while (0)
 
 // ---------------------------------------------------------------- validation (host only)
@@ -156,7 +162,7 @@ int allow_big_lds(K kernel, size_t bytes) {
 
 template <int D, typename FeatT, typename IoT>
 int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
-               const void *D_c, void *y, hipStream_t s) {
+               const void *D_c, void *y, hipStream_t s, const int32_t *perm = nullptr) {
     // tile variant: one level's index codebook and the tile's outputs fit in LDS
     const size_t c_stride = index_level_bytes(c);
     const int    fmt = c->index_format;
@@ -178,7 +184,7 @@ int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N,
             if (int rc = allow_big_lds(kernel, LDS)) return rc;                                         \
             LaunchTimer t(s, K_FWD);                                                                    \
             kernel<<<(unsigned)blocks, TILE, LDS, s>>>(                                                 \
-                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec);  \
+                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec, perm); \
         } while (0)
 #define CNGP_FWD_TILE_FMT(FMT)                                                                          \
         if (large) CNGP_FWD_TILE(FMT, kFwdTileLarge, lds_large); else CNGP_FWD_TILE(FMT, kFwdTile, lds)
@@ -195,7 +201,7 @@ int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N,
     LaunchTimer t(s, K_FWD);
 #define CNGP_FWD_SIMPLE_LAUNCH(FMT)                                                                     \
     encode_fwd_kernel<D, FeatT, IoT, FMT><<<(unsigned)blocks, kBlock, 0, s>>>(                          \
-        p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, pairs, (uint32_t)c_stride)
+        p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, pairs, (uint32_t)c_stride, perm)
     if (fmt == CNGP_IDX_PACKED4) CNGP_FWD_SIMPLE_LAUNCH(kFmtPacked4);
     else if (fmt == CNGP_IDX_BITS) CNGP_FWD_SIMPLE_LAUNCH(kFmtBits);
     else CNGP_FWD_SIMPLE_LAUNCH(kFmtU8);
@@ -867,6 +873,18 @@ int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const
     p.L_loaded = levels_loaded;
     hipStream_t s = (hipStream_t)stream;
     CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s);
+}
+
+int cngp_encode_fwd_permuted(const cngp_config *cfg, const float *x_sorted, const int32_t *perm, int64_t N, const void *D_f,
+                             const void *D_c, void *y, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0 || N > 0x7fffffffLL) return CNGP_ERR_INVALID;
+    if (N == 0) return CNGP_OK;
+    if (!x_sorted || !perm || !D_f || !y || (!D_c && !index_codebook_is_empty(cfg))) return CNGP_ERR_NULL;
+    if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
+    const Params p = make_params(cfg);
+    hipStream_t s = (hipStream_t)stream;
+    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x_sorted, N, D_f, D_c, y, s, perm);
 }
 
 int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const void *D_f,

@@ -11,14 +11,17 @@ namespace cngp {
 template <int D, typename FeatT, typename IoT, int FMT>
 __global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
     const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
-    const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t pairs, const uint32_t c_stride)
+    const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t pairs, const uint32_t c_stride,
+    const int32_t *__restrict__ perm)
 {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= pairs) return;
     const int64_t n = i / p.L;
     const int     l = (int)(i - n * p.L);
+    // with a permutation the encoding of point n is row perm[n] of y
+    const size_t  o = perm ? (size_t)perm[n] * p.L + l : (size_t)i;
     if (l >= p.L_loaded) {                        // level not loaded
-        store_pair(y, (size_t)i, 0.0f, 0.0f);
+        store_pair(y, o, 0.0f, 0.0f);
         return;
     }
 
@@ -48,7 +51,7 @@ __global__ __launch_bounds__(kBlock) void encode_fwd_kernel(
         y0 = fmaf(wt, feat[c].x, y0);
         y1 = fmaf(wt, feat[c].y, y1);
     }
-    store_pair(y, (size_t)i, y0, y1);
+    store_pair(y, o, y0, y1);
 }
 
 // Tile variant of the forward pass: a workgroup of TILE lanes takes TILE consecutive points through all levels.
@@ -102,7 +105,8 @@ __device__ __forceinline__ void stage_probes(uint8_t *probes, const uint8_t *__r
 template <int D, typename FeatT, typename IoT, int FMT, int TILE>
 __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
-    const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t N, const uint32_t c_stride, const int vec)
+    const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t N, const uint32_t c_stride, const int vec,
+    const int32_t *__restrict__ perm)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     uint8_t *probes = smem;                                  // D_c of the current level: 4-bit packed, or its exact-width bit string
@@ -146,8 +150,28 @@ __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     }
     __syncthreads();
 
-    // the tile's outputs are one contiguous block of y
     const int64_t rows = (N - n0 < TILE) ? N - n0 : TILE;
+    if (perm) {                                   // row r of the tile is row perm[n0 + r] of y: whole rows, piece by piece
+        const size_t row_bytes = (size_t)p.L * 2 * sizeof(IoT);
+        unsigned char       *ybytes = reinterpret_cast<unsigned char *>(y);
+        const unsigned char *src = reinterpret_cast<const unsigned char *>(out);
+        if (row_bytes % 16 == 0 && ((uintptr_t)y & 15u) == 0) {
+            const uint32_t pieces = (uint32_t)(row_bytes / 16);
+            for (uint32_t i = t; i < (uint32_t)rows * pieces; i += TILE) {
+                const uint32_t r = i / pieces, q = i % pieces;
+                *reinterpret_cast<uint4 *>(ybytes + (size_t)perm[n0 + r] * row_bytes + (size_t)q * 16) =
+                    *reinterpret_cast<const uint4 *>(src + (size_t)i * 16);
+            }
+        } else {
+            const uint32_t pieces = (uint32_t)(row_bytes / sizeof(IoT));
+            for (uint32_t i = t; i < (uint32_t)rows * pieces; i += TILE) {
+                const uint32_t r = i / pieces, q = i % pieces;
+                reinterpret_cast<IoT *>(ybytes + (size_t)perm[n0 + r] * row_bytes)[q] = reinterpret_cast<const IoT *>(src)[i];
+            }
+        }
+        return;
+    }
+    // the tile's outputs are one contiguous block of y
     const size_t  bytes = (size_t)rows * p.L * 2 * sizeof(IoT);
     unsigned char *dst = reinterpret_cast<unsigned char *>(y + (size_t)n0 * p.L * 2);
     const unsigned char *src = reinterpret_cast<const unsigned char *>(out);

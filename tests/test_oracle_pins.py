@@ -685,3 +685,42 @@ def test_model_sizes_consistent_with_table_3():
         bits = N_p.bit_length() - 1
         full = 16 * (N_f * 2 * 2 + N_c * bits / 8) / 1000.0
         assert 0.8 * full <= kB <= full
+
+
+# --------------------------------------------------------------------------- Morton order (optional reordering)
+
+def test_morton_codes_by_hand_and_by_string_interleaving():
+    # 2D, 10 bits per axis: q = (3, 5) -> x bits 011, y bits 101 -> y2 x2 y1 x1 y0 x0 = 1 0 0 1 1 1 = 39
+    s = 1.0 / 1024
+    pts = np.array([[0, 0], [1.5 * s, 0], [0, 1.5 * s], [3.2 * s, 5.9 * s], [1.0, 1.0], [-0.5, 2.0]], np.float32)
+    _, codes = oracle.morton_order(pts)
+    assert codes.tolist() == [0, 1, 2, 39, 2**20 - 1, int("10" * 10, 2)]
+    # 3D, 7 bits per axis: q = (1, 0, 0), (0, 1, 0), (0, 0, 1), (127, 127, 127)
+    t = 1.0 / 128
+    pts3 = np.array([[1.1 * t, 0, 0], [0, 1.1 * t, 0], [0, 0, 1.1 * t], [1, 1, 1], [2.5 * t, 0, 3.5 * t]], np.float32)
+    _, codes3 = oracle.morton_order(pts3)
+    assert codes3.tolist() == [1, 2, 4, 2**21 - 1, int("101100", 2)]               # q = (2, 0, 3): z1 y1 x1 z0 y0 x0 = 1 0 1 1 0 0
+    rng = np.random.default_rng(5)
+    for d, B in ((2, 10), (3, 7)):
+        x = rng.random((500, d), dtype=np.float32)
+        perm, codes = oracle.morton_order(x)
+        q = np.minimum((x.astype(np.float64) * (1 << B)).astype(np.int64), (1 << B) - 1)
+        for n in range(0, 500, 7):                               # bit strings, most significant first
+            bits = "".join(format(int(q[n, j]), f"0{B}b")[B - 1 - b] for b in reversed(range(B)) for j in reversed(range(d)))
+            assert int(bits, 2) == int(codes[n])
+        assert sorted(perm.tolist()) == list(range(500))
+        assert np.all(np.diff(codes[perm].astype(np.int64)) >= 0)
+        same = codes[perm][1:] == codes[perm][:-1]
+        assert np.all(perm[1:][same] > perm[:-1][same])          # stable: equal codes keep the order of the batch
+
+
+def test_morton_order_keeps_cells_together():
+    """Points of one cell of the 2^k grid form one contiguous run of the order (the prefix property of the curve)."""
+    rng = np.random.default_rng(6)
+    x = rng.random((4000, 3), dtype=np.float32)
+    perm, _ = oracle.morton_order(x)
+    for k in (1, 2, 4):
+        cell = np.floor(x[perm].astype(np.float64) * (1 << k)).astype(np.int64)
+        ident = (cell[:, 0] * 64 + cell[:, 1]) * 64 + cell[:, 2]
+        runs = 1 + np.count_nonzero(np.diff(ident))
+        assert runs == len(np.unique(ident))
