@@ -84,8 +84,40 @@ def paper_table2(args, np, torch, cngp, W, dev):
             cngp.profile_enable(False)
             # kernel: events directly around each launch; call: launches back to back, which the launch rate bounds
             ours[f"N_l={res}"] = {"kernel": round(ms * 1e3 / cnt, 2), "call_to_call": round(e0.elapsed_time(e1) * 1e3 / args.steps, 2)}
+        # training column: the paper times whole NeRF iterations; here the encoding's share of one, bake + forward +
+        # backward over the headline batch (L = 16, 2^18 ray samples), relative to the first row (plain hashing, N_f = 2^16)
+        base = W.WORKLOADS["nerf3d"]
+        w = W.custom(name="table2_train", cfg=3, d=3, L=16, F=2, N_f=N_f, N_c=N_c, N_p=N_p, N_min=16, N_max=2048, N=base.N,
+                     feat_dtype="f16", io_dtype="f16", points=base.points)
+        cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS)
+        x = torch.from_numpy(W.make_points(w)).to(dev)
+        D_f = torch.from_numpy(W.make_feature_codebook(w)).to(dev)
+        Dhat = torch.from_numpy(W.make_probe_logits(w)).to(dev)
+        dy = torch.from_numpy(W.make_upstream_grad(w)).to(dev)
+        D_c = torch.empty((w.L, cfg.index_cols), dtype=torch.uint8, device=dev)
+        y = torch.empty((w.N, 32), dtype=torch.float16, device=dev)
+        gF, gC = torch.empty((16, N_f, 2), device=dev), torch.empty((16, N_c, N_p), device=dev)
+        ws = cngp.alloc_workspace(cfg, w.N, dev)
+
+        def train_step():
+            cngp.bake_probes(cfg, Dhat, D_c)
+            cngp.encode_fwd(cfg, x, D_f, D_c, y)
+            cngp.encode_bwd(cfg, x, D_f, Dhat, dy, gF, gC, workspace=ws)
+        for _ in range(args.warmup):
+            train_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            train_step()
+        torch.cuda.synchronize()
+        step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         out_rows.append({"N_f": N_f, "N_c": N_c, "N_p": N_p, "us_per_2^18_lookups": ours,
-                         "paper_us_RTX_6000_Ada": paper_us})
+                         "paper_us_RTX_6000_Ada": paper_us,
+                         "encoding_fwd_bwd_ms_L16_2^18_points": round(step_ms, 4)})
+    for r, paper_ms in zip(out_rows, (5.4, 5.1, 4.5, 6.8, 6.8, 8.3, 8.5, 12.7, 14.1)):
+        r["relative_to_first_row"] = round(r["encoding_fwd_bwd_ms_L16_2^18_points"] / out_rows[0]["encoding_fwd_bwd_ms_L16_2^18_points"], 2)
+        r["paper_whole_iteration_ms_RTX_6000_Ada"] = paper_ms
+        r["paper_relative_to_first_row"] = round(paper_ms / 5.4, 2)
     print(json.dumps({"metric": "time of 2^18 forward lookups on one level (Table 2 of the paper, inference column)",
                       "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False,
                       "dtype": "f32", "data": "synthetic", "vs_baseline": None,

@@ -190,6 +190,8 @@ int cngp_encode_bwd_input(const cngp_config *cfg, const float *x, int64_t N, con
  * [6], [7] vertex chunks of the two roles on pre-reduced levels; [8] point chunks and [9] total slices
  * of the vertex-grid accumulation; [10] 1 = the hashed levels' references are binned by slice first, and then
  * [11], [12] workgroups that drain one bin of the feature / logit table and [13] point chunks of the binning;
+ * with [2] = 0 when a level's feature table is small enough (N_f <= 4096) to be accumulated whole in LDS by the
+ * workgroups that drain the confidence-table bins (one pass for both gradients, no pre-reduced levels);
  * [14] passes over runs of points (1 unless the batch is split to bound the scratch; [0] .. [13] then
  * describe the first pass). */
 enum { CNGP_PLAN_INFO_COUNT = 15 };

@@ -269,6 +269,7 @@ struct BwdPlan {
     size_t   lds_f, lds_c;              // dynamic LDS bytes of the two kernels
     size_t   sigma_off, dyT_off, G_off, ws_bytes;
     bool     binned;                    // hashed levels: references binned by slice first (cngp_bwd_binned.h)
+    bool     fused;                     // ... by slice of the confidence table only: a level's whole feature gradient sits in LDS beside it
     uint32_t bin_chunks, bin_chunk_pts; // point chunks of the count / scatter kernels
     uint32_t subs_f, subs_c;            // drain workgroups per bin
     size_t   cntF_off, cntC_off, baseF_off, baseC_off, recF_off, recC_off;
@@ -279,6 +280,8 @@ struct BwdPlan {
 };
 
 constexpr uint64_t kMaxAutoBinBytes = 8ull << 30;   // workspace the library asks for on its own initiative
+constexpr uint32_t kMaxFusedNf = 4096;          // largest feature table per level whose gradient is kept whole in LDS
+constexpr size_t   kFusedLdsBytes = 152 * 1024; // LDS of the workgroups that accumulate both gradients
 constexpr uint32_t kMinBinnedSlicesPerLevel = 24; // from here on binning the references beats the replicated scan
 constexpr uint32_t kMaxSlicesPerLevel = 128;   // beyond this the replicated scan costs more than global atomics
 constexpr int64_t  kMinSlicedRefs = 1 << 19;    // corner references (N * L * 2^d) below which launch overheads win
@@ -385,6 +388,17 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
         b.rows_c_log2 = ilog2(rows_c);
         b.slices_c = c->N_c / rows_c;
     }
+    // A small feature table (the paper's N_f = 2^6 .. 2^12): a level's whole feature gradient (fp64) and a copy of
+    // its codebook fit in LDS beside a slice of the confidence table, and one pass over that table's bins gives
+    // both gradients.  The confidence slice shrinks until everything fits in kFusedLdsBytes.
+    const size_t feat_lds = (size_t)c->N_f * (2 * sizeof(double) + (c->feat_dtype == CNGP_F16 ? 4 : 8));
+    bool fused_ok = c->N_p > 1 && c->N_f <= kMaxFusedNf;
+    uint32_t fused_rows_c_log2 = b.rows_c_log2;
+    while (fused_ok && (((size_t)1 << fused_rows_c_log2) * c->N_p * 8 + feat_lds > kFusedLdsBytes)) {
+        if (fused_rows_c_log2 == 0) fused_ok = false;
+        else --fused_rows_c_log2;
+    }
+    if (fused_ok && (c->N_c >> fused_rows_c_log2) > 8192) fused_ok = false;
     const uint32_t per_level = b.slices_f + b.slices_c;
     // a queued reference packs (row inside the slice, row of the other table) into 32 bits
     const bool keys_fit = b.rows_f_log2 + ilog2(c->N_c) <= 32 && b.rows_c_log2 + ilog2(groups) <= 32;
@@ -400,9 +414,14 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     // (the bins take 8 bytes per reference, level and table: not chosen unasked beyond kMaxAutoBinBytes)
     const uint64_t bin_bytes = ((uint64_t)N << c->d) * 8u * (uint64_t)c->L * (c->N_p > 1 ? 2u : 1u);
     const uint64_t bin_bytes_max = c->bin_bytes_max ? c->bin_bytes_max : kMaxAutoBinBytes;
-    b.binned = bin_ok && enough && per_level >= kMinBinnedSlicesPerLevel && bin_bytes <= bin_bytes_max;
+    b.binned = bin_ok && enough && (per_level >= kMinBinnedSlicesPerLevel || fused_ok) && bin_bytes <= bin_bytes_max;
     if (c->flags & CNGP_BWD_BINNED) b.binned = bin_ok;
     if (c->flags & (CNGP_BWD_DIRECT | CNGP_BWD_SLICED)) b.binned = false;
+    b.fused = b.binned && fused_ok;
+    if (b.fused) {
+        b.rows_c_log2 = fused_rows_c_log2;
+        b.slices_c = c->N_c >> fused_rows_c_log2;
+    }
     if (b.binned) b.sliced = true;
     if (c->flags & CNGP_BWD_DIRECT) b.sliced = false;
     if ((c->flags & CNGP_BWD_SLICED) && (uint64_t)per_level * 32u * 64u < 0x7fffffffull) b.sliced = true;
@@ -419,6 +438,7 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             const uint64_t slices = (verts + kDenseSliceVerts - 1) / kDenseSliceVerts;
             if (verts > kMaxDenseVerts || (N << c->d) < kMinRefsPerVertex * (int64_t)verts) break;
             if (slices * 2 > per_level && slices > 1) break;
+            if (b.fused) break;      // both gradients from one pass over the bins: cheaper than the grid sums and vertex scans (measured)
             if (b.binned && l == c->L - 1) break;                        // (at least one level stays hashed)
             b.dense.side[l] = res[l] + 2;
             b.dense.verts[l] = (uint32_t)verts;
@@ -452,6 +472,7 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
         };
         b.subs_f = subs(b.slices_f);
         b.subs_c = subs(b.slices_c);
+        if (b.fused) b.subs_f = 2;              // never one writer per entry: the feature gradient is cleared first and added to
     }
     const size_t queues = (size_t)kSlicedWaves * kRingBytes;
     b.lds_f = ((size_t)1 << b.rows_f_log2) * c->N_p * 2 * 8 + queues;
@@ -469,7 +490,7 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             b.baseF_off = b.cntC_off + align256((size_t)Lh * b.bin_chunks * b.slices_c * 4);
             b.baseC_off = b.baseF_off + align256((size_t)Lh * (b.slices_f + 1) * 4);
             b.recF_off = b.baseC_off + align256((size_t)Lh * (b.slices_c + 1) * 4);
-            b.recC_off = b.recF_off + align256((size_t)Lh * cap * 8);
+            b.recC_off = b.recF_off + (b.fused ? 0 : align256((size_t)Lh * cap * 8));
             b.cntG_off = b.recC_off + (b.slices_c ? align256((size_t)Lh * cap * 8) : 0);
             const size_t Ld = (size_t)b.dense.count;
             b.baseG_off = b.cntG_off + align256(Ld * b.bin_chunks * kGridBins * 4);
@@ -527,7 +548,7 @@ BinParams make_bin_params(const cngp_config *c, const BwdPlan &b, int64_t N) {
     std::memset(&bp, 0, sizeof(bp));
     bp.level0 = b.dense.count;
     bp.nlevels = c->L - b.dense.count;
-    bp.rows_f_log2 = b.rows_f_log2; bp.slices_f = b.slices_f;
+    bp.rows_f_log2 = b.rows_f_log2; bp.slices_f = b.fused ? 0 : b.slices_f;
     bp.rows_c_log2 = b.rows_c_log2; bp.slices_c = NP > 1 ? b.slices_c : 0;
     bp.chunks = b.bin_chunks; bp.chunk_pts = b.bin_chunk_pts;
     bp.cap = (uint32_t)((uint64_t)N << c->d);
@@ -600,7 +621,7 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     uint32_t wgs_c = 0, wgs_f = 0, wgs_cv = 0, wgs_fv = 0;
     const uint32_t slices_c = NP > 1 ? b.slices_c : 0;
     const SliceParams sp_c = role(b.rows_c_log2, slices_c, Geom{b.subs_c, 0}, Ld, Lh, wgs_c);
-    const SliceParams sp_f = role(b.rows_f_log2, b.slices_f, Geom{b.subs_f, 0}, Ld, Lh, wgs_f);
+    const SliceParams sp_f = role(b.rows_f_log2, b.fused ? 0u : b.slices_f, Geom{b.subs_f, 0}, Ld, Lh, wgs_f);
     BwdRoles vtx;
     std::memset(&vtx, 0, sizeof(vtx));
     vtx.sp[ROLE_LOGIT_VTX] = role(b.rows_c_log2, slices_c, b.logit_vtx, 0, Ld, wgs_cv);
@@ -609,6 +630,10 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     vtx.first[ROLE_FEAT_VTX] = wgs_cv;
     auto kernel = bin_drain_kernel<D, NP, FeatT, IoT>;
     size_t lds = b.lds_f > b.lds_c ? b.lds_f : b.lds_c;                 // slice + the vertex roles' ring buffers
+    if (b.fused) {
+        const size_t both = ((size_t)1 << b.rows_c_log2) * NP * 8 + (size_t)c->N_f * (2 * sizeof(double) + sizeof(typename RawPair<FeatT>::type));
+        if (both > lds) lds = both;
+    }
     if (int rc = allow_big_lds(kernel, lds)) return rc;
     const uint32_t total = wgs_c + wgs_f + wgs_cv + wgs_fv;
     if (total == 0) return CNGP_OK;
@@ -838,7 +863,7 @@ int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info) {
     const int64_t per = bwd_pass_points(cfg, N);
     const BwdPlan b = make_bwd_plan(cfg, per < N ? per : N);
     const int32_t v[CNGP_PLAN_INFO_COUNT] = {
-        b.sliced ? 1 : 0, b.dense.count, (int32_t)b.slices_f, (int32_t)b.slices_c,
+        b.sliced ? 1 : 0, b.dense.count, (int32_t)(b.fused ? 0 : b.slices_f), (int32_t)b.slices_c,
         (int32_t)b.feat_pts.chunks, (int32_t)b.logit_pts.chunks, (int32_t)b.feat_vtx.chunks,
         (int32_t)b.logit_vtx.chunks, (int32_t)b.grid.chunks, (int32_t)b.dense_slices,
         b.binned ? 1 : 0, (int32_t)b.subs_f, (int32_t)b.subs_c, (int32_t)b.bin_chunks,

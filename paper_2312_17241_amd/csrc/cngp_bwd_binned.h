@@ -36,6 +36,9 @@ struct BinParams {
     uint32_t cap;                         // records per level and role: N * 2^d
     int32_t  dense_bins;                  // 1: the pre-reduced coarse levels are binned too, by slice of their vertex grid
 };
+// slices_f = 0: no bins by feature-table slice.  That is the case of a small feature table (the paper's
+// N_f = 2^6 .. 2^11), whose whole level sits in LDS beside a slice of the confidence table: the workgroups
+// that drain the confidence-table bins then accumulate both gradients in one pass (drain_both).
 
 // Bins of a pre-reduced level: slices of kDenseSliceVerts vertices of its dense grid; every level is given
 // kGridBins of them (the largest grid that is pre-reduced has that many).
@@ -130,7 +133,7 @@ __device__ __forceinline__ void bin_count_block(
         for (int c = 0; c < (1 << D); ++c) {
             uint32_t h1, h2;
             corner_rows<D>(cell, p, c, h1, h2);
-            atomicAdd(&mine[h1 >> bp.rows_f_log2], 1u);
+            if (bp.slices_f) atomicAdd(&mine[h1 >> bp.rows_f_log2], 1u);
             if (bp.slices_c) atomicAdd(&mine[bp.slices_f + (h2 >> bp.rows_c_log2)], 1u);
         }
     }
@@ -285,8 +288,10 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
             uint32_t h1, h2;
             corner_rows<D>(cell, p, c, h1, h2);
             const uint32_t ref = ((uint32_t)n << D) | (uint32_t)c;
-            const uint32_t posF = atomicAdd(&cursor[h1 >> bp.rows_f_log2], 1u);
-            outF[posF] = make_uint2((h1 & lo_f) | (h2 << bp.rows_f_log2), ref);
+            if (bp.slices_f) {
+                const uint32_t posF = atomicAdd(&cursor[h1 >> bp.rows_f_log2], 1u);
+                outF[posF] = make_uint2((h1 & lo_f) | (h2 << bp.rows_f_log2), ref);
+            }
             if (bp.slices_c) {
                 const uint32_t posC = atomicAdd(&cursor[bp.slices_f + (h2 >> bp.rows_c_log2)], 1u);
                 outC[posC] = make_uint2((h2 & lo_c) | (h1 << bp.rows_c_log2), ref);
@@ -325,13 +330,15 @@ __device__ __forceinline__ void gather_steps(const uint4 &r, T (&g)[NP], Load lo
         gather_steps<NP, U + 1>(r, g, load);
     }
 }
-// ... and, a batch later, accumulates it with what the gather brought.
-template <int NP, int U, typename T, typename Accum>
+// ... and, a batch later, accumulates it with what the gather brought.  BOTH: the accumulation wants the
+// gather's offset as well (it is the second accumulator row).
+template <int NP, int U, bool BOTH, typename T, typename Accum>
 __device__ __forceinline__ void accum_steps(const uint4 &r, const T (&g)[NP], Accum accum) {
     if constexpr (U < NP) {
-        accum(group_bcast<NP, U>(r.w),
-              make_float2(__uint_as_float(group_bcast<NP, U>(r.y)), __uint_as_float(group_bcast<NP, U>(r.z))), g[U]);
-        accum_steps<NP, U + 1>(r, g, accum);
+        const float2 gy = make_float2(__uint_as_float(group_bcast<NP, U>(r.y)), __uint_as_float(group_bcast<NP, U>(r.z)));
+        if constexpr (BOTH) accum(group_bcast<NP, U>(r.w), gy, g[U], group_bcast<NP, U>(r.x));
+        else accum(group_bcast<NP, U>(r.w), gy, g[U]);
+        accum_steps<NP, U + 1, BOTH>(r, g, accum);
     }
 }
 
@@ -346,7 +353,9 @@ __device__ __forceinline__ void accum_steps(const uint4 &r, const T (&g)[NP], Ac
 // -- the record first, so that waiting for it next step leaves the younger gathers in flight.  Loads
 // are never predicated: a position past `end` re-reads the bin's last record and its gather result is
 // replaced by zero, so it adds nothing.
-template <int D, int NP, typename T, typename IoT, typename Load, typename Accum>
+// BOTH (records of a confidence-table bin, both gradients accumulated): the gather reads the row INSIDE the
+// slice (the softmax row of the record's own confidence row), the accumulator row is the other table's.
+template <int D, int NP, typename T, bool BOTH, typename IoT, typename Load, typename Accum>
 __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, const uint32_t beg, const uint32_t end,
                                               const float *__restrict__ x, const IoT *__restrict__ dy_l, const float res,
                                               const uint32_t rows_log2, Load load, Accum accum)
@@ -395,8 +404,9 @@ __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, con
         const float2 gy = pair_to_float2(y);
         // the key, decoded once per record: byte offset of the row the gather reads (candidate 0), and
         // byte offset of the accumulator row in LDS; the lanes of the group add their candidate's share
-        r = make_uint4((q.x >> rows_log2) * (uint32_t)(NP * sizeof(T)), __float_as_uint(wt * gy.x),
-                       __float_as_uint(wt * gy.y), (q.x & row_lo_mask) * (uint32_t)(NP * sizeof(double)));
+        const uint32_t inside = q.x & row_lo_mask, other = q.x >> rows_log2;
+        r = make_uint4((BOTH ? inside : other) * (uint32_t)(NP * sizeof(T)), __float_as_uint(wt * gy.x),
+                       __float_as_uint(wt * gy.y), (BOTH ? other : inside) * (uint32_t)(NP * sizeof(double)));
         gather_steps<NP, 0>(r, g, load);
     };
     // prologue: batches b, b + stride, b + 2 stride enter the pipeline
@@ -410,7 +420,7 @@ __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, con
         stage_a(b + 3 * stride, Q[P3]);                                                  \
         stage_b(Q[P2], X[P2], Y[P2]);                                                    \
         stage_c(b + stride, Q[P1], X[P1], Y[P1], R[P1], G[P1]);                          \
-        accum_steps<NP, 0>(R[P0], G[P0], accum);                                         \
+        accum_steps<NP, 0, BOTH>(R[P0], G[P0], accum);                                         \
         b += stride;                                                                     \
         if (b >= end) break;
     for (;;) {
@@ -537,7 +547,7 @@ __device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &s
     };
     uint32_t beg, end;
     bin_range(baseF, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<D, NP, float>(recF + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+    drain_records<D, NP, float, false>(recF + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
                                 (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     float *out = gD_f + (size_t)co.level * p.N_f * 2 + (size_t)co.slice * plane * 2;
@@ -573,7 +583,7 @@ __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &
     };
     uint32_t beg, end;
     bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<D, NP, Raw>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+    drain_records<D, NP, Raw, false>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
                               (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
@@ -582,6 +592,68 @@ __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &
     float       *out = gDhat_c + row0 * NP;
     for (uint32_t i = threadIdx.x; i < rows * NP; i += kSlicedBlock) {
         const double Q = acc[i];
+        const double s = (double)sig[i];
+        double dot = s * Q;
+#pragma unroll
+        for (int o = NP / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, NP);
+        const float v = (float)(s * (Q - dot));
+        if (sp.store_direct) out[i] = v;
+        else if (v != 0.0f) atomic_add(out + i, v);
+    }
+}
+
+// Small feature table: both gradients from the confidence-table bins in one pass.  LDS holds the slice of
+// Q accumulators (as drain_logit), fp64 accumulators for the level's WHOLE feature gradient, and a copy of the
+// level's feature codebook, so the only gather left per record is its softmax row -- from the 64 KB or so of
+// rows of this slice instead of the whole table.  The feature gradient goes out with atomics (every
+// workgroup of the level holds a share of it): the caller has cleared it.
+template <int D, int NP, typename FeatT, typename IoT>
+__device__ __forceinline__ void drain_both(const Params &p, const SliceParams &sp, const uint32_t wg, unsigned char *smem,
+                                           const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
+                                           const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
+                                           const uint2 *__restrict__ recC, const uint32_t *__restrict__ baseC,
+                                           const uint32_t cap, float *__restrict__ gD_f, float *__restrict__ gDhat_c)
+{
+    using Raw = typename RawPair<FeatT>::type;
+    const uint32_t rows = 1u << sp.rows_log2, plane = p.N_f;            // plane: feature entries of a level
+    double *accQ = reinterpret_cast<double *>(smem);                    // [rows][NP]
+    double *accF = accQ + (size_t)rows * NP;                            // [2][N_f]: feature 0 of every entry, then feature 1
+    Raw    *feat = reinterpret_cast<Raw *>(accF + 2 * (size_t)plane);   // [N_f]
+    const SliceCoord co = slice_coord(sp, wg);
+    if (co.index < 0) return;
+    const Raw *F_l = reinterpret_cast<const Raw *>(D_f + (size_t)co.level * p.N_f * 2);
+    for (uint32_t i = threadIdx.x; i < rows * NP + 2 * plane; i += kSlicedBlock) accQ[i] = 0.0;
+    for (uint32_t i = threadIdx.x; i < plane; i += kSlicedBlock) feat[i] = F_l[i];
+    __syncthreads();
+    const size_t   row0 = (size_t)co.level * p.N_c + (size_t)co.slice * rows;
+    const uint32_t k = (threadIdx.x & 63) % NP;
+    const char *sig_k = reinterpret_cast<const char *>(sigma + row0 * NP + k);          // this lane's candidate, this slice's rows
+    char       *accF_k = reinterpret_cast<char *>(accF + k), *accQ_k = reinterpret_cast<char *>(accQ + k);
+    const char *feat_k = reinterpret_cast<const char *>(feat + k);
+    auto load = [&](const uint32_t off) -> float { return *reinterpret_cast<const float *>(sig_k + off); };
+    // offF: byte offset of the feature row among fp64 accumulators (row * NP * 8); offS: of the confidence row
+    // among floats (row * NP * 4)
+    auto accum = [&](const uint32_t offF, const float2 g, const float s, const uint32_t offS) {
+        const float2 f = RawPair<FeatT>::to_float2(*reinterpret_cast<const Raw *>(feat_k + offF / 8u * sizeof(Raw)));
+        double *a = reinterpret_cast<double *>(accF_k + offF);
+        atomicAdd(a, (double)(s * g.x));
+        atomicAdd(a + plane, (double)(s * g.y));
+        atomicAdd(reinterpret_cast<double *>(accQ_k + 2u * offS), (double)fmaf(f.x, g.x, f.y * g.y));
+    };
+    uint32_t beg, end;
+    bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
+    drain_records<D, NP, float, true>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+                                      (float)p.N_l[co.level], sp.rows_log2, load, accum);
+    __syncthreads();
+    float *outF = gD_f + (size_t)co.level * p.N_f * 2;
+    for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) {     // i = entry * 2 + f
+        const float v = (float)accF[(i & 1u) * plane + (i >> 1)];
+        if (v != 0.0f) atomic_add(outF + i, v);
+    }
+    const float *sig = sigma + row0 * NP;
+    float       *out = gDhat_c + row0 * NP;
+    for (uint32_t i = threadIdx.x; i < rows * NP; i += kSlicedBlock) {
+        const double Q = accQ[i];
         const double s = (double)sig[i];
         double dot = s * Q;
 #pragma unroll
@@ -607,7 +679,10 @@ __global__ __launch_bounds__(kSlicedBlock) void bin_drain_kernel(
 {
     extern __shared__ __align__(16) unsigned char smem[];
     if (blockIdx.x < first_feat) {
-        if (NP > 1) drain_logit<D, NP, FeatT, IoT>(p, sp_c, blockIdx.x, smem, x, dyT, N, D_f, sigma, recC, baseC, cap, gDhat_c);
+        if constexpr (NP > 1) {
+            if (sp_f.nlevels == 0) drain_both<D, NP, FeatT, IoT>(p, sp_c, blockIdx.x, smem, x, dyT, N, D_f, sigma, recC, baseC, cap, gD_f, gDhat_c);
+            else drain_logit<D, NP, FeatT, IoT>(p, sp_c, blockIdx.x, smem, x, dyT, N, D_f, sigma, recC, baseC, cap, gDhat_c);
+        }
     } else if (blockIdx.x < first_vtx) {
         drain_feat<D, NP, IoT>(p, sp_f, blockIdx.x - first_feat, smem, x, dyT, N, sigma, recF, baseF, cap, gD_f);
     } else {

@@ -239,6 +239,25 @@ def test_sparse_backward_never_keeps_a_nan_before_a_number():
     check_bwd(w, x, D_f, Dhat, dy, top_k=4)
 
 
+@pytest.mark.parametrize("N_f,N_c,N_p,feat,io,d", [
+    (2**6, 2**10, 4, "f16", "f16", 3), (2**8, 2**16, 8, "f16", "f16", 3), (2**8, 2**12, 16, "f32", "f32", 3),
+    (2**12, 2**14, 16, "f16", "f32", 3), (2**12, 2**13, 2, "f32", "f16", 2), (2**10, 2**15, 8, "f16", "f16", 2)])
+def test_small_feature_tables_both_gradients_in_one_pass(N_f, N_c, N_p, feat, io, d):
+    """The paper's compressed configurations (N_f = 2^6 .. 2^12): the library bins by slice of the confidence table only
+    and the workgroups that drain those bins accumulate the level's whole feature gradient in LDS as well.  Enough
+    points for several workgroups per bin; with and without clearing first."""
+    w = W.custom(cfg=90, d=d, L=6, N_f=N_f, N_c=N_c, N_p=N_p, N_min=8, N_max=512, N=120000 + 11, feat_dtype=feat, io_dtype=io)
+    plan = cngp.bwd_plan_info(cngp.Config.from_workload(w), w.N)
+    assert plan["binned"] == 1 and plan["slices_f"] == 0 and plan["dense_levels"] == 0
+    x, D_f, Dhat, dy = tables(w)
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    check_bwd(w, x, D_f, Dhat, dy, paths=("auto", "binned_nopre", "sliced", "direct"))
+    gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=0, init=-0.5)
+    check_close("grad D_f (+=)", gF, gF_ref - 0.5, A_f + 0.5, fp16_out=False)
+    check_close("grad Dhat_c (+=)", gC, gC_ref - 0.5, A_c + 0.5, fp16_out=False)
+
+
 @pytest.mark.parametrize("zero", [True, False])
 @pytest.mark.parametrize("forced", [True, False])
 def test_binned_backward_in_several_passes(zero, forced):
