@@ -414,7 +414,8 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     // (the bins take 8 bytes per reference, level and table: not chosen unasked beyond kMaxAutoBinBytes)
     const uint64_t bin_bytes = ((uint64_t)N << c->d) * 8u * (uint64_t)c->L * (c->N_p > 1 ? 2u : 1u);
     const uint64_t bin_bytes_max = c->bin_bytes_max ? c->bin_bytes_max : kMaxAutoBinBytes;
-    b.binned = bin_ok && enough && (per_level >= kMinBinnedSlicesPerLevel || fused_ok) && bin_bytes <= bin_bytes_max;
+    // (with both gradients in one pass binning pays from four slices per level: below that the replicated scan is as fast)
+    b.binned = bin_ok && enough && (per_level >= kMinBinnedSlicesPerLevel || (fused_ok && per_level >= 4)) && bin_bytes <= bin_bytes_max;
     if (c->flags & CNGP_BWD_BINNED) b.binned = bin_ok;
     if (c->flags & (CNGP_BWD_DIRECT | CNGP_BWD_SLICED)) b.binned = false;
     b.fused = b.binned && fused_ok;

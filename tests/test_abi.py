@@ -196,10 +196,12 @@ def test_backward_plan_is_reported_on_the_host():
     assert cngp.bwd_plan_info(cngp.Config.from_workload(w, bin_bytes_max=1 << 20), w.N)["binned"] == 0    # too small to bin
     assert p["passes"] == 1 and cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_SLICED), 2**25)["passes"] == 1
     # the paper's compressed configurations (small N_f): binned by confidence-table slice only, both gradients in one pass
-    for N_f, N_c, N_p in ((2**8, 2**16, 8), (2**12, 2**12, 16), (2**6, 2**10, 4)):
+    for N_f, N_c, N_p, flag in ((2**8, 2**16, 8, 0), (2**12, 2**12, 16, 0), (2**6, 2**10, 4, cngp.BWD_BINNED)):
         small_f = W.custom(d=3, L=16, N_f=N_f, N_c=N_c, N_p=N_p, N_min=16, N_max=2048, N=2**18)
-        ps = cngp.bwd_plan_info(cngp.Config.from_workload(small_f), small_f.N)
+        ps = cngp.bwd_plan_info(cngp.Config.from_workload(small_f, flags=flag), small_f.N)
         assert ps["binned"] == 1 and ps["slices_f"] == 0 and ps["dense_levels"] == 0 and ps["slices_c"] >= 1
+    few = W.custom(d=3, L=16, N_f=2**6, N_c=2**10, N_p=4, N_min=16, N_max=2048, N=2**18)      # two slices per level: replicated scan
+    assert cngp.bwd_plan_info(cngp.Config.from_workload(few), few.N)["binned"] == 0
     assert cngp.bwd_plan_info(cngp.Config.from_workload(W.custom(d=3, L=16, N_f=2**13, N_c=2**10, N_p=4, N_min=16, N_max=2048, N=2**18)), 2**18)["slices_f"] > 0
     big = W.custom(d=3, L=16, N_f=2**24, N_c=2**24, N_p=2, N_min=16, N_max=2048, N=2**18)
     assert cngp.bwd_plan_info(cngp.Config.from_workload(big), big.N)["sliced"] == 0     # too many slices

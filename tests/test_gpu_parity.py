@@ -247,13 +247,13 @@ def test_small_feature_tables_both_gradients_in_one_pass(N_f, N_c, N_p, feat, io
     and the workgroups that drain those bins accumulate the level's whole feature gradient in LDS as well.  Enough
     points for several workgroups per bin; with and without clearing first."""
     w = W.custom(cfg=90, d=d, L=6, N_f=N_f, N_c=N_c, N_p=N_p, N_min=8, N_max=512, N=120000 + 11, feat_dtype=feat, io_dtype=io)
-    plan = cngp.bwd_plan_info(cngp.Config.from_workload(w), w.N)
+    plan = cngp.bwd_plan_info(cngp.Config.from_workload(w, flags=cngp.BWD_BINNED), w.N)
     assert plan["binned"] == 1 and plan["slices_f"] == 0 and plan["dense_levels"] == 0
     x, D_f, Dhat, dy = tables(w)
     D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
-    check_bwd(w, x, D_f, Dhat, dy, paths=("auto", "binned_nopre", "sliced", "direct"))
+    check_bwd(w, x, D_f, Dhat, dy, paths=("auto", "binned", "binned_nopre", "sliced", "direct"))
     gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy)
-    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=0, init=-0.5)
+    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=cngp.BWD_BINNED, init=-0.5)
     check_close("grad D_f (+=)", gF, gF_ref - 0.5, A_f + 0.5, fp16_out=False)
     check_close("grad Dhat_c (+=)", gC, gC_ref - 0.5, A_c + 0.5, fp16_out=False)
 
