@@ -102,6 +102,41 @@ __device__ __forceinline__ void stage_probes(uint8_t *probes, const uint8_t *__r
     }
 }
 
+// The same in two halves, for codebooks of at most kPrefetch 16-byte pieces per lane: `fetch` issues the loads of a
+// level's codebook into registers, `commit` writes them to LDS.  The kernel fetches level l + 1 before it works
+// on level l, so the latency of the copy hides behind the lookups instead of stalling the workgroup between two
+// barriers.
+constexpr int kPrefetch = 4;
+template <int TILE>
+__device__ __forceinline__ void fetch_probes(uint4 (&buf)[kPrefetch], const uint8_t *__restrict__ C_l, const uint32_t c_stride, const int t)
+{
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j) {
+        const uint32_t i = ((uint32_t)j * TILE + (uint32_t)t) * 16u;
+        if (i < c_stride) buf[j] = *reinterpret_cast<const uint4 *>(C_l + i);
+    }
+}
+template <int FMT, int TILE>
+__device__ __forceinline__ void commit_probes(uint8_t *probes, const uint4 (&buf)[kPrefetch], const uint32_t c_stride, const int t)
+{
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j) {
+        const uint32_t i = ((uint32_t)j * TILE + (uint32_t)t) * 16u;
+        if (i >= c_stride) continue;
+        if (FMT == kFmtU8) {                                             // 16 entries in, 8 bytes out
+            auto pack = [](uint32_t v) {                                 // 4 entries -> 2 bytes
+                v &= 0x0F0F0F0Fu;
+                v = (v | (v >> 4)) & 0x00FF00FFu;
+                return (v | (v >> 8)) & 0xFFFFu;
+            };
+            *reinterpret_cast<uint2 *>(probes + i / 2) =
+                make_uint2(pack(buf[j].x) | (pack(buf[j].y) << 16), pack(buf[j].z) | (pack(buf[j].w) << 16));
+        } else {
+            *reinterpret_cast<uint4 *>(probes + i) = buf[j];
+        }
+    }
+}
+
 template <int D, typename FeatT, typename IoT, int FMT, int TILE>
 __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
@@ -121,11 +156,17 @@ __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     for (int j = 0; j < D; ++j) xp[j] = valid ? x[n * D + j] : 0.0f;
 
     for (int l = p.L_loaded; l < p.L; ++l) store_pair(out, (size_t)t * p.L + l, 0.0f, 0.0f);    // levels that are not loaded
+    // the codebook of the next level travels in registers (small tiles only: with 1024-lane tiles it was slower, measured)
+    const bool ahead = TILE == kFwdTile && vec && c_stride <= (uint32_t)(kPrefetch * TILE * 16);
+    uint4 next[kPrefetch];
+    if (ahead && p.L_loaded > 0) fetch_probes<TILE>(next, D_c, c_stride, t);
     for (int l = 0; l < p.L_loaded; ++l) {
         const uint8_t *C_l = D_c + (size_t)l * c_stride;
         __syncthreads();                                                     // previous level's lookups are done
-        stage_probes<FMT, TILE>(probes, C_l, c_stride, lds_c, vec, t);
+        if (ahead) commit_probes<FMT, TILE>(probes, next, c_stride, t);
+        else stage_probes<FMT, TILE>(probes, C_l, c_stride, lds_c, vec, t);
         __syncthreads();
+        if (ahead && l + 1 < p.L_loaded) fetch_probes<TILE>(next, C_l + c_stride, c_stride, t);
 
         Cell<D> cell;
         cell.locate(xp, p.N_l[l]);
