@@ -175,16 +175,19 @@ int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N,
         // CU busy with large ones, take the large tile.
         const bool large = c_stride >= 8192 && lds_large <= 128 * 1024 && N >= (int64_t)kFwdTileLarge * 1024;
         const int  tile = large ? kFwdTileLarge : kFwdTile;
+        // a small feature codebook (the paper's compressed models) goes to LDS with the index codebook
+        const size_t   feat_bytes = (size_t)c->N_f * 2 * sizeof(FeatT);
+        const uint32_t feat_lds = (c->N_f <= 4096 && (large ? lds_large : lds) + feat_bytes <= 150 * 1024) ? (uint32_t)feat_bytes : 0u;
         const int64_t blocks = (N + tile - 1) / tile;
         if (int rc = check_blocks(blocks)) return rc;
         const int vec = (c_stride % 16 == 0 && ((uintptr_t)D_c & 15u) == 0) ? 1 : 0;
 #define CNGP_FWD_TILE(FMT, TILE, LDS)                                                                   \
         do {                                                                                            \
             auto kernel = encode_fwd_tile_kernel<D, FeatT, IoT, FMT, TILE>;                             \
-            if (int rc = allow_big_lds(kernel, LDS)) return rc;                                         \
+            if (int rc = allow_big_lds(kernel, LDS + feat_lds)) return rc;                              \
             LaunchTimer t(s, K_FWD);                                                                    \
-            kernel<<<(unsigned)blocks, TILE, LDS, s>>>(                                                 \
-                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec, perm); \
+            kernel<<<(unsigned)blocks, TILE, LDS + feat_lds, s>>>(                                      \
+                p, x, (const FeatT *)D_f, (const uint8_t *)D_c, (IoT *)y, N, (uint32_t)c_stride, vec, perm, feat_lds); \
         } while (0)
 #define CNGP_FWD_TILE_FMT(FMT)                                                                          \
         if (large) CNGP_FWD_TILE(FMT, kFwdTileLarge, lds_large); else CNGP_FWD_TILE(FMT, kFwdTile, lds)

@@ -141,12 +141,14 @@ template <int D, typename FeatT, typename IoT, int FMT, int TILE>
 __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
     const Params p, const float *__restrict__ x, const FeatT *__restrict__ D_f,
     const uint8_t *__restrict__ D_c, IoT *__restrict__ y, const int64_t N, const uint32_t c_stride, const int vec,
-    const int32_t *__restrict__ perm)
+    const int32_t *__restrict__ perm, const uint32_t feat_lds)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     uint8_t *probes = smem;                                  // D_c of the current level: 4-bit packed, or its exact-width bit string
     const uint32_t lds_c = (p.N_c + 1u) / 2u;                                // bytes of it
     IoT     *out = reinterpret_cast<IoT *>(smem + ((lds_c + 15u) & ~15u));   // [TILE][L * 2]
+    // feat_lds != 0: a level's feature codebook is small enough to sit in LDS too (the paper's compressed models), after the outputs
+    FeatT   *feats = reinterpret_cast<FeatT *>(reinterpret_cast<unsigned char *>(out) + (size_t)TILE * p.L * 2 * sizeof(IoT));
     const int     t = threadIdx.x;
     const int64_t n0 = (int64_t)blockIdx.x * TILE;
     const int64_t n = n0 + t;
@@ -165,12 +167,17 @@ __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
         __syncthreads();                                                     // previous level's lookups are done
         if (ahead) commit_probes<FMT, TILE>(probes, next, c_stride, t);
         else stage_probes<FMT, TILE>(probes, C_l, c_stride, lds_c, vec, t);
+        const FeatT *F_l = D_f + (size_t)l * p.N_f * 2;
+        if (feat_lds) {                                                      // N_f pairs: 4 or 8 bytes each, copied as 4-byte words
+            const uint32_t words = p.N_f * (uint32_t)(2 * sizeof(FeatT) / 4);
+            for (uint32_t i = t; i < words; i += TILE)
+                reinterpret_cast<uint32_t *>(feats)[i] = reinterpret_cast<const uint32_t *>(F_l)[i];
+        }
         __syncthreads();
         if (ahead && l + 1 < p.L_loaded) fetch_probes<TILE>(next, C_l + c_stride, c_stride, t);
 
         Cell<D> cell;
         cell.locate(xp, p.N_l[l]);
-        const FeatT *F_l = D_f + (size_t)l * p.N_f * 2;
         uint32_t idx[1 << D];
 #pragma unroll
         for (int c = 0; c < (1 << D); ++c)
@@ -178,8 +185,9 @@ __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
                      (FMT == kFmtBits ? read_probe_bits_lds(probes, cell.hash2(c) & p.c_mask, p.log2_Np)
                                       : read_probe<kFmtPacked4>(probes, cell.hash2(c) & p.c_mask));
         float2 feat[1 << D];
+        const FeatT *table = feat_lds ? feats : F_l;
 #pragma unroll
-        for (int c = 0; c < (1 << D); ++c) feat[c] = load_pair(F_l, idx[c]);
+        for (int c = 0; c < (1 << D); ++c) feat[c] = load_pair(table, idx[c]);
         float y0 = 0.0f, y1 = 0.0f;
 #pragma unroll
         for (int c = 0; c < (1 << D); ++c) {
