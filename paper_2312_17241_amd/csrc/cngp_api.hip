@@ -177,6 +177,7 @@ int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N,
         const int  tile = large ? kFwdTileLarge : kFwdTile;
         // a small feature codebook (the paper's compressed models) goes to LDS with the index codebook
         const size_t   feat_bytes = (size_t)c->N_f * 2 * sizeof(FeatT);
+        // (measured: a third faster at N_f = 2^10, even at 2^12, slower from 2^13: the copy then costs more than the gathers it saves)
         const uint32_t feat_lds = (c->N_f <= 4096 && (large ? lds_large : lds) + feat_bytes <= 150 * 1024) ? (uint32_t)feat_bytes : 0u;
         const int64_t blocks = (N + tile - 1) / tile;
         if (int rc = check_blocks(blocks)) return rc;
