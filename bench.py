@@ -159,7 +159,7 @@ def main():
                          "bytes): the reference that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, sharding); "
+        print("bench.py measures one GPU: this build has no multi-GPU path; "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
