@@ -78,8 +78,10 @@ __device__ __forceinline__ SliceCoord slice_coord(const SliceParams &sp, const u
     const uint32_t rem = unit % per_level;
     c.index = (j < per_xcd && unit < total) ? (int)(unit / per_level) : -1;
     c.level = sp.level0 + c.index;
-    c.slice = rem / sp.chunks;
-    c.chunk = rem % sp.chunks;
+    // chunk-major inside a level: the workgroups that run side by side on an XCD take the SAME run of points through
+    // neighbouring slices, so the points and their gradients are read from memory once per level, not once per slice
+    c.chunk = rem / sp.slices;
+    c.slice = rem % sp.slices;
     return c;
 }
 
