@@ -288,6 +288,7 @@ constexpr uint32_t kMaxFusedNf = 4096;          // largest feature table per lev
 constexpr size_t   kFusedLdsBytes = 152 * 1024; // LDS of the workgroups that accumulate both gradients
 constexpr uint32_t kMinBinnedSlicesPerLevel = 24; // from here on binning the references beats the replicated scan
 constexpr uint32_t kMaxSlicesPerLevel = 128;   // beyond this the replicated scan costs more than global atomics
+constexpr int64_t  kMinBinnedRefs = 1 << 21;    // corner references from which the library bins by itself (measured: 2^14 points of the headline shape)
 constexpr int64_t  kMinSlicedRefs = 1 << 19;    // corner references (N * L * 2^d) below which launch overheads win
 constexpr uint64_t kMaxDenseVerts = 32ull * kDenseSliceVerts;   // largest vertex grid that is pre-reduced
 constexpr int64_t  kMinRefsPerVertex = 4;      // below this reuse the vertex pass saves nothing
@@ -419,7 +420,8 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     const uint64_t bin_bytes = ((uint64_t)N << c->d) * 8u * (uint64_t)c->L * (c->N_p > 1 ? 2u : 1u);
     const uint64_t bin_bytes_max = c->bin_bytes_max ? c->bin_bytes_max : kMaxAutoBinBytes;
     // (with both gradients in one pass binning pays from four slices per level: below that the replicated scan is as fast)
-    b.binned = bin_ok && enough && (per_level >= kMinBinnedSlicesPerLevel || (fused_ok && per_level >= 4)) && bin_bytes <= bin_bytes_max;
+    const bool plenty = (N << c->d) * c->L >= kMinBinnedRefs;           // below, the three extra launches cost more than they save
+    b.binned = bin_ok && plenty && (per_level >= kMinBinnedSlicesPerLevel || (fused_ok && per_level >= 4)) && bin_bytes <= bin_bytes_max;
     if (c->flags & CNGP_BWD_BINNED) b.binned = bin_ok;
     if (c->flags & (CNGP_BWD_DIRECT | CNGP_BWD_SLICED)) b.binned = false;
     b.fused = b.binned && fused_ok;

@@ -262,13 +262,13 @@ def test_small_feature_tables_in_passes_with_the_sparse_variant():
     """The same mode with a bound on the binned references (three passes) and the top-2 sparse variant together."""
     w = W.custom(cfg=91, d=3, L=5, N_f=2**9, N_c=2**13, N_p=8, N_min=8, N_max=400, N=100000 + 3, feat_dtype="f16", io_dtype="f16")
     limit = 40000 * 8 * 8 * w.L * 2
-    cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS, bin_bytes_max=limit, top_k=2)
+    cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS | cngp.BWD_BINNED, bin_bytes_max=limit, top_k=2)
     plan = cngp.bwd_plan_info(cfg, w.N)
     assert plan["binned"] == 1 and plan["slices_f"] == 0 and plan["passes"] == 3
     x, D_f, Dhat, dy = tables(w)
     D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
     gF_ref, gC_ref, A_f, A_c = oracle.encode_bwd(w, x, D_f, Dhat, dy, top_k=2)
-    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS, bin_bytes_max=limit, top_k=2)
+    gF, gC = run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS | cngp.BWD_BINNED, bin_bytes_max=limit, top_k=2)
     check_close("grad D_f", gF, gF_ref, A_f, fp16_out=False)
     check_close("grad Dhat_c", gC, gC_ref, A_c, fp16_out=False)
 
