@@ -15,10 +15,16 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-@pytest.mark.parametrize("flags,n", [(0, 40000 + 3), (cngp.BWD_BINNED, 40000 + 3), (cngp.BWD_DIRECT, 5000)])
-def test_graph_replay_matches_the_oracle(flags, n):
-    w = W.custom(cfg=91, d=3, L=6, N_f=2**13, N_c=2**11, N_p=8, N_min=8, N_max=256, N=n, feat_dtype="f16", io_dtype="f16")
-    cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS | flags)
+@pytest.mark.parametrize("flags,n,N_f,passes", [
+    (0, 40000 + 3, 2**13, 1), (cngp.BWD_BINNED, 40000 + 3, 2**13, 1), (cngp.BWD_DIRECT, 5000, 2**13, 1),
+    (cngp.BWD_BINNED, 40000 + 3, 2**9, 1),          # small feature table: both gradients from one pass over the bins
+    (cngp.BWD_BINNED, 40000 + 3, 2**13, 3)])        # bounded bins: three passes inside the one call
+def test_graph_replay_matches_the_oracle(flags, n, N_f, passes):
+    w = W.custom(cfg=91, d=3, L=6, N_f=N_f, N_c=2**11, N_p=8, N_min=8, N_max=256, N=n, feat_dtype="f16", io_dtype="f16")
+    limit = 0 if passes == 1 else 16 * 1024 * 8 * 8 * w.L * 2
+    cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS | flags, bin_bytes_max=limit)
+    plan = cngp.bwd_plan_info(cfg, n)
+    assert plan["passes"] == passes and (plan["slices_f"] == 0) == (N_f == 2**9 and bool(flags & cngp.BWD_BINNED))
     x_h, D_f_h, Dhat_h, dy_h = W.make_points(w), W.make_feature_codebook(w), W.make_probe_logits(w), W.make_upstream_grad(w)
     D_f_h = (D_f_h.astype(np.float64) * 1e4).astype(D_f_h.dtype)
     x, D_f, Dhat, dy = (torch.from_numpy(a).to(DEV) for a in (x_h, D_f_h, Dhat_h, dy_h))
