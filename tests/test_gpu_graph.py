@@ -61,3 +61,42 @@ def test_graph_replay_matches_the_oracle(flags, n, N_f, passes):
         check_close(f"grad Dhat_c, replay {replay}", gC.cpu().numpy(), gC_ref, A_c, fp16_out=False)
         step()                                              # eager work between the replays
         (gF.sum() + gC.sum()).item()
+
+
+def test_graph_replay_of_the_morton_pipeline():
+    """cngp_morton_sort (its radix passes are rocPRIM's) and cngp_encode_fwd_permuted captured together: every
+    replay gives the oracle's permutation and the plain forward's bits."""
+    w = W.custom(cfg=70, d=3, L=5, N_f=2**11, N_c=2**9, N_p=8, N_min=4, N_max=300, N=50000 + 7, feat_dtype="f16", io_dtype="f16")
+    cfg = cngp.Config.from_workload(w)
+    x_h = W.make_points(w)
+    x = torch.from_numpy(x_h).to(DEV)
+    D_f = torch.from_numpy(W.make_feature_codebook(w)).to(DEV)
+    D_c = cngp.bake_probes(cfg, torch.from_numpy(W.make_probe_logits(w)).to(DEV))
+    y_plain = cngp.encode_fwd(cfg, x, D_f, D_c)
+    n = x.shape[0]
+    ws = torch.empty(int(cngp._lib.cngp_morton_sort_workspace_bytes(w.d, n)), dtype=torch.uint8, device=DEV)
+    perm = torch.empty(n, dtype=torch.int32, device=DEV)
+    xs, y = torch.empty_like(x), torch.empty_like(y_plain)
+
+    def step():
+        cngp._check(cngp._lib.cngp_morton_sort(w.d, x.data_ptr(), n, perm.data_ptr(), xs.data_ptr(), ws.data_ptr(), ws.numel(),
+                                               cngp._stream()))
+        cngp.encode_fwd_permuted(cfg, xs, perm, D_f, D_c, y)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    perm_ref, _ = oracle.morton_order(x_h)
+    for replay in range(4):
+        perm.fill_(-1); xs.fill_(float("nan")); y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        check_exact(f"perm, replay {replay}", perm.cpu().numpy(), perm_ref)
+        assert torch.equal(y.view(torch.int16), y_plain.view(torch.int16)), f"y, replay {replay}"
+        step()                                              # eager work between the replays
+        y.float().sum().item()
