@@ -289,6 +289,8 @@ typedef struct {
     double row_gather_Gps;       /* random 64-byte rows read by 16 lanes each, 1e9 rows per second   */
     double global_atomic_Gseg;   /* fp32 atomic adds to random 64-byte rows, 1e9 rows per second     */
     double lds_atomic_f64_Gps;   /* fp64 atomic adds in LDS (rows of 32), 1e9 adds per second, chip  */
+    double lds_atomic_f32_Gps;   /* the same access pattern with fp32 accumulators                   */
+    double lds_atomic_u32_Gps;   /* ... and with 32-bit integer accumulators                         */
 } cngp_rates;
 int cngp_measure_rates(cngp_rates *out, void *scratch, size_t scratch_bytes, void *stream);
 

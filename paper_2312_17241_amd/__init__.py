@@ -468,7 +468,8 @@ def debug_indices(cfg: Config, x, D_c):
 
 class CRates(ctypes.Structure):
     _fields_ = [(n, ctypes.c_double) for n in ("copy_GBps", "gather4_Gps", "row_gather_Gps",
-                                               "global_atomic_Gseg", "lds_atomic_f64_Gps")]
+                                               "global_atomic_Gseg", "lds_atomic_f64_Gps",
+                                               "lds_atomic_f32_Gps", "lds_atomic_u32_Gps")]
 
 
 def measure_rates(device="cuda") -> dict:

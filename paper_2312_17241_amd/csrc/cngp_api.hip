@@ -1256,14 +1256,15 @@ int cngp_measure_rates(cngp_rates *out, void *scratch, size_t scratch_bytes, voi
     out->row_gather_Gps = lane_ops / 16 / ms / 1e6;
     timed([&] { rate_rows_kernel<16, true><<<blocks, kBlock, 0, s>>>(tab, table_floats / 16 - 1, iters, sink); }, 3, ms);
     out->global_atomic_Gseg = lane_ops / 16 / ms / 1e6;
-    {
-        auto kernel = rate_lds_atomic_kernel;
-        const size_t lds = 16384 * sizeof(double);
+    auto lds_rate = [&](auto kernel, size_t lds, double &gps) {
         if (int r2 = allow_big_lds(kernel, lds)) rc = r2;
         const int lblocks = 1024, liters = 64;
         timed([&] { kernel<<<lblocks, 1024, lds, s>>>(liters, sink); }, 3, ms);
-        out->lds_atomic_f64_Gps = (double)lblocks * 1024 * liters * 8 / ms / 1e6;
-    }
+        gps = (double)lblocks * 1024 * liters * 8 / ms / 1e6;
+    };
+    lds_rate(rate_lds_atomic_kernel<double>, 16384 * sizeof(double), out->lds_atomic_f64_Gps);
+    lds_rate(rate_lds_atomic_kernel<float>, 16384 * sizeof(float), out->lds_atomic_f32_Gps);
+    lds_rate(rate_lds_atomic_kernel<uint32_t>, 16384 * sizeof(uint32_t), out->lds_atomic_u32_Gps);
     (void)hipEventDestroy(t0);
     (void)hipEventDestroy(t1);
     if (rc == CNGP_OK) rc = launch_status("cngp_measure_rates");

@@ -40,12 +40,17 @@ __global__ __launch_bounds__(kBlock) void rate_rows_kernel(float *__restrict__ t
     if (acc == 12345.678f) sink[0] = acc;          // keeps the loads alive
 }
 
-// fp64 atomic adds to random rows of 32 consecutive doubles in a 128 KB LDS array.
+// Atomic adds (no return value, workgroup scope) to random rows of 32 consecutive accumulators of type T in a
+// 64 KB (4-byte T) or 128 KB (fp64) LDS array: 16384 accumulators either way, 32 adjacent lanes per row, so that
+// the three accumulator types are measured on the same access pattern and with the same compiler flags as the
+// kernels of the library.
+template <typename T>
 __global__ __launch_bounds__(1024) void rate_lds_atomic_kernel(const int iters, float *__restrict__ sink)
 {
-    extern __shared__ double lds[];
-    constexpr uint32_t kDoubles = 16384, kRows = kDoubles / 32;
-    for (uint32_t i = threadIdx.x; i < kDoubles; i += 1024) lds[i] = 0.0;
+    extern __shared__ __align__(16) unsigned char rate_lds_raw[];
+    T *lds = reinterpret_cast<T *>(rate_lds_raw);
+    constexpr uint32_t kAccs = 16384, kRows = kAccs / 32;
+    for (uint32_t i = threadIdx.x; i < kAccs; i += 1024) lds[i] = T(0);
     __syncthreads();
     const uint32_t gid = blockIdx.x * 1024 + threadIdx.x, grp = gid / 32, k = gid % 32;
     uint32_t r[8];
@@ -53,10 +58,12 @@ __global__ __launch_bounds__(1024) void rate_lds_atomic_kernel(const int iters, 
     for (int j = 0; j < 8; ++j) r[j] = rate_mix(grp * 8u + j);
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) atomicAdd(lds + ((r[j] + it * 97u) & (kRows - 1)) * 32 + k, 1.0);
+        for (int j = 0; j < 8; ++j)
+            (void)__hip_atomic_fetch_add(lds + ((r[j] + it * 97u) & (kRows - 1)) * 32 + k, T(1), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     __syncthreads();
-    if (lds[threadIdx.x] == -1.0) sink[0] = 1.0f;
+    if (lds[threadIdx.x] == T(3)) sink[0] = 1.0f;    // (every accumulator ends far above 3: keeps the adds alive)
 }
 
 }  // namespace cngp

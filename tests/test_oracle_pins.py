@@ -724,3 +724,91 @@ def test_morton_order_keeps_cells_together():
         ident = (cell[:, 0] * 64 + cell[:, 1]) * 64 + cell[:, 2]
         runs = 1 + np.count_nonzero(np.diff(ident))
         assert runs == len(np.unique(ident))
+
+
+# --------------------------------------------------------------------------- tolerance scales, pinned from above
+# The GPU comparisons divide by magnitude sums the oracle returns (ymag, A_f, A_c, gmag, the decoder's
+# magnitudes).  The tests above bound them from below (magnitude >= |value|); a magnitude that came out too
+# large would loosen every comparison silently, so here each one is fixed exactly: by an identity of the
+# definition, by a regime in which no term cancels (magnitude == value), or by a written-out evaluation.
+
+def test_ymag_equals_value_without_cancellation():
+    w = small(d=3)
+    x, D_f, Dhat, _ = random_tables(w, seed=31)
+    D_c = oracle.bake_probes(Dhat)
+    y, ymag = oracle.encode_fwd(w, x, np.abs(D_f), D_c)              # non-negative codebook: nothing cancels
+    assert np.allclose(ymag, y, rtol=1e-14, atol=0)
+    y, ymag = oracle.encode_fwd(w, x, -np.abs(D_f), D_c)
+    assert np.allclose(ymag, -y, rtol=1e-14, atol=0)
+    y, ymag = oracle.encode_fwd(w, x, np.full_like(D_f, -0.375), D_c)   # constant codebook: the weights sum to one
+    assert np.allclose(ymag, 0.375, rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_feature_gradient_magnitude_mass_and_no_cancellation(d):
+    w = small(d=d)
+    x, D_f, Dhat, dy = random_tables(w, seed=37)
+    _, _, Af, _ = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    # interpolation weights and softmax weights are non-negative and each sum to one
+    want = np.abs(dy).reshape(w.N, w.L, w.F).sum(axis=0)
+    assert np.allclose(Af.sum(axis=1), want, rtol=1e-11, atol=0)
+    gDf, _, Af, _ = oracle.encode_bwd(w, x, D_f, Dhat, np.abs(dy))      # dy >= 0: every term is >= 0
+    assert np.allclose(Af, gDf, rtol=1e-13, atol=0)
+    for top_k in (1, 2):
+        gDf, _, Af, _ = oracle.encode_bwd(w, x, D_f, Dhat, np.abs(dy), top_k=top_k)
+        assert np.allclose(Af, gDf, rtol=1e-13, atol=0)
+        assert np.allclose(Af.sum(axis=1), want, rtol=1e-11, atol=0)
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_logit_gradient_magnitude_written_out(d):
+    """dy >= 0 and D_f >= 0: q_k >= 0, so the magnitude of the term sigma_k (q_k - qbar) is sigma_k (q_k + qbar).
+    Evaluated here with numpy from the index dump (pinned above) and a library softmax."""
+    from scipy.special import softmax
+    w = small(d=d)
+    x, D_f, Dhat, dy = random_tables(w, seed=41)
+    D_f, dy = np.abs(D_f), np.abs(dy)
+    gDf, gDc, _, Ac = oracle.encode_bwd(w, x, D_f, Dhat, dy)
+    base, h2, _, _, weight = oracle.indices(w, x, None, want_weight=True)
+    want = np.zeros_like(Ac)
+    sig = softmax(Dhat.astype(np.float64), axis=2)
+    for n, l, c in itertools.product(range(w.N), range(w.L), range(1 << d)):
+        g = weight[n, l, c] * dy[n, l * w.F:(l + 1) * w.F]
+        s = sig[l, h2[n, l, c]]
+        q = D_f[l, base[n, l, c]:base[n, l, c] + w.N_p] @ g
+        want[l, h2[n, l, c]] += s * (q + s @ q)
+    assert np.allclose(Ac, want, rtol=1e-12, atol=0)
+    # and in general: the magnitude depends on |D_f|, |dy| only
+    x, D_f2, _, dy2 = random_tables(w, seed=43)
+    a = oracle.encode_bwd(w, x, D_f2, Dhat, dy2)
+    b = oracle.encode_bwd(w, x, np.abs(D_f2), Dhat, np.abs(dy2))
+    assert np.allclose(a[2], b[2], rtol=1e-13, atol=0) and np.allclose(a[3], b[3], rtol=1e-13, atol=0)
+
+
+def test_input_gradient_magnitude_closed_form():
+    """One level, d = 2, one output column: gmag_x = N_l ((1 - fy)(|f00 g| + |f10 g|) + fy (|f01 g| + |f11 g|))."""
+    w1 = small(d=2, L=1, N_min=8, N_max=8, N=50)
+    x, D_f, Dhat, dy = random_tables(w1, seed=9)
+    D_c = oracle.bake_probes(Dhat)
+    dy[:, 1] = 0.0
+    *_, fidx = oracle.indices(w1, x, D_c)
+    f = np.abs(D_f[0, fidx[:, 0, :], 0] * dy[:, :1])
+    fx = (x[:, 0].astype(np.float32) * np.float32(8)).astype(np.float64) % 1.0
+    fy = (x[:, 1].astype(np.float32) * np.float32(8)).astype(np.float64) % 1.0
+    _, gmag = oracle.encode_bwd_input(w1, x, D_f, D_c, dy)
+    assert np.allclose(gmag[:, 0], 8.0 * ((1 - fy) * (f[:, 0] + f[:, 1]) + fy * (f[:, 2] + f[:, 3])), rtol=1e-12)
+    assert np.allclose(gmag[:, 1], 8.0 * ((1 - fx) * (f[:, 0] + f[:, 2]) + fx * (f[:, 1] + f[:, 3])), rtol=1e-12)
+
+
+def test_mlp_magnitudes_equal_values_without_cancellation():
+    rng = np.random.default_rng(3)
+    y, W1, W2, W3, dout = rng.random((20, 8)), rng.random((64, 8)), rng.random((64, 64)), rng.random((3, 64)), rng.random((20, 3))
+    out, mag, _ = oracle.mlp_fwd(y, W1, W2, W3, want_mag=True)
+    assert np.allclose(mag, out, rtol=1e-13, atol=0)
+    g, gm, _ = oracle.mlp_bwd(y, W1, W2, W3, dout)
+    for name in ("dy", "dW1", "dW2", "dW3"):
+        assert np.allclose(gm[name], g[name], rtol=1e-13, atol=0), name
+    # signs flipped in the last layer and upstream: magnitudes unchanged, values negated or kept
+    g2, gm2, _ = oracle.mlp_bwd(y, W1, W2, W3, -dout)
+    for name in ("dy", "dW1", "dW2", "dW3"):
+        assert np.allclose(gm2[name], gm[name], rtol=1e-13, atol=0) and np.allclose(g2[name], -g[name], rtol=1e-13, atol=0)
