@@ -174,6 +174,21 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N,
                     float *grad_D_f, float *grad_Dhat_c,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* cngp_encode_bwd for callers that cannot allocate device memory or size a workspace: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * cngp_encode_bwd without the workspace: the scratch (softmax table, level-major dL/dy, vertex sums, bins) lives in
+ * a static device array of cngp_static_scratch_bytes() = 64 MiB inside the library, which every GPU the library
+ * runs on holds from load to process end.  A batch whose binned references would not fit is taken in several
+ * passes inside the call; if the part that does not shrink with the passes (the softmax table L * N_c * N_p * 4
+ * bytes, dL/dy of one pass) still does not fit: CNGP_ERR_WORKSPACE, with the sizes in cngp_last_hip_error().
+ * Calls no hipMalloc / hipFree.  All calls on one GPU share that GPU's array: calls that overlap in time on one
+ * GPU (two streams, two threads) race; calls on one stream are ordered and safe.  Nothing in the array needs to
+ * survive between calls, and nothing in it is assumed to be zero. */
+size_t cngp_static_scratch_bytes(void);
+int cngp_encode_bwd_static(const cngp_config *cfg, const float *x, int64_t N,
+                           const void *D_f, const float *Dhat_c, const void *dy,
+                           float *grad_D_f, float *grad_Dhat_c, void *stream);
+
 /* Gradient with respect to the query points (not used by the paper; for losses on spatial derivatives such
  * as the normals of a signed distance field).  Inside a cell the feature index of Eq. 6 is constant, so
  * the derivative of the forward pass acts on the d-linear weights only:

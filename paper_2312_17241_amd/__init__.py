@@ -65,6 +65,10 @@ def _load():
     lib.cngp_encode_fwd_partial.restype = ctypes.c_int
     lib.cngp_encode_fwd_partial.argtypes = [cfgp, ctypes.c_int32, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.cngp_encode_bwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cngp_encode_bwd_static.restype = ctypes.c_int
+    lib.cngp_encode_bwd_static.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.cngp_static_scratch_bytes.restype = sz
+    lib.cngp_static_scratch_bytes.argtypes = []
     lib.cngp_morton_sort_workspace_bytes.restype = sz
     lib.cngp_morton_sort_workspace_bytes.argtypes = [ctypes.c_int32, i64]
     lib.cngp_morton_sort.restype = ctypes.c_int
@@ -298,6 +302,25 @@ def encode_bwd(cfg: Config, x, D_f, Dhat_c, dy, grad_D_f=None, grad_Dhat_c=None,
         _dev(dy, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "dy"),
         _dev(grad_D_f, torch.float32, (cfg.L, cfg.N_f, cfg.F), "grad_D_f"),
         _dev(grad_Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "grad_Dhat_c"), wp, wb, _stream()))
+    return grad_D_f, grad_Dhat_c
+
+
+def static_scratch_bytes() -> int:
+    return int(_lib.cngp_static_scratch_bytes())
+
+
+def encode_bwd_static(cfg: Config, x, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c):
+    """cngp_encode_bwd_static: the backward pass out of the library's static scratch array.  Allocates nothing,
+    here or in the library: both gradient tensors are the caller's."""
+    N = x.shape[0]
+    c = cfg.c()
+    _check(_lib.cngp_encode_bwd_static(
+        ctypes.byref(c), _dev(x, torch.float32, (N, cfg.d), "x"), N,
+        _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"),
+        _dev(Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "Dhat_c"),
+        _dev(dy, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "dy"),
+        _dev(grad_D_f, torch.float32, (cfg.L, cfg.N_f, cfg.F), "grad_D_f"),
+        _dev(grad_Dhat_c, torch.float32, (cfg.L, cfg.N_c, cfg.N_p), "grad_Dhat_c"), _stream()))
     return grad_D_f, grad_Dhat_c
 
 

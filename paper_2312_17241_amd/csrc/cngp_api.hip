@@ -38,6 +38,29 @@ namespace cngp { int record_hip_failure(hipError_t e, const char *what) { return
 namespace {
 #define CNGP_HIP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return hip_fail(e_, #call); } while (0)
 
+// ---------------------------------------------------------------- static scratch of the allocation-free entry point
+// cngp_encode_bwd_static works in this array instead of a caller's workspace.  Every GPU the library runs on
+// holds its own copy, at its own address, until the process ends.  In host code the array's NAME is only a
+// handle: the device address comes from hipGetSymbolAddress, once per device, and is what every launch gets.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr int    kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out) {
+    int dev = -1;
+    CNGP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CNGP_ERR_UNSUPPORTED;
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        CNGP_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return CNGP_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CNGP_OK;
+}
+
 // ---------------------------------------------------------------- validation (host only)
 int validate(const cngp_config *c) {
     if (!c) return CNGP_ERR_NULL;
@@ -965,6 +988,44 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     const Params p = make_params(cfg);
     // the LDS variants clear these ranges in their preparation launch, the direct one with a launch of its own
     CNGP_DISPATCH_TYPES(dispatch_bwd_np, cfg, p, b, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, workspace, z, s);
+}
+
+size_t cngp_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int cngp_encode_bwd_static(const cngp_config *cfg, const float *x, int64_t N, const void *D_f,
+                           const float *Dhat_c, const void *dy, float *grad_D_f, float *grad_Dhat_c, void *stream) {
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    if (!grad_D_f || !grad_Dhat_c) return CNGP_ERR_NULL;
+    if (N > 0 && (!x || !D_f || !Dhat_c || !dy)) return CNGP_ERR_NULL;
+    // The variant is the one cngp_encode_bwd would pick for (cfg, N).  Only the bins of the binned variant grow
+    // with N: they are bounded until everything fits the static array (the batch is then taken in several passes
+    // inside the one call, like any batch beyond cfg->bin_bytes_max) -- as long as a pass is still binned: this
+    // entry point never falls back to a slower variant behind the caller's back.
+    cngp_config c = *cfg;
+    size_t need = cngp_workspace_bytes(&c, N);
+    if (need > kStaticScratchBytes && N > 0) {
+        const int64_t per0 = bwd_pass_points(cfg, N);
+        const bool    binned = make_bwd_plan_uncached(cfg, per0 < N ? per0 : N).binned;
+        for (uint64_t bins = kStaticScratchBytes / 2; binned && bins >= ((uint64_t)1 << 20); bins /= 2) {
+            if (cfg->bin_bytes_max && cfg->bin_bytes_max < bins) continue;      // never beyond the caller's own bound
+            cngp_config t = *cfg;
+            t.bin_bytes_max = bins;
+            const int64_t per = bwd_pass_points(&t, N);
+            if (!make_bwd_plan_uncached(&t, per < N ? per : N).binned) break;   // passes too small to bin
+            const size_t  n = cngp_workspace_bytes(&t, N);
+            if (n <= kStaticScratchBytes) { c = t; need = n; break; }
+        }
+    }
+    if (need > kStaticScratchBytes) {
+        g_hip_error = "cngp_encode_bwd_static: this configuration and N need " + std::to_string(need) +
+                      " bytes of scratch, the static array holds " + std::to_string(kStaticScratchBytes) +
+                      "; use cngp_encode_bwd with a workspace";
+        return CNGP_ERR_WORKSPACE;
+    }
+    void *ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return cngp_encode_bwd(&c, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, ws, kStaticScratchBytes, stream);
 }
 
 int cngp_encode_bwd_input(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const void *D_c,
