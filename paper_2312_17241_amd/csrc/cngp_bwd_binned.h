@@ -305,11 +305,11 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
 template <int NP, int U>
 __device__ __forceinline__ uint32_t group_bcast(const uint32_t v) {
     if constexpr (NP == 16) {                                             // row_newbcast:U
-        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x150 + U, 0xF, 0xF, false);
+        return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x150 + U, 0xF, 0xF, true);
     } else if constexpr (NP == 4) {                                       // quad_perm:[U,U,U,U]
-        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, U * 0x55, 0xF, 0xF, false);
+        return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, U * 0x55, 0xF, 0xF, true);
     } else if constexpr (NP == 2) {                                       // quad_perm:[U,U,U+2,U+2]
-        return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, U * 0x05 + (U + 2) * 0x50, 0xF, 0xF, false);
+        return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, U * 0x05 + (U + 2) * 0x50, 0xF, 0xF, true);
     } else if constexpr (NP == 1) {
         return v;
     } else {
@@ -355,7 +355,8 @@ __device__ __forceinline__ void accum_steps(const uint4 &r, const T (&g)[NP], Ac
 // replaced by zero, so it adds nothing.
 // BOTH (records of a confidence-table bin, both gradients accumulated): the gather reads the row INSIDE the
 // slice (the softmax row of the record's own confidence row), the accumulator row is the other table's.
-template <int D, int NP, typename T, bool BOTH, typename IoT, typename Load, typename Accum>
+// ACC: doubles per candidate of an accumulator row (2 where both features of a row sit side by side).
+template <int D, int NP, typename T, bool BOTH, int ACC, typename IoT, typename Load, typename Accum>
 __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, const uint32_t beg, const uint32_t end,
                                               const float *__restrict__ x, const IoT *__restrict__ dy_l, const float res,
                                               const uint32_t rows_log2, Load load, Accum accum)
@@ -381,7 +382,9 @@ __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, con
     T     G[4][NP];
     auto stage_a = [&](const uint32_t base, uint2 &q) {
         const uint32_t i = base + lane;
-        q = rec[i < last ? i : last];
+        // streamed once: a non-temporal load keeps it out of the way of the rows that are gathered again and again
+        const unsigned long long raw = __builtin_nontemporal_load(reinterpret_cast<const unsigned long long *>(rec) + (i < last ? i : last));
+        q = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
     };
     auto stage_b = [&](const uint2 &q, float (&xp)[D], Pair &y) {
         const uint32_t n = q.y >> D;
@@ -406,7 +409,7 @@ __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, con
         // byte offset of the accumulator row in LDS; the lanes of the group add their candidate's share
         const uint32_t inside = q.x & row_lo_mask, other = q.x >> rows_log2;
         r = make_uint4((BOTH ? inside : other) * (uint32_t)(NP * sizeof(T)), __float_as_uint(wt * gy.x),
-                       __float_as_uint(wt * gy.y), (BOTH ? other : inside) * (uint32_t)(NP * sizeof(double)));
+                       __float_as_uint(wt * gy.y), (BOTH ? other : inside) * (uint32_t)(ACC * NP * sizeof(double)));
         gather_steps<NP, 0>(r, g, load);
     };
     // prologue: batches b, b + stride, b + 2 stride enter the pipeline
@@ -533,26 +536,28 @@ __device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &s
     if (co.index < 0) return;
     for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) acc[i] = 0.0;
     __syncthreads();
-    const float   *sig_l = sigma + (size_t)co.level * p.N_c * NP;
-    const uint32_t k = (threadIdx.x & 63) % NP;
-    const char    *sig_k = reinterpret_cast<const char *>(sig_l + k);          // this lane's candidate
+    // accumulators [row][f][k]: the NP lanes of a record add to NP consecutive doubles, and feature 1 sits a constant
+    // NP doubles behind feature 0 (an immediate offset of the LDS instruction)
+    const char    *sig_l = reinterpret_cast<const char *>(sigma + (size_t)co.level * p.N_c * NP);   // uniform: scalar base of the gathers
+    const uint32_t k = (threadIdx.x & 63) % NP, k4 = k * (uint32_t)sizeof(float);
     char          *acc_k = reinterpret_cast<char *>(acc + k);
     auto load = [&](const uint32_t off) -> float {           // off: byte offset of the softmax row
-        return NP == 1 ? 1.0f : *reinterpret_cast<const float *>(sig_k + off);
+        return NP == 1 ? 1.0f : *reinterpret_cast<const float *>(sig_l + (off + k4));
     };
     auto accum = [&](const uint32_t off, const float2 g, const float s) {      // off: byte offset of the accumulator row
         double *a = reinterpret_cast<double *>(acc_k + off);
         atomicAdd(a, (double)(s * g.x));
-        atomicAdd(a + plane, (double)(s * g.y));
+        atomicAdd(a + NP, (double)(s * g.y));
     };
     uint32_t beg, end;
     bin_range(baseF, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<D, NP, float, false>(recF + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
-                                (float)p.N_l[co.level], sp.rows_log2, load, accum);
+    drain_records<D, NP, float, false, 2>(recF + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+                                          (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     float *out = gD_f + (size_t)co.level * p.N_f * 2 + (size_t)co.slice * plane * 2;
     for (uint32_t i = threadIdx.x; i < plane * 2; i += kSlicedBlock) {     // i = (row * NP + k) * 2 + f
-        const float v = (float)acc[(i & 1u) * plane + (i >> 1)];
+        const uint32_t e = i >> 1;
+        const float v = (float)acc[(e / NP) * (2 * NP) + (i & 1u) * NP + (e % NP)];
         if (sp.store_direct) out[i] = v;
         else if (v != 0.0f) atomic_add(out + i, v);
     }
@@ -574,16 +579,17 @@ __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &
     const FeatT   *F_l = D_f + (size_t)co.level * p.N_f * 2;
     const uint32_t k = (threadIdx.x & 63) % NP;
     using Raw = typename RawPair<FeatT>::type;
-    const char *feat_k = reinterpret_cast<const char *>(reinterpret_cast<const Raw *>(F_l) + k);   // this lane's candidate
-    char       *acc_k = reinterpret_cast<char *>(acc + k);
-    auto load = [&](const uint32_t off) -> Raw { return *reinterpret_cast<const Raw *>(feat_k + off); };
+    const char    *feat_l = reinterpret_cast<const char *>(F_l);          // uniform: scalar base of the gathers
+    const uint32_t kb = k * (uint32_t)sizeof(Raw);                        // this lane's candidate
+    char          *acc_k = reinterpret_cast<char *>(acc + k);
+    auto load = [&](const uint32_t off) -> Raw { return *reinterpret_cast<const Raw *>(feat_l + (off + kb)); };
     auto accum = [&](const uint32_t off, const float2 g, const Raw raw) {
         const float2 feat = RawPair<FeatT>::to_float2(raw);
         atomicAdd(reinterpret_cast<double *>(acc_k + off), (double)fmaf(feat.x, g.x, feat.y * g.y));
     };
     uint32_t beg, end;
     bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<D, NP, Raw, false>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+    drain_records<D, NP, Raw, false, 1>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
                               (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
@@ -642,7 +648,7 @@ __device__ __forceinline__ void drain_both(const Params &p, const SliceParams &s
     };
     uint32_t beg, end;
     bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<D, NP, float, true>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+    drain_records<D, NP, float, true, 1>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
                                       (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     float *outF = gD_f + (size_t)co.level * p.N_f * 2;
