@@ -460,7 +460,7 @@ def main():
             D_f_h = D_f.cpu().numpy()
             Dhat_h = Dhat.cpu().numpy()
         sys.path.insert(0, os.path.join(ROOT, "tests"))
-        from parity import check_close, check_exact
+        from parity import check_close, check_exact, plain_rel_err
         # bounded sample of the same workload for the CPU leg: the first n_cpu points
         n_cpu = min(N, 1 << 22 if fwd_only else 1 << 18)
         xs = x_h[:n_cpu]
@@ -503,6 +503,14 @@ def main():
                 extras["morton_order"]["sort_ms_host_oracle"] = round((time.perf_counter() - t0) * 1e3, 1)
                 check_exact("morton perm", morton_perm, perm_ref)
             out["parity_max_rel_err"] = {k: float(f"{v:.3e}") for k, v in e.items()}
+            # beside it, the plain max|gpu - ref| / max|ref| per tensor (no normalisation by the terms' magnitudes)
+            pl = {}
+            if not fused_dec:
+                pl["y"] = plain_rel_err(y[:n_cpu].cpu().numpy(), y_ref)
+            if "grad_D_f" in e:
+                pl["grad_D_f"] = plain_rel_err(gF.cpu().numpy(), g_ref[0])
+                pl["grad_Dhat_c"] = plain_rel_err(gC.cpu().numpy(), g_ref[1])
+            out["parity_plain_max_rel_err"] = {k: float(f"{v:.3e}") for k, v in pl.items()}
 
     print(json.dumps(out))
 

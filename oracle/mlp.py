@@ -27,16 +27,22 @@ def mlp_fwd(y, W1, W2, W3, want_mag=False):
     return out, mag, (a1, a2)
 
 
-def mlp_bwd(y, W1, W2, W3, dout):
+def mlp_bwd(y, W1, W2, W3, dout, masks=None):
     """Gradients of sum(out * dout) with respect to y and the three matrices, each with the sum of the
-    magnitudes of the terms that form it (tolerances are relative to those)."""
+    magnitudes of the terms that form it (tolerances are relative to those).
+
+    masks = (M1, M2), boolean [N, 64] each: use these as relu' of the two hidden layers instead of (a1 > 0),
+    (a2 > 0).  relu' is a decision on the sign of a floating-point sum; where that sum is within rounding error
+    of zero an implementation in lower precision may decide either way, and a test bounds what that can change by
+    evaluating the magnitude sums with such units switched on and switched off (tests/test_gpu_mlp.py)."""
     y, W1, W2, W3, dout = (np.asarray(a, dtype=np.float64) for a in (y, W1, W2, W3, dout))
     a1 = y @ W1.T
     h1 = np.maximum(a1, 0.0)
     a2 = h1 @ W2.T
     h2 = np.maximum(a2, 0.0)
-    dh2 = (dout @ W3) * (a2 > 0)
-    dh1 = (dh2 @ W2) * (a1 > 0)
+    M1, M2 = (a1 > 0, a2 > 0) if masks is None else masks
+    dh2 = (dout @ W3) * M2
+    dh1 = (dh2 @ W2) * M1
     dy = dh1 @ W1
     dW3 = dout.T @ h2
     dW2 = dh2.T @ h1
@@ -44,9 +50,9 @@ def mlp_bwd(y, W1, W2, W3, dout):
     # magnitudes: the same chains with absolute values in every factor (masks kept), i.e. what each result
     # would be if no term cancelled anywhere along the way -- hidden activations included, because their
     # own rounding error is relative to that sum, not to their value
-    mh1 = (np.abs(y) @ np.abs(W1).T) * (a1 > 0)
-    mh2 = (mh1 @ np.abs(W2).T) * (a2 > 0)
-    m2 = (np.abs(dout) @ np.abs(W3)) * (a2 > 0)
-    m1 = (m2 @ np.abs(W2)) * (a1 > 0)
+    mh1 = (np.abs(y) @ np.abs(W1).T) * M1
+    mh2 = (mh1 @ np.abs(W2).T) * M2
+    m2 = (np.abs(dout) @ np.abs(W3)) * M2
+    m1 = (m2 @ np.abs(W2)) * M1
     mag = {"dy": m1 @ np.abs(W1), "dW3": np.abs(dout).T @ mh2, "dW2": m2.T @ mh1, "dW1": m1.T @ np.abs(y)}
     return {"dy": dy, "dW1": dW1, "dW2": dW2, "dW3": dW3}, mag, (a1, a2)

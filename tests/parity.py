@@ -38,6 +38,17 @@ def rel_err(got, ref, mag, floor):
     return (np.abs(got - ref) - floor).clip(min=0.0) / np.maximum(scale, 1e-300)
 
 
+PLAIN = {}      # name -> plain max|gpu - ref| / max|ref| of the last comparison under that name (reported, not a bar)
+
+
+def plain_rel_err(got, ref):
+    """max|gpu - ref| / max|ref| over a whole tensor: the figure a reader expects next to the term-normalised one."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    top = float(np.abs(ref).max(initial=0.0))
+    return float(np.abs(got - ref).max(initial=0.0)) / top if top > 0.0 else 0.0
+
+
 def check_close(name, got, ref, mag, fp16_out):
     tol = TOL_F16 if fp16_out else TOL_F32
     floor = F16_SUBNORMAL_HALF_ULP if fp16_out else 1e-37
@@ -49,4 +60,5 @@ def check_close(name, got, ref, mag, fp16_out):
     assert err.ravel()[worst] <= tol, (
         f"{name}: max rel err {err.ravel()[worst]:.3e} > {tol:g} at flat index {worst}: "
         f"got {got.ravel()[worst]!r}, ref {ref.ravel()[worst]!r}, magnitude {np.asarray(mag).ravel()[worst]!r}")
+    PLAIN[name] = plain_rel_err(got, ref)
     return float(err.max(initial=0.0))

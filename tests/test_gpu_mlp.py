@@ -3,10 +3,13 @@ oracle.  Bars: |gpu - ref| <= 2e-3 * M with M the sum of the magnitudes of the t
 (the oracle returns it): inputs, weights, hidden activations and hidden-layer gradients are each rounded to
 fp16 once (relative 2^-11 = 4.9e-4), three of those roundings stack up along the longest path.
 
-The backward pass decides relu'(a) on the sign of a pre-activation.  That decision is taken by both sides
-in their own arithmetic and can differ where |a| is within rounding error of zero, so the seeded batch is
-filtered with the ORACLE's pre-activations first: points with a hidden unit closer to zero than the
-kernel's own rounding can move it are dropped (about a tenth), which also makes the batch sizes ragged."""
+The backward pass decides relu'(a) on the sign of a pre-activation.  Both sides take that decision in their own
+arithmetic, and it can differ where |a| is within the kernel's rounding error of zero.  EVERY point of the batch
+is kept and compared.  Hidden units that close to zero are called ambiguous; for them either decision is accepted,
+and what the choice can change is bounded exactly: the magnitude sums of the oracle evaluated with all ambiguous
+units on, minus the same with all of them off, is the total magnitude of the terms that pass through such a unit,
+hence an upper bound on the difference between any two choices.  That slack is zero for every point without an
+ambiguous unit (its dL/dy is held to the plain bar) and a small part of the weight gradients' magnitude."""
 import numpy as np
 import pytest
 import torch
@@ -34,27 +37,43 @@ def make_case(seed, N, n_in, n_out, io):
     return y, W1, W2, W3, dout
 
 
-def drop_ambiguous(y, W1, W2, W3, dout, io):
-    """Keep the points whose hidden pre-activations all lie clearly on one side of zero.  The weights are
-    fp16 numbers; y is one too when it is stored as fp16, else the kernel rounds it (2^-11 relative).  The
-    kernel's first pre-activation then differs from the oracle's by that rounding and its fp32 summation
-    (1e-5 of the magnitude sum); the second one also by the rounding of every h1 to fp16."""
+def ambiguous_units(y, W1, W2, io):
+    """Boolean [N, 64] for each hidden layer: pre-activations closer to zero than the kernel's rounding can move them.
+    The weights are fp16 numbers; y is one too when it is stored as fp16, else the kernel rounds it (2^-11
+    relative).  The kernel's first pre-activation differs from the oracle's by that rounding and its fp32
+    summation (1e-5 of the magnitude sum); the second one also by the rounding of every h1 to fp16."""
     eps = 2.0 ** -11
+    # a sum of n independent roundings, each uniform within +-eps of its term: five standard deviations, and never
+    # more than the worst case
+    spread = lambda terms_sq, terms_abs: np.minimum(5.0 * eps / np.sqrt(3.0) * np.sqrt(terms_sq), eps * terms_abs)
     a1 = y @ W1.T
     m1 = np.abs(y) @ np.abs(W1).T
-    d1 = ((eps if io == cngp.F32 else 0.0) + 1e-5) * m1
+    d1 = 1e-5 * m1 + (spread((y * y) @ (W1 * W1).T, m1) if io == cngp.F32 else 0.0)
     h1 = np.maximum(a1, 0)
     a2 = h1 @ W2.T
-    d2 = (d1 + eps * h1) @ np.abs(W2).T + 2e-5 * (h1 @ np.abs(W2).T)
-    keep = (np.abs(a1) > d1).all(axis=1) & (np.abs(a2) > d2).all(axis=1)
-    return y[keep], dout[keep], float(keep.mean())
+    # (the first layer's 64 errors are independent of each other as well: they add in quadrature)
+    d2 = np.sqrt((d1 * d1) @ (W2 * W2).T) + spread((h1 * h1) @ (W2 * W2).T, h1 @ np.abs(W2).T) + 2e-5 * (h1 @ np.abs(W2).T)
+    return (np.abs(a1) <= d1, np.abs(a2) <= d2), (a1 > 0, a2 > 0)
 
 
-def check(name, got, ref, mag):
+def backward_reference(y, W1, W2, W3, dout, io):
+    """Oracle gradients, their magnitudes, and per result the slack the ambiguous units allow."""
+    (A1, A2), (P1, P2) = ambiguous_units(y, W1, W2, io)
+    g, mag, _ = oracle.mlp_bwd(y, W1, W2, W3, dout)
+    _, hi, _ = oracle.mlp_bwd(y, W1, W2, W3, dout, masks=(P1 | A1, P2 | A2))
+    _, lo, _ = oracle.mlp_bwd(y, W1, W2, W3, dout, masks=(P1 & ~A1, P2 & ~A2))
+    slack = {k: hi[k] - lo[k] for k in hi}
+    clear = ~(A1.any(axis=1) | A2.any(axis=1))                  # points without an ambiguous unit
+    assert np.all(slack["dy"][clear] == 0.0)
+    return g, hi, slack, float(clear.mean())
+
+
+def check(name, got, ref, mag, slack=None):
     got = np.asarray(got, dtype=np.float64)
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.isfinite(got).all(), name
-    err = np.abs(got - ref) / np.maximum(np.maximum(np.abs(ref), mag), 1e-30)
+    excess = np.abs(got - ref) - (0.0 if slack is None else slack)
+    err = excess.clip(min=0.0) / np.maximum(np.maximum(np.abs(ref), mag), 1e-30)
     worst = np.unravel_index(np.argmax(err), err.shape)
     assert err[worst] <= TOL_F16, f"{name}: rel err {err[worst]:.3e} at {worst}: got {got[worst]}, ref {ref[worst]}, mag {mag[worst]}"
     return float(err.max())
@@ -78,35 +97,35 @@ def test_mlp_forward(n_in, n_out, io, N):
 
 @pytest.mark.parametrize("n_in,n_out,io,N", CASES)
 def test_mlp_backward(n_in, n_out, io, N):
-    y, W1, W2, W3, dout = make_case(n_in * 100 + n_out + 7, N, n_in, n_out, io)
-    y, dout, kept = drop_ambiguous(y, W1, W2, W3, dout, io)
-    assert kept > 0.2 or N < 40          # the bounds are worst-case, so the filter is conservative
-    if y.shape[0] == 0:
-        pytest.skip("the only point of this case was ambiguous")
+    # (the single-point case takes the next seed: with this one its only point has a unit within rounding of zero)
+    y, W1, W2, W3, dout = make_case(n_in * 100 + n_out + 7 + (1 if N == 1 else 0), N, n_in, n_out, io)
+    g, mag, slack, clear = backward_reference(y, W1, W2, W3, dout, io)
+    assert clear >= 0.7, clear                  # most points have no ambiguous unit: they are held to the plain bar
+    for k in ("dW1", "dW2", "dW3"):             # and the slack is a small part of what the weight gradients are made of
+        assert N < 40 or slack[k].sum() <= 0.02 * mag[k].sum(), (k, slack[k].sum() / mag[k].sum())
     cfg = cngp.MlpConfig(n_in, n_out, io, flags=cngp.ZERO_GRADS)
     W = dev(np.concatenate([W1.ravel(), W2.ravel(), W3.ravel()]), torch.float16)
     tdt = torch.float16 if io == cngp.F16 else torch.float32
     gW = torch.full((cfg.weight_count,), float("nan"), device=DEV)
     dy, gW = cngp.mlp_bwd(cfg, dev(y, tdt), W, dev(dout, torch.float32), grad_W=gW)
     torch.cuda.synchronize()
-    g, mag, _ = oracle.mlp_bwd(y, W1, W2, W3, dout)
-    check("dy", dy.float().cpu().numpy(), g["dy"], mag["dy"])
+    check("dy", dy.float().cpu().numpy(), g["dy"], mag["dy"], slack["dy"])
     g1, g2, g3 = (t.cpu().numpy() for t in cfg.split(gW))
-    check("dW1", g1, g["dW1"], mag["dW1"])
-    check("dW2", g2, g["dW2"], mag["dW2"])
-    check("dW3", g3, g["dW3"], mag["dW3"])
+    check("dW1", g1, g["dW1"], mag["dW1"], slack["dW1"])
+    check("dW2", g2, g["dW2"], mag["dW2"], slack["dW2"])
+    check("dW3", g3, g["dW3"], mag["dW3"], slack["dW3"])
     # without the flag the gradient accumulates
     cfg2 = cngp.MlpConfig(n_in, n_out, io)
     _, gW2 = cngp.mlp_bwd(cfg2, dev(y, tdt), W, dev(dout, torch.float32), grad_W=gW.clone())
     torch.cuda.synchronize()
-    check("2 dW2", cfg.split(gW2)[1].cpu().numpy(), 2 * g["dW2"], 2 * mag["dW2"])
+    check("2 dW2", cfg.split(gW2)[1].cpu().numpy(), 2 * g["dW2"], 2 * mag["dW2"], 2 * slack["dW2"])
+    print(f"\nmlp_bwd n_in={n_in} n_out={n_out} N={N}: all {N} points compared, {clear:.1%} of them without an ambiguous unit")
 
 
 def test_mlp_full_size():
     """The benchmark's batch: 2^18 points, 32 inputs (L * F of the headline workload), RGB output."""
     N, n_in, n_out = 2**18, 32, 3
     y, W1, W2, W3, dout = make_case(99, N, n_in, n_out, cngp.F16)
-    y, dout, kept = drop_ambiguous(y, W1, W2, W3, dout, cngp.F16)
     cfg = cngp.MlpConfig(n_in, n_out, cngp.F16, flags=cngp.ZERO_GRADS)
     W = dev(np.concatenate([W1.ravel(), W2.ravel(), W3.ravel()]), torch.float16)
     out = cngp.mlp_fwd(cfg, dev(y, torch.float16), W)
@@ -114,10 +133,12 @@ def test_mlp_full_size():
     torch.cuda.synchronize()
     ref, mag, _ = oracle.mlp_fwd(y, W1, W2, W3, want_mag=True)
     check("out", out.cpu().numpy(), ref, mag)
-    g, gm, _ = oracle.mlp_bwd(y, W1, W2, W3, dout)
-    check("dy", dy.float().cpu().numpy(), g["dy"], gm["dy"])
+    g, gm, slack, clear = backward_reference(y, W1, W2, W3, dout, cngp.F16)
+    assert clear >= 0.7, clear
+    check("dy", dy.float().cpu().numpy(), g["dy"], gm["dy"], slack["dy"])
     for name, t in zip(("dW1", "dW2", "dW3"), cfg.split(gW)):
-        check(name, t.cpu().numpy(), g[name], gm[name])
+        assert slack[name].sum() <= 0.02 * gm[name].sum()
+        check(name, t.cpu().numpy(), g[name], gm[name], slack[name])
 
 
 def test_adam_step_on_a_plain_array():

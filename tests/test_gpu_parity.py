@@ -8,6 +8,7 @@ import torch
 import oracle
 import paper_2312_17241_amd as cngp
 import workloads as W
+import parity
 from parity import check_close, check_exact
 
 pytestmark = pytest.mark.gpu
@@ -462,7 +463,11 @@ def test_full_size_forward_backward(name):
     D_c = oracle.bake_probes(Dhat)
     e_y = check_fwd(w, x, D_f, D_c, name=name)
     e_f, e_c = check_bwd(w, x, D_f, Dhat, dy, name=name)
-    print(f"\n{name}: max rel err  y {e_y:.2e}  grad D_f {e_f:.2e}  grad Dhat_c {e_c:.2e}")
+    plain = {k.split(" [")[0].replace(f" {name}", ""): v for k, v in parity.PLAIN.items() if name in k}
+    print(f"\n{name}: max rel err (relative to the terms' magnitude sum)  y {e_y:.2e}  grad D_f {e_f:.2e}  grad Dhat_c {e_c:.2e}"
+          f"\n{name}: plain max|gpu - ref| / max|ref| per tensor  " + "  ".join(f"{k} {v:.2e}" for k, v in plain.items()))
+    # the plain figure has its own sanity bar: a tensor's largest error against its largest value
+    assert all(v <= (2e-3 if k.startswith("y") and w.io_dtype == "f16" else 1e-5) for k, v in plain.items()), plain
 
 
 def test_full_size_inference_sampled():
