@@ -46,86 +46,87 @@ def algorithmic_bytes(w, n, index_level_bytes=None):
     }
 
 
-def paper_table2(args, np, torch, cngp, W, dev):
-    """Table 2 of the paper, inference column: time of 2^18 lookups on a single resolution level (3D, F = 2, fp16
-    features).  The paper does not say which level; both ends of its range are measured (N_l = 16 and 2048).  Its
-    figures come from an NVIDIA RTX 6000 Ada and are quoted as context only."""
-    rows = [  # N_f, N_c, N_p, microseconds the paper prints
-        (2**16, 1, 1, 28.7), (2**14, 1, 1, 13.7), (2**8, 1, 1, 9.8),
-        (2**8, 2**12, 4, 10.1), (2**8, 2**16, 4, 10.1), (2**8, 2**12, 8, 10.1), (2**8, 2**16, 8, 10.2),
-        (2**8, 2**12, 16, 10.2), (2**8, 2**16, 16, 10.2)]
-    N = 1 << 18
-    out_rows = []
-    for N_f, N_c, N_p, paper_us in rows:
-        ours = {}
-        for res in (16, 2048):
-            w = W.custom(name="table2", cfg=7, d=3, L=1, F=2, N_f=N_f, N_c=N_c, N_p=N_p, N_min=res, N_max=res, N=N,
-                         feat_dtype="f16", io_dtype="f16")
-            fmt = cngp.IDX_BITS if N_p > 1 else cngp.IDX_U8
-            cfg = cngp.Config.from_workload(w, index_format=fmt)
-            x = torch.from_numpy(W.make_points(w)).to(dev)
-            D_f = torch.from_numpy(W.make_feature_codebook(w)).to(dev)
-            D_c = cngp.bake_probes(cfg, torch.from_numpy(W.make_probe_logits(w)).to(dev))
-            y = torch.empty((N, 2), dtype=torch.float16, device=dev)
-            for _ in range(args.warmup):
-                cngp.encode_fwd(cfg, x, D_f, D_c, y)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(args.steps):
-                cngp.encode_fwd(cfg, x, D_f, D_c, y)
-            e1.record()
-            torch.cuda.synchronize()
-            cngp.profile_enable(True)
-            cngp.profile_read()
-            for _ in range(args.steps):
-                cngp.encode_fwd(cfg, x, D_f, D_c, y)
-            torch.cuda.synchronize()
-            ms, cnt = cngp.profile_read()["encode_fwd"]
-            cngp.profile_enable(False)
-            # kernel: events directly around each launch; call: launches back to back, which the launch rate bounds
-            ours[f"N_l={res}"] = {"kernel": round(ms * 1e3 / cnt, 2), "call_to_call": round(e0.elapsed_time(e1) * 1e3 / args.steps, 2)}
-        # training column: the paper times whole NeRF iterations; here the encoding's share of one, bake + forward +
-        # backward over the headline batch (L = 16, 2^18 ray samples), relative to the first row (plain hashing, N_f = 2^16)
-        base = W.WORKLOADS["nerf3d"]
-        w = W.custom(name="table2_train", cfg=3, d=3, L=16, F=2, N_f=N_f, N_c=N_c, N_p=N_p, N_min=16, N_max=2048, N=base.N,
-                     feat_dtype="f16", io_dtype="f16", points=base.points)
-        cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS)
-        x = torch.from_numpy(W.make_points(w)).to(dev)
-        D_f = torch.from_numpy(W.make_feature_codebook(w)).to(dev)
-        Dhat = torch.from_numpy(W.make_probe_logits(w)).to(dev)
-        dy = torch.from_numpy(W.make_upstream_grad(w)).to(dev)
-        D_c = torch.empty((w.L, cfg.index_cols), dtype=torch.uint8, device=dev)
-        y = torch.empty((w.N, 32), dtype=torch.float16, device=dev)
-        gF, gC = torch.empty((16, N_f, 2), device=dev), torch.empty((16, N_c, N_p), device=dev)
-        ws = cngp.alloc_workspace(cfg, w.N, dev)
 
-        def train_step():
-            cngp.bake_probes(cfg, Dhat, D_c)
-            cngp.encode_fwd(cfg, x, D_f, D_c, y)
-            cngp.encode_bwd(cfg, x, D_f, Dhat, dy, gF, gC, workspace=ws)
-        for _ in range(args.warmup):
-            train_step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            train_step()
-        torch.cuda.synchronize()
-        step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        out_rows.append({"N_f": N_f, "N_c": N_c, "N_p": N_p, "us_per_2^18_lookups": ours,
-                         "paper_us_RTX_6000_Ada": paper_us,
-                         "encoding_fwd_bwd_ms_L16_2^18_points": round(step_ms, 4)})
-    for r, paper_ms in zip(out_rows, (5.4, 5.1, 4.5, 6.8, 6.8, 8.3, 8.5, 12.7, 14.1)):
-        r["relative_to_first_row"] = round(r["encoding_fwd_bwd_ms_L16_2^18_points"] / out_rows[0]["encoding_fwd_bwd_ms_L16_2^18_points"], 2)
-        r["paper_whole_iteration_ms_RTX_6000_Ada"] = paper_ms
-        r["paper_relative_to_first_row"] = round(paper_ms / 5.4, 2)
-    print(json.dumps({"metric": "time of 2^18 forward lookups on one level (Table 2 of the paper, inference column)",
-                      "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False,
-                      "dtype": "f32", "data": "synthetic", "vs_baseline": None,
-                      "config": {"workload": "d=3 L=1 F=2, 2^18 uniform points, D_f fp16, D_c at log2(N_p) bits per entry"},
-                      "note": "kernel = HIP events directly around each launch; call_to_call = launches back to back on one stream "
-                              "(bounded by the launch rate at this size); the paper's column is another GPU (context, not a target) "
-                              "and does not say which level it measured",
-                      "rows": out_rows}))
+def sources_sha16():
+    """Hash of the library's sources: profiles/hbm_traffic.json is only quoted while it was measured on these."""
+    import hashlib
+    h = hashlib.sha256()
+    base = os.path.join(ROOT, "paper_2312_17241_amd", "csrc")
+    for f in sorted(os.listdir(base)) + [os.path.join("..", "..", "include", "cngp.h")]:
+        h.update(open(os.path.join(base, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def distinct_vertices(np, x_h, res, sample=1 << 20):
+    """Grid vertices the batch touches, per level (the 2^d corners of every point's cell).  Exact up to `sample`
+    points; a larger batch is extrapolated from its first `sample` points with the occupancy law
+    V(R) = G (1 - exp(-R / G)), G fitted to the sample.  Measurement of the input, used only for the roofline."""
+    n, d = x_h.shape
+    xs = x_h[:sample]
+    out = []
+    for nl in res:
+        v0 = np.floor(xs * np.float32(nl)).astype(np.int64)
+        ids = []
+        for c in range(1 << d):
+            v = v0 + np.array([(c >> i) & 1 for i in range(d)], dtype=np.int64)
+            vid = v[:, 0]
+            for i in range(1, d):
+                vid = vid * (int(nl) + 2) + v[:, i]
+            ids.append(vid)
+        V = int(np.unique(np.concatenate(ids)).size)
+        R = xs.shape[0] << d
+        if n > xs.shape[0] and V < R:
+            lo, hi = float(V), float(V) * 1e6                 # solve G (1 - exp(-R / G)) = V for G by bisection
+            for _ in range(200):
+                G = 0.5 * (lo + hi)
+                if G * -np.expm1(-R / G) < V:
+                    lo = G
+                else:
+                    hi = G
+            V = int(G * -np.expm1(-(n << d) / G))
+        elif n > xs.shape[0]:
+            V = n << d
+        out.append(V)
+    return out
+
+
+def level_rooflines(w, n, index_level_bytes, res, V, rates, fwd_only):
+    """The applicable roofline, level by level: t_l = max(t_stream, t_rand, t_atomic), summed over the levels.
+      t_stream  the level's share of the compulsory bytes (points and outputs split evenly over the levels, the
+                level's own tables) at the measured streaming rate of a cache-resident working set
+      t_rand    rows that must be fetched at random AFTER reuse -- min(corner references, distinct vertices touched)
+                per table -- at the measured random gather rate of the cache level that holds the level's tables
+                (forward: one feature entry per vertex; backward: one softmax row and one feature row per vertex)
+      t_atomic  backward: every row of the two gradient tables that is touched must reach memory at least once,
+                at the measured rate of global atomic row updates
+    Times in microseconds."""
+    fb = 2 if w.feat_dtype == "f16" else 4
+    iob = 2 if w.io_dtype == "f16" else 4
+    corners = 1 << w.d
+    R = n * corners
+    near = 4 << 20                                            # one XCD's L2
+    rows = []
+    for l in range(w.L):
+        reused = min(R, V[l])
+        D_f_l, D_c_l = w.N_f * w.F * fb, index_level_bytes
+        Dhat_l, gD_f_l = w.N_c * w.N_p * 4, w.N_f * w.F * 4
+        pts = n * (4 * w.d / w.L + w.F * iob)
+        f_stream = (pts + D_f_l + D_c_l) / rates["copy_GBps"] * 1e-3
+        f_rand = reused / (rates["gather4_Gps"] if D_f_l <= near else rates["gather4_far_Gps"]) * 1e-3
+        row = {"level": l, "N_l": int(res[l]), "refs": R, "distinct_vertices": int(V[l]),
+               "fwd": {"t_stream_us": round(f_stream, 3), "t_rand_us": round(f_rand, 3),
+                       "t_roof_us": round(max(f_stream, f_rand), 3), "binds": "stream" if f_stream >= f_rand else "rand"}}
+        if not fwd_only:
+            b_stream = (pts + D_f_l + 2 * Dhat_l + gD_f_l) / rates["copy_GBps"] * 1e-3
+            gather = rates["row_gather_Gps"] if D_f_l + Dhat_l <= near else rates["row_gather_far_Gps"]
+            b_rand = (2 if w.N_p > 1 else 0) * reused / gather * 1e-3
+            segs = min(reused, w.N_f // w.N_p) * max(1, w.N_p * w.F * 4 // 64) + (min(reused, w.N_c) * max(1, w.N_p * 4 // 64) if w.N_p > 1 else 0)
+            b_atomic = segs / rates["global_atomic_Gseg"] * 1e-3
+            t = max(b_stream, b_rand, b_atomic)
+            row["bwd"] = {"t_stream_us": round(b_stream, 3), "t_rand_us": round(b_rand, 3), "t_atomic_us": round(b_atomic, 3),
+                          "t_roof_us": round(t, 3), "binds": "stream" if t == b_stream else "rand" if t == b_rand else "atomic"}
+        rows.append(row)
+    return rows
 
 
 def main():
@@ -149,9 +150,6 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements reported beside the headline: per-step median / min, cold caches, "
                          "Morton-ordered points")
-    ap.add_argument("--paper-table2", action="store_true",
-                    help="instead of a workload: the forward-only measurement of the paper's Table 2 (2^18 lookups on a single "
-                         "level, 3D) for its nine rows, with the paper's own figures (another GPU) beside ours as context")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -174,9 +172,6 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     dev = "cuda:0"
-    if args.paper_table2:
-        paper_table2(args, np, torch, cngp, W, dev)
-        return
     w = W.WORKLOADS[args.workload]
     fwd_only = args.workload in ("infer3d", "infer3d_plain", "compact3d")
     fmt = {"infer3d": cngp.IDX_PACKED4, "compact3d": cngp.IDX_BITS}.get(args.workload, cngp.IDX_U8)
@@ -378,12 +373,18 @@ def main():
     dom = max(per_kernel, key=lambda k: per_kernel[k]["ms"])
     dom_ms_per_step = per_kernel[dom]["ms"] / args.steps        # all parts of that kind, per step
     achieved = alg[dom] / (dom_ms_per_step * 1e-3) / 1e9
-    traffic = None
+    # HBM-side traffic of that kernel kind: rocprofv3 FETCH_SIZE / WRITE_SIZE of this same command, kept in
+    # profiles/hbm_traffic.json with a hash of the library sources it was measured on; not quoted when stale
+    traffic, traffic_note = None, "profiles/hbm_traffic.json has no entry for this workload"
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"{dom}:{args.workload}")
+        tj = json.load(open(tpath))
+        if tj.get("_sources_sha16") != sources_sha16():
+            traffic_note = "profiles/hbm_traffic.json was measured on other kernel sources: not quoted"
+        elif f"{dom}:{args.workload}" in tj:
+            traffic, traffic_note = tj[f"{dom}:{args.workload}"], "rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain 1 GiB copy"
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic, "traffic_note": traffic_note,
                 "algorithmic_bytes_per_launch": alg[dom], "avg_launch_us": round(dom_ms_per_step * 1e3, 2)}
 
     out = {
@@ -392,6 +393,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "ms_per_step_with_events": round((t3 - t2) * 1e3 / args.steps, 4),
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "storage_dtypes": {"D_f": w.feat_dtype, "y_and_dy": w.io_dtype, "Dhat_c_and_gradients": "f32",
+                           "note": "dtype is the arithmetic type: every product and sum is fp32 (fp64 in the LDS accumulators)"},
         "config": {"workload": f"{w.name}: d={w.d} L={w.L} F={w.F} N_f={w.N_f} N_c={w.N_c} N_p={w.N_p} "
                                f"N_min={w.N_min} N_max={w.N_max} points={N} ({w.points}) "
                                f"D_f={w.feat_dtype} y/dy={w.io_dtype}",
@@ -407,27 +410,59 @@ def main():
         "kernel_parts": {k: v["parts"] for k, v in per_kernel.items() if len(v["parts"]) > 1},
     }
 
-    # Applicable roofline: the tables are cache resident, so the forward pass is bound by random gathers
-    # and the backward pass by scatter-add atomics.  Both rates are measured now, on this device.
+    # Applicable roofline, level by level (level_rooflines above): the tables are cache resident, so what binds a level is
+    # the larger of its streaming share, its random row fetches after reuse, and (backward) the gradient rows that must
+    # reach memory.  Rates are measured now, on this device; every level is also timed alone through the same entry
+    # points (an L = 1 configuration at that level's resolution with that level's tables).
     rates = cngp.measure_rates(dev)
-    corners = 1 << w.d
-    t_fwd = per_kernel["encode_mlp_fwd" if fused_dec else "encode_fwd"]["ms"] / args.steps * 1e-3
-    gathers = N * w.L * corners                                  # D_f entries the forward must fetch
+    res = cngp.level_resolutions(cfg)
+    V = distinct_vertices(np, x_h, res)
+    levels = level_rooflines(w, N, cfg.index_cols, res, V, rates, fwd_only)
+    t_fwd = per_kernel["encode_mlp_fwd" if fused_dec else "encode_fwd"]["ms"] / args.steps * 1e3          # us
+    if not args.no_extras:
+        y_l = torch.empty((N, w.F), dtype=y.dtype, device=dev)
+        for l, row in enumerate(levels):
+            w_l = W.custom(name="level", cfg=w.cfg, d=w.d, L=1, F=w.F, N_f=w.N_f, N_c=w.N_c, N_p=w.N_p, N_min=int(res[l]),
+                           N_max=int(res[l]), N=N, feat_dtype=w.feat_dtype, io_dtype=w.io_dtype, points=w.points)
+            cfg_l = cngp.Config.from_workload(w_l, index_format=fmt, flags=cngp.ZERO_GRADS | bwd_flag, top_k=args.top_k)
+            ws_l = cngp.alloc_workspace(cfg_l, N, dev)
+            if not fwd_only:
+                dy_l = dy[:, l * w.F:(l + 1) * w.F].contiguous()
+            def one_level():
+                cngp.encode_fwd(cfg_l, x, D_f[l:l + 1], D_c[l:l + 1], y_l, workspace=ws_l)
+                if not fwd_only:
+                    cngp.encode_bwd(cfg_l, x, D_f[l:l + 1], Dhat[l:l + 1], dy_l, gF[l:l + 1], gC[l:l + 1], workspace=ws_l)
+            for _ in range(2):
+                one_level()
+            cngp.profile_enable(True)
+            cngp.profile_read()
+            for _ in range(5):
+                one_level()
+            torch.cuda.synchronize()
+            kl = cngp.profile_read()
+            cngp.profile_enable(False)
+            row["fwd"]["alone_us"] = round(sum(ms for k, (ms, c) in kl.items() if k == "encode_fwd") * 1e3 / 5, 2)
+            if not fwd_only:
+                row["bwd"]["alone_us"] = round(sum(ms for k, (ms, c) in kl.items() if k.startswith("encode_bwd") or k == "zero") * 1e3 / 5, 2)
+                row["bwd"]["alone_variant"] = "binned" if cngp.bwd_plan_info(cfg_l, N)["binned"] else "sliced" if cngp.bwd_plan_info(cfg_l, N)["sliced"] else "direct"
+            del ws_l
+        step()                                                   # y, gF, gC of the whole configuration again, for the check below
+        torch.cuda.synchronize()
+    roof_fwd = sum(r["fwd"]["t_roof_us"] for r in levels)
     out["applicable_roofline"] = {
+        "definition": "per level t_l = max(streaming share, random row fetches after reuse, gradient rows to memory) at rates "
+                      "measured in this run; t_roof = sum over levels; frac = t_roof / measured time of the whole call",
         "measured_rates": {k: round(v, 1) for k, v in rates.items()},
-        "fwd": {"bound": "random 4-byte gathers (D_f entries; the D_c lookups are served from LDS)",
-                "achieved": round(gathers / t_fwd / 1e9, 1), "peak": round(rates["gather4_Gps"], 1),
-                "unit": "G gathers/s", "frac": round(gathers / t_fwd / 1e9 / rates["gather4_Gps"], 3)}}
+        "fwd": {"t_roof_us": round(roof_fwd, 2), "measured_us": round(t_fwd, 2), "frac": round(roof_fwd / t_fwd, 4)},
+        "per_level": levels}
     if not fwd_only:
-        t_bwd = (per_kernel["encode_bwd"]["ms"] + per_kernel.get("zero", {"ms": 0.0})["ms"]) / args.steps * 1e-3
-        updates = N * w.L * corners * w.N_p * (3 if w.N_p > 1 else 2)   # scalar += the backward pass defines
-        out["applicable_roofline"]["bwd"] = {
-            "bound": "scatter-add updates (2 feature + 1 logit per candidate) against the fastest atomic of the "
-                     "chip, LDS fp64; as global fp32 atomics they would take 'global_atomic_floor_ms'",
-            "achieved": round(updates / t_bwd / 1e9, 1), "peak": round(rates["lds_atomic_f64_Gps"], 1),
-            "unit": "G updates/s", "frac": round(updates / t_bwd / 1e9 / rates["lds_atomic_f64_Gps"], 3),
-            "global_atomic_floor_ms": round(updates / 16 / rates["global_atomic_Gseg"] / 1e6, 3),
-            "measured_ms": round(t_bwd * 1e3, 3)}
+        t_bwd = (per_kernel["encode_bwd"]["ms"] + per_kernel.get("zero", {"ms": 0.0})["ms"]) / args.steps * 1e3
+        roof_bwd = sum(r["bwd"]["t_roof_us"] for r in levels)
+        out["applicable_roofline"]["bwd"] = {"t_roof_us": round(roof_bwd, 2), "measured_us": round(t_bwd, 2),
+                                             "frac": round(roof_bwd / t_bwd, 4)}
+        out["applicable_roofline"]["frac"] = round((roof_fwd + roof_bwd) / (t_fwd + t_bwd), 4)
+    else:
+        out["applicable_roofline"]["frac"] = out["applicable_roofline"]["fwd"]["frac"]
 
     if with_opt:
         t_opt = per_kernel["adam_step_bake"]["ms"] / args.steps * 1e-3

@@ -212,6 +212,15 @@ int cngp_encode_bwd_input(const cngp_config *cfg, const float *x, int64_t N, con
 enum { CNGP_PLAN_INFO_COUNT = 15 };
 int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info);
 
+/* Where cngp_encode_bwd keeps what in its workspace for this configuration and N (one pass of it, when the batch is
+ * taken in passes).  Host only; for tests of the plan: region i covers bytes [regions[2i], regions[2i] + regions[2i+1])
+ * -- the softmax table, the level-major dL/dy, the per-vertex sums, then for the binned variant the count matrices,
+ * bin starts and records of the two tables and of the pre-reduced levels.  No two regions may overlap, every one
+ * starts on a 256-byte boundary and ends inside cngp_workspace_bytes(cfg, N).  Returns the number of regions
+ * (at most CNGP_PLAN_REGIONS; 0 for the variant that needs no workspace) or a negative status. */
+enum { CNGP_PLAN_REGIONS = 12 };
+int cngp_bwd_plan_layout(const cngp_config *cfg, int64_t N, uint64_t *regions);
+
 /* Bake (Fig. 3; Sec. 3): D_c[l][r] = index of the largest confidence value in row r of D^_c.
  * Ties: lowest index; NaN never wins; an all-NaN row gives 0.  Result always < N_p.
  *   Dhat_c dev float32 [L, N_c, N_p];  D_c dev, written in cfg->index_format. */
@@ -299,13 +308,17 @@ int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const 
  *   scratch  dev, at least 64 MiB, 256-byte aligned; contents are overwritten.
  * Unlike the other entry points this one waits for its kernels (it returns host-side numbers). */
 typedef struct {
-    double copy_GBps;            /* streaming copy, bytes read + written per second / 1e9            */
+    double copy_GBps;            /* streaming copy of 32 MB to 32 MB, bytes read + written per second / 1e9: a working
+                                    set that stays in the 256 MB memory-side cache, as the tables and the batch of
+                                    a training step do; a copy from DRAM (1 GiB) runs at about 4.5e3 here         */
     double gather4_Gps;          /* random 4-byte gathers from a 4 MB table, 1e9 per second          */
     double row_gather_Gps;       /* random 64-byte rows read by 16 lanes each, 1e9 rows per second   */
     double global_atomic_Gseg;   /* fp32 atomic adds to random 64-byte rows, 1e9 rows per second     */
     double lds_atomic_f64_Gps;   /* fp64 atomic adds in LDS (rows of 32), 1e9 adds per second, chip  */
     double lds_atomic_f32_Gps;   /* the same access pattern with fp32 accumulators                   */
     double lds_atomic_u32_Gps;   /* ... and with 32-bit integer accumulators                         */
+    double row_gather_far_Gps;   /* random 64-byte rows from a 32 MB table (beyond the 4 MB L2 of an XCD) */
+    double gather4_far_Gps;      /* random 4-byte gathers from that table                            */
 } cngp_rates;
 int cngp_measure_rates(cngp_rates *out, void *scratch, size_t scratch_bytes, void *stream);
 

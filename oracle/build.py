@@ -22,5 +22,22 @@ def build(force: bool = False) -> str:
     return LIB
 
 
+def build_sanitized() -> str:
+    """The oracle with its exerciser (sanitize_main.c) as one program under AddressSanitizer and
+    UndefinedBehaviorSanitizer, runtimes linked statically so that nothing has to be preloaded.  Returns the path of
+    the program (in the git-ignored _build/ folder at the repository root); tests/test_oracle_pins.py runs it."""
+    out_dir = os.path.join(os.path.dirname(HERE), "_build")
+    os.makedirs(out_dir, exist_ok=True)
+    exe = os.path.join(out_dir, "oracle_sanitize_check")
+    main = os.path.join(HERE, "sanitize_main.c")
+    if os.path.exists(exe) and os.path.getmtime(exe) >= max(os.path.getmtime(SRC), os.path.getmtime(main)):
+        return exe
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan", "-Wall", "-Wextra", "-o", exe, main, SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 if __name__ == "__main__":
-    print(build(force=True))
+    import sys
+    print(build_sanitized() if "--sanitize" in sys.argv else build(force=True))

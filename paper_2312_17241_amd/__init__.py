@@ -97,6 +97,8 @@ def _load():
     lib.cngp_debug_indices.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.cngp_bwd_plan_info.restype = ctypes.c_int
     lib.cngp_bwd_plan_info.argtypes = [cfgp, i64, vp]
+    lib.cngp_bwd_plan_layout.restype = ctypes.c_int
+    lib.cngp_bwd_plan_layout.argtypes = [cfgp, i64, vp]
     lib.cngp_measure_rates.restype = ctypes.c_int
     lib.cngp_measure_rates.argtypes = [vp, vp, sz, vp]
     lib.cngp_profile_enable.restype = ctypes.c_int
@@ -219,6 +221,16 @@ def bwd_plan_info(cfg: Config, N: int) -> dict:
              "chunks_feat_vtx", "chunks_logit_vtx", "chunks_grid", "grid_slices",
              "binned", "drain_wgs_feat", "drain_wgs_logit", "bin_chunks", "passes")
     return dict(zip(names, list(info)))
+
+
+def bwd_plan_layout(cfg: Config, N: int):
+    """[(offset, bytes)] of the workspace regions encode_bwd would use (see cngp_bwd_plan_layout)."""
+    reg = (ctypes.c_uint64 * 24)()
+    c = cfg.c()
+    k = _lib.cngp_bwd_plan_layout(ctypes.byref(c), N, reg)
+    if k < 0:
+        _check(k)
+    return [(int(reg[2 * i]), int(reg[2 * i + 1])) for i in range(k)]
 
 
 def alloc_workspace(cfg: Config, N: int, device="cuda"):
@@ -492,7 +504,7 @@ def debug_indices(cfg: Config, x, D_c):
 class CRates(ctypes.Structure):
     _fields_ = [(n, ctypes.c_double) for n in ("copy_GBps", "gather4_Gps", "row_gather_Gps",
                                                "global_atomic_Gseg", "lds_atomic_f64_Gps",
-                                               "lds_atomic_f32_Gps", "lds_atomic_u32_Gps")]
+                                               "lds_atomic_f32_Gps", "lds_atomic_u32_Gps", "row_gather_far_Gps", "gather4_far_Gps")]
 
 
 def measure_rates(device="cuda") -> dict:

@@ -40,5 +40,32 @@ def build(force: bool = True, extra=()) -> str:
     return LIB
 
 
+def build_host_sanitized() -> str:
+    """The library's host code (validation, plan, workspace layout) with its exerciser csrc/host_check_main.cpp as one
+    program, AddressSanitizer and UndefinedBehaviorSanitizer on the HOST side only (the device side is compiled as
+    always; nothing of it runs).  About two minutes; the result lives in the git-ignored _build/ folder and is
+    rebuilt only when a source is newer.  tests/test_abi.py runs it."""
+    out_dir = os.path.join(os.path.dirname(HERE), "_build")
+    os.makedirs(out_dir, exist_ok=True)
+    exe = os.path.join(out_dir, "cngp_host_sanitize_check")
+    main = os.path.join(CSRC, "host_check_main.cpp")
+    srcs = [os.path.join(CSRC, f) for f in SOURCES + HEADERS] + [main]
+    if os.path.exists(exe) and os.path.getmtime(exe) >= max(os.path.getmtime(f) for f in srcs):
+        return exe
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC", "-O3")] + ["-O1", "-g"]
+    cmd = [hipcc] + flags + san + ["-o", exe, main] + [os.path.join(CSRC, s) for s in SOURCES]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc (host sanitizers) failed:\n" + "\n".join(
+            ln for ln in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in ln))
+    return exe
+
+
 if __name__ == "__main__":
-    print(build(force=True, extra=sys.argv[1:]))
+    if "--host-sanitizers" in sys.argv:
+        print(build_host_sanitized())
+    else:
+        print(build(force=True, extra=sys.argv[1:]))

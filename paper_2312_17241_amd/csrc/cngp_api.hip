@@ -902,6 +902,37 @@ int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info) {
     return CNGP_OK;
 }
 
+int cngp_bwd_plan_layout(const cngp_config *cfg, int64_t N, uint64_t *regions) {
+    if (!regions) return CNGP_ERR_NULL;
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    const int64_t per = bwd_pass_points(cfg, N);
+    const int64_t n = per < N ? per : N;
+    const BwdPlan b = make_bwd_plan(cfg, n);
+    if (!b.sliced || n == 0) return 0;
+    // what the kernels index, region by region (not the differences of the offsets: those would prove nothing)
+    const uint64_t io = cfg->io_dtype == CNGP_F16 ? 2 : 4;
+    const uint64_t Ld = (uint64_t)b.dense.count, Lh = (uint64_t)cfg->L - Ld, cap = (uint64_t)n << cfg->d;
+    int k = 0;
+    auto add = [&](size_t off, uint64_t bytes) { regions[2 * k] = off; regions[2 * k + 1] = bytes; ++k; };
+    add(b.sigma_off, (uint64_t)cfg->L * cfg->N_c * cfg->N_p * 4);
+    add(b.dyT_off, (uint64_t)n * cfg->L * cfg->F * io);
+    add(b.G_off, (uint64_t)b.dense_verts * 2 * 4);
+    if (b.binned) {
+        const uint64_t sf = b.fused ? 0 : b.slices_f, sc = cfg->N_p > 1 ? b.slices_c : 0;
+        add(b.cntF_off, Lh * b.bin_chunks * sf * 4);
+        add(b.cntC_off, Lh * b.bin_chunks * sc * 4);
+        add(b.baseF_off, sf ? Lh * (sf + 1) * 4 : 0);
+        add(b.baseC_off, sc ? Lh * (sc + 1) * 4 : 0);
+        add(b.recF_off, sf ? Lh * cap * 8 : 0);
+        add(b.recC_off, sc ? Lh * cap * 8 : 0);
+        add(b.cntG_off, Ld * b.bin_chunks * kGridBins * 4);
+        add(b.baseG_off, Ld ? Ld * (kGridBins + 1) * 4 : 0);
+        add(b.recG_off, Ld * cap * 8);
+    }
+    return k;
+}
+
 int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const void *D_c,
                     void *y, void *workspace, size_t workspace_bytes, void *stream) {
     if (int rc = validate(cfg)) return rc;
@@ -1317,6 +1348,11 @@ int cngp_measure_rates(cngp_rates *out, void *scratch, size_t scratch_bytes, voi
     out->row_gather_Gps = lane_ops / 16 / ms / 1e6;
     timed([&] { rate_rows_kernel<16, true><<<blocks, kBlock, 0, s>>>(tab, table_floats / 16 - 1, iters, sink); }, 3, ms);
     out->global_atomic_Gseg = lane_ops / 16 / ms / 1e6;
+    const uint32_t far_floats = (32u << 20) / 4;                    // 32 MB table: beyond every L2, in the memory-side cache
+    timed([&] { rate_rows_kernel<16, false><<<blocks, kBlock, 0, s>>>(tab, far_floats / 16 - 1, iters, sink); }, 3, ms);
+    out->row_gather_far_Gps = lane_ops / 16 / ms / 1e6;
+    timed([&] { rate_rows_kernel<1, false><<<blocks, kBlock, 0, s>>>(tab, far_floats - 1, iters, sink); }, 3, ms);
+    out->gather4_far_Gps = lane_ops / ms / 1e6;
     auto lds_rate = [&](auto kernel, size_t lds, double &gps) {
         if (int r2 = allow_big_lds(kernel, lds)) rc = r2;
         const int lblocks = 1024, liters = 64;

@@ -226,3 +226,54 @@ def test_product_does_not_import_the_oracle():
     for f in os.listdir(os.path.join(ROOT, "oracle")):
         if f.endswith((".py", ".c")):
             assert "paper_2312_17241_amd" not in open(os.path.join(ROOT, "oracle", f)).read(), f
+
+
+def test_backward_plan_layout_stays_inside_the_workspace():
+    """For seeded random configurations and batch sizes, on every backward variant: the regions of the workspace the
+    kernels index (cngp_bwd_plan_layout computes them from the kernels' own extents) are 256-byte aligned, do not
+    overlap, and end inside cngp_workspace_bytes; the plan's counts are consistent with each other."""
+    rng = np.random.default_rng(2024)
+    seen = {"direct": 0, "sliced": 0, "binned": 0, "passes": 0, "fused": 0}
+    for it in range(400):
+        d = int(rng.choice([2, 3]))
+        N_p = int(2 ** rng.integers(0, 5))
+        N_f = int(2 ** rng.integers(max(2, int(np.log2(N_p))), 21))
+        N_c = int(2 ** rng.integers(1, 19))
+        L = int(rng.integers(1, 17))
+        N_min = int(rng.integers(1, 33))
+        N_max = int(N_min * 2 ** rng.integers(0, 9))
+        N = int(rng.choice([1, 63, 4097, 70001, 2**18, 2**20 + 5, 2**22]))
+        flags = int(rng.choice([0, 0, cngp.BWD_SLICED, cngp.BWD_BINNED, cngp.BWD_BINNED | cngp.BWD_NO_PREREDUCE, cngp.BWD_SLICED | cngp.BWD_NO_PREREDUCE]))
+        bound = int(rng.choice([0, 0, 1 << 20, 1 << 26, 1 << 30]))
+        w = W.custom(cfg=7, d=d, L=L, N_f=N_f, N_c=N_c, N_p=N_p, N_min=N_min, N_max=N_max, N=N,
+                     feat_dtype=str(rng.choice(["f16", "f32"])), io_dtype=str(rng.choice(["f16", "f32"])))
+        cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS | flags, bin_bytes_max=bound)
+        total = cngp.workspace_bytes(cfg, N)
+        plan = cngp.bwd_plan_info(cfg, N)
+        regions = cngp.bwd_plan_layout(cfg, N)
+        assert (len(regions) == 0) == (plan["sliced"] == 0), (w, plan)
+        spans = sorted((o, o + b) for o, b in regions if b > 0)
+        for o, e in spans:
+            assert o % 256 == 0 and e <= total, (w, plan, o, e, total)
+        for (o0, e0), (o1, e1) in zip(spans, spans[1:]):
+            assert e0 <= o1, (w, plan, spans)
+        assert plan["passes"] >= 1 and 0 <= plan["dense_levels"] <= L
+        if plan["binned"]:
+            assert plan["sliced"] == 1 and plan["bin_chunks"] >= 1 and plan["drain_wgs_feat"] >= 1
+            assert len(regions) == 12
+        seen["binned" if plan["binned"] else "sliced" if plan["sliced"] else "direct"] += 1
+        seen["passes"] += plan["passes"] > 1
+        seen["fused"] += plan["binned"] == 1 and plan["slices_f"] == 0
+    assert min(seen.values()) >= 5, seen          # the sweep reaches every variant
+
+
+def test_host_code_runs_clean_under_sanitizers():
+    """csrc/host_check_main.cpp drives validation, level table, storage sizes, the backward plan and its workspace
+    layout through the C ABI for 300 seeded random configurations (valid and invalid) in a program whose host side
+    is built with AddressSanitizer and UndefinedBehaviorSanitizer.  No kernel is launched.  The first run compiles
+    the program (about two minutes); later runs reuse it until a source changes."""
+    import subprocess
+    from paper_2312_17241_amd.build import build_host_sanitized
+    exe = build_host_sanitized()
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0 and "clean" in res.stdout, res.stdout + res.stderr

@@ -812,3 +812,18 @@ def test_mlp_magnitudes_equal_values_without_cancellation():
     g2, gm2, _ = oracle.mlp_bwd(y, W1, W2, W3, -dout)
     for name in ("dy", "dW1", "dW2", "dW3"):
         assert np.allclose(gm2[name], gm[name], rtol=1e-13, atol=0) and np.allclose(g2[name], -g[name], rtol=1e-13, atol=0)
+
+
+# --------------------------------------------------------------------------- memory safety of the oracle itself
+
+def test_oracle_runs_clean_under_sanitizers():
+    """oracle/sanitize_main.c calls every oracle function on small inputs (both dimensions, every probing range,
+    F = 1, 2, 4, the sparse variant, NaN and infinite confidences, the cube's corners) in a program built with
+    AddressSanitizer and UndefinedBehaviorSanitizer: an out-of-bounds index or an overflowing conversion aborts it."""
+    import subprocess
+    import sys
+    sys.path.insert(0, os.path.join(os.path.dirname(GOLDEN), "..", "oracle"))
+    from oracle.build import build_sanitized
+    exe = build_sanitized()
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0 and "clean" in res.stdout, res.stdout + res.stderr
