@@ -40,7 +40,7 @@ typedef enum {
     CNGP_OK              =  0,
     CNGP_ERR_NULL        = -1,  /* a required pointer is NULL                                  */
     CNGP_ERR_INVALID     = -2,  /* a size is out of range or not a power of two where required  */
-    CNGP_ERR_UNSUPPORTED = -3,  /* valid in the paper's terms, not built here (e.g. F != 2)     */
+    CNGP_ERR_UNSUPPORTED = -3,  /* valid in the paper's terms, not built here (e.g. F = 3)      */
     CNGP_ERR_WORKSPACE   = -4,  /* workspace missing, misaligned or smaller than required       */
     CNGP_ERR_HIP         = -5   /* a HIP call failed; see cngp_last_hip_error()                 */
 } cngp_status;
@@ -78,7 +78,10 @@ enum {
 typedef struct {
     int32_t  d;            /* dimension of the input domain, 2 or 3                            */
     int32_t  L;            /* number of resolution levels, 1 .. 32                             */
-    int32_t  F;            /* features per codebook entry; only 2 is built                     */
+    int32_t  F;            /* features per codebook entry: 1, 2, 4 or 8 (the paper's value is 2, and 2 is the
+                              width every kernel works in: the others run as ceil(F / 2) passes over pairs of
+                              features, need the workspace also for cngp_encode_fwd, and are refused
+                              (CNGP_ERR_UNSUPPORTED) by the entry points that take no workspace)  */
     uint32_t N_f;          /* entries of the feature codebook per level, power of two          */
     uint32_t N_c;          /* rows of the index codebook per level, power of two               */
     uint32_t N_p;          /* probing range, power of two, 1 .. 16, N_p <= N_f                 */
@@ -109,8 +112,9 @@ int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l);
  * (per level, i.e. the distance between consecutive levels, and in total).  Any output may be NULL.  Host only. */
 int cngp_storage_bytes(const cngp_config *cfg, size_t *D_f_bytes, size_t *D_c_level_bytes, size_t *D_c_bytes);
 
-/* Bytes of device scratch the calls below need for N points (may be 0).  The workspace
- * must be 256-byte aligned; its contents are undefined before and after each call.
+/* Bytes of device scratch the calls below need for N points (may be 0; with F = 2 only cngp_encode_bwd uses it, with
+ * another F the forward passes do as well: one pair of features at a time is copied out of D_f, y, dL/dy and back).
+ * The workspace must be 256-byte aligned; its contents are undefined before and after each call.
  * Returns 0 for an invalid configuration as well (the encode calls then report the error). */
 size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N);
 

@@ -286,7 +286,7 @@ def encode_fwd_permuted(cfg: Config, x_sorted, perm, D_f, D_c, y=None):
     return y
 
 
-def encode_fwd_partial(cfg: Config, levels_loaded, x, D_f, D_c, y=None):
+def encode_fwd_partial(cfg: Config, levels_loaded, x, D_f, D_c, y=None, workspace=None):
     """cngp_encode_fwd_partial: only the first `levels_loaded` levels are read, the others encode to zero."""
     N = x.shape[0]
     if y is None:
@@ -295,7 +295,7 @@ def encode_fwd_partial(cfg: Config, levels_loaded, x, D_f, D_c, y=None):
     _check(_lib.cngp_encode_fwd_partial(
         ctypes.byref(c), int(levels_loaded), _dev(x, torch.float32, (N, cfg.d), "x"), N,
         _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"), _dc(cfg, D_c),
-        _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), ctypes.c_void_p(0), 0, _stream()))
+        _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), *_ws(workspace), _stream()))
     return y
 
 

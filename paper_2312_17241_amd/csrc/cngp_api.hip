@@ -80,7 +80,7 @@ int validate(const cngp_config *c) {
     if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE | CNGP_FWD_SIMPLE | CNGP_BWD_BINNED)) return CNGP_ERR_INVALID;
     if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & (CNGP_BWD_SLICED | CNGP_BWD_BINNED))) return CNGP_ERR_INVALID;
     if (c->top_k > c->N_p || c->reserved != 0) return CNGP_ERR_INVALID;
-    if (c->F != 2) return CNGP_ERR_UNSUPPORTED;
+    if (c->F != 1 && c->F != 2 && c->F != 4 && c->F != 8) return CNGP_ERR_UNSUPPORTED;
     return CNGP_OK;
 }
 
@@ -122,13 +122,13 @@ int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INV
 // ---------------------------------------------------------------- per-kernel timing
 enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_PREP, K_BWD_SLICED, K_BWD_SLICED_V, K_BWD_GRID_DRAIN,
                 K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD,
-                K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_FUSED_FWD, K_COUNT };
+                K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_FUSED_FWD, K_PLANES, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_prepare",
                                            "encode_bwd_sliced_points_and_grid", "encode_bwd_sliced_vertices",
                                            "encode_bwd_bin_grid_sums", "bake_probes", "zero", "debug_indices",
                                            "adam_step_bake", "mlp_fwd", "mlp_bwd",
                                            "encode_bwd_bin_offsets", "encode_bwd_bin_scatter",
-                                           "encode_bwd_bin_drain", "encode_bwd_input", "encode_mlp_fwd"};
+                                           "encode_bwd_bin_drain", "encode_bwd_input", "encode_mlp_fwd", "feature_planes"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -834,6 +834,102 @@ int launch_fused_fwd(const cngp_config *c, const Params &p, const MlpDims &d, co
 }  // namespace
 
 namespace {
+// Workspace of the entry points for entries of two features (every kernel's native width).
+size_t workspace_bytes_pairs(const cngp_config *cfg, int64_t N) {
+    const int64_t per = bwd_pass_points(cfg, N);
+    if (per >= N) return make_bwd_plan(cfg, N).ws_bytes;
+    const size_t  most = make_bwd_plan_uncached(cfg, per).ws_bytes;          // the last pass is the shorter one
+    const size_t  last = make_bwd_plan_uncached(cfg, N - (N - 1) / per * per).ws_bytes;
+    return most > last ? most : last;
+}
+
+// ---------------------------------------------------------------- feature widths other than two
+// F = 1, 4, 8 run as ceil(F / 2) passes over pair planes (cngp_kernels.h, plane_take_kernel): behind the workspace
+// of the two-feature problem sit one plane of D_f, one plane of y or dL/dy, and one plane of grad D_f.
+struct PlaneSpace { size_t pairs, D_off, io_off, g_off, total; };
+cngp_config as_pairs(const cngp_config *c) { cngp_config p = *c; p.F = 2; return p; }
+PlaneSpace plane_space(const cngp_config *c, int64_t N) {
+    const cngp_config c2 = as_pairs(c);
+    PlaneSpace ps;
+    ps.pairs = align256(workspace_bytes_pairs(&c2, N));
+    ps.D_off = ps.pairs;
+    ps.io_off = ps.D_off + align256((size_t)c->L * c->N_f * 2 * (c->feat_dtype == CNGP_F16 ? 2 : 4));
+    ps.g_off = ps.io_off + align256((size_t)N * c->L * 2 * (c->io_dtype == CNGP_F16 ? 2 : 4));
+    ps.total = ps.g_off + align256((size_t)c->L * c->N_f * 2 * sizeof(float));
+    return ps;
+}
+
+template <typename T>
+int take_plane(const void *src, void *dst, int64_t rows, int F, int plane, hipStream_t s) {
+    if (rows <= 0) return CNGP_OK;
+    const int64_t blocks = (rows + kBlock - 1) / kBlock;
+    if (int rc = check_blocks(blocks)) return rc;
+    LaunchTimer t(s, K_PLANES);
+    plane_take_kernel<T><<<(unsigned)blocks, kBlock, 0, s>>>((const T *)src, (T *)dst, rows, F, plane);
+    return launch_status("plane_take_kernel");
+}
+template <typename T>
+int put_plane(const void *src, void *dst, int64_t rows, int F, int plane, bool accumulate, hipStream_t s) {
+    if (rows <= 0) return CNGP_OK;
+    const int64_t blocks = (rows + kBlock - 1) / kBlock;
+    if (int rc = check_blocks(blocks)) return rc;
+    LaunchTimer t(s, K_PLANES);
+    plane_put_kernel<T><<<(unsigned)blocks, kBlock, 0, s>>>((const T *)src, (T *)dst, rows, F, plane, accumulate ? 1 : 0);
+    return launch_status("plane_put_kernel");
+}
+int take_plane_dt(int dtype, const void *src, void *dst, int64_t rows, int F, int plane, hipStream_t s) {
+    return dtype == CNGP_F16 ? take_plane<__half>(src, dst, rows, F, plane, s) : take_plane<float>(src, dst, rows, F, plane, s);
+}
+int put_plane_dt(int dtype, const void *src, void *dst, int64_t rows, int F, int plane, bool acc, hipStream_t s) {
+    return dtype == CNGP_F16 ? put_plane<__half>(src, dst, rows, F, plane, acc, s) : put_plane<float>(src, dst, rows, F, plane, acc, s);
+}
+bool plane_workspace_ok(const void *ws, size_t bytes, const PlaneSpace &ps) {
+    return ws && ((uintptr_t)ws & 255u) == 0 && bytes >= ps.total;
+}
+
+int fwd_planes(const cngp_config *cfg, int32_t levels_loaded, const float *x, int64_t N, const void *D_f, const void *D_c,
+               void *y, void *workspace, size_t workspace_bytes, void *stream) {
+    const PlaneSpace ps = plane_space(cfg, N);
+    if (!plane_workspace_ok(workspace, workspace_bytes, ps)) return CNGP_ERR_WORKSPACE;
+    const cngp_config c2 = as_pairs(cfg);
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    for (int p = 0; p < (cfg->F + 1) / 2; ++p) {
+        if (int rc = take_plane_dt(cfg->feat_dtype, D_f, ws + ps.D_off, (int64_t)levels_loaded * cfg->N_f, cfg->F, p, s)) return rc;
+        if (int rc = cngp_encode_fwd_partial(&c2, levels_loaded, x, N, ws + ps.D_off, D_c, ws + ps.io_off, workspace, ps.pairs, stream)) return rc;
+        if (int rc = put_plane_dt(cfg->io_dtype, ws + ps.io_off, y, N * cfg->L, cfg->F, p, false, s)) return rc;
+    }
+    return CNGP_OK;
+}
+
+int bwd_planes(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const float *Dhat_c, const void *dy,
+               float *grad_D_f, float *grad_Dhat_c, void *workspace, size_t workspace_bytes, void *stream) {
+    hipStream_t s = (hipStream_t)stream;
+    const bool zero_first = (cfg->flags & CNGP_ZERO_GRADS) != 0;
+    if (N == 0) {                                   // nothing to add; clear if asked
+        ZeroList z;
+        if (zero_first) { z.add(grad_D_f, (int64_t)cfg->L * cfg->N_f * cfg->F); z.add(grad_Dhat_c, (int64_t)cfg->L * cfg->N_c * cfg->N_p); }
+        return z.launch(s);
+    }
+    const PlaneSpace ps = plane_space(cfg, N);
+    if (!plane_workspace_ok(workspace, workspace_bytes, ps)) return CNGP_ERR_WORKSPACE;
+    cngp_config c2 = as_pairs(cfg);
+    c2.flags &= ~(uint32_t)CNGP_ZERO_GRADS;         // the plane of grad D_f is cleared here, grad D^_c once if asked
+    char  *ws = (char *)workspace;
+    float *gp = (float *)(ws + ps.g_off);
+    for (int p = 0; p < (cfg->F + 1) / 2; ++p) {
+        ZeroList z;
+        z.add(gp, (int64_t)cfg->L * cfg->N_f * 2);
+        if (p == 0 && zero_first) z.add(grad_Dhat_c, (int64_t)cfg->L * cfg->N_c * cfg->N_p);
+        if (int rc = z.launch(s)) return rc;
+        if (int rc = take_plane_dt(cfg->feat_dtype, D_f, ws + ps.D_off, (int64_t)cfg->L * cfg->N_f, cfg->F, p, s)) return rc;
+        if (int rc = take_plane_dt(cfg->io_dtype, dy, ws + ps.io_off, N * cfg->L, cfg->F, p, s)) return rc;
+        if (int rc = cngp_encode_bwd(&c2, x, N, ws + ps.D_off, Dhat_c, ws + ps.io_off, gp, grad_Dhat_c, workspace, ps.pairs, stream)) return rc;
+        if (int rc = put_plane<float>(gp, grad_D_f, (int64_t)cfg->L * cfg->N_f, cfg->F, p, !zero_first, s)) return rc;
+    }
+    return CNGP_OK;
+}
+
 int adam_coefficients(const cngp_adam *o, AdamCoef *a) {
     if (!(o->lr >= 0.0f) || !std::isfinite(o->lr)) return CNGP_ERR_INVALID;
     if (!(o->beta1 >= 0.0f && o->beta1 < 1.0f) || !(o->beta2 >= 0.0f && o->beta2 < 1.0f)) return CNGP_ERR_INVALID;
@@ -860,7 +956,7 @@ const char *cngp_error_string(int status) {
     case CNGP_OK:              return "success";
     case CNGP_ERR_NULL:        return "a required pointer is NULL";
     case CNGP_ERR_INVALID:     return "invalid argument (size out of range or not a power of two)";
-    case CNGP_ERR_UNSUPPORTED: return "configuration not supported by this build (F must be 2)";
+    case CNGP_ERR_UNSUPPORTED: return "valid in the paper's terms, not supported by this entry point (F other than 1, 2, 4, 8; F != 2 where no workspace can hold the pair planes)";
     case CNGP_ERR_WORKSPACE:   return "workspace missing, misaligned or too small";
     case CNGP_ERR_HIP:         return "a HIP call failed (see cngp_last_hip_error)";
     default:                   return "unknown status";
@@ -879,17 +975,16 @@ int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l) {
 
 size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N) {
     if (validate(cfg) != CNGP_OK || N <= 0) return 0;
-    const int64_t per = bwd_pass_points(cfg, N);
-    if (per >= N) return make_bwd_plan(cfg, N).ws_bytes;
-    const size_t  most = make_bwd_plan_uncached(cfg, per).ws_bytes;          // the last pass is the shorter one
-    const size_t  last = make_bwd_plan_uncached(cfg, N - (N - 1) / per * per).ws_bytes;
-    return most > last ? most : last;
+    if (cfg->F != 2) return plane_space(cfg, N).total;
+    return workspace_bytes_pairs(cfg, N);
 }
 
 int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info) {
     if (!info) return CNGP_ERR_NULL;
     if (int rc = validate(cfg)) return rc;
     if (N < 0) return CNGP_ERR_INVALID;
+    const cngp_config pairs = as_pairs(cfg);                // other widths run as passes over pairs of features
+    cfg = &pairs;
     const int64_t per = bwd_pass_points(cfg, N);
     const BwdPlan b = make_bwd_plan(cfg, per < N ? per : N);
     const int32_t v[CNGP_PLAN_INFO_COUNT] = {
@@ -906,6 +1001,8 @@ int cngp_bwd_plan_layout(const cngp_config *cfg, int64_t N, uint64_t *regions) {
     if (!regions) return CNGP_ERR_NULL;
     if (int rc = validate(cfg)) return rc;
     if (N < 0) return CNGP_ERR_INVALID;
+    const cngp_config pairs = as_pairs(cfg);
+    cfg = &pairs;
     const int64_t per = bwd_pass_points(cfg, N);
     const int64_t n = per < N ? per : N;
     const BwdPlan b = make_bwd_plan(cfg, n);
@@ -940,7 +1037,7 @@ int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     if (N == 0) return CNGP_OK;
     if (!x || !D_f || !y || (!D_c && !index_codebook_is_empty(cfg))) return CNGP_ERR_NULL;
     if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
-    (void)workspace; (void)workspace_bytes;
+    if (cfg->F != 2) return fwd_planes(cfg, cfg->L, x, N, D_f, D_c, y, workspace, workspace_bytes, stream);
     const Params p = make_params(cfg);
     hipStream_t s = (hipStream_t)stream;
     CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s);
@@ -954,7 +1051,7 @@ int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const
     if (!x || !y) return CNGP_ERR_NULL;
     if (levels_loaded > 0 && (!D_f || (!D_c && !index_codebook_is_empty(cfg)))) return CNGP_ERR_NULL;
     if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
-    (void)workspace; (void)workspace_bytes;
+    if (cfg->F != 2) return fwd_planes(cfg, levels_loaded, x, N, D_f, D_c, y, workspace, workspace_bytes, stream);
     Params p = make_params(cfg);
     p.L_loaded = levels_loaded;
     hipStream_t s = (hipStream_t)stream;
@@ -965,6 +1062,7 @@ int cngp_encode_fwd_permuted(const cngp_config *cfg, const float *x_sorted, cons
                              const void *D_c, void *y, void *stream) {
     if (int rc = validate(cfg)) return rc;
     if (N < 0 || N > 0x7fffffffLL) return CNGP_ERR_INVALID;
+    if (cfg->F != 2) return CNGP_ERR_UNSUPPORTED;           // (no workspace argument to hold the pair planes)
     if (N == 0) return CNGP_OK;
     if (!x_sorted || !perm || !D_f || !y || (!D_c && !index_codebook_is_empty(cfg))) return CNGP_ERR_NULL;
     if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
@@ -980,6 +1078,7 @@ int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     if (N < 0) return CNGP_ERR_INVALID;
     if (!grad_D_f || !grad_Dhat_c) return CNGP_ERR_NULL;
     if (N > 0 && (!x || !D_f || !Dhat_c || !dy)) return CNGP_ERR_NULL;
+    if (cfg->F != 2) return bwd_planes(cfg, x, N, D_f, Dhat_c, dy, grad_D_f, grad_Dhat_c, workspace, workspace_bytes, stream);
     hipStream_t s = (hipStream_t)stream;
     const int64_t per = bwd_pass_points(cfg, N);
     if (per < N) {      // several passes over runs of points; the first one clears if asked, the rest accumulate
@@ -1062,6 +1161,7 @@ int cngp_encode_bwd_static(const cngp_config *cfg, const float *x, int64_t N, co
 int cngp_encode_bwd_input(const cngp_config *cfg, const float *x, int64_t N, const void *D_f, const void *D_c,
                           const void *dy, float *grad_x, void *stream) {
     if (int rc = validate(cfg)) return rc;
+    if (cfg->F != 2) return CNGP_ERR_UNSUPPORTED;           // (no workspace argument to hold the pair planes)
     if (N < 0) return CNGP_ERR_INVALID;
     if (N == 0) return CNGP_OK;
     if (!x || !D_f || !dy || !grad_x || (!D_c && !index_codebook_is_empty(cfg))) return CNGP_ERR_NULL;
@@ -1248,6 +1348,7 @@ int cngp_encode_mlp_fwd(const cngp_config *cfg, const cngp_mlp_config *mlp, cons
     if (int rc = validate(cfg)) return rc;
     MlpDims d;
     if (int rc = mlp_dims(mlp, &d)) return rc;
+    if (cfg->F != 2) return CNGP_ERR_UNSUPPORTED;
     if (d.n_in != cfg->L * cfg->F) return CNGP_ERR_INVALID;
     if (N < 0) return CNGP_ERR_INVALID;
     if (N == 0) return CNGP_OK;

@@ -466,6 +466,41 @@ __global__ __launch_bounds__(kBlock) void debug_indices_kernel(
 }
 
 // ------------------------------------------------------------------ fill with zeros
+// ------------------------------------------------------------------ feature widths other than two
+// Every kernel of the library works on codebook entries of two features (the paper's F, Table 1).  F = 1, 4 and 8 are
+// taken two features at a time: the interpolation and the feature gradient act on every feature by itself, and the
+// logit gradient is a sum over the features, so a codebook of F features per entry is ceil(F / 2) codebooks of two
+// that share their indices.  These two kernels move one such pair plane out of and into an array whose rows hold F
+// values: rows of D_f ([L * N_f, F]), of y and dL/dy ([N * L, F]), of grad D_f.  A missing second feature (F = 1)
+// reads as zero and is not written.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void plane_take_kernel(const T *__restrict__ src, T *__restrict__ dst, const int64_t rows,
+                                                           const int F, const int plane)
+{
+    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r >= rows) return;
+    const int f0 = 2 * plane;
+    dst[2 * r] = src[r * F + f0];
+    dst[2 * r + 1] = (f0 + 1 < F) ? src[r * F + f0 + 1] : T(0.0f);
+}
+
+// dst[r][2 plane (+ 1)] = src[r][0 (1)], or += when `accumulate`.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void plane_put_kernel(const T *__restrict__ src, T *__restrict__ dst, const int64_t rows,
+                                                          const int F, const int plane, const int accumulate)
+{
+    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r >= rows) return;
+    const int f0 = 2 * plane;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        if (f0 + j >= F) break;
+        T *o = dst + r * F + f0 + j;
+        if (accumulate) *o = T((float)*o + (float)src[2 * r + j]);
+        else *o = src[2 * r + j];
+    }
+}
+
 // Clears up to kZeroSegments float arrays in one launch; blockIdx.y selects the array.
 constexpr int kZeroSegments = 6;
 struct ZeroSegments {

@@ -88,7 +88,7 @@ def test_reserved_field_must_be_zero_and_top_k_up_to_the_probing_range_is_valid(
 
 
 def test_unsupported_feature_width():
-    c = base_cfg(F=4).c()
+    c = base_cfg(F=3).c()                # 1, 2, 4 and 8 are built; the others are valid in the paper's terms only
     one = ctypes.c_void_p(256)
     assert cngp._lib.cngp_encode_fwd(ctypes.byref(c), one, 8, one, one, one, None, 0, None) == cngp.ERR_UNSUPPORTED
     out = np.zeros(16, np.uint32)        # the level table does not depend on F
