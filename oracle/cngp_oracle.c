@@ -27,6 +27,9 @@
  *       vertex is v0 + 1; no half-voxel offset.  Zero-weight corners are still looked up.
  *   R3  pi  = (1, 2654435761, 805459861)           (the constants of the cited Instant NGP paper)
  *   R4  pi' = (1580030173, 1367130559, 3037000507) (this build's choice; parity unpinned by the paper)
+ *   R16 a fourth input dimension (d = 4; the paper's experiments have d = 2 and 3, Table 1) takes a fourth prime in
+ *       each hash: 1920767767 and 2479700537, the next primes above 2^32/sqrt(5) and 2^32/sqrt(3) (this build's
+ *       choice; parity unpinned by the paper).  d <= 4.
  *   R5  all hashing in uint32 with wrap-around; hash2 is reduced mod N_c; N_f, N_c, N_p powers of two.
  *   R6  every level owns its codebooks; every level is hashed.
  *   R7  softmax has no temperature; D_f values used in the logit gradient are the current ones.
@@ -46,8 +49,8 @@
 #include <stdlib.h>
 #include <string.h>
 
-static const uint32_t PRIMES_HASH[3]  = {1u, 2654435761u, 805459861u};
-static const uint32_t PRIMES_HASH2[3] = {1580030173u, 1367130559u, 3037000507u};
+static const uint32_t PRIMES_HASH[4]  = {1u, 2654435761u, 805459861u, 1920767767u};
+static const uint32_t PRIMES_HASH2[4] = {1580030173u, 1367130559u, 3037000507u, 2479700537u};
 
 /* Table 1 (N_min, N_max, L) with reading R1. */
 int cngp_oracle_level_resolutions(uint32_t N_min, uint32_t N_max, int L, uint32_t *N_l)

@@ -18,8 +18,8 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 M32 = 0xFFFFFFFF
 
 # Constants as the readings fix them (Eq. 3: "large prime numbers, optionally pi_0 = 1").
-PI = (1, 2654435761, 805459861)
-PI2 = (1580030173, 1367130559, 3037000507)
+PI = (1, 2654435761, 805459861, 1920767767)
+PI2 = (1580030173, 1367130559, 3037000507, 2479700537)
 
 
 def py_hash(v, primes):
@@ -68,7 +68,7 @@ def _is_prime(n):
 def test_hash_constants_are_distinct_primes():
     for p in PI[1:] + PI2:
         assert _is_prime(p) and p < 2**32
-    assert len(set(PI + PI2)) == 6
+    assert len(set(PI + PI2)) == 8
     assert PI[0] == 1                      # "optionally pi_0 = 1" (Eq. 3)
 
 
@@ -130,7 +130,7 @@ def test_index_closed_forms_at_origin():
     assert base[:, 0, 0].tolist() == [(w.N_p * i) % w.N_f for i in range(8)]
 
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_indices_match_bigint_evaluation_and_bit_concatenation(d):
     """Every index of the dump equals an evaluation of Eq. 3 / Eq. 6 with Python integers, and
     Eq. 6's arithmetic form equals the bitwise concatenation described in the Fig. 3 caption:
@@ -188,7 +188,7 @@ def resolved_grid(w, Nl, D_f_level, D_c_level):
     return T
 
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_forward_equals_library_interpolation_of_resolved_grid(d):
     w = small(d=d)
     x, D_f, Dhat, _ = random_tables(w, seed=11)
@@ -278,7 +278,7 @@ def loss_soft(w, x, D_f, Dhat, dy):
     return float(np.sum(oracle.encode_soft_fwd(w, x, D_f, Dhat) * dy))
 
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_soft_forward_is_softmax_mix_of_hard_forwards(d):
     """With N_c = 1 the relaxed forward is the softmax-weighted mix of the N_p hard forwards."""
     w = small(d=d, N_c=1, N_p=4, L=2)
@@ -294,7 +294,7 @@ def test_soft_forward_is_softmax_mix_of_hard_forwards(d):
     assert np.allclose(ys, mix, rtol=0, atol=1e-14)
 
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_backward_adjoint_identity(d):
     """The relaxed forward is linear in D_f, so <y~(D_f), dy> = <D_f, gD_f> exactly."""
     w = small(d=d)
@@ -306,7 +306,7 @@ def test_backward_adjoint_identity(d):
     assert np.all(Af >= np.abs(gDf) - 1e-12) and np.all(Ac >= np.abs(gDc) - 1e-12)
 
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_backward_matches_finite_differences(d):
     w = small(d=d, N=120)
     x, D_f, Dhat, dy = random_tables(w, seed=17)
@@ -333,7 +333,7 @@ def test_backward_matches_finite_differences(d):
         assert abs(fd - gDc[i]) <= 1e-6 * max(1.0, abs(gDc[i]))
 
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_backward_invariants(d):
     w = small(d=d)
     x, D_f, Dhat, dy = random_tables(w, seed=19)
@@ -578,7 +578,7 @@ def test_adam_matches_library_optimiser():
 
 # --------------------------------------------------------------------------- gradient with respect to the points
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_input_gradient_is_the_derivative_of_the_pinned_forward(d):
     """Central differences of the hard forward (pinned above by brute force) at points well inside their
     cells on every level: the forward is d-linear there, so a small step stays exact up to rounding."""
@@ -744,7 +744,7 @@ def test_ymag_equals_value_without_cancellation():
     assert np.allclose(ymag, 0.375, rtol=0, atol=1e-15)
 
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_feature_gradient_magnitude_mass_and_no_cancellation(d):
     w = small(d=d)
     x, D_f, Dhat, dy = random_tables(w, seed=37)
@@ -760,7 +760,7 @@ def test_feature_gradient_magnitude_mass_and_no_cancellation(d):
         assert np.allclose(Af.sum(axis=1), want, rtol=1e-11, atol=0)
 
 
-@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("d", [2, 3, 4])
 def test_logit_gradient_magnitude_written_out(d):
     """dy >= 0 and D_f >= 0: q_k >= 0, so the magnitude of the term sigma_k (q_k - qbar) is sigma_k (q_k + qbar).
     Evaluated here with numpy from the index dump (pinned above) and a library softmax."""
