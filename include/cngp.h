@@ -76,7 +76,7 @@ enum {
 
 /* Hyper-parameters of the encoding (Table 1 of the paper, same symbols). */
 typedef struct {
-    int32_t  d;            /* dimension of the input domain, 2 or 3                            */
+    int32_t  d;            /* dimension of the input domain: 2, 3 or 4 (Morton sort: 2 or 3)  */
     int32_t  L;            /* number of resolution levels, 1 .. 32                             */
     int32_t  F;            /* features per codebook entry: 1, 2, 4 or 8 (the paper's value is 2, and 2 is the
                               width every kernel works in: the others run as ceil(F / 2) passes over pairs of

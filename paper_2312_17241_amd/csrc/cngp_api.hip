@@ -64,7 +64,7 @@ int static_scratch(void **out) {
 // ---------------------------------------------------------------- validation (host only)
 int validate(const cngp_config *c) {
     if (!c) return CNGP_ERR_NULL;
-    if (c->d != 2 && c->d != 3) return CNGP_ERR_INVALID;
+    if (c->d < 2 || c->d > 4) return CNGP_ERR_INVALID;
     if (c->L < 1 || c->L > kMaxLevels) return CNGP_ERR_INVALID;
     if (c->F < 1) return CNGP_ERR_INVALID;
     if (!is_pow2(c->N_f) || !is_pow2(c->N_c) || !is_pow2(c->N_p)) return CNGP_ERR_INVALID;
@@ -795,8 +795,12 @@ int dispatch_bwd_np(const cngp_config *c, const Params &p, const BwdPlan &b, con
             if (f16) return io16 ? FN<2, __half, __half>(__VA_ARGS__) : FN<2, __half, float>(__VA_ARGS__); \
             return io16 ? FN<2, float, __half>(__VA_ARGS__) : FN<2, float, float>(__VA_ARGS__);  \
         }                                                                                        \
-        if (f16) return io16 ? FN<3, __half, __half>(__VA_ARGS__) : FN<3, __half, float>(__VA_ARGS__);     \
-        return io16 ? FN<3, float, __half>(__VA_ARGS__) : FN<3, float, float>(__VA_ARGS__);      \
+        if (cfg->d == 3) {                                                                       \
+            if (f16) return io16 ? FN<3, __half, __half>(__VA_ARGS__) : FN<3, __half, float>(__VA_ARGS__); \
+            return io16 ? FN<3, float, __half>(__VA_ARGS__) : FN<3, float, float>(__VA_ARGS__);  \
+        }                                                                                        \
+        if (f16) return io16 ? FN<4, __half, __half>(__VA_ARGS__) : FN<4, __half, float>(__VA_ARGS__);     \
+        return io16 ? FN<4, float, __half>(__VA_ARGS__) : FN<4, float, float>(__VA_ARGS__);      \
     } while (0)
 
 }  // namespace
@@ -1410,7 +1414,7 @@ int cngp_debug_indices(const cngp_config *cfg, const float *x, int64_t N, const 
     if (cfg->index_format == CNGP_IDX_PACKED4) CNGP_DBG(D, kFmtPacked4);   \
     else if (cfg->index_format == CNGP_IDX_BITS) CNGP_DBG(D, kFmtBits);    \
     else CNGP_DBG(D, kFmtU8)
-    if (cfg->d == 2) { CNGP_DBG_FMT(2); } else { CNGP_DBG_FMT(3); }
+    if (cfg->d == 2) { CNGP_DBG_FMT(2); } else if (cfg->d == 3) { CNGP_DBG_FMT(3); } else { CNGP_DBG_FMT(4); }
 #undef CNGP_DBG_FMT
 #undef CNGP_DBG
     return launch_status("debug_indices_kernel");

@@ -12,8 +12,10 @@ constexpr int kBlock = 256;          // threads per workgroup = 4 wavefronts of 
 
 // Eq. 3: hash(v) = XOR_i v_i * pi_i in uint32.  pi: the primes of the hash encoding the
 // method generalises (pi_0 = 1); pi2: a second, disjoint set for hash2 (Sec. 3).
-__device__ constexpr uint32_t kPi[3]  = {1u, 2654435761u, 805459861u};
-__device__ constexpr uint32_t kPi2[3] = {1580030173u, 1367130559u, 3037000507u};
+// The fourth entries serve a fourth input dimension (the paper's experiments stop at three): the next primes
+// above 2^32 / sqrt(5) and 2^32 / sqrt(3).
+__device__ constexpr uint32_t kPi[4]  = {1u, 2654435761u, 805459861u, 1920767767u};
+__device__ constexpr uint32_t kPi2[4] = {1580030173u, 1367130559u, 3037000507u, 2479700537u};
 
 // Everything a kernel needs to know about the encoding, passed by value.
 struct Params {
