@@ -86,10 +86,10 @@ __device__ __forceinline__ uint32_t probe_base(uint32_t h1, const Params &p) {
 constexpr int kFmtU8 = 0, kFmtPacked4 = 1, kFmtBits = 2;
 
 template <int FMT>
-__device__ __forceinline__ uint32_t read_probe(const uint8_t *D_c_level, uint32_t r, uint32_t bits = 4) {
+__device__ __forceinline__ uint32_t read_probe(const uint8_t *D_c_level, uint32_t r, uint32_t bits) {
     if (FMT == kFmtPacked4) {
         uint32_t b = D_c_level[r >> 1];
-        return (b >> ((r & 1u) * 4u)) & 0xFu;
+        return (b >> ((r & 1u) * 4u)) & ((1u << bits) - 1u);
     }
     if (FMT == kFmtBits) {
         if (bits == 0) return 0u;
@@ -99,7 +99,7 @@ __device__ __forceinline__ uint32_t read_probe(const uint8_t *D_c_level, uint32_
         if (sh + bits > 32u) v |= W[w + 1] << (32u - sh);          // only 3-bit entries ever straddle a word
         return v & ((1u << bits) - 1u);
     }
-    return D_c_level[r];
+    return D_c_level[r] & ((1u << bits) - 1u);
 }
 
 // Exact-width entry from a copy of the level's bit string in LDS.  Only 3-bit entries can straddle two

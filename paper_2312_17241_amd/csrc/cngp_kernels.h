@@ -183,7 +183,7 @@ __global__ __launch_bounds__(TILE) void encode_fwd_tile_kernel(
         for (int c = 0; c < (1 << D); ++c)
             idx[c] = probe_base(cell.hash1(c), p) +
                      (FMT == kFmtBits ? read_probe_bits_lds(probes, cell.hash2(c) & p.c_mask, p.log2_Np)
-                                      : read_probe<kFmtPacked4>(probes, cell.hash2(c) & p.c_mask));
+                                      : read_probe<kFmtPacked4>(probes, cell.hash2(c) & p.c_mask, p.log2_Np));
         float2 feat[1 << D];
         const FeatT *table = feat_lds ? feats : F_l;
 #pragma unroll
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(TILE) void encode_bwd_input_kernel(
             const uint32_t r = cell.hash2(c) & p.c_mask;
             const uint32_t probe = !STAGED ? read_probe<FMT>(C_l, r, p.log2_Np)
                                  : FMT == kFmtBits ? read_probe_bits_lds(probes, r, p.log2_Np)
-                                                   : read_probe<kFmtPacked4>(probes, r);
+                                                   : read_probe<kFmtPacked4>(probes, r, p.log2_Np);
             idx[c] = probe_base(cell.hash1(c), p) + probe;
         }
         float2 feat[1 << D];

@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kFusedTile) void encode_mlp_fwd_kernel(
             for (int c = 0; c < (1 << D); ++c)
                 idx[c] = probe_base(cell.hash1(c), p) +
                          (FMT == kFmtBits ? read_probe_bits_lds(probes, cell.hash2(c) & p.c_mask, p.log2_Np)
-                                          : read_probe<kFmtPacked4>(probes, cell.hash2(c) & p.c_mask));
+                                          : read_probe<kFmtPacked4>(probes, cell.hash2(c) & p.c_mask, p.log2_Np));
             float2 feat[1 << D];
 #pragma unroll
             for (int c = 0; c < (1 << D); ++c) feat[c] = load_pair(F_l, idx[c]);

@@ -492,3 +492,25 @@ def test_full_size_inference_sampled():
     y1 = cngp.encode_fwd(cfg1, dev(x), dev(D_f), dev(zeros))
     y1_ref, y1mag = oracle.encode_fwd(w1, x[pick], D_f, zeros)
     check_close("y hash grid sample", host(y1[torch.from_numpy(pick).to(DEV)]), y1_ref, y1mag, fp16_out=True)
+
+
+def test_probe_entries_beyond_the_probe_range_are_masked():
+    """The header requires every D_c entry to be below N_p; the kernels nevertheless mask what they read to the probe
+    range, so a corrupt codebook cannot move a lookup out of its feature codebook.  Entries with extra high bits give
+    exactly the output of the clean codebook (the last level is left clean: nothing here relies on the mask to stay
+    inside the allocation)."""
+    w = W.custom(cfg=88, d=3, L=4, N_f=2**10, N_c=2**8, N_p=4, N_min=4, N_max=64, N=3000 + 5)
+    x, D_f = W.make_points(w), W.make_feature_codebook(w)
+    D_c = oracle.bake_probes(W.make_probe_logits(w))
+    rng = np.random.default_rng(11)
+    for fmt, top in ((cngp.IDX_U8, 64), (cngp.IDX_PACKED4, 4)):
+        bad = D_c.copy()
+        bad[:-1] += (w.N_p * rng.integers(0, top, bad[:-1].shape)).astype(np.uint8)
+        assert bad.max() >= w.N_p
+        pack = (lambda a: dev(a)) if fmt == cngp.IDX_U8 else (lambda a: cngp.pack4(dev(a)))
+        for flags in (0, cngp.FWD_SIMPLE):
+            cfg = cngp.Config.from_workload(w, index_format=fmt, flags=flags)
+            y_clean = cngp.encode_fwd(cfg, dev(x), dev(D_f), pack(D_c))
+            y_bad = cngp.encode_fwd(cfg, dev(x), dev(D_f), pack(bad))
+            torch.cuda.synchronize()
+            assert torch.equal(y_clean, y_bad)
