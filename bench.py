@@ -90,13 +90,16 @@ def distinct_vertices(np, x_h, res, sample=1 << 20):
     return out
 
 
-def level_rooflines(w, n, index_level_bytes, res, V, rates, fwd_only):
+def level_rooflines(w, n, index_level_bytes, res, V, rates, fwd_only, lds_share=0.0):
     """The applicable roofline, level by level: t_l = max(t_stream, t_rand, t_atomic), summed over the levels.
       t_stream  the level's share of the compulsory bytes (points and outputs split evenly over the levels, the
                 level's own tables) at the measured streaming rate of a cache-resident working set
       t_rand    rows that must be fetched at random AFTER reuse -- min(corner references, distinct vertices touched)
                 per table -- at the measured random gather rate of the cache level that holds the level's tables
-                (forward: one feature entry per vertex; backward: one softmax row and one feature row per vertex)
+                (forward: one feature entry per vertex; backward: one softmax row and one feature row per vertex).
+                Forward with the level-resident kernel: the share `lds_share` of a level's feature codebook that a
+                CU's LDS holds is looked up there -- every reference, LDS has no reuse to offer -- at the measured
+                random LDS read rate, the rest as above
       t_atomic  backward: every row of the two gradient tables that is touched must reach memory at least once,
                 at the measured rate of global atomic row updates
     Times in microseconds."""
@@ -112,7 +115,9 @@ def level_rooflines(w, n, index_level_bytes, res, V, rates, fwd_only):
         Dhat_l, gD_f_l = w.N_c * w.N_p * 4, w.N_f * w.F * 4
         pts = n * (4 * w.d / w.L + w.F * iob)
         f_stream = (pts + D_f_l + D_c_l) / rates["copy_GBps"] * 1e-3
-        f_rand = reused / (rates["gather4_Gps"] if D_f_l <= near else rates["gather4_far_Gps"]) * 1e-3
+        f_rand = (1.0 - lds_share) * reused / (rates["gather4_Gps"] if D_f_l <= near else rates["gather4_far_Gps"]) * 1e-3
+        if lds_share > 0.0:
+            f_rand += lds_share * R / rates["lds_gather4_Gps"] * 1e-3
         row = {"level": l, "N_l": int(res[l]), "refs": R, "distinct_vertices": int(V[l]),
                "fwd": {"t_stream_us": round(f_stream, 3), "t_rand_us": round(f_rand, 3),
                        "t_roof_us": round(max(f_stream, f_rand), 3), "binds": "stream" if f_stream >= f_rand else "rand"}}
@@ -365,7 +370,7 @@ def main():
     alg = algorithmic_bytes(w, N, cfg.index_cols)
     per_kernel = {}
     for name, (ms, cnt) in kernels.items():
-        kind = "encode_bwd" if name.startswith("encode_bwd") else name
+        kind = "encode_bwd" if name.startswith("encode_bwd") else "encode_fwd" if name in ("encode_fwd", "encode_fwd_rows") else name
         d = per_kernel.setdefault(kind, {"ms": 0.0, "launches": 0, "parts": {}})
         d["ms"] += ms
         d["launches"] += cnt
@@ -406,6 +411,7 @@ def main():
         "roofline": roofline,
         "beside_the_headline": extras or None,
         "bwd_plan": None if fwd_only else cngp.bwd_plan_info(cfg, N),
+        "fwd_plan": cngp.fwd_plan_info(cfg, N) if ws is not None else {"level_resident": 0},
         "kernels_us_per_step": {k: round(v["ms"] * 1e3 / args.steps, 2) for k, v in per_kernel.items()},
         "kernel_parts": {k: v["parts"] for k, v in per_kernel.items() if len(v["parts"]) > 1},
     }
@@ -417,7 +423,9 @@ def main():
     rates = cngp.measure_rates(dev)
     res = cngp.level_resolutions(cfg)
     V = distinct_vertices(np, x_h, res)
-    levels = level_rooflines(w, N, cfg.index_cols, res, V, rates, fwd_only)
+    fplan = cngp.fwd_plan_info(cfg, N) if ws is not None else {"level_resident": 0}
+    lds_share = fplan["resident_entries"] / w.N_f if fplan["level_resident"] else 0.0
+    levels = level_rooflines(w, N, cfg.index_cols, res, V, rates, fwd_only, lds_share)
     t_fwd = per_kernel["encode_mlp_fwd" if fused_dec else "encode_fwd"]["ms"] / args.steps * 1e3          # us
     if not args.no_extras:
         y_l = torch.empty((N, w.F), dtype=y.dtype, device=dev)
@@ -441,7 +449,7 @@ def main():
             torch.cuda.synchronize()
             kl = cngp.profile_read()
             cngp.profile_enable(False)
-            row["fwd"]["alone_us"] = round(sum(ms for k, (ms, c) in kl.items() if k == "encode_fwd") * 1e3 / 5, 2)
+            row["fwd"]["alone_us"] = round(sum(ms for k, (ms, c) in kl.items() if k in ("encode_fwd", "encode_fwd_rows")) * 1e3 / 5, 2)
             if not fwd_only:
                 row["bwd"]["alone_us"] = round(sum(ms for k, (ms, c) in kl.items() if k.startswith("encode_bwd") or k == "zero") * 1e3 / 5, 2)
                 row["bwd"]["alone_variant"] = "binned" if cngp.bwd_plan_info(cfg_l, N)["binned"] else "sliced" if cngp.bwd_plan_info(cfg_l, N)["sliced"] else "direct"

@@ -70,8 +70,14 @@ enum {
                             /* neither of the two: the library picks by table size and N                   */
     CNGP_BWD_NO_PREREDUCE = 8u, /* LDS variant only: do not pre-reduce coarse levels per grid vertex       */
     CNGP_FWD_SIMPLE = 16u,  /* force the forward variant that reads D_c from memory, not from LDS          */
-    CNGP_BWD_BINNED = 32u   /* LDS variant: bin the references of the hashed levels by slice first instead */
+    CNGP_BWD_BINNED = 32u,  /* LDS variant: bin the references of the hashed levels by slice first instead */
                             /* of scanning all points once per slice (more workspace, see plan info)       */
+    CNGP_FWD_LEVEL = 64u,   /* force the level-resident forward variant (a workgroup keeps one level's     */
+                            /* codebooks in LDS and streams the points; needs cngp_fwd_workspace_bytes);   */
+                            /* CNGP_ERR_UNSUPPORTED / CNGP_ERR_WORKSPACE where it cannot run                */
+    CNGP_FWD_TILE = 128u    /* never take the level-resident variant                                       */
+                            /* none of the three forward flags: the library picks by table size and N; the */
+                            /* three variants give bit-identical encodings                                 */
 };
 
 /* Hyper-parameters of the encoding (Table 1 of the paper, same symbols). */
@@ -117,6 +123,17 @@ int cngp_storage_bytes(const cngp_config *cfg, size_t *D_f_bytes, size_t *D_c_le
  * The workspace must be 256-byte aligned; its contents are undefined before and after each call.
  * Returns 0 for an invalid configuration as well (the encode calls then report the error). */
 size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N);
+
+/* The part of it the forward calls use: room for a level-major copy of the encodings (N * L * F values of io_dtype)
+ * when the level-resident variant would be taken for this configuration and N, else 0 (F != 2: the pair planes,
+ * as above).  A forward call that is given less runs the tile variant instead, with the same result. */
+size_t cngp_fwd_workspace_bytes(const cngp_config *cfg, int64_t N);
+
+/* How a forward call with enough workspace would run: info[0] = 1 if the level-resident variant is taken, info[1] =
+ * entries of a level's feature codebook it keeps in LDS (of N_f), info[2] = runs of points a level is cut into (the
+ * grid has that many workgroups per level), info[3] = bytes of LDS per workgroup.  Host only. */
+enum { CNGP_FWD_PLAN_INFO_COUNT = 4 };
+int cngp_fwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info);
 
 /* Forward encoding (Eq. 6; Fig. 3: enclosing vertices, two hashes, probe lookup, feature
  * gather, d-linear interpolation, concatenation over levels; the forward pass uses the baked
@@ -323,6 +340,7 @@ typedef struct {
     double lds_atomic_u32_Gps;   /* ... and with 32-bit integer accumulators                         */
     double row_gather_far_Gps;   /* random 64-byte rows from a 32 MB table (beyond the 4 MB L2 of an XCD) */
     double gather4_far_Gps;      /* random 4-byte gathers from that table                            */
+    double lds_gather4_Gps;      /* random 4-byte reads of a 128 KB LDS table, every lane its own address */
 } cngp_rates;
 int cngp_measure_rates(cngp_rates *out, void *scratch, size_t scratch_bytes, void *stream);
 

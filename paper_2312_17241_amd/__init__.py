@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libcngp.so")
 
 F32, F16 = 0, 1
 IDX_U8, IDX_PACKED4, IDX_BITS = 0, 1, 2
-ZERO_GRADS, BWD_DIRECT, BWD_SLICED, BWD_NO_PREREDUCE, FWD_SIMPLE, BWD_BINNED = 1, 2, 4, 8, 16, 32
+ZERO_GRADS, BWD_DIRECT, BWD_SLICED, BWD_NO_PREREDUCE, FWD_SIMPLE, BWD_BINNED, FWD_LEVEL, FWD_TILE = 1, 2, 4, 8, 16, 32, 64, 128
 
 OK, ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
 
@@ -59,6 +59,8 @@ def _load():
     lib.cngp_level_resolutions.argtypes = [cfgp, vp]
     lib.cngp_workspace_bytes.restype = sz
     lib.cngp_workspace_bytes.argtypes = [cfgp, i64]
+    lib.cngp_fwd_workspace_bytes.restype = sz
+    lib.cngp_fwd_workspace_bytes.argtypes = [cfgp, i64]
     lib.cngp_encode_fwd.restype = ctypes.c_int
     lib.cngp_encode_fwd.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.cngp_encode_bwd.restype = ctypes.c_int
@@ -97,6 +99,8 @@ def _load():
     lib.cngp_debug_indices.argtypes = [cfgp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.cngp_bwd_plan_info.restype = ctypes.c_int
     lib.cngp_bwd_plan_info.argtypes = [cfgp, i64, vp]
+    lib.cngp_fwd_plan_info.restype = ctypes.c_int
+    lib.cngp_fwd_plan_info.argtypes = [cfgp, i64, vp]
     lib.cngp_bwd_plan_layout.restype = ctypes.c_int
     lib.cngp_bwd_plan_layout.argtypes = [cfgp, i64, vp]
     lib.cngp_measure_rates.restype = ctypes.c_int
@@ -210,6 +214,20 @@ def storage_bytes(cfg: Config) -> dict:
 def workspace_bytes(cfg: Config, N: int) -> int:
     c = cfg.c()
     return int(_lib.cngp_workspace_bytes(ctypes.byref(c), N))
+
+
+def fwd_workspace_bytes(cfg: Config, N: int) -> int:
+    """Bytes the forward calls use of a workspace (0: none; with less they run the tile variant, same result)."""
+    c = cfg.c()
+    return int(_lib.cngp_fwd_workspace_bytes(ctypes.byref(c), N))
+
+
+def fwd_plan_info(cfg: Config, N: int) -> dict:
+    """How encode_fwd would run for (cfg, N) when it is given its workspace (see cngp_fwd_plan_info)."""
+    info = (ctypes.c_int32 * 4)()
+    c = cfg.c()
+    _check(_lib.cngp_fwd_plan_info(ctypes.byref(c), N, info))
+    return dict(zip(("level_resident", "resident_entries", "parts", "lds_bytes"), list(info)))
 
 
 def bwd_plan_info(cfg: Config, N: int) -> dict:
@@ -504,7 +522,8 @@ def debug_indices(cfg: Config, x, D_c):
 class CRates(ctypes.Structure):
     _fields_ = [(n, ctypes.c_double) for n in ("copy_GBps", "gather4_Gps", "row_gather_Gps",
                                                "global_atomic_Gseg", "lds_atomic_f64_Gps",
-                                               "lds_atomic_f32_Gps", "lds_atomic_u32_Gps", "row_gather_far_Gps", "gather4_far_Gps")]
+                                               "lds_atomic_f32_Gps", "lds_atomic_u32_Gps", "row_gather_far_Gps", "gather4_far_Gps",
+                                               "lds_gather4_Gps")]
 
 
 def measure_rates(device="cuda") -> dict:

@@ -2,6 +2,7 @@
 // selection and launches.  See include/cngp.h for the contract of every entry point.
 #include "../../include/cngp.h"
 #include "cngp_kernels.h"
+#include "cngp_fwd_level.h"
 #include "cngp_bwd_sliced.h"
 #include "cngp_bwd_binned.h"
 #include "cngp_rates.h"
@@ -77,8 +78,9 @@ int validate(const cngp_config *c) {
     if (c->io_dtype != CNGP_F32 && c->io_dtype != CNGP_F16) return CNGP_ERR_INVALID;
     if (c->index_format != CNGP_IDX_U8 && c->index_format != CNGP_IDX_PACKED4 && c->index_format != CNGP_IDX_BITS) return CNGP_ERR_INVALID;
     if (c->index_format == CNGP_IDX_PACKED4 && c->N_c < 2) return CNGP_ERR_INVALID;
-    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE | CNGP_FWD_SIMPLE | CNGP_BWD_BINNED)) return CNGP_ERR_INVALID;
+    if (c->flags & ~(uint32_t)(CNGP_ZERO_GRADS | CNGP_BWD_DIRECT | CNGP_BWD_SLICED | CNGP_BWD_NO_PREREDUCE | CNGP_FWD_SIMPLE | CNGP_BWD_BINNED | CNGP_FWD_LEVEL | CNGP_FWD_TILE)) return CNGP_ERR_INVALID;
     if ((c->flags & CNGP_BWD_DIRECT) && (c->flags & (CNGP_BWD_SLICED | CNGP_BWD_BINNED))) return CNGP_ERR_INVALID;
+    if ((c->flags & CNGP_FWD_LEVEL) && (c->flags & (CNGP_FWD_SIMPLE | CNGP_FWD_TILE))) return CNGP_ERR_INVALID;
     if (c->top_k > c->N_p || c->reserved != 0) return CNGP_ERR_INVALID;
     if (c->F != 1 && c->F != 2 && c->F != 4 && c->F != 8) return CNGP_ERR_UNSUPPORTED;
     return CNGP_OK;
@@ -122,13 +124,14 @@ int check_blocks(int64_t blocks) { return (blocks > 0x7fffffffLL) ? CNGP_ERR_INV
 // ---------------------------------------------------------------- per-kernel timing
 enum KernelId { K_FWD = 0, K_BWD_DIRECT, K_BWD_PREP, K_BWD_SLICED, K_BWD_SLICED_V, K_BWD_GRID_DRAIN,
                 K_BAKE, K_ZERO, K_DEBUG, K_ADAM, K_MLP_FWD, K_MLP_BWD,
-                K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_FUSED_FWD, K_PLANES, K_COUNT };
+                K_BWD_BIN_OFFSETS, K_BWD_BIN_SCATTER, K_BWD_BIN_DRAIN, K_BWD_INPUT, K_FUSED_FWD, K_PLANES, K_FWD_ROWS, K_COUNT };
 const char *const kKernelNames[K_COUNT] = {"encode_fwd", "encode_bwd_direct", "encode_bwd_prepare",
                                            "encode_bwd_sliced_points_and_grid", "encode_bwd_sliced_vertices",
                                            "encode_bwd_bin_grid_sums", "bake_probes", "zero", "debug_indices",
                                            "adam_step_bake", "mlp_fwd", "mlp_bwd",
                                            "encode_bwd_bin_offsets", "encode_bwd_bin_scatter",
-                                           "encode_bwd_bin_drain", "encode_bwd_input", "encode_mlp_fwd", "feature_planes"};
+                                           "encode_bwd_bin_drain", "encode_bwd_input", "encode_mlp_fwd", "feature_planes",
+                                           "encode_fwd_rows"};
 
 struct TimedLaunch { int id; hipEvent_t t0, t1; };
 bool g_profile = false;
@@ -183,9 +186,87 @@ int allow_big_lds(K kernel, size_t bytes) {
     return e == hipSuccess ? CNGP_OK : hip_fail(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
 }
 
+// Level-resident forward (cngp_fwd_level.h): which calls take it, and its launch shape.  Host arithmetic only.
+struct FwdLevelPlan {
+    bool     use = false;
+    uint32_t resident = 0;       // entries of a level's feature codebook that sit in LDS
+    size_t   lds = 0;            // dynamic LDS of the kernel
+    int64_t  parts = 0, per_part = 0;
+    size_t   yT_bytes = 0;       // the level-major copy of the encodings: the workspace this variant needs
+};
+constexpr size_t  kLevelLdsBudget = 156 * 1024;
+constexpr int64_t kLevelPartPoints = 65536;              // points per workgroup when the batch is large
+
+FwdLevelPlan fwd_level_plan(const cngp_config *c, int levels_loaded, int64_t N) {
+    FwdLevelPlan f;
+    if (c->F != 2 || levels_loaded < 1 || N <= 0 || (c->flags & (CNGP_FWD_SIMPLE | CNGP_FWD_TILE))) return f;
+    const size_t entry = 2 * (c->feat_dtype == CNGP_F16 ? 2 : 4), io = c->io_dtype == CNGP_F16 ? 2 : 4;
+    const size_t probes = (((size_t)c->N_c + 1) / 2 + 15) & ~(size_t)15;
+    if (((size_t)c->N_f * entry) % 16 != 0 || probes > 64 * 1024) return f;
+    size_t resident = (kLevelLdsBudget - probes) / entry;
+    if (resident > c->N_f) resident = c->N_f;
+    resident &= ~(size_t)3;                                              // whole 16-byte pieces
+    // Measured on nerf3d's, image2d's and the compressed model's tables from 2^12 to 2^24 points: never slower than the
+    // tile variant (1.2x - 3x faster), also when only a seventh of a level's feature codebook fits (sdf3d, 1.15x: the
+    // workgroups of a level run on one XCD, so a level's table is held by one L2 instead of all eight).  So it is taken
+    // whenever it can run -- except for a few thousand points, where its second launch costs more than it saves.
+    if (!(c->flags & CNGP_FWD_LEVEL) && N * levels_loaded < ((int64_t)1 << 15)) return f;
+    f.use = true;
+    f.resident = (uint32_t)resident;
+    f.lds = probes + resident * entry + 16;
+    const int64_t step = (int64_t)kLevelBlock * kLevelUnroll;
+    int64_t parts = 256 / levels_loaded;                                 // one workgroup per CU at least ...
+    if (parts < N / kLevelPartPoints) parts = N / kLevelPartPoints;       // ... and many short ones for a large batch: the levels differ in cost
+    if (parts > (N + step - 1) / step) parts = (N + step - 1) / step;
+    if (parts < 1) parts = 1;
+    f.per_part = ((N + parts - 1) / parts + step - 1) / step * step;
+    f.parts = (N + f.per_part - 1) / f.per_part;
+    f.yT_bytes = (size_t)N * c->L * 2 * io;
+    return f;
+}
+
+template <int D, typename FeatT, typename IoT>
+int launch_fwd_level(const cngp_config *c, const FwdLevelPlan &f, const Params &p, const float *x, int64_t N, const void *D_f,
+                     const void *D_c, void *y, void *yT, hipStream_t s, const int32_t *perm) {
+    const size_t  c_stride = index_level_bytes(c);
+    const int64_t blocks = f.parts * p.L_loaded;
+    if (int rc = check_blocks(blocks)) return rc;
+    const int vec = (c_stride % 16 == 0 && ((uintptr_t)D_c & 15u) == 0) ? 1 : 0;
+#define CNGP_FWD_LEVEL_LAUNCH(FMT)                                                                          \
+    do {                                                                                                    \
+        auto kernel = encode_fwd_level_kernel<D, FeatT, IoT, FMT>;                                          \
+        if (int rc = allow_big_lds(kernel, f.lds)) return rc;                                               \
+        LaunchTimer t(s, K_FWD);                                                                            \
+        kernel<<<(unsigned)blocks, kLevelBlock, f.lds, s>>>(p, x, (const FeatT *)D_f, (const uint8_t *)D_c, \
+                                                            (IoT *)yT, N, (uint32_t)c_stride, vec, f.resident, f.per_part); \
+    } while (0)
+    if (c->index_format == CNGP_IDX_PACKED4) CNGP_FWD_LEVEL_LAUNCH(kFmtPacked4);
+    else if (c->index_format == CNGP_IDX_BITS) CNGP_FWD_LEVEL_LAUNCH(kFmtBits);
+    else CNGP_FWD_LEVEL_LAUNCH(kFmtU8);
+#undef CNGP_FWD_LEVEL_LAUNCH
+    if (int rc = launch_status("encode_fwd_level_kernel")) return rc;
+    const int64_t tiles = (N + kRowsTile - 1) / kRowsTile;
+    if (int rc = check_blocks(tiles)) return rc;
+    const size_t lds = (size_t)kRowsTile * (c->L + 1) * 2 * sizeof(IoT);
+    {
+        LaunchTimer t(s, K_FWD_ROWS);
+        level_major_to_rows_kernel<IoT><<<(unsigned)tiles, kRowsTile, lds, s>>>((const IoT *)yT, (IoT *)y, N, c->L, p.L_loaded, perm);
+    }
+    return launch_status("level_major_to_rows_kernel");
+}
+
 template <int D, typename FeatT, typename IoT>
 int launch_fwd(const cngp_config *c, const Params &p, const float *x, int64_t N, const void *D_f,
-               const void *D_c, void *y, hipStream_t s, const int32_t *perm = nullptr) {
+               const void *D_c, void *y, hipStream_t s, const int32_t *perm = nullptr,
+               void *workspace = nullptr, size_t workspace_bytes = 0) {
+    // level-resident variant: large batches, when the caller lent the room for the level-major copy
+    {
+        const FwdLevelPlan f = fwd_level_plan(c, p.L_loaded, N);
+        const bool room = workspace && workspace_bytes >= f.yT_bytes && ((uintptr_t)workspace & 255u) == 0 &&
+                          ((uintptr_t)D_f & 15u) == 0;
+        if (f.use && room) return launch_fwd_level<D, FeatT, IoT>(c, f, p, x, N, D_f, D_c, y, workspace, s, perm);
+        if ((c->flags & CNGP_FWD_LEVEL) != 0) return f.use ? CNGP_ERR_WORKSPACE : CNGP_ERR_UNSUPPORTED;
+    }
     // tile variant: one level's index codebook and the tile's outputs fit in LDS
     const size_t c_stride = index_level_bytes(c);
     const int    fmt = c->index_format;
@@ -855,7 +936,8 @@ cngp_config as_pairs(const cngp_config *c) { cngp_config p = *c; p.F = 2; return
 PlaneSpace plane_space(const cngp_config *c, int64_t N) {
     const cngp_config c2 = as_pairs(c);
     PlaneSpace ps;
-    ps.pairs = align256(workspace_bytes_pairs(&c2, N));
+    const size_t bwd = workspace_bytes_pairs(&c2, N), fwd = fwd_level_plan(&c2, c2.L, N).yT_bytes;
+    ps.pairs = align256(bwd > fwd ? bwd : fwd);
     ps.D_off = ps.pairs;
     ps.io_off = ps.D_off + align256((size_t)c->L * c->N_f * 2 * (c->feat_dtype == CNGP_F16 ? 2 : 4));
     ps.g_off = ps.io_off + align256((size_t)N * c->L * 2 * (c->io_dtype == CNGP_F16 ? 2 : 4));
@@ -980,7 +1062,27 @@ int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l) {
 size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N) {
     if (validate(cfg) != CNGP_OK || N <= 0) return 0;
     if (cfg->F != 2) return plane_space(cfg, N).total;
-    return workspace_bytes_pairs(cfg, N);
+    const size_t bwd = workspace_bytes_pairs(cfg, N), fwd = fwd_level_plan(cfg, cfg->L, N).yT_bytes;
+    return bwd > fwd ? bwd : fwd;
+}
+
+int cngp_fwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info) {
+    if (!info) return CNGP_ERR_NULL;
+    if (int rc = validate(cfg)) return rc;
+    if (N < 0) return CNGP_ERR_INVALID;
+    const cngp_config pairs = as_pairs(cfg);
+    const FwdLevelPlan f = fwd_level_plan(&pairs, cfg->L, N);
+    info[0] = f.use ? 1 : 0;
+    info[1] = (int32_t)f.resident;
+    info[2] = (int32_t)(f.parts > 0x7fffffffLL ? 0x7fffffffLL : f.parts);
+    info[3] = (int32_t)(f.lds);
+    return CNGP_OK;
+}
+
+size_t cngp_fwd_workspace_bytes(const cngp_config *cfg, int64_t N) {
+    if (validate(cfg) != CNGP_OK || N <= 0) return 0;
+    if (cfg->F != 2) return plane_space(cfg, N).total;
+    return fwd_level_plan(cfg, cfg->L, N).yT_bytes;
 }
 
 int cngp_bwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info) {
@@ -1044,7 +1146,7 @@ int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N, const voi
     if (cfg->F != 2) return fwd_planes(cfg, cfg->L, x, N, D_f, D_c, y, workspace, workspace_bytes, stream);
     const Params p = make_params(cfg);
     hipStream_t s = (hipStream_t)stream;
-    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s);
+    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s, nullptr, workspace, workspace_bytes);
 }
 
 int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const float *x, int64_t N, const void *D_f,
@@ -1059,7 +1161,7 @@ int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const
     Params p = make_params(cfg);
     p.L_loaded = levels_loaded;
     hipStream_t s = (hipStream_t)stream;
-    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s);
+    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x, N, D_f, D_c, y, s, nullptr, workspace, workspace_bytes);
 }
 
 int cngp_encode_fwd_permuted(const cngp_config *cfg, const float *x_sorted, const int32_t *perm, int64_t N, const void *D_f,
@@ -1467,6 +1569,7 @@ int cngp_measure_rates(cngp_rates *out, void *scratch, size_t scratch_bytes, voi
     lds_rate(rate_lds_atomic_kernel<double>, 16384 * sizeof(double), out->lds_atomic_f64_Gps);
     lds_rate(rate_lds_atomic_kernel<float>, 16384 * sizeof(float), out->lds_atomic_f32_Gps);
     lds_rate(rate_lds_atomic_kernel<uint32_t>, 16384 * sizeof(uint32_t), out->lds_atomic_u32_Gps);
+    lds_rate(rate_lds_gather_kernel, 32768 * sizeof(uint32_t), out->lds_gather4_Gps);
     (void)hipEventDestroy(t0);
     (void)hipEventDestroy(t1);
     if (rc == CNGP_OK) rc = launch_status("cngp_measure_rates");

@@ -66,4 +66,25 @@ __global__ __launch_bounds__(1024) void rate_lds_atomic_kernel(const int iters, 
     if (lds[threadIdx.x] == T(3)) sink[0] = 1.0f;    // (every accumulator ends far above 3: keeps the adds alive)
 }
 
+// Random 4-byte reads of a 128 KB LDS table, every lane its own address (the lookups of the level-resident forward
+// kernel): 8 independent reads per lane and iteration.
+__global__ __launch_bounds__(1024) void rate_lds_gather_kernel(const int iters, float *__restrict__ sink)
+{
+    extern __shared__ __align__(16) unsigned char rate_lds_raw[];
+    uint32_t *lds = reinterpret_cast<uint32_t *>(rate_lds_raw);
+    constexpr uint32_t kWords = 32768;
+    for (uint32_t i = threadIdx.x; i < kWords; i += 1024) lds[i] = i;
+    __syncthreads();
+    const uint32_t gid = blockIdx.x * 1024 + threadIdx.x;
+    uint32_t r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = rate_mix(gid * 8u + j);
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += lds[(r[j] + it * 0x9e3779b1u) & (kWords - 1)];
+    }
+    if (acc == 0x12345678u) sink[0] = 1.0f;          // keeps the reads alive
+}
+
 }  // namespace cngp

@@ -62,7 +62,7 @@ BAD = [
     dict(d=1), dict(d=5), dict(L=0), dict(L=33), dict(F=0),
     dict(N_f=0), dict(N_f=3000), dict(N_c=0), dict(N_c=100), dict(N_p=0), dict(N_p=3), dict(N_p=32),
     dict(N_p=16, N_f=8), dict(N_min=0), dict(N_max=8), dict(N_max=2**25),
-    dict(feat_dtype=2), dict(io_dtype=-1), dict(index_format=3), dict(flags=64), dict(flags=6), dict(flags=34),
+    dict(feat_dtype=2), dict(io_dtype=-1), dict(index_format=3), dict(flags=256), dict(flags=64 | 128), dict(flags=64 | 16), dict(flags=6), dict(flags=34),
     dict(index_format=cngp.IDX_PACKED4, N_c=1, N_p=1), dict(top_k=17), dict(N_p=4, top_k=5),
 ]
 

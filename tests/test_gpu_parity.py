@@ -317,7 +317,9 @@ def test_sliced_backward_needs_workspace():
     with pytest.raises(cngp.CngpError) as e:
         cngp.encode_bwd(cfg, dev(x), dev(D_f), dev(Dhat), dev(dy), workspace=None)
     assert e.value.status == cngp.ERR_WORKSPACE
-    assert cngp.workspace_bytes(cngp.Config.from_workload(w, flags=cngp.BWD_DIRECT), w.N) == 0
+    direct = cngp.Config.from_workload(w, flags=cngp.BWD_DIRECT)              # the backward needs none, the forward may
+    assert cngp.workspace_bytes(direct, w.N) == cngp.fwd_workspace_bytes(direct, w.N)
+    assert cngp.workspace_bytes(cngp.Config.from_workload(w, flags=cngp.BWD_DIRECT | cngp.FWD_TILE), w.N) == 0
 
 
 # ------------------------------------------------------------------ edge cases
