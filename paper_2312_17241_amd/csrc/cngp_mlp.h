@@ -5,18 +5,23 @@
 //
 // The only dense contraction of the method, hence the only user of the matrix cores here.  Everything is
 // computed transposed, points along the columns: one wavefront owns 32 points and every layer is
-//     (weights as the A operand, 32 x 8 per instruction) x (activations^T as the B operand, 8 x 32)
-// with v_mfma_f32_32x32x8_f16.  The accumulator layout of that instruction (lane = column, four
-// consecutive rows per register group) IS its B operand layout, so the activations of one layer feed the
-// next straight from registers: after ReLU and rounding to fp16, accumulator registers 4j .. 4j+3 of row
-// tile t are the B operand of K-step 4t + j.  Only the weight gradients, which contract over the points,
-// need a transpose; it goes through a per-wavefront tile in LDS.
+//     (weights as the A operand, 32 x 16 per instruction) x (activations^T as the B operand, 16 x 32)
+// with v_mfma_f32_32x32x16_f16.  The accumulator layout (lane = column, four consecutive rows per register
+// group, the two halves of the wavefront four rows apart) feeds the next layer straight from registers:
+// after ReLU and rounding to fp16, accumulator registers 4j .. 4j+3 of row tile t hold rows
+// 32t + 8j + 4h .. + 3 (h = lane / 32), a "quarter step"; two quarter steps 2s', 2s'+1 side by side are
+// this lane's eight B values of K-step s'.  That is not the instruction's natural K order (rows
+// 16s' + 8h .. + 7) but a permutation of it inside the step, and a contraction does not care about the
+// order of its terms as long as both operands use the same one: the weights are staged in LDS in that
+// order.  Only the weight gradients, which contract over the points, need a transpose; it goes through a
+// per-wavefront tile in LDS.
 #pragma once
 #include "cngp_bwd_sliced.h"   // wave_lds_fence
 
 namespace cngp {
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float    acc16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kMlpHidden = 64;
@@ -25,17 +30,21 @@ constexpr int kMlpMaxIn = 32, kMlpMaxOut = 16;
 
 struct MlpDims {
     int n_in, n_out;
-    int ks1;                                   // K-steps of layer 1: ceil(n_in / 8)
-    int ks3;                                   // K-steps of the transposed output layer: ceil(n_out / 8)
+    int ks1;                                   // quarter steps (8 rows) of layer 1: ceil(n_in / 8)
+    int ks3;                                   // quarter steps of the transposed output layer: ceil(n_out / 8)
     int vec_in, vec_out;                       // rows of y (and dL/dy) / of dL/dout can be read four values at a time
 };
 
-// Slots of the weight operands in LDS; a slot holds one half4 per lane (512 bytes), ready to be used as
-// the A operand of one instruction.
+// Slots of the weight operands in LDS, counted in quarter steps (one half4 per lane: rows 8s + 4h .. + 3 of the
+// contraction).  Slots 2p and 2p + 1 lie side by side per lane, so that operand p of an instruction is one
+// 16-byte read: half8 number p * 64 + lane.
 enum : int { kOpW1 = 0, kOpW2 = 8, kOpW3 = 24, kOpW3T = 32, kOpW2T = 36, kOpW1T = 52, kOpFwdSlots = 32, kOpAllSlots = 60 };
 
-__device__ __forceinline__ acc16_t mfma(const half4_t a, const half4_t b, const acc16_t c) {
-    return __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ half8_t cat(const half4_t lo, const half4_t hi) {
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+__device__ __forceinline__ acc16_t mfma(const half8_t a, const half8_t b, const acc16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
 __device__ __forceinline__ acc16_t acc_zero() {
@@ -55,8 +64,9 @@ __device__ __forceinline__ _Float16 w_at(const __half *W, int rows, int cols, bo
 // they are, with wide coalesced loads (`raw`: room for weight_count halves, 16-byte aligned, may be reused
 // after the barrier at the end); building the operand layout from global memory element by element is a
 // chain of dependent cache round trips that costs more than the whole forward pass of a small batch.
-__device__ __forceinline__ void stage_operands(half4_t *ops, __half *raw, const __half *W, const MlpDims d,
+__device__ __forceinline__ void stage_operands(half8_t *ops8, __half *raw, const __half *W, const MlpDims d,
                                                const int slots) {
+    half4_t *ops = reinterpret_cast<half4_t *>(ops8);
     const int count = kMlpHidden * d.n_in + kMlpHidden * kMlpHidden + kMlpHidden * d.n_out;
     if ((reinterpret_cast<uintptr_t>(W) & 15u) == 0) {
         for (int i = threadIdx.x * 8; i < count; i += kMlpBlock * 8) {
@@ -82,7 +92,7 @@ __device__ __forceinline__ void stage_operands(half4_t *ops, __half *raw, const 
         half4_t v;
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = w_at(M, rows, cols, tr, 32 * t + row, 8 * s + k4 + j);
-        ops[e] = v;
+        ops[(((slot >> 1) * 64 + lane) << 1) + (slot & 1)] = v;
     }
     __syncthreads();
 }
@@ -180,13 +190,13 @@ __device__ __forceinline__ void load_inputs(const MlpDims d, const IoT *__restri
 }
 
 // H.yb holds the inputs on entry.
-__device__ __forceinline__ void hidden_layers(const half4_t *ops, const MlpDims d, const int lane, Hidden &H) {
+__device__ __forceinline__ void hidden_layers(const half8_t *ops, const MlpDims d, const int lane, Hidden &H) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         acc16_t a = acc_zero();
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            if (s < d.ks1) a = mfma(ops[(kOpW1 + 4 * t + s) * 64 + lane], H.yb[s], a);
+        for (int s = 0; s < 2; ++s)
+            if (2 * s < d.ks1) a = mfma(ops[(kOpW1 / 2 + 2 * t + s) * 64 + lane], cat(H.yb[2 * s], H.yb[2 * s + 1]), a);
         H.m1[t] = positive_mask(a);
         relu_to_b(a, H.h1, t);
     }
@@ -194,7 +204,7 @@ __device__ __forceinline__ void hidden_layers(const half4_t *ops, const MlpDims 
     for (int t = 0; t < 2; ++t) {
         acc16_t a = acc_zero();
 #pragma unroll
-        for (int s = 0; s < 8; ++s) a = mfma(ops[(kOpW2 + 8 * t + s) * 64 + lane], H.h1[s], a);
+        for (int s = 0; s < 4; ++s) a = mfma(ops[(kOpW2 / 2 + 4 * t + s) * 64 + lane], cat(H.h1[2 * s], H.h1[2 * s + 1]), a);
         H.m2[t] = positive_mask(a);
         relu_to_b(a, H.h2, t);
     }
@@ -220,7 +230,7 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
     float *__restrict__ out, const int64_t tiles)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    half4_t *ops = reinterpret_cast<half4_t *>(smem);
+    half8_t *ops = reinterpret_cast<half8_t *>(smem);
     stage_operands(ops, reinterpret_cast<__half *>(smem + kMlpFwdOps), W, d, kOpFwdSlots);
     const int lane = threadIdx.x & 63, k4 = 4 * (lane >> 5);
     const int64_t waves = (int64_t)gridDim.x * (kMlpBlock / 64);
@@ -236,7 +246,7 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
         hidden_layers(ops, d, lane, H);
         acc16_t o = acc_zero();
 #pragma unroll
-        for (int s = 0; s < 8; ++s) o = mfma(ops[(kOpW3 + s) * 64 + lane], H.h2[s], o);
+        for (int s = 0; s < 4; ++s) o = mfma(ops[(kOpW3 / 2 + s) * 64 + lane], cat(H.h2[2 * s], H.h2[2 * s + 1]), o);
         if (pt < N) {
 #pragma unroll
             for (int r = 0; r < 8; ++r) {                       // rows 0 .. 15 of the tile are the outputs
@@ -264,7 +274,7 @@ __global__ __launch_bounds__(kFusedTile) void encode_mlp_fwd_kernel(
     const int64_t tiles, const uint32_t c_stride, const int vec)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    half4_t  *ops = reinterpret_cast<half4_t *>(smem);
+    half8_t  *ops = reinterpret_cast<half8_t *>(smem);
     _Float16 *ytile = reinterpret_cast<_Float16 *>(smem + kMlpFwdOps);                      // [kFusedTile][kFusedStride]
     unsigned char *rest = smem + kMlpFwdOps + (size_t)kFusedTile * kFusedStride * sizeof(_Float16);
     uint8_t  *probes = rest;                                 // the raw weights first, then each level's index codebook
@@ -323,7 +333,7 @@ __global__ __launch_bounds__(kFusedTile) void encode_mlp_fwd_kernel(
             hidden_layers(ops, d, lane, H);
             acc16_t o = acc_zero();
 #pragma unroll
-            for (int s = 0; s < 8; ++s) o = mfma(ops[(kOpW3 + s) * 64 + lane], H.h2[s], o);
+            for (int s = 0; s < 4; ++s) o = mfma(ops[(kOpW3 / 2 + s) * 64 + lane], cat(H.h2[2 * s], H.h2[2 * s + 1]), o);
             const int64_t pt = n0 + row;
             if (pt < N) {
 #pragma unroll
@@ -347,9 +357,11 @@ __device__ __forceinline__ void put_rows(_Float16 *tile, const int row0, const h
         for (int j = 0; j < 4; ++j) tile[(row0 + 8 * s + k4 + j) * kTileStride + p] = b[s][j];
 }
 
-// Operand whose K index runs over the 32 points: row 32u + lane % 32, points 8s + 4h .. + 3.
-__device__ __forceinline__ half4_t get_op(const _Float16 *tile, const int row0, const int u, const int s, const int lane) {
-    return *reinterpret_cast<const half4_t *>(tile + (row0 + 32 * u + (lane & 31)) * kTileStride + 8 * s + 4 * (lane >> 5));
+// Operand whose K index runs over the 32 points: row 32u + lane % 32, points 16s + 8h .. + 7 (both operands of
+// these products come from the tile, so the instruction's natural K order serves).
+__device__ __forceinline__ half8_t get_op(const _Float16 *tile, const int row0, const int u, const int s, const int lane) {
+    const _Float16 *q = tile + (row0 + 32 * u + (lane & 31)) * kTileStride + 16 * s + 8 * (lane >> 5);
+    return cat(*reinterpret_cast<const half4_t *>(q), *reinterpret_cast<const half4_t *>(q + 4));
 }
 
 template <typename IoT>
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
     const float *__restrict__ dout, IoT *__restrict__ dy, float *__restrict__ gW, const int64_t tiles)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    half4_t  *ops = reinterpret_cast<half4_t *>(smem);
+    half8_t  *ops = reinterpret_cast<half8_t *>(smem);
     _Float16 *tile = reinterpret_cast<_Float16 *>(smem + (size_t)kOpAllSlots * 64 * sizeof(half4_t)) +
                      (size_t)(threadIdx.x >> 6) * kTileRows * kTileStride;
     stage_operands(ops, reinterpret_cast<__half *>(smem + (size_t)kOpAllSlots * 64 * sizeof(half4_t)), W, d, kOpAllSlots);
@@ -396,22 +408,20 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
 #pragma unroll
         for (int t = 0; t < 2; ++t) {                           // dL/dh2 = W3^T dout, where h2 was active
             acc16_t g = acc_zero();
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-                if (s < d.ks3) g = mfma(ops[(kOpW3T + 2 * t + s) * 64 + lane], db[s], g);
+            g = mfma(ops[(kOpW3T / 2 + t) * 64 + lane], cat(db[0], db[1]), g);   // rows beyond n_out are zero in both operands
             mask_to_b(g, H.m2[t], dh2, t);
         }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {                           // dL/dh1 = W2^T dL/dh2, where h1 was active
             acc16_t g = acc_zero();
 #pragma unroll
-            for (int s = 0; s < 8; ++s) g = mfma(ops[(kOpW2T + 8 * t + s) * 64 + lane], dh2[s], g);
+            for (int s = 0; s < 4; ++s) g = mfma(ops[(kOpW2T / 2 + 4 * t + s) * 64 + lane], cat(dh2[2 * s], dh2[2 * s + 1]), g);
             mask_to_b(g, H.m1[t], dh1, t);
         }
         {                                                       // dL/dy = W1^T dL/dh1
             acc16_t g = acc_zero();
 #pragma unroll
-            for (int s = 0; s < 8; ++s) g = mfma(ops[(kOpW1T + s) * 64 + lane], dh1[s], g);
+            for (int s = 0; s < 4; ++s) g = mfma(ops[(kOpW1T / 2 + s) * 64 + lane], cat(dh1[2 * s], dh1[2 * s + 1]), g);
             if (pt < N) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {                   // register group q: input dimensions 8q + 4h .. + 3
@@ -437,9 +447,9 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_bwd_kernel(
         put_rows<2>(tile, kRowDo, db, lane);
         wave_lds_fence();
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const half4_t yT = get_op(tile, kRowY, 0, s, lane), doT = get_op(tile, kRowDo, 0, s, lane);
-            half4_t h1T[2], h2T[2], d1T[2], d2T[2];
+        for (int s = 0; s < 2; ++s) {
+            const half8_t yT = get_op(tile, kRowY, 0, s, lane), doT = get_op(tile, kRowDo, 0, s, lane);
+            half8_t h1T[2], h2T[2], d1T[2], d2T[2];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 h1T[u] = get_op(tile, kRowH1, u, s, lane);
