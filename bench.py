@@ -335,7 +335,7 @@ def main():
                 def sorted_step():
                     cngp.bake_probes(cfg, Dhat, D_c)
                     p_, xs_ = cngp.morton_sort(x, workspace=sort_ws)
-                    cngp.encode_fwd_permuted(cfg, xs_, p_, D_f, D_c, y)
+                    cngp.encode_fwd_permuted(cfg, xs_, p_, D_f, D_c, y, workspace=ws)
                 y_plain = y.clone()
                 for _ in range(args.warmup):
                     sorted_step()

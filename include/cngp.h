@@ -167,12 +167,14 @@ int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const
  * N <= 2^31 - 1.  The sorting passes are rocPRIM's radix sort.
  * cngp_encode_fwd_permuted: the forward encoding of x_sorted with row i of the result written to row perm[i] of
  * y, so y is in the order of the caller's original points and equals cngp_encode_fwd on them bit for bit.
- * perm must be a permutation of 0 .. N-1 (not checked: any other content writes outside y or leaves rows unset). */
+ * perm must be a permutation of 0 .. N-1 (not checked: any other content writes outside y or leaves rows unset).
+ * workspace as for cngp_encode_fwd (cngp_fwd_workspace_bytes; NULL / 0: the tile variant). */
 size_t cngp_morton_sort_workspace_bytes(int32_t d, int64_t N);
 int cngp_morton_sort(int32_t d, const float *x, int64_t N, int32_t *perm, float *x_sorted,
                      void *workspace, size_t workspace_bytes, void *stream);
 int cngp_encode_fwd_permuted(const cngp_config *cfg, const float *x_sorted, const int32_t *perm, int64_t N,
-                             const void *D_f, const void *D_c, void *y, void *stream);
+                             const void *D_f, const void *D_c, void *y,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 /* Backward pass (Sec. 3 "Training"; Fig. 3: straight-through estimator).  The gradient of the
  * forward pass with the hard maximum replaced by a softmax over each row of D^_c: for every

@@ -76,7 +76,7 @@ def _load():
     lib.cngp_morton_sort.restype = ctypes.c_int
     lib.cngp_morton_sort.argtypes = [ctypes.c_int32, vp, i64, vp, vp, vp, sz, vp]
     lib.cngp_encode_fwd_permuted.restype = ctypes.c_int
-    lib.cngp_encode_fwd_permuted.argtypes = [cfgp, vp, vp, i64, vp, vp, vp, vp]
+    lib.cngp_encode_fwd_permuted.argtypes = [cfgp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.cngp_bake_probes.restype = ctypes.c_int
     lib.cngp_bake_probes.argtypes = [cfgp, vp, vp, vp]
     lib.cngp_encode_bwd_input.restype = ctypes.c_int
@@ -291,7 +291,7 @@ def morton_sort(x, workspace=None):
     return perm, x_sorted
 
 
-def encode_fwd_permuted(cfg: Config, x_sorted, perm, D_f, D_c, y=None):
+def encode_fwd_permuted(cfg: Config, x_sorted, perm, D_f, D_c, y=None, workspace=None):
     """cngp_encode_fwd_permuted: row perm[i] of y = encoding of x_sorted[i] (y in the order of the original points)."""
     N = x_sorted.shape[0]
     if y is None:
@@ -300,7 +300,7 @@ def encode_fwd_permuted(cfg: Config, x_sorted, perm, D_f, D_c, y=None):
     _check(_lib.cngp_encode_fwd_permuted(
         ctypes.byref(c), _dev(x_sorted, torch.float32, (N, cfg.d), "x_sorted"), _dev(perm, torch.int32, (N,), "perm"), N,
         _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"), _dc(cfg, D_c),
-        _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), _stream()))
+        _dev(y, _TORCH_DT[cfg.io_dtype], (N, cfg.L * cfg.F), "y"), *_ws(workspace), _stream()))
     return y
 
 

@@ -1165,16 +1165,16 @@ int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const
 }
 
 int cngp_encode_fwd_permuted(const cngp_config *cfg, const float *x_sorted, const int32_t *perm, int64_t N, const void *D_f,
-                             const void *D_c, void *y, void *stream) {
+                             const void *D_c, void *y, void *workspace, size_t workspace_bytes, void *stream) {
     if (int rc = validate(cfg)) return rc;
     if (N < 0 || N > 0x7fffffffLL) return CNGP_ERR_INVALID;
-    if (cfg->F != 2) return CNGP_ERR_UNSUPPORTED;           // (no workspace argument to hold the pair planes)
+    if (cfg->F != 2) return CNGP_ERR_UNSUPPORTED;
     if (N == 0) return CNGP_OK;
     if (!x_sorted || !perm || !D_f || !y || (!D_c && !index_codebook_is_empty(cfg))) return CNGP_ERR_NULL;
     if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
     const Params p = make_params(cfg);
     hipStream_t s = (hipStream_t)stream;
-    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x_sorted, N, D_f, D_c, y, s, perm);
+    CNGP_DISPATCH_TYPES(launch_fwd, cfg, p, x_sorted, N, D_f, D_c, y, s, perm, workspace, workspace_bytes);
 }
 
 int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N, const void *D_f,

@@ -63,6 +63,13 @@ def test_forward_through_the_permutation_equals_the_plain_forward(d, N_p, feat, 
     cngp.encode_fwd_permuted(cfg, xs, perm, D_f, D_c, y2)
     torch.cuda.synchronize()
     assert torch.equal(y.view(torch.int16 if io == "f16" else torch.int32), y2.view(torch.int16 if io == "f16" else torch.int32))
+    if not flags:                                   # with room for the level-major copy: the level-resident variant, same bits
+        y3 = torch.full_like(y, float("nan"))
+        ws = cngp.alloc_workspace(cfg, w.N)
+        assert cngp.fwd_plan_info(cfg, w.N)["level_resident"] == 1 and ws is not None
+        cngp.encode_fwd_permuted(cfg, xs, perm, D_f, D_c, y3, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(y2, y3)
     y_ref, ymag = oracle.encode_fwd(w, W.make_points(w), W.make_feature_codebook(w), oracle.bake_probes(W.make_probe_logits(w)))
     from parity import check_close
     check_close("y through the permutation", y2.cpu().numpy(), y_ref, ymag, fp16_out=(io == "f16"))
