@@ -97,7 +97,7 @@ typedef struct {
     int32_t  io_dtype;     /* cngp_dtype of y and dL/dy                                        */
     int32_t  index_format; /* cngp_index_format of D_c                                         */
     uint32_t flags;        /* bitwise OR of the CNGP_* flags above                             */
-    uint64_t bin_bytes_max; /* most workspace cngp_encode_bwd spends on binned references (8 bytes per
+    uint64_t bin_bytes_max; /* most workspace cngp_encode_bwd spends on binned references (4 bytes per
                               corner reference, level and gradient table); 0 = 8 GiB.  A larger batch
                               is taken in several passes inside the one call                      */
     uint32_t top_k;        /* cngp_encode_bwd only.  0 or N_p: the paper's backward (softmax over all N_p

@@ -520,8 +520,8 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
     const bool bin_ok = keys_fit && N > 0 && ((uint64_t)N << c->d) < (1ull << 31) &&
                         b.slices_f <= 8192 && b.slices_c <= 8192 &&
                         (uint64_t)c->N_c * c->N_p <= (1ull << 29) && c->N_f <= (1u << 28);
-    // (the bins take 8 bytes per reference, level and table: not chosen unasked beyond kMaxAutoBinBytes)
-    const uint64_t bin_bytes = ((uint64_t)N << c->d) * 8u * (uint64_t)c->L * (c->N_p > 1 ? 2u : 1u);
+    // (the bins take 4 bytes per reference, level and table: not chosen unasked beyond kMaxAutoBinBytes)
+    const uint64_t bin_bytes = ((uint64_t)N << c->d) * kRecordBytes * (uint64_t)c->L * (c->N_p > 1 ? 2u : 1u);
     const uint64_t bin_bytes_max = c->bin_bytes_max ? c->bin_bytes_max : kMaxAutoBinBytes;
     // (with both gradients in one pass binning pays from four slices per level: below that the replicated scan is as fast)
     const bool plenty = (N << c->d) * c->L >= kMinBinnedRefs;           // below, the three extra launches cost more than they save
@@ -601,12 +601,12 @@ BwdPlan make_bwd_plan_uncached(const cngp_config *c, int64_t N) {
             b.baseF_off = b.cntC_off + align256((size_t)Lh * b.bin_chunks * b.slices_c * 4);
             b.baseC_off = b.baseF_off + align256((size_t)Lh * (b.slices_f + 1) * 4);
             b.recF_off = b.baseC_off + align256((size_t)Lh * (b.slices_c + 1) * 4);
-            b.recC_off = b.recF_off + (b.fused ? 0 : align256((size_t)Lh * cap * 8));
-            b.cntG_off = b.recC_off + (b.slices_c ? align256((size_t)Lh * cap * 8) : 0);
+            b.recC_off = b.recF_off + (b.fused ? 0 : align256((size_t)Lh * cap * kRecordBytes));
+            b.cntG_off = b.recC_off + (b.slices_c ? align256((size_t)Lh * cap * kRecordBytes) : 0);
             const size_t Ld = (size_t)b.dense.count;
             b.baseG_off = b.cntG_off + align256(Ld * b.bin_chunks * kGridBins * 4);
             b.recG_off = b.baseG_off + align256(Ld * (kGridBins + 1) * 4);
-            b.ws_bytes = b.recG_off + align256(Ld * cap * 8);
+            b.ws_bytes = b.recG_off + align256(Ld * cap * kRecordBytes);
             // workgroups per slice of a level's grid: about 2^15 references each
             uint32_t next = 0;
             for (int l = 0; l < b.dense.count; ++l) {
@@ -642,7 +642,7 @@ int64_t bwd_pass_points(const cngp_config *c, int64_t N) {
     if (N <= 0 || (c->flags & (CNGP_BWD_DIRECT | CNGP_BWD_SLICED))) return N;
     int64_t most = (((int64_t)1 << 31) - 1) >> c->d;
     if (!(c->flags & CNGP_BWD_BINNED) || c->bin_bytes_max) {
-        const int64_t per_point = ((int64_t)8 << c->d) * c->L * (c->N_p > 1 ? 2 : 1);
+        const int64_t per_point = ((int64_t)kRecordBytes << c->d) * c->L * (c->N_p > 1 ? 2 : 1);
         const int64_t by_bytes = (int64_t)((c->bin_bytes_max ? c->bin_bytes_max : kMaxAutoBinBytes) / (uint64_t)per_point);
         if (by_bytes < most) most = by_bytes;
     }
@@ -680,9 +680,9 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     char *ws = (char *)workspace;
     uint32_t *cntF = (uint32_t *)(ws + b.cntF_off), *cntC = (uint32_t *)(ws + b.cntC_off);
     uint32_t *baseF = (uint32_t *)(ws + b.baseF_off), *baseC = (uint32_t *)(ws + b.baseC_off);
-    uint2    *recF = (uint2 *)(ws + b.recF_off), *recC = (uint2 *)(ws + b.recC_off);
+    BinRecord *recF = (BinRecord *)(ws + b.recF_off), *recC = (BinRecord *)(ws + b.recC_off);
     uint32_t *cntG = (uint32_t *)(ws + b.cntG_off), *baseG = (uint32_t *)(ws + b.baseG_off);
-    uint2    *recG = (uint2 *)(ws + b.recG_off);
+    BinRecord *recG = (BinRecord *)(ws + b.recG_off);
     const bool zero_first = (c->flags & CNGP_ZERO_GRADS) != 0;
     const BinParams bp = make_bin_params<NP>(c, b, N);
     const int64_t blocks = (int64_t)(Lh + Ld) * bp.chunks;
@@ -690,7 +690,7 @@ int launch_bwd_binned(const cngp_config *c, const Params &p, const BwdPlan &b, c
     const size_t lds_bins = (size_t)most_bins_of(bp) * sizeof(uint32_t);
     // One wavefront per chunk keeps a bin's records in the order of the points, which the drain's gathers
     // like (measured: drain 7 % faster); with many bins a lone wavefront fills its cache lines too slowly
-    // for the memory system to merge the 8-byte writes, and four wavefronts sharing the cursors write
+    // for the memory system to merge the 4-byte writes, and four wavefronts sharing the cursors write
     // 1.7 times faster (measured at 64 bins per level).
     const unsigned bin_block = bp.slices_f + bp.slices_c >= 48 ? 256u : (unsigned)kBinBlock;
     {
@@ -1127,11 +1127,11 @@ int cngp_bwd_plan_layout(const cngp_config *cfg, int64_t N, uint64_t *regions) {
         add(b.cntC_off, Lh * b.bin_chunks * sc * 4);
         add(b.baseF_off, sf ? Lh * (sf + 1) * 4 : 0);
         add(b.baseC_off, sc ? Lh * (sc + 1) * 4 : 0);
-        add(b.recF_off, sf ? Lh * cap * 8 : 0);
-        add(b.recC_off, sc ? Lh * cap * 8 : 0);
+        add(b.recF_off, sf ? Lh * cap * kRecordBytes : 0);
+        add(b.recC_off, sc ? Lh * cap * kRecordBytes : 0);
         add(b.cntG_off, Ld * b.bin_chunks * kGridBins * 4);
         add(b.baseG_off, Ld ? Ld * (kGridBins + 1) * 4 : 0);
-        add(b.recG_off, Ld * cap * 8);
+        add(b.recG_off, Ld * cap * kRecordBytes);
     }
     return k;
 }

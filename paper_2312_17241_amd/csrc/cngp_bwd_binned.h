@@ -6,16 +6,16 @@
 //   1. count    per (level, chunk of points): how many references go to each slice of the feature
 //               table (by hash) and of the confidence table (by hash2); histogram in LDS
 //   2. offsets  exclusive prefix sums: where every (chunk, slice) writes inside the level's record array
-//   3. scatter  the same walk again, every reference written as an 8-byte record
-//               { row inside the slice | row of the other table << rows_log2,  point index * 2^d + corner }
+//   3. scatter  the same walk again, every reference written as a 4-byte record  point index * 2^d + corner
 //               to its slice's bin, positions handed out by LDS counters that start at the offsets
 //   4. drain    a workgroup owns a slice as fp64 accumulators in LDS, as in the sliced variant, but reads
-//               only its own bin, coalesced, one record per lane: the lane re-derives weight * dL/dy of its
-//               record from the point (a dozen instructions per record, against 8 more bytes written and read
-//               per record otherwise); record loads run two batches ahead, the gathers the records ask
-//               for (softmax row / feature row) one batch ahead of the LDS atomics that consume them
-// Per reference this replaces the replicated hashing and the ring-buffer emission by one 8-byte write
-// and one 8-byte read per table, which is the better trade from a few dozen slices per level upwards and the
+//               only its own bin, coalesced, one record per lane: the lane re-derives the two hashed rows and
+//               weight * dL/dy of its record from the point (some thirty instructions per record, against 12
+//               more bytes written and read per record if the record carried them: the scatter is bound by
+//               its writes); record loads run two batches ahead, the gathers the records ask for (softmax
+//               row / feature row) one batch ahead of the LDS atomics that consume them
+// Per reference this replaces the replicated hashing and the ring-buffer emission by one 4-byte write
+// and one 4-byte read per table, which is the better trade from a few dozen slices per level upwards and the
 // only workable one for tables of thousands of slices.
 #pragma once
 #include "cngp_bwd_sliced.h"
@@ -27,6 +27,10 @@ namespace cngp {
 // records (the points and their upstream gradients) fall into a few cache lines instead of one line per
 // record; the host launches 256 lanes instead when there are many bins.
 constexpr int kBinBlock = 64;
+
+// A binned corner reference: point index * 2^d + corner (the host keeps N * 2^d below 2^31 per pass).
+using BinRecord = uint32_t;
+constexpr size_t kRecordBytes = sizeof(BinRecord);
 
 struct BinParams {
     int32_t  level0, nlevels;             // the hashed levels
@@ -238,16 +242,16 @@ template <int D>
 __global__ __launch_bounds__(256) void bin_scatter_kernel(
     const Params p, const BinParams bp, const DenseLevels dl, const float *__restrict__ x, const int64_t N,
     const uint32_t *__restrict__ cntF, const uint32_t *__restrict__ cntC, const uint32_t *__restrict__ cntG,
-    uint2 *__restrict__ recF, uint2 *__restrict__ recC, uint2 *__restrict__ recG)
+    BinRecord *__restrict__ recF, BinRecord *__restrict__ recC, BinRecord *__restrict__ recG)
 {
     extern __shared__ uint32_t cursor[];                    // [max(slices_f + slices_c, kGridBins)]
     const uint32_t li = blockIdx.x / bp.chunks, chunk = blockIdx.x % bp.chunks;
-    if (li >= (uint32_t)bp.nlevels) {                       // a pre-reduced level: record = { vertex inside its slice, reference }
+    if (li >= (uint32_t)bp.nlevels) {                       // a pre-reduced level, binned by slice of its vertex grid
         const uint32_t ld = li - (uint32_t)bp.nlevels;
         const uint32_t *rowG = cntG + ((size_t)ld * bp.chunks + chunk) * kGridBins;
         for (uint32_t s = threadIdx.x; s < kGridBins; s += blockDim.x) cursor[s] = rowG[s];
         __syncthreads();
-        uint2 *outG = recG + (size_t)ld * bp.cap;
+        BinRecord *outG = recG + (size_t)ld * bp.cap;
         const int64_t m0 = (int64_t)chunk * bp.chunk_pts;
         const int64_t m1 = (m0 + bp.chunk_pts < N) ? m0 + bp.chunk_pts : N;
         for (int64_t n = m0 + threadIdx.x; n < m1; n += blockDim.x) {
@@ -259,7 +263,7 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
 #pragma unroll
             for (int c = 0; c < (1 << D); ++c) {
                 const uint32_t pos = atomicAdd(&cursor[grid_bin(v[c])], 1u);
-                outG[pos] = make_uint2(v[c] % kDenseSliceVerts, ((uint32_t)n << D) | (uint32_t)c);
+                outG[pos] = ((uint32_t)n << D) | (uint32_t)c;
             }
         }
         return;
@@ -272,9 +276,8 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
         for (uint32_t s = threadIdx.x; s < bp.slices_c; s += blockDim.x) cursor[bp.slices_f + s] = rowC[s];
     }
     __syncthreads();
-    uint2 *outF = recF + (size_t)li * bp.cap;
-    uint2 *outC = recC + (size_t)li * bp.cap;
-    const uint32_t lo_f = (1u << bp.rows_f_log2) - 1u, lo_c = (1u << bp.rows_c_log2) - 1u;
+    BinRecord *outF = recF + (size_t)li * bp.cap;
+    BinRecord *outC = recC + (size_t)li * bp.cap;
     const int64_t  n0 = (int64_t)chunk * bp.chunk_pts;
     const int64_t  n1 = (n0 + bp.chunk_pts < N) ? n0 + bp.chunk_pts : N;
     for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
@@ -290,11 +293,11 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
             const uint32_t ref = ((uint32_t)n << D) | (uint32_t)c;
             if (bp.slices_f) {
                 const uint32_t posF = atomicAdd(&cursor[h1 >> bp.rows_f_log2], 1u);
-                outF[posF] = make_uint2((h1 & lo_f) | (h2 << bp.rows_f_log2), ref);
+                outF[posF] = ref;
             }
             if (bp.slices_c) {
                 const uint32_t posC = atomicAdd(&cursor[bp.slices_f + (h2 >> bp.rows_c_log2)], 1u);
-                outC[posC] = make_uint2((h2 & lo_c) | (h1 << bp.rows_c_log2), ref);
+                outC[posC] = ref;
             }
         }
     }
@@ -356,8 +359,9 @@ __device__ __forceinline__ void accum_steps(const uint4 &r, const T (&g)[NP], Ac
 // BOTH (records of a confidence-table bin, both gradients accumulated): the gather reads the row INSIDE the
 // slice (the softmax row of the record's own confidence row), the accumulator row is the other table's.
 // ACC: doubles per candidate of an accumulator row (2 where both features of a row sit side by side).
-template <int D, int NP, typename T, bool BOTH, int ACC, typename IoT, typename Load, typename Accum>
-__device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, const uint32_t beg, const uint32_t end,
+// BY_FEAT: the bin belongs to a slice of the feature table (rows by hash), else of the confidence table (hash2).
+template <int D, int NP, typename T, bool BOTH, int ACC, bool BY_FEAT, typename IoT, typename Load, typename Accum>
+__device__ __forceinline__ void drain_records(const Params &p, const BinRecord *__restrict__ rec, const uint32_t beg, const uint32_t end,
                                               const float *__restrict__ x, const IoT *__restrict__ dy_l, const float res,
                                               const uint32_t rows_log2, Load load, Accum accum)
 {
@@ -369,45 +373,52 @@ __device__ __forceinline__ void drain_records(const uint2 *__restrict__ rec, con
     const uint32_t last = end - 1u;
     using Pair = typename std::conditional<sizeof(IoT) == 2, uint32_t, float2>::type;   // dL/dy of a level as stored
     // Four stages, a batch apart, over four register buffers (unrolled four times, so no buffer is copied):
-    //   A  this lane's record of a batch                          (coalesced 8-byte load)
+    //   A  this lane's record of a batch                          (coalesced 4-byte load)
     //   B  the record's point and upstream gradient               (gathers by point index)
-    //   C  weight * dL/dy from those, and the gathers the keys of the batch ask for
+    //   C  the record's two table rows and weight * dL/dy from those, and the gathers the rows ask for
     //   D  accumulate
     // Each stage consumes what the stage before it loaded one step earlier; within a step the loads are
     // issued A, B, C, so that a wait for an older stage's data leaves the younger loads in flight.
-    uint2 Q[4];
+    BinRecord Q[4];
     float X[4][D];
     Pair  Y[4];
     uint4 R[4];                                              // gather offset, weight * dL/dy (two floats), LDS offset
     T     G[4][NP];
-    auto stage_a = [&](const uint32_t base, uint2 &q) {
+    auto stage_a = [&](const uint32_t base, BinRecord &q) {
         const uint32_t i = base + lane;
         // streamed once: a non-temporal load keeps it out of the way of the rows that are gathered again and again
-        const unsigned long long raw = __builtin_nontemporal_load(reinterpret_cast<const unsigned long long *>(rec) + (i < last ? i : last));
-        q = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
+        q = __builtin_nontemporal_load(rec + (i < last ? i : last));
     };
-    auto stage_b = [&](const uint2 &q, float (&xp)[D], Pair &y) {
-        const uint32_t n = q.y >> D;
+    auto stage_b = [&](const BinRecord &q, float (&xp)[D], Pair &y) {
+        const uint32_t n = q >> D;
 #pragma unroll
         for (int j = 0; j < D; ++j) xp[j] = x[(size_t)n * D + j];
         y = reinterpret_cast<const Pair *>(dy_l)[n];
     };
-    auto stage_c = [&](const uint32_t base, const uint2 &q, const float (&xp)[D], const Pair &y, uint4 &r, T (&g)[NP]) {
-        const uint32_t c = q.y & ((1u << D) - 1u);
-        float wt = (base + lane < end) ? 1.0f : 0.0f;        // beyond the bin: contributes nothing
+    auto stage_c = [&](const uint32_t base, const BinRecord &q, const float (&xp)[D], const Pair &y, uint4 &r, T (&g)[NP]) {
+        const uint32_t c = q & ((1u << D) - 1u);
+        float    wt = (base + lane < end) ? 1.0f : 0.0f;     // beyond the bin: contributes nothing
+        uint32_t h1 = 0, h2 = 0;                             // Eq. 3 for this corner, as in Cell<D>
         {
 #pragma clang fp contract(off)
 #pragma unroll
             for (int j = 0; j < D; ++j) {
-                const float pos = xp[j] * res;               // one rounded fp32 multiply
-                const float w = pos - floorf(pos);
-                wt *= ((c >> j) & 1u) ? w : 1.0f - w;
+                const float    pos = xp[j] * res;            // one rounded fp32 multiply
+                const float    fl = floorf(pos);
+                const float    w = pos - fl;
+                const uint32_t up = (c >> j) & 1u;
+                wt *= up ? w : 1.0f - w;
+                const uint32_t v = (uint32_t)fl + up;
+                h1 ^= v * kPi[j];
+                h2 ^= v * kPi2[j];
             }
         }
+        h1 &= p.row_mask;
+        h2 &= p.c_mask;
         const float2 gy = pair_to_float2(y);
-        // the key, decoded once per record: byte offset of the row the gather reads (candidate 0), and
-        // byte offset of the accumulator row in LDS; the lanes of the group add their candidate's share
-        const uint32_t inside = q.x & row_lo_mask, other = q.x >> rows_log2;
+        // once per record: byte offset of the row the gather reads (candidate 0), and byte offset of the
+        // accumulator row in LDS; the lanes of the group add their candidate's share
+        const uint32_t inside = (BY_FEAT ? h1 : h2) & row_lo_mask, other = BY_FEAT ? h2 : h1;
         r = make_uint4((BOTH ? inside : other) * (uint32_t)(NP * sizeof(T)), __float_as_uint(wt * gy.x),
                        __float_as_uint(wt * gy.y), (BOTH ? other : inside) * (uint32_t)(ACC * NP * sizeof(double)));
         gather_steps<NP, 0>(r, g, load);
@@ -458,7 +469,7 @@ struct GridDrainPlan {
 template <int D, typename IoT>
 __global__ __launch_bounds__(kSlicedBlock) void bin_grid_drain_kernel(
     const Params p, const DenseLevels dl, const GridDrainPlan gp, const float *__restrict__ x,
-    const IoT *__restrict__ dyT, const int64_t N, const uint2 *__restrict__ recG,
+    const IoT *__restrict__ dyT, const int64_t N, const BinRecord *__restrict__ recG,
     const uint32_t *__restrict__ baseG, const uint32_t cap, float *__restrict__ G)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -476,15 +487,16 @@ __global__ __launch_bounds__(kSlicedBlock) void bin_grid_drain_kernel(
     bin_range(baseG, kGridBins, (uint32_t)ld, slice, sub, subs, beg, end);
     if (beg < end) {
         using Pair = typename std::conditional<sizeof(IoT) == 2, uint32_t, float2>::type;
-        const uint2   *rec = recG + (size_t)ld * cap;
+        const BinRecord *rec = recG + (size_t)ld * cap;
+        const uint32_t side = dl.side[ld];
         const Pair    *dy_l = reinterpret_cast<const Pair *>(dyT + (size_t)ld * N * 2);
         const float    res = (float)p.N_l[ld];
         const uint32_t last = end - 1u;
         struct Point { float xp[D]; Pair y; };
         auto record = [&](const uint32_t i) { return rec[i < last ? i : last]; };
-        auto point = [&](const uint2 q) {
+        auto point = [&](const BinRecord q) {
             Point pt;
-            const uint32_t n = q.y >> D;
+            const uint32_t n = q >> D;
 #pragma unroll
             for (int j = 0; j < D; ++j) pt.xp[j] = x[(size_t)n * D + j];
             pt.y = dy_l[n];
@@ -492,25 +504,31 @@ __global__ __launch_bounds__(kSlicedBlock) void bin_grid_drain_kernel(
         };
         // record loads run two steps ahead, the point and gradient they name one step ahead
         uint32_t i = beg + threadIdx.x;
-        uint2 q0 = record(i), q1 = record(i + kSlicedBlock);
+        BinRecord q0 = record(i), q1 = record(i + kSlicedBlock);
         Point p0 = point(q0);
         for (; i < end; i += kSlicedBlock) {
-            const uint2 q2 = record(i + 2 * kSlicedBlock);
+            const BinRecord q2 = record(i + 2 * kSlicedBlock);
             const Point p1 = point(q1);
-            const uint32_t c = q0.y & ((1u << D) - 1u);
-            float wt = 1.0f;
+            const uint32_t c = q0 & ((1u << D) - 1u);
+            float    wt = 1.0f;
+            uint32_t v = 0, stride = 1;                     // the corner's vertex number, as corner_vertices gives it
             {
 #pragma clang fp contract(off)
 #pragma unroll
                 for (int j = 0; j < D; ++j) {
-                    const float pos = p0.xp[j] * res;       // one rounded fp32 multiply
-                    const float w = pos - floorf(pos);
-                    wt *= ((c >> j) & 1u) ? w : 1.0f - w;
+                    const float    pos = p0.xp[j] * res;    // one rounded fp32 multiply
+                    const float    fl = floorf(pos);
+                    const float    w = pos - fl;
+                    const uint32_t up = (c >> j) & 1u;
+                    wt *= up ? w : 1.0f - w;
+                    v += ((uint32_t)fl + up) * stride;
+                    stride *= side;
                 }
             }
+            const uint32_t at = 2u * (v % kDenseSliceVerts);    // inside the slice whatever the point was
             const float2 g = pair_to_float2(p0.y);
-            atomicAdd(acc + 2 * q0.x, (double)(wt * g.x));
-            atomicAdd(acc + 2 * q0.x + 1, (double)(wt * g.y));
+            atomicAdd(acc + at, (double)(wt * g.x));
+            atomicAdd(acc + at + 1, (double)(wt * g.y));
             q0 = q1; q1 = q2; p0 = p1;
         }
     }
@@ -527,7 +545,7 @@ __global__ __launch_bounds__(kSlicedBlock) void bin_grid_drain_kernel(
 template <int D, int NP, typename IoT>
 __device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &sp, const uint32_t wg, unsigned char *smem,
                                            const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
-                                           const float *__restrict__ sigma, const uint2 *__restrict__ recF,
+                                           const float *__restrict__ sigma, const BinRecord *__restrict__ recF,
                                            const uint32_t *__restrict__ baseF, const uint32_t cap, float *__restrict__ gD_f)
 {
     const uint32_t rows = 1u << sp.rows_log2, plane = rows * NP;
@@ -551,7 +569,7 @@ __device__ __forceinline__ void drain_feat(const Params &p, const SliceParams &s
     };
     uint32_t beg, end;
     bin_range(baseF, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<D, NP, float, false, 2>(recF + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+    drain_records<D, NP, float, false, 2, true>(p, recF + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
                                           (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     float *out = gD_f + (size_t)co.level * p.N_f * 2 + (size_t)co.slice * plane * 2;
@@ -567,7 +585,7 @@ template <int D, int NP, typename FeatT, typename IoT>
 __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &sp, const uint32_t wg, unsigned char *smem,
                                             const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
                                             const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
-                                            const uint2 *__restrict__ recC, const uint32_t *__restrict__ baseC,
+                                            const BinRecord *__restrict__ recC, const uint32_t *__restrict__ baseC,
                                             const uint32_t cap, float *__restrict__ gDhat_c)
 {
     const uint32_t rows = 1u << sp.rows_log2;
@@ -589,7 +607,7 @@ __device__ __forceinline__ void drain_logit(const Params &p, const SliceParams &
     };
     uint32_t beg, end;
     bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<D, NP, Raw, false, 1>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+    drain_records<D, NP, Raw, false, 1, false>(p, recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
                               (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     // softmax Jacobian per row, then out to HBM; NP consecutive lanes hold one row
@@ -617,7 +635,7 @@ template <int D, int NP, typename FeatT, typename IoT>
 __device__ __forceinline__ void drain_both(const Params &p, const SliceParams &sp, const uint32_t wg, unsigned char *smem,
                                            const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
                                            const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
-                                           const uint2 *__restrict__ recC, const uint32_t *__restrict__ baseC,
+                                           const BinRecord *__restrict__ recC, const uint32_t *__restrict__ baseC,
                                            const uint32_t cap, float *__restrict__ gD_f, float *__restrict__ gDhat_c)
 {
     using Raw = typename RawPair<FeatT>::type;
@@ -648,7 +666,7 @@ __device__ __forceinline__ void drain_both(const Params &p, const SliceParams &s
     };
     uint32_t beg, end;
     bin_range(baseC, sp.slices, (uint32_t)co.index, co.slice, co.chunk, sp.chunks, beg, end);
-    drain_records<D, NP, float, true, 1>(recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
+    drain_records<D, NP, float, true, 1, false>(p, recC + (size_t)co.index * cap, beg, end, x, dyT + (size_t)co.level * N * 2,
                                       (float)p.N_l[co.level], sp.rows_log2, load, accum);
     __syncthreads();
     float *outF = gD_f + (size_t)co.level * p.N_f * 2;
@@ -678,7 +696,7 @@ __global__ __launch_bounds__(kSlicedBlock) void bin_drain_kernel(
     const Params p, const SliceParams sp_c, const SliceParams sp_f, const uint32_t first_feat, const uint32_t first_vtx,
     const float *__restrict__ x, const IoT *__restrict__ dyT, const int64_t N,
     const FeatT *__restrict__ D_f, const float *__restrict__ sigma,
-    const uint2 *__restrict__ recF, const uint2 *__restrict__ recC,
+    const BinRecord *__restrict__ recF, const BinRecord *__restrict__ recC,
     const uint32_t *__restrict__ baseF, const uint32_t *__restrict__ baseC, const uint32_t cap,
     const BwdRoles vtx, const DenseLevels dl, const float *__restrict__ G,
     float *__restrict__ gD_f, float *__restrict__ gDhat_c)

@@ -21,7 +21,7 @@ DEV = "cuda"
     (cngp.BWD_BINNED, 40000 + 3, 2**13, 3)])        # bounded bins: three passes inside the one call
 def test_graph_replay_matches_the_oracle(flags, n, N_f, passes):
     w = W.custom(cfg=91, d=3, L=6, N_f=N_f, N_c=2**11, N_p=8, N_min=8, N_max=256, N=n, feat_dtype="f16", io_dtype="f16")
-    limit = 0 if passes == 1 else 16 * 1024 * 8 * 8 * w.L * 2
+    limit = 0 if passes == 1 else 16 * 1024 * 8 * 4 * w.L * 2
     cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS | flags, bin_bytes_max=limit)
     plan = cngp.bwd_plan_info(cfg, n)
     assert plan["passes"] == passes and (plan["slices_f"] == 0) == (N_f == 2**9 and bool(flags & cngp.BWD_BINNED))

@@ -262,7 +262,7 @@ def test_small_feature_tables_both_gradients_in_one_pass(N_f, N_c, N_p, feat, io
 def test_small_feature_tables_in_passes_with_the_sparse_variant():
     """The same mode with a bound on the binned references (three passes) and the top-2 sparse variant together."""
     w = W.custom(cfg=91, d=3, L=5, N_f=2**9, N_c=2**13, N_p=8, N_min=8, N_max=400, N=100000 + 3, feat_dtype="f16", io_dtype="f16")
-    limit = 40000 * 8 * 8 * w.L * 2
+    limit = 40000 * 8 * 4 * w.L * 2
     cfg = cngp.Config.from_workload(w, flags=cngp.ZERO_GRADS | cngp.BWD_BINNED, bin_bytes_max=limit, top_k=2)
     plan = cngp.bwd_plan_info(cfg, w.N)
     assert plan["binned"] == 1 and plan["slices_f"] == 0 and plan["passes"] == 3
@@ -281,7 +281,7 @@ def test_binned_backward_in_several_passes(zero, forced):
     inside the one call: the first pass clears (if asked), the others add; the last run is shorter."""
     w = W.custom(cfg=84, d=3, L=8, N_f=2**16, N_c=2**14, N_p=16, N_min=16, N_max=1024, N=150000 + 7,
                  feat_dtype="f16", io_dtype="f16")
-    per_point = 8 * 2**w.d * w.L * 2
+    per_point = 4 * 2**w.d * w.L * 2              # 4-byte records, both tables
     limit = 40000 * per_point                       # 39 * 1024 points per pass
     flags = (cngp.ZERO_GRADS if zero else 0) | (cngp.BWD_BINNED if forced else 0)
     cfg = cngp.Config.from_workload(w, flags=flags, bin_bytes_max=limit)

@@ -54,7 +54,7 @@ def _both(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS, **over):
 
 def test_static_scratch_backward_two_calls_in_a_row():
     assert cngp.static_scratch_bytes() == 64 << 20
-    # first call: binned variant whose bins (2^17 points: 134 MB) exceed the scratch, so it runs in passes
+    # first call: binned variant whose bins (2^17 points: 67 MB) with the softmax table exceed the scratch, so it runs in passes
     w, x, D_f, Dhat, dy = _case(1 << 17, 41)
     cfg = _both(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS | cngp.BWD_BINNED)
     assert cngp.bwd_plan_info(cfg, w.N)["binned"] == 1
