@@ -518,10 +518,20 @@ def main():
             g_ref = oracle.encode_bwd(w, xs, D_f_h, Dhat_h, dy_h[:n_cpu], want_abs=not args.no_check, top_k=args.top_k)
         t_cpu = time.perf_counter() - t0
         if not args.no_cpu_baseline:
-            out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 1), "unit": "points/s",
+            # the same pass again until about ten seconds of CPU work are on the clock (the first pass above is kept for the
+            # self-check; the oracle is run as it stands, magnitudes included)
+            cpu_passes = 1
+            while t_cpu < 10.0 and cpu_passes < 200:
+                t0 = time.perf_counter()
+                oracle.encode_fwd(w, xs, D_f_h, oracle.bake_probes(Dhat_h))
+                if not fwd_only:
+                    oracle.encode_bwd(w, xs, D_f_h, Dhat_h, dy_h[:n_cpu], want_abs=not args.no_check, top_k=args.top_k)
+                t_cpu += time.perf_counter() - t0
+                cpu_passes += 1
+            out["cpu_baseline"] = {"value": round(n_cpu * cpu_passes / t_cpu, 1), "unit": "points/s",
                                    "cores": oracle.num_threads(), "kind": "oracle",
-                                   "sample": f"first {n_cpu} of {N} points, one pass of bake + fwd"
-                                             + ("" if fwd_only else " + bwd") + f", {t_cpu:.2f} s"}
+                                   "sample": f"first {n_cpu} of {N} points, {cpu_passes} passes of bake + fwd"
+                                             + ("" if fwd_only else " + bwd") + f", {t_cpu:.1f} s in all"}
         if not args.no_check:
             # self-check of the timed configuration against the oracle (same launch configuration)
             if fmt == cngp.IDX_BITS:
