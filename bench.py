@@ -318,6 +318,32 @@ def main():
         extras["cold_cache"] = {"ms_per_step_median": round(t[len(t) // 2], 4), "ms_per_step_min": round(t[0], 4), "n": len(t),
                                 "value": round(N / (t[len(t) // 2] * 1e-3), 1), "unit": "points/s",
                                 "note": "512 MiB scrub buffer written before every step"}
+        if not with_opt and not args.with_decoder and w.io_dtype == "f16":
+            # the same step with fp32 encodings and upstream gradients (y, dL/dy): twice the streamed bytes
+            w32 = W.custom(name=w.name + "_f32io", cfg=w.cfg, d=w.d, L=w.L, F=w.F, N_f=w.N_f, N_c=w.N_c, N_p=w.N_p,
+                           N_min=w.N_min, N_max=w.N_max, N=N, feat_dtype=w.feat_dtype, io_dtype="f32", points=w.points)
+            cfg32 = cngp.Config.from_workload(w32, index_format=fmt, flags=cngp.ZERO_GRADS | bwd_flag, top_k=args.top_k)
+            y32 = torch.empty((N, w.L * w.F), dtype=torch.float32, device=dev)
+            ws32 = cngp.alloc_workspace(cfg32, N, dev)
+            dy32 = None if fwd_only else dy.float()
+            def step32():
+                cngp.bake_probes(cfg32, Dhat, D_c)
+                cngp.encode_fwd(cfg32, x, D_f, D_c, y32, workspace=ws32)
+                if not fwd_only:
+                    cngp.encode_bwd(cfg32, x, D_f, Dhat, dy32, gF, gC, workspace=ws32)
+            for _ in range(args.warmup):
+                step32()
+            torch.cuda.synchronize()
+            f0 = time.perf_counter()
+            for _ in range(args.steps):
+                step32()
+            torch.cuda.synchronize()
+            f1 = time.perf_counter()
+            extras["fp32_io"] = {"value": round(N * args.steps / (f1 - f0), 1), "unit": "points/s",
+                                 "ms_per_step": round((f1 - f0) * 1e3 / args.steps, 4),
+                                 "note": "y and dL/dy as fp32 instead of fp16, everything else as in the headline"}
+            del y32, ws32, dy32
+            step()                                               # gF, gC, D_c of the headline configuration again
         if not with_opt and not args.with_decoder:
             # Morton order (cngp_morton_sort): the same batch with its points sorted along the Z-order curve
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -532,6 +558,18 @@ def main():
                                    "cores": oracle.num_threads(), "kind": "oracle",
                                    "sample": f"first {n_cpu} of {N} points, {cpu_passes} passes of bake + fwd"
                                              + ("" if fwd_only else " + bwd") + f", {t_cpu:.1f} s in all"}
+            # and on one thread, one pass over a shorter run of the same points
+            n_one = min(n_cpu, 1 << 16)
+            threads = oracle.num_threads()
+            oracle.set_threads(1)
+            t0 = time.perf_counter()
+            oracle.encode_fwd(w, x_h[:n_one], D_f_h, oracle.bake_probes(Dhat_h))
+            if not fwd_only:
+                oracle.encode_bwd(w, x_h[:n_one], D_f_h, Dhat_h, dy_h[:n_one], want_abs=not args.no_check, top_k=args.top_k)
+            t_one = time.perf_counter() - t0
+            oracle.set_threads(threads)
+            out["cpu_baseline"]["one_thread"] = {"value": round(n_one / t_one, 1), "unit": "points/s",
+                                                 "sample": f"first {n_one} points, one pass, {t_one:.1f} s"}
         if not args.no_check:
             # self-check of the timed configuration against the oracle (same launch configuration)
             if fmt == cngp.IDX_BITS:

@@ -39,11 +39,15 @@ def _f64(a):
 
 
 def num_threads() -> int:
-    """Threads the OpenMP loops of the oracle use (OMP_NUM_THREADS or all cores)."""
-    env = os.environ.get("OMP_NUM_THREADS")
-    if env:
-        return int(env.split(",")[0])
-    return len(os.sched_getaffinity(0))
+    """Threads the OpenMP loops of the oracle use, as the OpenMP runtime reports them."""
+    f = lib().cngp_oracle_max_threads
+    f.restype = ctypes.c_int
+    return int(f())
+
+
+def set_threads(n: int) -> None:
+    """Number of threads for the following oracle calls (the timing of the oracle on one core)."""
+    lib().cngp_oracle_set_threads(ctypes.c_int(int(n)))
 
 
 def level_resolutions(N_min, N_max, L) -> np.ndarray:

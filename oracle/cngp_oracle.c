@@ -48,6 +48,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 static const uint32_t PRIMES_HASH[4]  = {1u, 2654435761u, 805459861u, 1920767767u};
 static const uint32_t PRIMES_HASH2[4] = {1580030173u, 1367130559u, 3037000507u, 2479700537u};
@@ -339,3 +342,21 @@ void cngp_oracle_encode_bwd_input(int d, int L, int F, uint32_t N_f, uint32_t N_
     }
 }
 
+/* Threads the parallel loops above use, and a way to change that (timing of the oracle on one core). */
+int cngp_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void cngp_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
