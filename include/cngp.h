@@ -118,8 +118,11 @@ int cngp_level_resolutions(const cngp_config *cfg, uint32_t *out_N_l);
  * (per level, i.e. the distance between consecutive levels, and in total).  Any output may be NULL.  Host only. */
 int cngp_storage_bytes(const cngp_config *cfg, size_t *D_f_bytes, size_t *D_c_level_bytes, size_t *D_c_bytes);
 
-/* Bytes of device scratch the calls below need for N points (may be 0; with F = 2 only cngp_encode_bwd uses it, with
- * another F the forward passes do as well: one pair of features at a time is copied out of D_f, y, dL/dy and back).
+/* Bytes of device scratch the calls below use for N points (may be 0): the larger of what cngp_encode_bwd needs
+ * (softmax table, level-major dL/dy, bins; CNGP_ERR_WORKSPACE without it) and what the forward calls can use
+ * (cngp_fwd_workspace_bytes below; without it they run a slower variant with the same result).  With F != 2 one pair
+ * of features at a time is copied out of D_f, y, dL/dy and back, and those planes sit in the workspace too (the
+ * forward calls then need it as well).
  * The workspace must be 256-byte aligned; its contents are undefined before and after each call.
  * Returns 0 for an invalid configuration as well (the encode calls then report the error). */
 size_t cngp_workspace_bytes(const cngp_config *cfg, int64_t N);
@@ -141,7 +144,8 @@ int cngp_fwd_plan_info(const cngp_config *cfg, int64_t N, int32_t *info);
  *   x    dev  float32 [N, d], inside [0,1]^d; scaled per level as one fp32 multiply x * N_l
  *   D_f  dev  feat_dtype [L, N_f, F]
  *   D_c  dev  index_format, see above
- *   y    dev  io_dtype [N, L*F], written (not accumulated); fp32 arithmetic, one final rounding */
+ *   y    dev  io_dtype [N, L*F], written (not accumulated); fp32 arithmetic, one final rounding
+ *   workspace  dev, may be NULL (see above); the variants differ in speed only, their encodings are bit-identical */
 int cngp_encode_fwd(const cngp_config *cfg, const float *x, int64_t N,
                     const void *D_f, const void *D_c, void *y,
                     void *workspace, size_t workspace_bytes, void *stream);
