@@ -480,8 +480,13 @@ def test_full_size_inference_sampled():
     D_f = W.make_feature_codebook(w)
     D_c = oracle.bake_probes(W.make_probe_logits(w))
     cfg = cngp.Config.from_workload(w, index_format=cngp.IDX_PACKED4)
-    y = cngp.encode_fwd(cfg, dev(x), dev(D_f), cngp.pack4(dev(D_c)))
+    # as the benchmark runs it: with the workspace, i.e. the level-resident variant; the tile variant gives the same bits
+    assert cngp.fwd_plan_info(cfg, w.N)["level_resident"] == 1
+    y = cngp.encode_fwd(cfg, dev(x), dev(D_f), cngp.pack4(dev(D_c)), workspace=cngp.alloc_workspace(cfg, w.N))
+    y_tile = cngp.encode_fwd(cfg, dev(x), dev(D_f), cngp.pack4(dev(D_c)))
     torch.cuda.synchronize()
+    assert torch.equal(y, y_tile)
+    del y_tile
     pick = np.random.default_rng(5).choice(w.N, 1 << 16, replace=False)
     pick[:2] = [0, w.N - 1]
     y_ref, ymag = oracle.encode_fwd(w, x[pick], D_f, D_c)
@@ -491,7 +496,7 @@ def test_full_size_inference_sampled():
                   feat_dtype="f16", io_dtype="f16")
     cfg1 = cngp.Config.from_workload(w1)
     zeros = np.zeros((16, 1), np.uint8)
-    y1 = cngp.encode_fwd(cfg1, dev(x), dev(D_f), dev(zeros))
+    y1 = cngp.encode_fwd(cfg1, dev(x), dev(D_f), dev(zeros), workspace=cngp.alloc_workspace(cfg1, w.N))
     y1_ref, y1mag = oracle.encode_fwd(w1, x[pick], D_f, zeros)
     check_close("y hash grid sample", host(y1[torch.from_numpy(pick).to(DEV)]), y1_ref, y1mag, fp16_out=True)
 

@@ -94,8 +94,11 @@ def test_large_tile_forward(fmt):
                cngp.IDX_BITS: dev(oracle.pack_index_bits(D_c, w.N_p))}[fmt]
     y = cngp.encode_fwd(cngp.Config.from_workload(w, index_format=fmt), dev(x), dev(D_f), D_c_dev)
     y_simple = cngp.encode_fwd(cngp.Config.from_workload(w, index_format=fmt, flags=cngp.FWD_SIMPLE), dev(x), dev(D_f), D_c_dev)
+    cfg = cngp.Config.from_workload(w, index_format=fmt)
+    y_level = cngp.encode_fwd(cfg, dev(x), dev(D_f), D_c_dev, workspace=cngp.alloc_workspace(cfg, n))   # level-resident
     torch.cuda.synchronize()
-    assert torch.equal(y, y_simple)
+    assert torch.equal(y, y_simple) and torch.equal(y, y_level)
+    assert cngp.fwd_plan_info(cfg, n)["resident_entries"] == w.N_f       # the whole feature codebook of a level in LDS
     pick = np.r_[0:4096, n - 4096:n]
     y_ref, ymag = oracle.encode_fwd(w, x[pick], D_f, D_c)
     check_close("y", y.float().cpu().numpy()[pick], y_ref, ymag, fp16_out=True)
