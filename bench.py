@@ -58,23 +58,34 @@ def sources_sha16():
 
 
 def distinct_vertices(np, x_h, res, sample=1 << 20):
-    """Grid vertices the batch touches, per level (the 2^d corners of every point's cell).  Exact up to `sample`
-    points; a larger batch is extrapolated from its first `sample` points with the occupancy law
-    V(R) = G (1 - exp(-R / G)), G fitted to the sample.  Measurement of the input, used only for the roofline."""
+    """Per level: the grid vertices the batch touches and its corner references, counting only corners whose
+    interpolation weight is not exactly zero (a point on a face of its cell has corners that contribute nothing, in
+    either direction; the kernels skip them, so the bound must not count them either).  Exact up to `sample` points; a
+    larger batch is extrapolated from its first `sample` points with the occupancy law V(R) = G (1 - exp(-R / G)), G
+    fitted to the sample.  Measurement of the input, used only for the roofline.  Returns (vertices, references)."""
     n, d = x_h.shape
     xs = x_h[:sample]
-    out = []
+    out_v, out_r = [], []
     for nl in res:
-        v0 = np.floor(xs * np.float32(nl)).astype(np.int64)
+        pos = xs * np.float32(nl)                                 # fp32 product, as the kernels form it
+        fl = np.floor(pos)
+        on_face = (pos - fl) == 0                                 # fraction exactly zero along that axis
+        v0 = fl.astype(np.int64)
         ids = []
         for c in range(1 << d):
-            v = v0 + np.array([(c >> i) & 1 for i in range(d)], dtype=np.int64)
+            bits = [(c >> i) & 1 for i in range(d)]
+            v = v0 + np.array(bits, dtype=np.int64)
+            dead = np.zeros(xs.shape[0], dtype=bool)              # weight zero: an upper corner along an axis with fraction 0
+            for i in range(d):
+                if bits[i]:
+                    dead |= on_face[:, i]
             vid = v[:, 0]
             for i in range(1, d):
                 vid = vid * (int(nl) + 2) + v[:, i]
-            ids.append(vid)
-        V = int(np.unique(np.concatenate(ids)).size)
-        R = xs.shape[0] << d
+            ids.append(vid[~dead])
+        ids = np.concatenate(ids)
+        V = int(np.unique(ids).size)
+        R = int(ids.size)
         if n > xs.shape[0] and V < R:
             lo, hi = float(V), float(V) * 1e6                 # solve G (1 - exp(-R / G)) = V for G by bisection
             for _ in range(200):
@@ -83,14 +94,17 @@ def distinct_vertices(np, x_h, res, sample=1 << 20):
                     lo = G
                 else:
                     hi = G
-            V = int(G * -np.expm1(-(n << d) / G))
+            R = int(R * (n / xs.shape[0]))
+            V = int(G * -np.expm1(-R / G))
         elif n > xs.shape[0]:
-            V = n << d
-        out.append(V)
-    return out
+            R = int(R * (n / xs.shape[0]))
+            V = R
+        out_v.append(V)
+        out_r.append(R)
+    return out_v, out_r
 
 
-def level_rooflines(w, n, index_level_bytes, res, V, rates, fwd_only, lds_share=0.0):
+def level_rooflines(w, n, index_level_bytes, res, V, refs, rates, fwd_only, lds_share=0.0):
     """The applicable roofline, level by level: t_l = max(t_stream, t_rand, t_atomic), summed over the levels.
       t_stream  the level's share of the compulsory bytes (points and outputs split evenly over the levels, the
                 level's own tables) at the measured streaming rate of a cache-resident working set
@@ -105,11 +119,10 @@ def level_rooflines(w, n, index_level_bytes, res, V, rates, fwd_only, lds_share=
     Times in microseconds."""
     fb = 2 if w.feat_dtype == "f16" else 4
     iob = 2 if w.io_dtype == "f16" else 4
-    corners = 1 << w.d
-    R = n * corners
     near = 4 << 20                                            # one XCD's L2
     rows = []
     for l in range(w.L):
+        R = refs[l]                                           # corner references of weight != 0
         reused = min(R, V[l])
         D_f_l, D_c_l = w.N_f * w.F * fb, index_level_bytes
         Dhat_l, gD_f_l = w.N_c * w.N_p * 4, w.N_f * w.F * 4
@@ -448,10 +461,10 @@ def main():
     # points (an L = 1 configuration at that level's resolution with that level's tables).
     rates = cngp.measure_rates(dev)
     res = cngp.level_resolutions(cfg)
-    V = distinct_vertices(np, x_h, res)
+    V, refs = distinct_vertices(np, x_h, res)
     fplan = cngp.fwd_plan_info(cfg, N) if ws is not None else {"level_resident": 0}
     lds_share = fplan["resident_entries"] / w.N_f if fplan["level_resident"] else 0.0
-    levels = level_rooflines(w, N, cfg.index_cols, res, V, rates, fwd_only, lds_share)
+    levels = level_rooflines(w, N, cfg.index_cols, res, V, refs, rates, fwd_only, lds_share)
     t_fwd = per_kernel["encode_mlp_fwd" if fused_dec else "encode_fwd"]["ms"] / args.steps * 1e3          # us
     if not args.no_extras:
         y_l = torch.empty((N, w.F), dtype=y.dtype, device=dev)

@@ -194,6 +194,9 @@ int cngp_encode_fwd_permuted(const cngp_config *cfg, const float *x_sorted, cons
  *   grad_D_f     dev float32 [L, N_f, F]      accumulated (+=), or cleared first with CNGP_ZERO_GRADS
  *   grad_Dhat_c  dev float32 [L, N_c, N_p]    same
  * Sums are formed with floating-point atomics: their order, hence the last bits, vary run to run.
+ * A vertex whose interpolation weight is exactly zero (the point lies on a face of its cell) contributes exactly
+ * nothing; the variants that accumulate in LDS leave such references out altogether, so a non-finite dL/dy or
+ * D_f entry reaches the gradients only through the vertices of non-zero weight (every point has at least one).
  * A batch whose binned references would pass cfg->bin_bytes_max is taken in several passes over runs of
  * points, each adding onto the one before, inside the one call (cngp_bwd_plan_info reports how many). */
 int cngp_encode_bwd(const cngp_config *cfg, const float *x, int64_t N,

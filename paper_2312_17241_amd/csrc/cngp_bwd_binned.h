@@ -77,6 +77,22 @@ __device__ __forceinline__ void corner_vertices(const float (&xp)[D], const floa
     }
 }
 
+// A corner whose interpolation weight is exactly zero (the point lies on a face of its cell: clipped samples
+// do) adds exactly nothing to either gradient, so it is never binned.  The weight is the product the drain
+// itself forms (no factor below 2^-24, so the product of up to four cannot underflow to zero).
+template <int D>
+__device__ __forceinline__ float corner_weight(const float (&xp)[D], const float res, const int c) {
+#pragma clang fp contract(off)
+    float wt = 1.0f;
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        const float pos = xp[j] * res;                      // one rounded fp32 multiply
+        const float w = pos - floorf(pos);
+        wt *= ((c >> j) & 1) ? w : 1.0f - w;
+    }
+    return wt;
+}
+
 // Slice of the feature table (role 0) / confidence table (role 1) a corner's hashes select.
 template <int D>
 __device__ __forceinline__ void corner_rows(const Cell<D> &cell, const Params &p, const int c, uint32_t &h1, uint32_t &h2) {
@@ -108,7 +124,8 @@ __device__ __forceinline__ void bin_count_block(
             uint32_t v[1 << D];
             corner_vertices<D>(xp, (float)p.N_l[ld], dl.side[ld], v);
 #pragma unroll
-            for (int c = 0; c < (1 << D); ++c) atomicAdd(&own[grid_bin(v[c])], 1u);
+            for (int c = 0; c < (1 << D); ++c)
+                if (corner_weight<D>(xp, (float)p.N_l[ld], c) != 0.0f) atomicAdd(&own[grid_bin(v[c])], 1u);
         }
         __syncthreads();
         uint32_t *rowG = cntG + ((size_t)ld * bp.chunks + chunk) * kGridBins;
@@ -135,6 +152,7 @@ __device__ __forceinline__ void bin_count_block(
         cell.locate(xp, p.N_l[l]);
 #pragma unroll
         for (int c = 0; c < (1 << D); ++c) {
+            if (cell.weight(c) == 0.0f) continue;
             uint32_t h1, h2;
             corner_rows<D>(cell, p, c, h1, h2);
             if (bp.slices_f) atomicAdd(&mine[h1 >> bp.rows_f_log2], 1u);
@@ -262,6 +280,7 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
             corner_vertices<D>(xp, (float)p.N_l[ld], dl.side[ld], v);
 #pragma unroll
             for (int c = 0; c < (1 << D); ++c) {
+                if (corner_weight<D>(xp, (float)p.N_l[ld], c) == 0.0f) continue;
                 const uint32_t pos = atomicAdd(&cursor[grid_bin(v[c])], 1u);
                 outG[pos] = ((uint32_t)n << D) | (uint32_t)c;
             }
@@ -288,6 +307,7 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
         cell.locate(xp, p.N_l[l]);
 #pragma unroll
         for (int c = 0; c < (1 << D); ++c) {
+            if (cell.weight(c) == 0.0f) continue;
             uint32_t h1, h2;
             corner_rows<D>(cell, p, c, h1, h2);
             const uint32_t ref = ((uint32_t)n << D) | (uint32_t)c;

@@ -301,6 +301,14 @@ __device__ __forceinline__ void scan_chunk(const Params &p, const SliceParams &s
                 for (int i = 0; i < D; ++i) h ^= ((c >> i) & 1) ? b[i] : a[i];
                 if ((h & slice_sel) == slice_val) accepted |= 1u << c;
             }
+            // a corner with weight exactly zero (the point on a face of its cell) adds nothing: never emitted
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                uint32_t upper = 0;                                 // the corners whose bit i is set
+#pragma unroll
+                for (int c = 0; c < (1 << D); ++c) upper |= (uint32_t)((c >> i) & 1) << c;
+                if (w[i] == 0.0f) accepted &= ~upper;
+            }
             if (!valid) accepted = 0;
         }
 

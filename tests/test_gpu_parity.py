@@ -50,10 +50,11 @@ def run_bwd(w, x, D_f, Dhat, dy, flags=cngp.ZERO_GRADS, init=None, **over):
 
 
 def check_fwd(w, x, D_f, D_c, index_format=cngp.IDX_U8, name=""):
-    """Both forward variants (index codebook staged in LDS; read from memory) against the oracle."""
+    """The forward variants (the library's own choice given a workspace: level-resident where it can run; tile: index
+    codebook staged in LDS per tile; simple: everything read from memory) against the oracle."""
     y_ref, ymag = oracle.encode_fwd(w, x, D_f, D_c)
     worst = 0.0
-    for variant, flags in (("tile", 0), ("simple", cngp.FWD_SIMPLE)):
+    for variant, flags in (("own choice", 0), ("tile", cngp.FWD_TILE), ("simple", cngp.FWD_SIMPLE)):
         y = run_fwd(w, x, D_f, D_c, index_format, flags)
         worst = max(worst, check_close(f"y {name} [{variant}]", y, y_ref, ymag, fp16_out=(w.io_dtype == "f16")))
     return worst
@@ -521,3 +522,23 @@ def test_probe_entries_beyond_the_probe_range_are_masked():
             y_bad = cngp.encode_fwd(cfg, dev(x), dev(D_f), pack(bad))
             torch.cuda.synchronize()
             assert torch.equal(y_clean, y_bad)
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_points_on_cell_faces_and_grid_vertices(d):
+    """Corners of weight exactly zero are skipped by the LDS variants of the backward pass (no record, no emission:
+    they add exactly nothing); the oracle adds their zeros.  Half of all coordinates sit on multiples of 1/16 here,
+    i.e. on cell faces of every level whose resolution is a multiple of 16, a tenth of the points are clipped to the
+    faces of the cube, some lie on grid vertices: every variant, both directions."""
+    w = W.custom(cfg=86 + d, d=d, L=6, N_f=2**13, N_c=2**11, N_p=8, N_min=16, N_max=512, N=60000 + 3,
+                 feat_dtype="f16", io_dtype="f16")
+    x, D_f, Dhat, dy = tables(w)
+    rng = np.random.default_rng(17)
+    snap = rng.random(x.shape) < 0.5
+    x[snap] = np.round(x[snap] * 16.0) / 16.0
+    edge = rng.random(x.shape[0]) < 0.1
+    x[edge] = np.round(x[edge])
+    assert np.mean(x == np.round(x * 16) / 16) > 0.5
+    D_f = (D_f.astype(np.float64) * 1e4).astype(D_f.dtype)
+    check_fwd(w, x, D_f, oracle.bake_probes(Dhat), name="faces")
+    check_bwd(w, x, D_f, Dhat, dy, name="faces")
