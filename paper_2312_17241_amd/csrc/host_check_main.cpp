@@ -54,6 +54,13 @@ int main() {
         const size_t ws = cngp_workspace_bytes(&c, N);
         const int rp = cngp_bwd_plan_info(&c, N, info);
         const int rr = cngp_bwd_plan_layout(&c, N, regions);
+        int32_t finfo[CNGP_FWD_PLAN_INFO_COUNT] = {0, 0, 0, 0};
+        const int    rf = cngp_fwd_plan_info(&c, N, finfo);
+        const size_t fws = cngp_fwd_workspace_bytes(&c, N);
+        if (rf == CNGP_OK) {            // the level-resident forward: resident entries and LDS within their limits, room inside the workspace
+            if (finfo[0] && ((uint32_t)finfo[1] > c.N_f || finfo[3] > 160 * 1024 || finfo[2] < 1 || fws > ws)) bad |= 2048;
+            if (!finfo[0] && c.F == 2 && fws != 0) bad |= 4096;
+        }
         if (rp == CNGP_OK) {
             if (rl != CNGP_OK || rs != CNGP_OK || rr < 0) bad |= 1;
             for (int i = 0; i < rr; ++i)

@@ -267,6 +267,35 @@ def test_backward_plan_layout_stays_inside_the_workspace():
     assert min(seen.values()) >= 5, seen          # the sweep reaches every variant
 
 
+def test_forward_plan_is_within_the_chip_and_the_workspace():
+    """The level-resident forward variant for seeded random configurations: the resident part of a level's feature
+    codebook is a whole number of 16-byte pieces, at most the codebook; index codebook and resident part fit 160 KB of
+    LDS; the level-major copy it needs fits cngp_workspace_bytes; the flags that force a variant are honoured."""
+    rng = np.random.default_rng(77)
+    taken = 0
+    for it in range(300):
+        N_p = int(2 ** rng.integers(0, 5))
+        N_f = int(2 ** rng.integers(max(2, int(np.log2(N_p))), 22))
+        feat, io = str(rng.choice(["f16", "f32"])), str(rng.choice(["f16", "f32"]))
+        w = W.custom(cfg=8, d=int(rng.choice([2, 3, 4])), L=int(rng.integers(1, 17)), N_f=N_f, N_c=int(2 ** rng.integers(0, 21)),
+                     N_p=N_p, N_min=4, N_max=256, N=int(rng.choice([1, 500, 4097, 2**17, 2**22 + 3])), feat_dtype=feat, io_dtype=io)
+        cfg = cngp.Config.from_workload(w, flags=int(rng.choice([0, 0, cngp.FWD_LEVEL])))
+        plan = cngp.fwd_plan_info(cfg, w.N)
+        need = cngp.fwd_workspace_bytes(cfg, w.N)
+        entry = 2 * (2 if feat == "f16" else 4)
+        if plan["level_resident"]:
+            taken += 1
+            assert 0 < plan["resident_entries"] <= N_f and (plan["resident_entries"] * entry) % 16 == 0, (w, plan)
+            assert plan["lds_bytes"] <= 160 * 1024 and plan["lds_bytes"] >= plan["resident_entries"] * entry + (w.N_c + 1) // 2
+            assert plan["parts"] >= 1
+            assert need == w.N * w.L * 2 * (2 if io == "f16" else 4) <= cngp.workspace_bytes(cfg, w.N)
+        else:
+            assert need == 0, (w, plan)
+        tile = cngp.Config.from_workload(w, flags=cngp.FWD_TILE)
+        assert cngp.fwd_plan_info(tile, w.N)["level_resident"] == 0 and cngp.fwd_workspace_bytes(tile, w.N) == 0
+    assert taken >= 100
+
+
 def test_host_code_runs_clean_under_sanitizers():
     """csrc/host_check_main.cpp drives validation, level table, storage sizes, the backward plan and its workspace
     layout through the C ABI for 300 seeded random configurations (valid and invalid) in a program whose host side
