@@ -52,7 +52,8 @@ def sources_sha16():
     import hashlib
     h = hashlib.sha256()
     base = os.path.join(ROOT, "paper_2312_17241_amd", "csrc")
-    for f in sorted(os.listdir(base)) + [os.path.join("..", "..", "include", "cngp.h")]:
+    kernel_sources = [f for f in sorted(os.listdir(base)) if not f.endswith("_main.cpp")]     # (not the host-only check program)
+    for f in kernel_sources + [os.path.join("..", "..", "include", "cngp.h")]:
         h.update(open(os.path.join(base, f), "rb").read())
     return h.hexdigest()[:16]
 

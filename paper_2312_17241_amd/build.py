@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcngp.so")
 SOURCES = ["cngp_api.hip", "cngp_sort.hip"]
-HEADERS = ["cngp_device.h", "cngp_kernels.h", "cngp_bwd_sliced.h", "cngp_bwd_binned.h", "cngp_optim.h", "cngp_mlp.h", "cngp_rates.h", os.path.join("..", "..", "include", "cngp.h")]
+HEADERS = ["cngp_device.h", "cngp_kernels.h", "cngp_fwd_level.h", "cngp_bwd_sliced.h", "cngp_bwd_binned.h", "cngp_optim.h", "cngp_mlp.h", "cngp_rates.h", os.path.join("..", "..", "include", "cngp.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
