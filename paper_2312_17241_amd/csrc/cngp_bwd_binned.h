@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kOffsetsBlock) void bin_offsets_kernel(
     const BinParams bp, uint32_t *__restrict__ cntF, uint32_t *__restrict__ cntC, uint32_t *__restrict__ cntG,
     uint32_t *__restrict__ baseF, uint32_t *__restrict__ baseC, uint32_t *__restrict__ baseG, const uint32_t lds_words)
 {
-    extern __shared__ uint32_t mat[];
+    extern __shared__ __align__(16) uint32_t mat[];
     __shared__ uint32_t part[kOffsetsBlock];                // [segment][slice lane]: sum of the thread's run
     __shared__ uint32_t carry;                              // records of the slices handled in earlier rounds
     // workgroups 0 .. 2 nlevels - 1: (hashed level, table); then one per pre-reduced level
@@ -207,7 +207,13 @@ __global__ __launch_bounds__(kOffsetsBlock) void bin_offsets_kernel(
     const uint32_t elems = bp.chunks * slices;
     const bool     in_lds = elems <= lds_words;
     uint32_t      *cnt = in_lds ? mat : gcnt;
-    if (in_lds)
+    // (the copies in and out move 16 bytes per lane and step: word by word they were a chain of memory latencies that
+    // took longer than the scans)
+    const bool wide = in_lds && elems % 4u == 0 && (reinterpret_cast<uintptr_t>(gcnt) & 15u) == 0;
+    if (wide)
+        for (uint32_t i = threadIdx.x; i < elems / 4u; i += kOffsetsBlock)
+            reinterpret_cast<uint4 *>(mat)[i] = reinterpret_cast<const uint4 *>(gcnt)[i];
+    else if (in_lds)
         for (uint32_t i = threadIdx.x; i < elems; i += kOffsetsBlock) mat[i] = gcnt[i];
     if (threadIdx.x == 0) carry = 0u;
     __syncthreads();
@@ -251,7 +257,11 @@ __global__ __launch_bounds__(kOffsetsBlock) void bin_offsets_kernel(
     if (threadIdx.x == 0) base[slices] = carry;
     if (in_lds) {
         __syncthreads();
-        for (uint32_t i = threadIdx.x; i < elems; i += kOffsetsBlock) gcnt[i] = mat[i];
+        if (wide)
+            for (uint32_t i = threadIdx.x; i < elems / 4u; i += kOffsetsBlock)
+                reinterpret_cast<uint4 *>(gcnt)[i] = reinterpret_cast<const uint4 *>(mat)[i];
+        else
+            for (uint32_t i = threadIdx.x; i < elems; i += kOffsetsBlock) gcnt[i] = mat[i];
     }
 }
 
