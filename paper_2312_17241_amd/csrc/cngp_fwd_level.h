@@ -45,17 +45,33 @@ __global__ __launch_bounds__(kLevelBlock) void encode_fwd_level_kernel(
     IoT           *out = yT + (size_t)l * (size_t)N * 2;
     const uint32_t N_l = p.N_l[l];
 
-    for (int64_t n0 = n_begin + t; n0 < n_end; n0 += (int64_t)kLevelUnroll * kLevelBlock) {
+    // the coordinates of the next step's points are loaded while this step's lookups are under way
+    constexpr int64_t kStep = (int64_t)kLevelUnroll * kLevelBlock;
+    float xnext[kLevelUnroll][D];
+    auto fetch = [&](const int64_t first) {
+#pragma unroll
+        for (int u = 0; u < kLevelUnroll; ++u) {
+            const int64_t n = first + (int64_t)u * kLevelBlock;
+#pragma unroll
+            for (int j = 0; j < D; ++j) xnext[u][j] = n < n_end ? x[n * D + j] : 0.0f;
+        }
+    };
+    fetch(n_begin + t);
+    for (int64_t n0 = n_begin + t; n0 < n_end; n0 += kStep) {
         uint32_t idx[kLevelUnroll][1 << D];
         float    wt[kLevelUnroll][1 << D];
         bool     live[kLevelUnroll];
+        float    xcur[kLevelUnroll][D];
+#pragma unroll
+        for (int u = 0; u < kLevelUnroll; ++u)
+#pragma unroll
+            for (int j = 0; j < D; ++j) xcur[u][j] = xnext[u][j];
+        fetch(n0 + kStep);
 #pragma unroll
         for (int u = 0; u < kLevelUnroll; ++u) {
             const int64_t n = n0 + (int64_t)u * kLevelBlock;
             live[u] = n < n_end;
-            float xp[D];
-#pragma unroll
-            for (int j = 0; j < D; ++j) xp[j] = live[u] ? x[n * D + j] : 0.0f;
+            const float (&xp)[D] = xcur[u];
             Cell<D> cell;
             cell.locate(xp, N_l);
 #pragma unroll
@@ -105,8 +121,15 @@ __global__ __launch_bounds__(kRowsTile) void level_major_to_rows_kernel(
     const Pair   *src = reinterpret_cast<const Pair *>(yT);
     Pair          zero;
     __builtin_memset(&zero, 0, sizeof(zero));
-    for (int l = 0; l < L; ++l)
-        tile[t * (L + 1) + l] = (l < L_loaded && t < rows) ? src[(size_t)l * (size_t)N + (size_t)(n0 + t)] : zero;
+    for (int l0 = 0; l0 < L; l0 += 8) {                     // eight levels' loads in flight, then their LDS writes
+        Pair v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            v[j] = (l0 + j < L_loaded && t < rows) ? src[(size_t)(l0 + j) * (size_t)N + (size_t)(n0 + t)] : zero;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (l0 + j < L) tile[t * (L + 1) + l0 + j] = v[j];
+    }
     __syncthreads();
     Pair *dst = reinterpret_cast<Pair *>(y);
     for (int i = t; i < (int)rows * L; i += kRowsTile) {
