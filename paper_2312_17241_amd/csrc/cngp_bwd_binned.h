@@ -334,11 +334,16 @@ __global__ __launch_bounds__(256) void bin_scatter_kernel(
 }
 
 // ------------------------------------------------------------------ drain
-// Value of lane `u` of this lane's group of NP lanes.  Groups of 16 (a DPP row), 4 and 2 (inside a quad): one VALU move.
+// Value of lane `u` of this lane's group of NP lanes.  Groups of 16 (a DPP row), 4 and 2 (inside a quad): one VALU move;
+// groups of 8 (half a row): two, each writing the two banks of four lanes of its half (a cross-lane read through the
+// LDS crossbar instead cost the drain a fifth of its time at N_p = 8).
 template <int NP, int U>
 __device__ __forceinline__ uint32_t group_bcast(const uint32_t v) {
     if constexpr (NP == 16) {                                             // row_newbcast:U
         return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x150 + U, 0xF, 0xF, true);
+    } else if constexpr (NP == 8) {                                       // row_newbcast:U into banks 0-1, row_newbcast:8+U into banks 2-3
+        const int lo = __builtin_amdgcn_update_dpp(0, (int)v, 0x150 + U, 0xF, 0x3, false);
+        return (uint32_t)__builtin_amdgcn_update_dpp(lo, (int)v, 0x150 + 8 + U, 0xF, 0xC, false);
     } else if constexpr (NP == 4) {                                       // quad_perm:[U,U,U,U]
         return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, U * 0x55, 0xF, 0xF, true);
     } else if constexpr (NP == 2) {                                       // quad_perm:[U,U,U+2,U+2]
