@@ -82,7 +82,7 @@ enum {
 
 /* Hyper-parameters of the encoding (Table 1 of the paper, same symbols). */
 typedef struct {
-    int32_t  d;            /* dimension of the input domain: 2, 3 or 4 (Morton sort: 2 or 3)  */
+    int32_t  d;            /* dimension of the input domain: 2, 3 or 4                         */
     int32_t  L;            /* number of resolution levels, 1 .. 32                             */
     int32_t  F;            /* features per codebook entry: 1, 2, 4 or 8 (the paper's value is 2, and 2 is the
                               width every kernel works in: the others run as ceil(F / 2) passes over pairs of
@@ -162,13 +162,14 @@ int cngp_encode_fwd_partial(const cngp_config *cfg, int32_t levels_loaded, const
  * between neighbouring vertices, but neighbouring points share the vertices of the coarse levels, so a batch
  * in Morton order is encoded mostly from the first-level cache: measured 2x on uniformly random points).
  * cngp_morton_sort: code(x) = the interleaved bits (bit b of coordinate j at position b * d + j) of
- * q_j = min(max(floor(x_j * 2^B), 0), 2^B - 1), B = 7 (d = 3) or 10 (d = 2); perm = the STABLE ascending order of
+ * q_j = min(max(floor(x_j * 2^B), 0), 2^B - 1), B = 10, 7, 5 for d = 2, 3, 4; perm = the STABLE ascending order of
  * the codes, i.e. perm[i] is the index of the i-th point in Morton order, and x_sorted[i] = x[perm[i]].
  *   x         dev float32 [N, d]
  *   perm      dev int32 [N], written
  *   x_sorted  dev float32 [N, d], written; may be NULL
- *   workspace dev, 256-byte aligned, cngp_morton_sort_workspace_bytes(d, N) bytes (0 = invalid d or N, or no device)
- * N <= 2^31 - 1.  The sorting passes are rocPRIM's radix sort.
+ *   workspace dev, 256-byte aligned, cngp_morton_sort_workspace_bytes(d, N) bytes (0 = invalid d or N): two key
+ *             columns, one index column, and 128 counters per tile of 8192 points (about 12 bytes per point)
+ * N <= 2^31 - 1.  The sort is this library's own: a stable radix sort of (code, index), 7 bits per pass.
  * cngp_encode_fwd_permuted: the forward encoding of x_sorted with row i of the result written to row perm[i] of
  * y, so y is in the order of the caller's original points and equals cngp_encode_fwd on them bit for bit.
  * perm must be a permutation of 0 .. N-1 (not checked: any other content writes outside y or leaves rows unset).

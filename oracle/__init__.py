@@ -217,12 +217,12 @@ def storage_bytes(w, index_bits_exact=True):
 
 def morton_order(x):
     """Order of a batch of points along the Morton (Z-order) curve: not part of the paper's method, an optional
-    reordering of the queries.  code(x) interleaves the bits of q_j = min(max(floor(x_j 2^B), 0), 2^B - 1), B = 7 in
-    3D and 10 in 2D, with bit b of coordinate j at position b d + j; the order is the stable ascending sort of the
+    reordering of the queries.  code(x) interleaves the bits of q_j = min(max(floor(x_j 2^B), 0), 2^B - 1), B = 10 in
+    2D, 7 in 3D and 5 in 4D, with bit b of coordinate j at position b d + j; the order is the stable ascending sort of the
     codes.  Returns (perm int32 [N], codes uint32 [N]); a NaN coordinate counts as 0."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     N, d = x.shape
-    B = 7 if d == 3 else 10
+    B = {2: 10, 3: 7, 4: 5}[d]
     v = np.floor(x.astype(np.float64) * float(1 << B))           # the scaling by a power of two is exact in fp32 too
     v = np.where(np.isnan(v), 0.0, v)
     q = np.clip(v, 0, (1 << B) - 1).astype(np.uint32)

@@ -282,7 +282,7 @@ def morton_sort(x, workspace=None):
         return perm, x_sorted
     need = int(_lib.cngp_morton_sort_workspace_bytes(d, N))
     if need == 0:
-        raise CngpError(ERR_INVALID, "morton_sort: d must be 2 or 3 and N below 2^31 (and a device present)")
+        raise CngpError(ERR_INVALID, "morton_sort: d must be 2, 3 or 4 and N below 2^31")
     if workspace is None or workspace.numel() * workspace.element_size() < need:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     wp, wb = _ws(workspace)

@@ -8,6 +8,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 
 static uint64_t g_state = 0x243F6A8885A308D3ull;
 static uint64_t next_u64() {                       // splitmix64
@@ -80,6 +81,12 @@ int main() {
     m.n_in = 40;
     if (cngp_mlp_weight_count(&m) != 0 || cngp_mlp_fwd(&m, nullptr, 8, nullptr, nullptr, nullptr) == CNGP_OK) bad |= 512;
     for (int s = 1; s >= -7; --s) if (!cngp_error_string(s)[0]) bad |= 1024;
+    // the sort's workspace: three columns of N words plus 128 counters per tile of 8192 points and 128 totals
+    for (int64_t N : {(int64_t)1, (int64_t)8192, (int64_t)8193, (int64_t)1 << 24, (int64_t)0x7fffffff}) {
+        const size_t col = ((size_t)N * 4 + 255) / 256 * 256, tiles = ((size_t)N + 8191) / 8192;
+        if (cngp_morton_sort_workspace_bytes(3, N) != 3 * col + (tiles * 512 + 255) / 256 * 256 + 512) bad |= 8192;
+    }
+    if (cngp_morton_sort_workspace_bytes(5, 100) != 0 || cngp_morton_sort(3, nullptr, 5, nullptr, nullptr, nullptr, 0, nullptr) == CNGP_OK) bad |= 8192;
     if (bad) { std::fprintf(stderr, "host sanitizer run: inconsistent results, mask %d\n", bad); return 1; }
     std::printf("host sanitizer run: clean\n");
     return 0;

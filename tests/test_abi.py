@@ -296,6 +296,19 @@ def test_forward_plan_is_within_the_chip_and_the_workspace():
     assert taken >= 100
 
 
+def test_morton_sort_workspace_is_host_arithmetic():
+    """Two key columns, one index column, 128 counters per tile of 8192 points, 128 totals; no device is asked."""
+    a = lambda v: (v + 255) // 256 * 256
+    f = cngp._lib.cngp_morton_sort_workspace_bytes
+    for N in (1, 8192, 8193, 2**24, 2**31 - 1):
+        tiles = (N + 8191) // 8192
+        assert f(3, N) == f(2, N) == f(4, N) == 3 * a(4 * N) + a(128 * 4 * tiles) + a(128 * 4)
+    assert f(3, 0) == 0 and f(3, -5) == 0 and f(3, 2**31) == 0 and f(5, 100) == 0 and f(1, 100) == 0
+    assert cngp._lib.cngp_morton_sort(3, None, 0, None, None, None, 0, None) == cngp.OK
+    assert cngp._lib.cngp_morton_sort(3, None, 10, None, None, None, 0, None) == cngp.ERR_NULL
+    assert cngp._lib.cngp_morton_sort(5, None, 10, None, None, None, 0, None) == cngp.ERR_INVALID
+
+
 def test_host_code_runs_clean_under_sanitizers():
     """csrc/host_check_main.cpp drives validation, level table, storage sizes, the backward plan and its workspace
     layout through the C ABI for 300 seeded random configurations (valid and invalid) in a program whose host side

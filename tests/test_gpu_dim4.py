@@ -143,8 +143,8 @@ def test_fused_encode_and_decoder():
     check("decoder(encode(x)) d=4", fused.cpu().numpy(), ref, mag)
 
 
-def test_morton_sort_is_for_two_and_three_dimensions():
-    x = torch.rand((1000, 4), device=DEV)
+def test_morton_sort_is_for_two_to_four_dimensions():
+    x = torch.rand((1000, 5), device=DEV)
     with pytest.raises(cngp.CngpError) as e:
         cngp.morton_sort(x)
     assert e.value.status == cngp.ERR_INVALID

@@ -64,7 +64,7 @@ def test_graph_replay_matches_the_oracle(flags, n, N_f, passes):
 
 
 def test_graph_replay_of_the_morton_pipeline():
-    """cngp_morton_sort (its radix passes are rocPRIM's) and cngp_encode_fwd_permuted captured together: every
+    """cngp_morton_sort and cngp_encode_fwd_permuted captured together: every
     replay gives the oracle's permutation and the plain forward's bits."""
     w = W.custom(cfg=70, d=3, L=5, N_f=2**11, N_c=2**9, N_p=8, N_min=4, N_max=300, N=50000 + 7, feat_dtype="f16", io_dtype="f16")
     cfg = cngp.Config.from_workload(w)

@@ -27,8 +27,8 @@ def points(d, N, seed):
     return x
 
 
-@pytest.mark.parametrize("d", [2, 3])
-@pytest.mark.parametrize("N", [1, 63, 257, 5000, 200003])
+@pytest.mark.parametrize("d", [2, 3, 4])
+@pytest.mark.parametrize("N", [1, 63, 257, 5000, 8192, 8193, 3 * 8192 - 1, 200003])
 def test_morton_sort_matches_the_oracle_bit_for_bit(d, N):
     x = points(d, N, seed=100 + d * 7 + N % 11)
     perm_ref, _ = oracle.morton_order(x)
@@ -36,6 +36,24 @@ def test_morton_sort_matches_the_oracle_bit_for_bit(d, N):
     torch.cuda.synchronize()
     check_exact("perm", perm.cpu().numpy(), perm_ref)
     check_exact("x_sorted", xs.cpu().numpy().view(np.uint32), x[perm_ref].view(np.uint32))
+
+
+def test_morton_sort_of_two_million_points():
+    """244 tiles and a ragged last one; every digit's run crosses many tiles."""
+    x = points(3, 2_000_003, seed=9)
+    perm_ref, _ = oracle.morton_order(x)
+    perm, xs = cngp.morton_sort(torch.from_numpy(x).to(DEV))
+    check_exact("perm", perm.cpu().numpy(), perm_ref)
+    check_exact("x_sorted", xs.cpu().numpy().view(np.uint32), x[perm_ref].view(np.uint32))
+
+
+def test_morton_sort_twice_in_one_workspace():
+    """The second call finds the first call's counters and keys in the workspace and must not depend on them."""
+    xa, xb = points(3, 50_000, seed=21), points(3, 20_001, seed=22)
+    ws = torch.empty(int(cngp._lib.cngp_morton_sort_workspace_bytes(3, 50_000)), dtype=torch.uint8, device=DEV)
+    for x in (xa, xb, xa):
+        perm, _ = cngp.morton_sort(torch.from_numpy(x).to(DEV), workspace=ws)
+        check_exact("perm", perm.cpu().numpy(), oracle.morton_order(x)[0])
 
 
 def test_morton_sort_of_a_clustered_batch():
@@ -94,7 +112,7 @@ def test_sort_argument_errors():
     perm = torch.empty(100, dtype=torch.int32, device=DEV)
     lib = cngp._lib
     import ctypes
-    assert lib.cngp_morton_sort(4, x.data_ptr(), 100, perm.data_ptr(), None, None, 0, None) == cngp.ERR_INVALID
+    assert lib.cngp_morton_sort(5, x.data_ptr(), 100, perm.data_ptr(), None, None, 0, None) == cngp.ERR_INVALID
     assert lib.cngp_morton_sort(3, x.data_ptr(), 100, None, None, None, 0, None) == cngp.ERR_NULL
     assert lib.cngp_morton_sort(3, x.data_ptr(), 100, perm.data_ptr(), None, None, 0, None) == cngp.ERR_WORKSPACE
     assert lib.cngp_morton_sort(3, x.data_ptr(), 0, None, None, None, 0, None) == cngp.OK

@@ -700,8 +700,13 @@ def test_morton_codes_by_hand_and_by_string_interleaving():
     pts3 = np.array([[1.1 * t, 0, 0], [0, 1.1 * t, 0], [0, 0, 1.1 * t], [1, 1, 1], [2.5 * t, 0, 3.5 * t]], np.float32)
     _, codes3 = oracle.morton_order(pts3)
     assert codes3.tolist() == [1, 2, 4, 2**21 - 1, int("101100", 2)]               # q = (2, 0, 3): z1 y1 x1 z0 y0 x0 = 1 0 1 1 0 0
+    # 4D, 5 bits per axis: single low bits of each axis, the corner of the cube, q = (0, 3, 0, 1): w0 = 8, y0 = 2, y1 = 32
+    u = 1.0 / 32
+    pts4 = np.array([[1.1 * u, 0, 0, 0], [0, 1.1 * u, 0, 0], [0, 0, 1.1 * u, 0], [0, 0, 0, 1.1 * u], [1, 1, 1, 1], [0, 3.5 * u, 0, 1.5 * u]], np.float32)
+    _, codes4 = oracle.morton_order(pts4)
+    assert codes4.tolist() == [1, 2, 4, 8, 2**20 - 1, 8 + 2 + 32]
     rng = np.random.default_rng(5)
-    for d, B in ((2, 10), (3, 7)):
+    for d, B in ((2, 10), (3, 7), (4, 5)):
         x = rng.random((500, d), dtype=np.float32)
         perm, codes = oracle.morton_order(x)
         q = np.minimum((x.astype(np.float64) * (1 << B)).astype(np.int64), (1 << B) - 1)
