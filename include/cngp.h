@@ -304,12 +304,18 @@ typedef struct cngp_mlp_config {
 size_t cngp_mlp_weight_count(const cngp_mlp_config *cfg);     /* 64 n_in + 64 * 64 + 64 n_out; 0 if invalid */
 int cngp_mlp_fwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const void *W, float *out, void *stream);
 
-/* Encoding and decoder in one kernel, for inference: out = decoder(encode(x)) without the encoded features
- * going to memory.  Equal to cngp_encode_fwd followed by cngp_mlp_fwd (the features pass as fp16 either way).
- * Needs mlp->n_in == cfg->L * cfg->F and an index codebook whose level fits in LDS (N_c <= 2^17 entries);
- * otherwise CNGP_ERR_UNSUPPORTED: make the two calls instead.  mlp->io_dtype and flags are ignored. */
+/* Encoding and decoder in one call, for inference: out = decoder(encode(x)).  Equal, bit for bit, to
+ * cngp_encode_fwd followed by cngp_mlp_fwd (the features pass as fp16 either way).
+ *   workspace dev, 256-byte aligned, N * L * F * 2 bytes (= cngp_fwd_workspace_bytes of the same configuration with
+ *             fp16 encodings), or NULL / 0.
+ * With the workspace (and a configuration the level-resident forward takes): that forward writes its level-major
+ * fp16 encodings into the workspace and the decoder reads them as they lie, so the kernel that turns them into
+ * rows of y and y itself are saved.  Without: one kernel in which the encoded features never go to memory, which
+ * is slower than the two separate calls and needs an index codebook whose level fits in LDS (N_c <= 2^17 entries;
+ * otherwise CNGP_ERR_UNSUPPORTED).  Needs mlp->n_in == cfg->L * cfg->F and F = 2; mlp->io_dtype and flags are ignored. */
 int cngp_encode_mlp_fwd(const cngp_config *cfg, const cngp_mlp_config *mlp, const float *x, int64_t N,
-                        const void *D_f, const void *D_c, const void *W, float *out, void *stream);
+                        const void *D_f, const void *D_c, const void *W, float *out,
+                        void *workspace, size_t workspace_bytes, void *stream);
 
 /* Backward pass of the decoder for L = sum(out * dout): recomputes the hidden layers, then
  *   dy      dev io_dtype [N, n_in]    written: dL/dy, the upstream gradient cngp_encode_bwd takes

@@ -86,7 +86,7 @@ def _load():
     lib.cngp_mlp_fwd.restype = ctypes.c_int
     lib.cngp_mlp_fwd.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.cngp_encode_mlp_fwd.restype = ctypes.c_int
-    lib.cngp_encode_mlp_fwd.argtypes = [cfgp, vp, vp, i64, vp, vp, vp, vp, vp]
+    lib.cngp_encode_mlp_fwd.argtypes = [cfgp, vp, vp, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.cngp_mlp_bwd.restype = ctypes.c_int
     lib.cngp_mlp_bwd.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
     lib.cngp_adam_step.restype = ctypes.c_int
@@ -474,16 +474,18 @@ def mlp_fwd(cfg: MlpConfig, y, W, out=None):
     return out
 
 
-def encode_mlp_fwd(cfg: Config, mcfg: MlpConfig, x, D_f, D_c, W, out=None):
-    """cngp_encode_mlp_fwd: decoder(encode(x)) in one kernel; float32 [N, n_out]."""
+def encode_mlp_fwd(cfg: Config, mcfg: MlpConfig, x, D_f, D_c, W, out=None, workspace=None):
+    """cngp_encode_mlp_fwd: decoder(encode(x)) in one call; float32 [N, n_out].  workspace: N * L * F * 2 bytes (or a
+    workspace of alloc_workspace for an fp16-output configuration) lets the level-resident forward feed the decoder."""
     N = x.shape[0]
     if out is None:
         out = torch.empty((N, mcfg.n_out), dtype=torch.float32, device=x.device)
     c, m = cfg.c(), mcfg.c()
+    wp, wb = _ws(workspace)
     _check(_lib.cngp_encode_mlp_fwd(
         ctypes.byref(c), ctypes.cast(ctypes.byref(m), ctypes.c_void_p), _dev(x, torch.float32, (N, cfg.d), "x"), N,
         _dev(D_f, _TORCH_DT[cfg.feat_dtype], (cfg.L, cfg.N_f, cfg.F), "D_f"), _dc(cfg, D_c),
-        _dev(W, torch.float16, (mcfg.weight_count,), "W"), _dev(out, torch.float32, (N, mcfg.n_out), "out"), _stream()))
+        _dev(W, torch.float16, (mcfg.weight_count,), "W"), _dev(out, torch.float32, (N, mcfg.n_out), "out"), wp, wb, _stream()))
     return out
 
 

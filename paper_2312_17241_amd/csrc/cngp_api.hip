@@ -227,7 +227,7 @@ FwdLevelPlan fwd_level_plan(const cngp_config *c, int levels_loaded, int64_t N) 
 
 template <int D, typename FeatT, typename IoT>
 int launch_fwd_level(const cngp_config *c, const FwdLevelPlan &f, const Params &p, const float *x, int64_t N, const void *D_f,
-                     const void *D_c, void *y, void *yT, hipStream_t s, const int32_t *perm) {
+                     const void *D_c, void *y, void *yT, hipStream_t s, const int32_t *perm, bool rows = true) {
     const size_t  c_stride = index_level_bytes(c);
     const int64_t blocks = f.parts * p.L_loaded;
     if (int rc = check_blocks(blocks)) return rc;
@@ -245,6 +245,7 @@ int launch_fwd_level(const cngp_config *c, const FwdLevelPlan &f, const Params &
     else CNGP_FWD_LEVEL_LAUNCH(kFmtU8);
 #undef CNGP_FWD_LEVEL_LAUNCH
     if (int rc = launch_status("encode_fwd_level_kernel")) return rc;
+    if (!rows) return CNGP_OK;                               // the caller reads the level-major array itself
     const int64_t tiles = (N + kRowsTile - 1) / kRowsTile;
     if (int rc = check_blocks(tiles)) return rc;
     const size_t lds = (size_t)kRowsTile * (c->L + 1) * 2 * sizeof(IoT);
@@ -1450,7 +1451,8 @@ int cngp_mlp_fwd(const cngp_mlp_config *cfg, const void *y, int64_t N, const voi
 }
 
 int cngp_encode_mlp_fwd(const cngp_config *cfg, const cngp_mlp_config *mlp, const float *x, int64_t N,
-                        const void *D_f, const void *D_c, const void *W, float *out, void *stream) {
+                        const void *D_f, const void *D_c, const void *W, float *out,
+                        void *workspace, size_t workspace_bytes, void *stream) {
     if (int rc = validate(cfg)) return rc;
     MlpDims d;
     if (int rc = mlp_dims(mlp, &d)) return rc;
@@ -1462,6 +1464,28 @@ int cngp_encode_mlp_fwd(const cngp_config *cfg, const cngp_mlp_config *mlp, cons
     if (cfg->index_format == CNGP_IDX_BITS && ((uintptr_t)D_c & 3u)) return CNGP_ERR_INVALID;
     const Params p = make_params(cfg);
     hipStream_t s = (hipStream_t)stream;
+    // With room for the level-major fp16 encodings: the level-resident forward without its rows kernel, and the
+    // decoder reading the planes as they are.
+    {
+        cngp_config c16 = *cfg;
+        c16.io_dtype = CNGP_F16;
+        const FwdLevelPlan f = fwd_level_plan(&c16, cfg->L, N);
+        if (f.use && workspace && workspace_bytes >= f.yT_bytes && ((uintptr_t)workspace & 255u) == 0 && ((uintptr_t)D_f & 15u) == 0) {
+            int rc;
+            const bool f16 = cfg->feat_dtype == CNGP_F16;
+            if (cfg->d == 2) rc = f16 ? launch_fwd_level<2, __half, __half>(&c16, f, p, x, N, D_f, D_c, nullptr, workspace, s, nullptr, false)
+                                      : launch_fwd_level<2, float, __half>(&c16, f, p, x, N, D_f, D_c, nullptr, workspace, s, nullptr, false);
+            else if (cfg->d == 3) rc = f16 ? launch_fwd_level<3, __half, __half>(&c16, f, p, x, N, D_f, D_c, nullptr, workspace, s, nullptr, false)
+                                           : launch_fwd_level<3, float, __half>(&c16, f, p, x, N, D_f, D_c, nullptr, workspace, s, nullptr, false);
+            else rc = f16 ? launch_fwd_level<4, __half, __half>(&c16, f, p, x, N, D_f, D_c, nullptr, workspace, s, nullptr, false)
+                          : launch_fwd_level<4, float, __half>(&c16, f, p, x, N, D_f, D_c, nullptr, workspace, s, nullptr, false);
+            if (rc) return rc;
+            const int64_t tiles = (N + 31) / 32;
+            LaunchTimer t(s, K_MLP_FWD);
+            mlp_fwd_kernel<__half, true><<<mlp_blocks(tiles, 3, 4), kMlpBlock, kMlpFwdLds, s>>>(d, (const __half *)workspace, N, (const __half *)W, out, tiles);
+            return launch_status("mlp_fwd_kernel");
+        }
+    }
     CNGP_DISPATCH_TYPES(launch_fused_fwd, cfg, p, d, x, N, D_f, D_c, W, out, s);
 }
 

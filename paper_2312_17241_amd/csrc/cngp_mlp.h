@@ -189,6 +189,24 @@ __device__ __forceinline__ void load_inputs(const MlpDims d, const IoT *__restri
     for (int s = 0; s < 4; ++s) yb[s] = load_b(y, pt, N, d.n_in, 8 * s + k4, d.vec_in != 0);
 }
 
+// The same from a level-major array yT[n_in / 2][N] of fp16 pairs (what the level-resident forward of the encoding
+// writes before its rows kernel): four halves of a row are two neighbouring planes' pairs, and the 32 lanes of a
+// tile read 128 contiguous bytes of each plane.
+__device__ __forceinline__ void load_inputs_planes(const MlpDims d, const uint32_t *__restrict__ yT, const int64_t pt,
+                                                   const int64_t N, const int lane, half4_t (&yb)[4]) {
+    const int k2 = 2 * (lane >> 5);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int l0 = 4 * s + k2;
+        uint2 v = make_uint2(0u, 0u);
+        if (pt < N) {
+            if (2 * l0 < d.n_in) v.x = yT[(size_t)l0 * (size_t)N + (size_t)pt];
+            if (2 * l0 + 2 < d.n_in) v.y = yT[(size_t)(l0 + 1) * (size_t)N + (size_t)pt];
+        }
+        yb[s] = *reinterpret_cast<const half4_t *>(&v);
+    }
+}
+
 // H.yb holds the inputs on entry.
 __device__ __forceinline__ void hidden_layers(const half8_t *ops, const MlpDims d, const int lane, Hidden &H) {
 #pragma unroll
@@ -224,11 +242,16 @@ static_assert(kMlpRawBytes <= (size_t)(kMlpBlock / 64) * kTileRows * kTileStride
 static_assert(kMlpAccBytes <= (size_t)(kMlpBlock / 64) * kTileRows * kTileStride * sizeof(_Float16), "the reduction shares the tile region");
 
 // ------------------------------------------------------------------ forward
-template <typename IoT>
+// PLANES: y is the level-major array of fp16 pairs described at load_inputs_planes (IoT = __half, n_in even).
+template <typename IoT, bool PLANES = false>
 __global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
     const MlpDims d, const IoT *__restrict__ y, const int64_t N, const __half *__restrict__ W,
     float *__restrict__ out, const int64_t tiles)
 {
+    auto fetch = [&](const int64_t pt, const int lane, half4_t (&yb)[4]) {
+        if constexpr (PLANES) load_inputs_planes(d, reinterpret_cast<const uint32_t *>(y), pt, N, lane, yb);
+        else load_inputs(d, y, pt, N, lane, yb);
+    };
     extern __shared__ __align__(16) unsigned char smem[];
     half8_t *ops = reinterpret_cast<half8_t *>(smem);
     stage_operands(ops, reinterpret_cast<__half *>(smem + kMlpFwdOps), W, d, kOpFwdSlots);
@@ -236,13 +259,13 @@ __global__ __launch_bounds__(kMlpBlock) void mlp_fwd_kernel(
     const int64_t waves = (int64_t)gridDim.x * (kMlpBlock / 64);
     int64_t tile = (int64_t)blockIdx.x * (kMlpBlock / 64) + (threadIdx.x >> 6);
     half4_t next[4];
-    load_inputs(d, y, tile * 32 + (lane & 31), N, lane, next);
+    fetch(tile * 32 + (lane & 31), lane, next);
     for (; tile < tiles; tile += waves) {
         const int64_t pt = tile * 32 + (lane & 31);
         Hidden H;
 #pragma unroll
         for (int s = 0; s < 4; ++s) H.yb[s] = next[s];
-        load_inputs(d, y, (tile + waves) * 32 + (lane & 31), N, lane, next);     // next tile, in flight during this one
+        fetch((tile + waves) * 32 + (lane & 31), lane, next);                    // next tile, in flight during this one
         hidden_layers(ops, d, lane, H);
         acc16_t o = acc_zero();
 #pragma unroll

@@ -114,6 +114,15 @@ def test_null_pointers_and_negative_counts():
     assert lib.cngp_debug_indices(ctypes.byref(c), None, 8, one, one, one, one, one, None) == cngp.ERR_NULL
     assert lib.cngp_debug_indices(ctypes.byref(c), one, 8, None, one, one, one, None, None) == cngp.ERR_NULL
     assert lib.cngp_level_resolutions(ctypes.byref(c), None) == cngp.ERR_NULL
+    # encoding + decoder in one call: checked on the host in the same way, with or without a workspace
+    b = base_cfg()
+    m, m_bad = cngp.MlpConfig(b.L * b.F, 3).c(), cngp.MlpConfig(b.L * b.F - 2, 3).c()
+    mp = lambda v: ctypes.cast(ctypes.byref(v), ctypes.c_void_p)
+    assert lib.cngp_encode_mlp_fwd(ctypes.byref(c), mp(m), None, 8, one, one, one, one, None, 0, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_mlp_fwd(ctypes.byref(c), mp(m), one, 8, one, one, None, one, one, 1 << 20, None) == cngp.ERR_NULL
+    assert lib.cngp_encode_mlp_fwd(ctypes.byref(c), mp(m), one, -1, one, one, one, one, None, 0, None) == cngp.ERR_INVALID
+    assert lib.cngp_encode_mlp_fwd(ctypes.byref(c), mp(m_bad), one, 8, one, one, one, one, None, 0, None) == cngp.ERR_INVALID
+    assert lib.cngp_encode_mlp_fwd(ctypes.byref(c), mp(m), None, 0, None, None, None, None, None, 0, None) == cngp.OK
 
 
 def test_adam_step_bake_rejects_bad_arguments():

@@ -188,9 +188,17 @@ def test_fused_encode_and_decoder(fmt, d, L, N_p, N_c, feat, io, n_out, N):
     two = cngp.mlp_fwd(mcfg, y, Wd)
     torch.cuda.synchronize()
     assert torch.equal(fused, two)
+    # with room for the level-major fp16 encodings: level-resident forward + the decoder reading the planes
+    need = N * L * 2 * 2
+    ws = torch.empty(need + 256, dtype=torch.uint8, device=DEV)
+    level = cngp.Config.from_workload(w, index_format=fmt, flags=cngp.FWD_LEVEL)
+    planes = cngp.encode_mlp_fwd(level, mcfg, dev(x_h), dev(D_f_h), D_c, Wd, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(planes, two)
     y_ref, _ = oracle.encode_fwd(w, x_h, D_f_h, D_c_h)
     ref, mag, _ = oracle.mlp_fwd(y_ref, W1, W2, W3, want_mag=True)
     check("decoder(encode(x))", fused.cpu().numpy(), ref, mag)
+    check("decoder(encode(x)), level-major", planes.cpu().numpy(), ref, mag)
 
 
 def test_fused_encode_and_decoder_refuses_what_it_cannot_do():
