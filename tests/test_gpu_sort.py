@@ -47,6 +47,16 @@ def test_morton_sort_of_two_million_points():
     check_exact("x_sorted", xs.cpu().numpy().view(np.uint32), x[perm_ref].view(np.uint32))
 
 
+def test_morton_sort_at_the_inference_batch_size():
+    """2^24 uniformly random points (the forward-only workload's batch): 2048 full tiles, every count near 2^17."""
+    rng = np.random.default_rng(77)
+    x = rng.random((2**24, 3), dtype=np.float32)
+    perm_ref, _ = oracle.morton_order(x)
+    perm, xs = cngp.morton_sort(torch.from_numpy(x).to(DEV))
+    check_exact("perm", perm.cpu().numpy(), perm_ref)
+    check_exact("x_sorted", xs.cpu().numpy().view(np.uint32), x[perm_ref].view(np.uint32))
+
+
 def test_morton_sort_twice_in_one_workspace():
     """The second call finds the first call's counters and keys in the workspace and must not depend on them."""
     xa, xb = points(3, 50_000, seed=21), points(3, 20_001, seed=22)
